@@ -1,0 +1,335 @@
+"""CPU checker for the partially-linear FFN hot path.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, fp64 numpy statement of what the method computes, written from
+the paper (arXiv 2501.10054) so that a reader can check it against the text by
+eye.  Only the tests, the smoke check and the benchmark's CPU-baseline leg may
+import this file; the GPU library never does, and this file imports nothing
+from the GPU library.
+
+Orientation.  The paper writes row vectors, FFN(x) = sigma(x W1) W2 with W1 of
+size d x h (Sec. "Opportunity").  Here tokens are column vectors and the weight
+arrays are the transposes, the layout a Linear layer stores:
+
+    W1 : h x d   (row j  = neuron j's input weights,  paper W1[:, j])
+    W2 : d x h   (col j  = neuron j's output weights, paper W2[j, :])
+    FFN(x) = W2 . sigma(W1 x + b1) + b2
+
+so the paper's folded matrix C is W'^T and its folded bias B is b'^T.  Paper
+symbols (a, b) for slope and intercept are (a_j, c_j) here because b1/b2 name
+the layer biases; the paper's range [l1, l2) is [lo_j, hi_j).
+
+Every floating-point step is fp64 unless a comment says the value is rounded to
+fp32 because the library interface carries it as fp32.
+
+Pins (tests/test_oracle_pins.py): the paper's printed two-neuron example, its
+2x2 folding example, the standard normal CDF table for GELU, closed forms for
+the least-squares fit, a literal per-neuron rank-1 fold, brute-force integer
+dot products, and the all-flagged / none-flagged identities.
+
+parity unpinned: nothing on the gated path.  (The integer predictor below is a
+reading of "a quantised copy of W1", Sec. "Predictor Generation"; the paper
+prints no numbers for it, so it is pinned by brute force and by the printed
+example's flag set, not by a published value.)
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+
+import numpy as np
+from scipy.special import erf as _erf
+
+ACTS = ("gelu_erf", "gelu_tanh", "relu", "identity")
+
+
+# ---------------------------------------------------------------------------
+# activation  (Sec. "Opportunity": sigma between the two weight matrices)
+# ---------------------------------------------------------------------------
+def act(z, kind: str = "gelu_erf"):
+    """sigma(z).  GELU is z * Phi(z) with Phi the standard normal CDF; the tanh
+    form is the usual approximation of it; ReLU is max(z, 0)."""
+    z = np.asarray(z, dtype=np.float64)
+    if kind == "gelu_erf":
+        return 0.5 * z * (1.0 + _erf(z / math.sqrt(2.0)))
+    if kind == "gelu_tanh":
+        return 0.5 * z * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (z + 0.044715 * z ** 3)))
+    if kind == "relu":
+        return np.maximum(z, 0.0)
+    if kind == "identity":
+        return z.copy()
+    raise ValueError(kind)
+
+
+def _f64(x):
+    return None if x is None else np.asarray(x, dtype=np.float64)
+
+
+def preact(W1, b1, X):
+    """z = W1 x + b1 for every row x of X (n x d) -> n x h.  The activation
+    input of each neuron (Sec. "Non-linear Function Approximation", step 1)."""
+    Z = _f64(X) @ _f64(W1).T
+    if b1 is not None:
+        Z = Z + _f64(b1)[None, :]
+    return Z
+
+
+# ---------------------------------------------------------------------------
+# dense FFN  (Sec. "Opportunity", FFN(x) = sigma(x W1) W2)
+# ---------------------------------------------------------------------------
+def dense(W1, b1, W2, b2, X, kind: str = "gelu_erf"):
+    """Exact FFN for every row of X (n x d) -> n x d."""
+    Y = act(preact(W1, b1, X), kind) @ _f64(W2).T
+    if b2 is not None:
+        Y = Y + _f64(b2)[None, :]
+    return Y
+
+
+# ---------------------------------------------------------------------------
+# calibration  (Sec. "Insights" 2 and Sec. "Non-linear Function Approximation":
+# a range holding a portion t of the calibration inputs, then a least-squares
+# line through sigma on that range)
+# ---------------------------------------------------------------------------
+def quantile_linear(sorted_vals: np.ndarray, q: float) -> float:
+    """Quantile by linear interpolation between order statistics at position
+    q*(N-1)."""
+    n = sorted_vals.shape[0]
+    pos = q * (n - 1)
+    i = int(math.floor(pos))
+    i = min(max(i, 0), n - 1)
+    g = pos - i
+    i1 = min(i + 1, n - 1)
+    return float(sorted_vals[i] + g * (sorted_vals[i1] - sorted_vals[i]))
+
+
+def fit_line(z: np.ndarray, g: np.ndarray, fallback_point: float, kind: str):
+    """Ordinary least squares of g on z: slope cov(z,g)/var(z), intercept
+    mean(g) - slope*mean(z).  Degenerate sets (fewer than two samples, or all z
+    equal) give slope 0 and the mean of g (sigma at the range's left end if
+    there is no sample at all)."""
+    n = z.shape[0]
+    if n == 0:
+        return 0.0, float(act(fallback_point, kind))
+    zbar = z.mean()
+    gbar = g.mean()
+    var = ((z - zbar) ** 2).sum()
+    if n < 2 or var <= 0.0:
+        return 0.0, float(gbar)
+    cov = ((z - zbar) * (g - gbar)).sum()
+    a = cov / var
+    return float(a), float(gbar - a * zbar)
+
+
+def calibrate(W1, b1, X_cal, coverage, kind: str = "gelu_erf"):
+    """Per neuron: [lo, hi) = central `coverage` quantile range of its
+    calibration pre-activations, (a, c) = least-squares line through sigma over
+    the calibration samples with lo <= z < hi.
+
+    `coverage` is a scalar t or an array of h per-neuron values.  lo and hi are
+    rounded to fp32 (the interface carries them as fp32) *before* the in-range
+    test that selects the fit samples.  Returns four float32 arrays of length h.
+    """
+    Z = preact(W1, b1, X_cal)                      # n x h
+    n, h = Z.shape
+    t = np.broadcast_to(np.asarray(coverage, dtype=np.float64), (h,))
+    lo = np.empty(h, np.float32)
+    hi = np.empty(h, np.float32)
+    a = np.empty(h, np.float32)
+    c = np.empty(h, np.float32)
+    for j in range(h):
+        zj = Z[:, j]
+        zs = np.sort(zj)
+        lo[j] = np.float32(quantile_linear(zs, (1.0 - t[j]) / 2.0))
+        hi[j] = np.float32(quantile_linear(zs, (1.0 + t[j]) / 2.0))
+        sel = (zj >= np.float64(lo[j])) & (zj < np.float64(hi[j]))
+        aj, cj = fit_line(zj[sel], act(zj[sel], kind), float(lo[j]), kind)
+        a[j] = np.float32(aj)
+        c[j] = np.float32(cj)
+    return lo, hi, a, c
+
+
+# ---------------------------------------------------------------------------
+# constant folding  (Sec. "Constant Folded Matrix Generation")
+# ---------------------------------------------------------------------------
+def fold(W1, b1, W2, b2, a, c):
+    """W' = W2 diag(a) W1 (d x d),  b' = W2 (c + a*b1) + b2 (d).
+
+    This is the sum over neurons of the per-neuron folded pair
+    (a_n W1[:,n] W2[n,:], b_n W2[n,:]) in the paper's orientation, transposed,
+    with the layer biases (which the paper sets to zero for presentation)
+    carried through: a_j (W1[j].x + b1_j) + c_j = a_j W1[j].x + (c_j + a_j b1_j).
+    """
+    W1 = _f64(W1); W2 = _f64(W2); a = _f64(a); c = _f64(c)
+    Wp = (W2 * a[None, :]) @ W1
+    k = c if b1 is None else c + a * _f64(b1)
+    bp = W2 @ k
+    if b2 is not None:
+        bp = bp + _f64(b2)
+    return Wp, bp
+
+
+# ---------------------------------------------------------------------------
+# predictor  (Sec. "Predictor Generation": a quantised copy of W1 that is just
+# good enough to tell which neurons leave their range)
+# ---------------------------------------------------------------------------
+@dataclass
+class Sketch:
+    Q: np.ndarray      # h x d int8, round-to-nearest symmetric per-row codes of W1
+    s: np.ndarray      # h fp64 row scales, W1[j] ~ s[j] * Q[j]
+    tlo: np.ndarray    # h fp32, (lo - b1) / s
+    thi: np.ndarray    # h fp32, (hi - b1) / s
+
+
+def sketch(W1, b1, lo, hi) -> Sketch:
+    """int8 sketch of W1 and the range bounds expressed in sketch units.
+
+    s_j = max_k |W1[j,k]| / 127 ; q_jk = rint(W1[j,k] / s_j) (ties to even),
+    clamped to [-127, 127].  The test lo <= s_j*(q_j . x) + b1_j < hi becomes
+    tlo_j <= q_j . x < thi_j with tlo = (lo-b1)/s, thi = (hi-b1)/s, both rounded
+    once to fp32.  A neuron whose weights are all zero has z = b1_j for every
+    token: it is never flagged if b1_j lies in its range and always otherwise.
+    """
+    W1 = _f64(W1)
+    h, d = W1.shape
+    lo = _f64(lo); hi = _f64(hi)
+    b = np.zeros(h) if b1 is None else _f64(b1)
+    s = np.abs(W1).max(axis=1) / 127.0
+    Q = np.zeros((h, d), np.int8)
+    tlo = np.empty(h, np.float32)
+    thi = np.empty(h, np.float32)
+    for j in range(h):
+        if s[j] > 0.0:
+            q = np.rint(W1[j] / s[j])
+            Q[j] = np.clip(q, -127, 127).astype(np.int8)
+            tlo[j] = np.float32((lo[j] - b[j]) / s[j])
+            thi[j] = np.float32((hi[j] - b[j]) / s[j])
+        elif lo[j] <= b[j] < hi[j]:
+            tlo[j] = -np.inf
+            thi[j] = np.inf
+        else:                       # empty interval: the neuron is always flagged
+            tlo[j] = np.inf
+            thi[j] = np.inf
+    return Sketch(Q=Q, s=s, tlo=tlo, thi=thi)
+
+
+def quantize_token(x):
+    """int8 code of one token with a power-of-two scale.
+
+    m = max|x_k|; e = floor(log2 m) - 6, so |x_k| / 2^e < 128;
+    xq_k = rint(x_k / 2^e) clamped to [-127, 127].  A zero token has e = 0 and
+    xq = 0.  Returns (xq int8[d], e int).
+    """
+    x = _f64(x)
+    m = float(np.abs(x).max()) if x.size else 0.0
+    if m == 0.0:
+        return np.zeros(x.shape, np.int8), 0
+    e = math.frexp(m)[1] - 1 - 6          # frexp: m = f * 2^k with 0.5 <= f < 1
+    xq = np.clip(np.rint(np.ldexp(x, -e)), -127, 127).astype(np.int8)
+    return xq, e
+
+
+def predict(sk: Sketch, x):
+    """Flags of one token: neuron j is flagged unless tlo_j <= v_j < thi_j with
+    v_j = fp32(acc_j) * 2^e and acc_j = sum_k Q[j,k] * xq[k] (an exact integer).
+    A NaN bound or value flags the neuron (the test is a negated AND)."""
+    xq, e = quantize_token(x)
+    # every partial sum is an integer below 2^53, so the fp64 product is exact
+    acc = sk.Q.astype(np.float64) @ xq.astype(np.float64)
+    acc = acc.astype(np.int64)
+    v = np.ldexp(acc.astype(np.float32), e).astype(np.float32)
+    with np.errstate(invalid="ignore"):
+        inside = (v >= sk.tlo) & (v < sk.thi)
+    return ~inside
+
+
+# ---------------------------------------------------------------------------
+# online forward  (Sec. "Inference Runtime": speculative approximation, then
+# result fixing for the neurons the predictor names)
+# ---------------------------------------------------------------------------
+@dataclass
+class Folded:
+    d: int
+    h: int
+    kind: str
+    W1: np.ndarray
+    b1: np.ndarray | None
+    W2: np.ndarray
+    a: np.ndarray
+    c: np.ndarray
+    Wp: np.ndarray
+    bp: np.ndarray
+    sk: Sketch
+
+
+def build(W1, b1, W2, b2, lo, hi, a, c, kind: str = "gelu_erf", wp_round=None) -> Folded:
+    """Everything the online path needs.  `wp_round`, if given, is applied to W'
+    once (e.g. rounding to the storage dtype) for the storage-matched variant."""
+    Wp, bp = fold(W1, b1, W2, b2, a, c)
+    if wp_round is not None:
+        Wp = np.asarray(wp_round(Wp), dtype=np.float64)
+    h, d = np.shape(W1)
+    return Folded(d=d, h=h, kind=kind, W1=_f64(W1), b1=_f64(b1), W2=_f64(W2),
+                  a=_f64(a), c=_f64(c), Wp=Wp, bp=bp, sk=sketch(W1, b1, lo, hi))
+
+
+def fix_terms(F: Folded, x, flags):
+    """delta_j = sigma(z_j) - (a_j z_j + c_j) for the flagged neurons (exact
+    weights): remove the speculative linear result, add the true one."""
+    idx = np.flatnonzero(flags)
+    z = F.W1[idx] @ _f64(x)
+    if F.b1 is not None:
+        z = z + F.b1[idx]
+    return idx, act(z, F.kind) - (F.a[idx] * z + F.c[idx])
+
+
+def forward_token(F: Folded, x, flags=None):
+    """y = W'x + b' + sum_{j flagged} delta_j W2[:, j].  Every flagged neuron is
+    fixed whether or not its exact z turns out to be in range.  Returns
+    (y fp64[d], flags bool[h])."""
+    x = _f64(x)
+    if flags is None:
+        flags = predict(F.sk, x)
+    y = F.Wp @ x + F.bp
+    idx, delta = fix_terms(F, x, flags)
+    y = y + F.W2[:, idx] @ delta
+    return y, flags
+
+
+def forward(F: Folded, X, flags=None):
+    """Batched forward, strictly per token (a token is fixed only for the
+    neurons its own predictor pass flagged).  X: n x d -> (Y n x d, flags n x h)."""
+    X = _f64(X)
+    n = X.shape[0]
+    Y = np.empty((n, F.d))
+    FL = np.empty((n, F.h), bool)
+    for t in range(n):
+        Y[t], FL[t] = forward_token(F, X[t], None if flags is None else flags[t])
+    return Y, FL
+
+
+# ---------------------------------------------------------------------------
+# helpers used by the tests of the stacked configuration and of bf16 storage
+# ---------------------------------------------------------------------------
+def rmsnorm(Y, eps: float = 1e-6):
+    """x = y / sqrt(mean(y^2) + eps), unit gain, per token (row)."""
+    Y = _f64(Y)
+    return Y / np.sqrt((Y * Y).mean(axis=-1, keepdims=True) + eps)
+
+
+def to_bf16(x):
+    """Nearest bfloat16 (ties to even) of fp64/fp32 values, returned as fp64.
+    Goes through fp32 first, as a conversion from an fp32 accumulator does."""
+    f = np.asarray(x, dtype=np.float64).astype(np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    r = ((u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000).astype(np.uint32)
+    return r.view(np.float32).astype(np.float64).reshape(np.shape(x))
+
+
+def pack_mask(flags):
+    """bool n x h -> uint32 n x ceil(h/32); bit (j % 32) of word j // 32."""
+    flags = np.atleast_2d(np.asarray(flags, bool))
+    n, h = flags.shape
+    w = (h + 31) // 32
+    pad = np.zeros((n, w * 32), bool)
+    pad[:, :h] = flags
+    bits = pad.reshape(n, w, 32).astype(np.uint32)
+    return (bits << np.arange(32, dtype=np.uint32)[None, None, :]).sum(axis=2, dtype=np.uint64).astype(np.uint32)
