@@ -1,0 +1,189 @@
+/*
+ * libtardis -- partially-linear feed-forward network for one AMD MI355X (gfx950).
+ *
+ * The method (arXiv 2501.10054, "Accelerating Large Language Models through
+ * Partially Linear Feed-Forward Network") replaces each FFN neuron's activation
+ * by a line a_j*z + c_j inside a calibrated input range [lo_j, hi_j), folds
+ * W2*diag(a)*W1 into one d x d matrix W' with bias b', and at run time computes
+ * y = W'x + b', asks a cheap predictor which neurons leave their range, and
+ * repairs exactly those neurons with the original weights and activation.
+ *
+ * Orientation.  The paper writes row vectors, FFN(x) = sigma(x W1) W2 with W1 of
+ * size d x h.  This interface uses the transposed, Linear-layer layout:
+ *
+ *     W1 : h x d row-major  (row j    = neuron j's input weights)
+ *     W2 : d x h row-major  (column j = neuron j's output weights)
+ *     FFN(x) = W2 * sigma(W1 x + b1) + b2
+ *
+ * so the paper's folded matrix C is W'^T and its slope/intercept (a, b) are
+ * (a_j, c_j) here.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE memory owned by the caller, contiguous,
+ *     row-major, 16-byte aligned, unless a parameter says "host".
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Online calls only enqueue work: they never synchronise the host and never
+ *     allocate.  Offline calls (calibrate, fold) allocate and free temporaries
+ *     and may synchronise.
+ *   - Errors are reported by return code only.  Arguments are validated before
+ *     anything is launched; an asynchronous GPU fault surfaces at the caller's
+ *     next synchronisation.  One stream at a time may use a handle.
+ *   - Ranges are half open: a neuron is "in range" iff lo_j <= z_j < hi_j.
+ */
+#ifndef TARDIS_H
+#define TARDIS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TARDIS_VERSION 1
+
+typedef struct tardis_layer_s* tardis_handle_t; /* opaque: one folded FFN layer */
+
+typedef enum {
+    TARDIS_OK = 0,
+    TARDIS_ERR_INVALID_ARG = 1, /* NULL where data is required, bad enum, misaligned */
+    TARDIS_ERR_SHAPE = 2,       /* non-positive or unsupported sizes */
+    TARDIS_ERR_DTYPE = 3,       /* dtype not supported by this call */
+    TARDIS_ERR_STATE = 4,       /* handle not usable for this call */
+    TARDIS_ERR_OOM = 5,         /* device allocation failed */
+    TARDIS_ERR_HIP = 6          /* any other HIP runtime error */
+} tardis_status_t;
+
+typedef enum {
+    TARDIS_ACT_GELU_ERF = 0, /* z * Phi(z) */
+    TARDIS_ACT_GELU_TANH = 1,
+    TARDIS_ACT_RELU = 2,
+    TARDIS_ACT_IDENTITY = 3
+} tardis_act_t;
+
+typedef enum {
+    TARDIS_F32 = 0,
+    TARDIS_BF16 = 1
+} tardis_dtype_t;
+
+/* One FFN layer (Sec. "Opportunity": FFN(x) = sigma(x W1) W2, here transposed
+ * and with the optional biases the paper omits for presentation).
+ * `dtype` is the storage type of W1, W2, b1, b2 and of the tokens x and
+ * outputs y of the online calls. */
+typedef struct {
+    int64_t d;       /* model width  (>= 1) */
+    int64_t h;       /* hidden width (>= 1) */
+    int32_t dtype;   /* tardis_dtype_t */
+    int32_t act;     /* tardis_act_t   */
+    const void* W1;  /* h x d */
+    const void* b1;  /* h, or NULL for zero */
+    const void* W2;  /* d x h */
+    const void* b2;  /* d, or NULL for zero */
+} tardis_ffn_desc;
+
+typedef struct {
+    int32_t sketch_bits;   /* predictor code width; 8 is the only supported value */
+    int32_t folded_dtype;  /* storage of W'; must equal desc.dtype */
+    int64_t max_batch;     /* largest n accepted by the batched online calls (>= 1) */
+    int32_t deterministic; /* reserved, must be 0 */
+    int32_t reserved;
+} tardis_fold_opts;
+
+/* ---------------------------------------------------------------- offline */
+
+/* Range selection and linear fit (Sec. "Insights", Insight 2, and Sec.
+ * "Non-linear Function Approximation": a range holding a portion t of each
+ * neuron's calibration inputs, then a least-squares line through the activation
+ * on that range).  For every neuron j: z_ij = W1[j].x_i + b1_j over the n_cal
+ * calibration tokens; lo_j, hi_j = the (1-t)/2 and (1+t)/2 quantiles (linear
+ * interpolation between order statistics); a_j, c_j = ordinary least squares of
+ * sigma(z) on z over the samples with lo_j <= z < hi_j (slope 0 and the mean of
+ * sigma if fewer than two distinct samples).
+ *
+ *   X_cal     n_cal x d tokens, desc->dtype.   1 <= n_cal <= 32768.
+ *   coverage  the in-range portion t in (0, 1], used for every neuron when
+ *             coverage_per_neuron is NULL.
+ *   coverage_per_neuron  optional device array of h per-neuron portions.
+ *   lo, hi, a, c  device float arrays of length h, written by the call.
+ * Synchronises the stream before returning (temporaries are freed). */
+tardis_status_t tardis_calibrate(const tardis_ffn_desc* desc, const void* X_cal, int64_t n_cal,
+                                 float coverage, const float* coverage_per_neuron,
+                                 float* lo, float* hi, float* a, float* c, void* stream);
+
+/* Constant folding and predictor construction (Sec. "Constant Folded Matrix
+ * Generation" and Sec. "Predictor Generation").  Builds
+ *     W' = W2 diag(a) W1            (d x d, stored in desc->dtype, rounded once)
+ *     b' = W2 (c + a*b1) + b2       (d, fp32)
+ * and the predictor: an int8 round-to-nearest per-row symmetric code Q of W1
+ * (s_j = max_k|W1[j,k]|/127, q_jk = rint(W1[j,k]/s_j)) with the range bounds in
+ * code units, tlo_j = fp32((lo_j-b1_j)/s_j), thi_j = fp32((hi_j-b1_j)/s_j).
+ *
+ * W1, b1, b2 are BORROWED: they must stay valid and unchanged until
+ * tardis_destroy (the repair step reads W1 in place).  W2 is copied into a
+ * neuron-major h x d transpose owned by the handle and may be released.
+ * lo, hi, a, c (device, length h) are copied.  All working memory of the online
+ * calls, sized by opts->max_batch, is allocated here.  opts may be NULL
+ * (sketch_bits 8, folded_dtype = desc->dtype, max_batch 1).
+ * Synchronises the stream before returning. */
+tardis_status_t tardis_fold(const tardis_ffn_desc* desc, const float* lo, const float* hi,
+                            const float* a, const float* c, const tardis_fold_opts* opts,
+                            void* stream, tardis_handle_t* out);
+
+/* ----------------------------------------------------------------- online */
+
+/* One token through the folded layer (Sec. "Inference Runtime"): speculative
+ * result W'x + b', predictor pass, and for every flagged neuron j the repair
+ *     z_j = W1[j].x + b1_j,  y += (sigma(z_j) - (a_j z_j + c_j)) * W2[:, j].
+ * Every flagged neuron is repaired whether or not its exact z_j is in range.
+ * The predictor: m = max|x_k|, e = floor(log2 m) - 6, xq_k = clamp(rint(x_k /
+ * 2^e), -127, 127); acc_j = sum_k q_jk xq_k (int32); v_j = fp32(acc_j) * 2^e;
+ * neuron j is flagged unless tlo_j <= v_j < thi_j.  x with a non-finite entry
+ * gives unspecified (but memory-safe) results.
+ *   x  d values, desc dtype.   y  d values, desc dtype.  x and y must not alias. */
+tardis_status_t tardis_ffn_forward(tardis_handle_t L, const void* x, void* y, void* stream);
+
+/* n tokens (1 <= n <= max_batch), strictly per token: token t is repaired only
+ * for the neurons its own predictor pass flagged.  x, y: n x d. */
+tardis_status_t tardis_ffn_forward_batched(tardis_handle_t L, const void* x, int64_t n, void* y,
+                                           void* stream);
+
+/* The unmodified FFN, y = W2 sigma(W1 x + b1) + b2, on the same streaming
+ * kernels: the dense baseline the folded path is measured against.
+ * 1 <= n <= max_batch.  x, y: n x d. */
+tardis_status_t tardis_dense_forward(tardis_handle_t L, const void* x, int64_t n, void* y,
+                                     void* stream);
+
+/* ------------------------------------------------------------- inspection */
+
+/* Copies of the folded state (stream-ordered).  Wp: d x d in desc dtype; bp: d
+ * floats.  Either may be NULL. */
+tardis_status_t tardis_get_folded(tardis_handle_t L, void* Wp, float* bp, void* stream);
+
+/* Q: h x d int8; tlo, thi: h floats.  Any may be NULL. */
+tardis_status_t tardis_get_predictor_state(tardis_handle_t L, int8_t* Q, float* tlo, float* thi,
+                                           void* stream);
+
+/* Predictor output of the most recent online call on this handle, for its n
+ * tokens (stream-ordered copies into caller buffers; any may be NULL):
+ *   mask    n x ceil(h/32) words; bit (j%32) of word j/32 set iff neuron j flagged
+ *   counts  n ints, flagged neurons per token
+ *   list    n x h ints; row t holds token t's flagged indices in its first
+ *           counts[t] slots, in unspecified order (the mask is canonical)
+ * n must equal the token count of that call. */
+tardis_status_t tardis_get_last_outliers(tardis_handle_t L, int64_t n, uint32_t* mask,
+                                         int32_t* counts, int32_t* list, void* stream);
+
+/* Frees everything the handle owns.  The caller must have synchronised every
+ * stream that used it.  NULL is accepted. */
+tardis_status_t tardis_destroy(tardis_handle_t L);
+
+/* Static, NUL-terminated description of a status code (host). */
+const char* tardis_status_string(tardis_status_t s);
+
+/* TARDIS_VERSION the library was built with. */
+int32_t tardis_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TARDIS_H */

@@ -1,0 +1,200 @@
+// C-ABI entry points of libtardis: argument validation, handle lifetime and
+// dispatch.  No kernel lives here.
+#include <new>
+
+#include "common.h"
+
+namespace {
+
+constexpr int64_t kMaxD = 32768;          // token + its int8 code must fit in LDS
+constexpr int64_t kMaxH = 1 << 22;
+constexpr int64_t kMaxCal = 32768;        // one neuron's samples are sorted in LDS
+constexpr int64_t kMaxBatch = 4096;
+constexpr size_t kTokenLdsCap = 60 * 1024;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+tardis_status_t check_desc(const tardis_ffn_desc* desc) {
+    if (!desc || !desc->W1 || !desc->W2) return TARDIS_ERR_INVALID_ARG;
+    if (desc->dtype != TARDIS_F32 && desc->dtype != TARDIS_BF16) return TARDIS_ERR_DTYPE;
+    if (desc->act < TARDIS_ACT_GELU_ERF || desc->act > TARDIS_ACT_IDENTITY) return TARDIS_ERR_INVALID_ARG;
+    if (desc->d < 1 || desc->h < 1 || desc->d > kMaxD || desc->h > kMaxH) return TARDIS_ERR_SHAPE;
+    if (!aligned16(desc->W1) || !aligned16(desc->W2)) return TARDIS_ERR_INVALID_ARG;
+    const size_t es = td_elem_size(desc->dtype);
+    if ((size_t)desc->d * (es + 1) + 16 > kTokenLdsCap) return TARDIS_ERR_SHAPE;
+    return TARDIS_OK;
+}
+
+template <typename P> tardis_status_t dev_alloc(P** p, size_t bytes) {
+    void* v = nullptr;
+    hipError_t e = hipMalloc(&v, bytes ? bytes : 16);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        *p = nullptr;
+        return e == hipErrorOutOfMemory ? TARDIS_ERR_OOM : TARDIS_ERR_HIP;
+    }
+    *p = static_cast<P*>(v);
+    return TARDIS_OK;
+}
+
+void free_layer(tardis_layer_s* L) {
+    if (!L) return;
+    void* owned[] = {L->W2T, L->W2, L->Wp, L->bp, L->Q, L->tlo, L->thi, L->a, L->c,
+                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync};
+    for (void* p : owned)
+        if (p) (void)hipFree(p);
+    delete L;
+}
+
+tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const float* hi, const float* a,
+                          const float* c, const tardis_fold_opts* opts, hipStream_t s, tardis_layer_s* L) {
+    const int64_t d = desc->d, h = desc->h;
+    const size_t es = td_elem_size(desc->dtype);
+    L->d = d;
+    L->h = h;
+    L->dtype = desc->dtype;
+    L->act = desc->act;
+    L->max_batch = opts ? opts->max_batch : 1;
+    L->mask_words = (h + 31) / 32;
+    L->W1 = desc->W1;
+    L->b1 = desc->b1;
+    L->b2 = desc->b2;
+    L->last_n = 0;
+    const size_t nb = (size_t)L->max_batch;
+    TD_TRY(dev_alloc(reinterpret_cast<char**>(&L->W2T), (size_t)h * d * es));
+    TD_TRY(dev_alloc(reinterpret_cast<char**>(&L->W2), (size_t)h * d * es));
+    TD_TRY(dev_alloc(reinterpret_cast<char**>(&L->Wp), (size_t)d * d * es));
+    TD_TRY(dev_alloc(&L->bp, (size_t)d * 4));
+    TD_TRY(dev_alloc(&L->Q, (size_t)h * d));
+    TD_TRY(dev_alloc(&L->tlo, (size_t)h * 4));
+    TD_TRY(dev_alloc(&L->thi, (size_t)h * 4));
+    TD_TRY(dev_alloc(&L->a, (size_t)h * 4));
+    TD_TRY(dev_alloc(&L->c, (size_t)h * 4));
+    TD_TRY(dev_alloc(&L->yacc, nb * d * 4));
+    TD_TRY(dev_alloc(&L->mask, nb * L->mask_words * 4));
+    TD_TRY(dev_alloc(&L->counts, nb * 4));
+    TD_TRY(dev_alloc(&L->list, nb * h * 4));
+    TD_TRY(dev_alloc(reinterpret_cast<char**>(&L->hidden), nb * h * es));
+    TD_TRY(dev_alloc(&L->sync, 256));
+    TD_HIP(hipMemsetAsync(L->sync, 0, 256, s));
+    TD_HIP(hipMemsetAsync(L->counts, 0, nb * 4, s));
+    TD_HIP(hipMemsetAsync(L->mask, 0, nb * L->mask_words * 4, s));
+    TD_HIP(hipMemsetAsync(L->yacc, 0, nb * d * 4, s));
+    TD_HIP(hipMemcpyAsync(L->a, a, (size_t)h * 4, hipMemcpyDeviceToDevice, s));
+    TD_HIP(hipMemcpyAsync(L->c, c, (size_t)h * 4, hipMemcpyDeviceToDevice, s));
+    TD_HIP(hipMemcpyAsync(L->W2, desc->W2, (size_t)h * d * es, hipMemcpyDeviceToDevice, s));
+    TD_TRY(td_transpose(desc->W2, L->W2T, d, h, desc->dtype, s));
+    TD_TRY(td_build_sketch(desc->W1, desc->b1, lo, hi, h, d, desc->dtype, L->Q, L->tlo, L->thi, s));
+    TD_TRY(td_fold(desc, L->a, L->c, L->Wp, L->bp, s));
+    TD_HIP(hipStreamSynchronize(s));
+    return TARDIS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+tardis_status_t tardis_calibrate(const tardis_ffn_desc* desc, const void* X_cal, int64_t n_cal, float coverage,
+                                 const float* coverage_per_neuron, float* lo, float* hi, float* a, float* c,
+                                 void* stream) {
+    TD_TRY(check_desc(desc));
+    if (!X_cal || !lo || !hi || !a || !c) return TARDIS_ERR_INVALID_ARG;
+    if (!aligned16(X_cal)) return TARDIS_ERR_INVALID_ARG;
+    if (n_cal < 1 || n_cal > kMaxCal) return TARDIS_ERR_SHAPE;
+    if (!coverage_per_neuron && !(coverage > 0.0f && coverage <= 1.0f)) return TARDIS_ERR_INVALID_ARG;
+    return td_calibrate(desc, X_cal, n_cal, coverage, coverage_per_neuron, lo, hi, a, c,
+                        static_cast<hipStream_t>(stream));
+}
+
+tardis_status_t tardis_fold(const tardis_ffn_desc* desc, const float* lo, const float* hi, const float* a,
+                            const float* c, const tardis_fold_opts* opts, void* stream, tardis_handle_t* out) {
+    if (!out) return TARDIS_ERR_INVALID_ARG;
+    *out = nullptr;
+    TD_TRY(check_desc(desc));
+    if (!lo || !hi || !a || !c) return TARDIS_ERR_INVALID_ARG;
+    if (opts) {
+        if (opts->sketch_bits != 8) return TARDIS_ERR_INVALID_ARG;
+        if (opts->folded_dtype != desc->dtype) return TARDIS_ERR_DTYPE;
+        if (opts->max_batch < 1 || opts->max_batch > kMaxBatch) return TARDIS_ERR_SHAPE;
+        if (opts->deterministic != 0) return TARDIS_ERR_INVALID_ARG;
+    }
+    tardis_layer_s* L = new (std::nothrow) tardis_layer_s();
+    if (!L) return TARDIS_ERR_OOM;
+    tardis_status_t st = fold_impl(desc, lo, hi, a, c, opts, static_cast<hipStream_t>(stream), L);
+    if (st != TARDIS_OK) {
+        (void)hipDeviceSynchronize();
+        free_layer(L);
+        return st;
+    }
+    *out = L;
+    return TARDIS_OK;
+}
+
+tardis_status_t tardis_ffn_forward(tardis_handle_t L, const void* x, void* y, void* stream) {
+    return tardis_ffn_forward_batched(L, x, 1, y, stream);
+}
+
+tardis_status_t tardis_ffn_forward_batched(tardis_handle_t L, const void* x, int64_t n, void* y, void* stream) {
+    if (!L) return TARDIS_ERR_STATE;
+    if (!x || !y || x == y) return TARDIS_ERR_INVALID_ARG;
+    if (n < 1 || n > L->max_batch) return TARDIS_ERR_SHAPE;
+    return td_forward(L, x, n, y, static_cast<hipStream_t>(stream));
+}
+
+tardis_status_t tardis_dense_forward(tardis_handle_t L, const void* x, int64_t n, void* y, void* stream) {
+    if (!L) return TARDIS_ERR_STATE;
+    if (!x || !y || x == y) return TARDIS_ERR_INVALID_ARG;
+    if (n < 1 || n > L->max_batch) return TARDIS_ERR_SHAPE;
+    return td_dense_forward(L, x, n, y, static_cast<hipStream_t>(stream));
+}
+
+tardis_status_t tardis_get_folded(tardis_handle_t L, void* Wp, float* bp, void* stream) {
+    if (!L) return TARDIS_ERR_STATE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (Wp) TD_HIP(hipMemcpyAsync(Wp, L->Wp, (size_t)L->d * L->d * td_elem_size(L->dtype), hipMemcpyDeviceToDevice, s));
+    if (bp) TD_HIP(hipMemcpyAsync(bp, L->bp, (size_t)L->d * 4, hipMemcpyDeviceToDevice, s));
+    return TARDIS_OK;
+}
+
+tardis_status_t tardis_get_predictor_state(tardis_handle_t L, int8_t* Q, float* tlo, float* thi, void* stream) {
+    if (!L) return TARDIS_ERR_STATE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (Q) TD_HIP(hipMemcpyAsync(Q, L->Q, (size_t)L->h * L->d, hipMemcpyDeviceToDevice, s));
+    if (tlo) TD_HIP(hipMemcpyAsync(tlo, L->tlo, (size_t)L->h * 4, hipMemcpyDeviceToDevice, s));
+    if (thi) TD_HIP(hipMemcpyAsync(thi, L->thi, (size_t)L->h * 4, hipMemcpyDeviceToDevice, s));
+    return TARDIS_OK;
+}
+
+tardis_status_t tardis_get_last_outliers(tardis_handle_t L, int64_t n, uint32_t* mask, int32_t* counts,
+                                         int32_t* list, void* stream) {
+    if (!L) return TARDIS_ERR_STATE;
+    if (n < 1 || n != L->last_n) return TARDIS_ERR_STATE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t nn = (size_t)n;
+    if (mask) TD_HIP(hipMemcpyAsync(mask, L->mask, nn * L->mask_words * 4, hipMemcpyDeviceToDevice, s));
+    if (counts) TD_HIP(hipMemcpyAsync(counts, L->counts, nn * 4, hipMemcpyDeviceToDevice, s));
+    if (list) TD_HIP(hipMemcpyAsync(list, L->list, nn * L->h * 4, hipMemcpyDeviceToDevice, s));
+    return TARDIS_OK;
+}
+
+tardis_status_t tardis_destroy(tardis_handle_t L) {
+    free_layer(L);
+    return TARDIS_OK;
+}
+
+const char* tardis_status_string(tardis_status_t s) {
+    switch (s) {
+        case TARDIS_OK: return "ok";
+        case TARDIS_ERR_INVALID_ARG: return "invalid argument";
+        case TARDIS_ERR_SHAPE: return "unsupported shape or size";
+        case TARDIS_ERR_DTYPE: return "unsupported dtype";
+        case TARDIS_ERR_STATE: return "handle not usable for this call";
+        case TARDIS_ERR_OOM: return "device out of memory";
+        case TARDIS_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+int32_t tardis_version(void) { return TARDIS_VERSION; }
+
+}  // extern "C"

@@ -1,0 +1,150 @@
+// Shared declarations of libtardis: the layer handle, status helpers and the
+// small device-side numeric helpers every kernel file uses.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/tardis.h"
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+typedef unsigned int td_u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte load
+
+#define TD_WAVE 64
+
+#define TD_HIP(expr)                                                              \
+    do {                                                                          \
+        hipError_t e__ = (expr);                                                  \
+        if (e__ != hipSuccess)                                                    \
+            return (e__ == hipErrorOutOfMemory) ? TARDIS_ERR_OOM : TARDIS_ERR_HIP; \
+    } while (0)
+
+#define TD_TRY(expr)                          \
+    do {                                      \
+        tardis_status_t s__ = (expr);         \
+        if (s__ != TARDIS_OK) return s__;     \
+    } while (0)
+
+// Everything one folded layer owns.  Pointers are device memory.
+struct tardis_layer_s {
+    int64_t d, h;
+    int32_t dtype, act;
+    int64_t max_batch;
+    int64_t mask_words;  // ceil(h/32)
+    // borrowed from the caller
+    const void* W1;  // h x d
+    const void* b1;  // h or null
+    const void* b2;  // d or null
+    // owned
+    void* W2T;     // h x d, neuron-major copy of W2
+    void* W2;      // d x h, copy of W2 as given (dense baseline)
+    void* Wp;      // d x d folded matrix
+    float* bp;     // d folded bias
+    int8_t* Q;     // h x d predictor codes
+    float* tlo;    // h
+    float* thi;    // h
+    float* a;      // h
+    float* c;      // h
+    // working memory of the online calls (sized by max_batch)
+    float* yacc;       // max_batch x d fp32 accumulator
+    uint32_t* mask;    // max_batch x mask_words
+    int32_t* counts;   // max_batch flagged-neuron counters
+    int32_t* list;     // max_batch x h flagged indices
+    float* hidden;     // max_batch x h activations for the dense baseline
+    int32_t* sync;     // small block of device counters (zero between calls)
+    int64_t last_n;    // token count of the most recent online call
+};
+
+static inline size_t td_elem_size(int32_t dtype) { return dtype == TARDIS_BF16 ? 2 : 4; }
+
+// ---------------------------------------------------------------- device helpers
+__device__ __forceinline__ float td_bf16_to_f32(bf16_t v) {
+    return __uint_as_float(((uint32_t)v) << 16);
+}
+
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ bf16_t td_f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (bf16_t)((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+// 16-byte load of data that is read once (weights streamed from HBM)
+__device__ __forceinline__ td_u32x4 td_load_stream16(const void* p) {
+    return __builtin_nontemporal_load(static_cast<const td_u32x4*>(p));
+}
+
+template <typename T> __device__ __forceinline__ float td_load(const T* p);
+template <> __device__ __forceinline__ float td_load<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float td_load<bf16_t>(const bf16_t* p) { return td_bf16_to_f32(*p); }
+
+template <typename T> __device__ __forceinline__ void td_store(T* p, float v);
+template <> __device__ __forceinline__ void td_store<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void td_store<bf16_t>(bf16_t* p, float v) { *p = td_f32_to_bf16(v); }
+
+__device__ __forceinline__ float td_wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ int td_wave_sum_i(int v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float td_wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// sigma(z) for the four supported activations (fp32)
+__device__ __forceinline__ float td_act(float z, int act) {
+    switch (act) {
+        case TARDIS_ACT_GELU_ERF:
+            return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f));
+        case TARDIS_ACT_GELU_TANH: {
+            float u = 0.79788456080286535588f * (z + 0.044715f * z * z * z);
+            return 0.5f * z * (1.0f + tanhf(u));
+        }
+        case TARDIS_ACT_RELU:
+            return z > 0.0f ? z : 0.0f;
+        default:
+            return z;
+    }
+}
+
+// fp64 version for the offline fit
+__device__ __forceinline__ double td_act_f64(double z, int act) {
+    switch (act) {
+        case TARDIS_ACT_GELU_ERF:
+            return 0.5 * z * (1.0 + erf(z * 0.70710678118654752440));
+        case TARDIS_ACT_GELU_TANH: {
+            double u = 0.79788456080286535588 * (z + 0.044715 * z * z * z);
+            return 0.5 * z * (1.0 + tanh(u));
+        }
+        case TARDIS_ACT_RELU:
+            return z > 0.0 ? z : 0.0;
+        default:
+            return z;
+    }
+}
+
+// ---------------------------------------------------------------- internal launchers
+// (each validates nothing: the C-ABI layer in api.cpp has already done so)
+
+// offline.hip
+tardis_status_t td_transpose(const void* src, void* dst, int64_t rows, int64_t cols, int32_t dtype, hipStream_t s);
+tardis_status_t td_build_sketch(const void* W1, const void* b1, const float* lo, const float* hi, int64_t h,
+                                int64_t d, int32_t dtype, int8_t* Q, float* tlo, float* thi, hipStream_t s);
+tardis_status_t td_fold(const tardis_ffn_desc* desc, const float* a, const float* c, void* Wp, float* bp,
+                        hipStream_t s);
+tardis_status_t td_calibrate(const tardis_ffn_desc* desc, const void* X, int64_t n, float coverage,
+                             const float* cov_pn, float* lo, float* hi, float* a, float* c, hipStream_t s);
+// gemm.hip:  C[m][n] = sum_k A[m][k] * B[n][k]  (+ C if accumulate) (+ row_bias[m]); C fp32, ldc = N
+tardis_status_t td_gemm_nt(const void* A, const void* B, float* C, int64_t M, int64_t N, int64_t K,
+                           int32_t dtype, int accumulate, const void* row_bias, hipStream_t s);
+// forward.hip
+tardis_status_t td_forward(tardis_layer_s* L, const void* x, int64_t n, void* y, hipStream_t s);
+tardis_status_t td_dense_forward(tardis_layer_s* L, const void* x, int64_t n, void* y, hipStream_t s);

@@ -1,0 +1,352 @@
+// Offline steps: range selection and line fit (calibrate), constant folding,
+// predictor construction, and the layout copies the online path needs.
+#include "common.h"
+
+namespace {
+
+constexpr int kBlock = 256;
+
+// ------------------------------------------------------------------ transpose
+// dst[c][r] = src[r][c], element size 2 or 4 bytes.
+template <typename E>
+__global__ void __launch_bounds__(256)
+transpose_kernel(const E* __restrict__ src, E* __restrict__ dst, int64_t rows, int64_t cols) {
+    __shared__ E tile[32][33];
+    const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;  // 32 x 8
+    const int64_t c0 = (int64_t)blockIdx.x * 32, r0 = (int64_t)blockIdx.y * 32;
+#pragma unroll
+    for (int i = 0; i < 32; i += 8) {
+        const int64_t r = r0 + ty + i, c = c0 + tx;
+        if (r < rows && c < cols) tile[ty + i][tx] = src[r * cols + c];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 32; i += 8) {
+        const int64_t c = c0 + ty + i, r = r0 + tx;
+        if (r < rows && c < cols) dst[c * rows + r] = tile[tx][ty + i];
+    }
+}
+
+// ------------------------------------------------------- scaled transpose (fold)
+// P = diag(a) W1 (h x d) written transposed (d x h).  For bf16 storage the fp32
+// product is split into a bf16 head and a bf16 remainder so that the folded
+// matrix is accumulated from ~16 significant bits instead of 8 (the paper's
+// Sec. "Precision Effects on Reordering FFN" finds bf16 intermediates visibly
+// worse than fp32).
+__global__ void __launch_bounds__(256)
+scale_transpose_bf16_kernel(const bf16_t* __restrict__ W1, const float* __restrict__ a, bf16_t* __restrict__ Phi,
+                            bf16_t* __restrict__ Plo, int64_t h, int64_t d) {
+    __shared__ float tile[32][33];
+    const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
+    const int64_t k0 = (int64_t)blockIdx.x * 32, j0 = (int64_t)blockIdx.y * 32;
+#pragma unroll
+    for (int i = 0; i < 32; i += 8) {
+        const int64_t j = j0 + ty + i, k = k0 + tx;
+        if (j < h && k < d) tile[ty + i][tx] = a[j] * td_bf16_to_f32(W1[j * d + k]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 32; i += 8) {
+        const int64_t k = k0 + ty + i, j = j0 + tx;
+        if (j < h && k < d) {
+            const float p = tile[tx][ty + i];
+            const bf16_t hi = td_f32_to_bf16(p);
+            Phi[k * h + j] = hi;
+            Plo[k * h + j] = td_f32_to_bf16(p - td_bf16_to_f32(hi));
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256)
+scale_transpose_f32_kernel(const float* __restrict__ W1, const float* __restrict__ a, float* __restrict__ P,
+                           int64_t h, int64_t d) {
+    __shared__ float tile[32][33];
+    const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
+    const int64_t k0 = (int64_t)blockIdx.x * 32, j0 = (int64_t)blockIdx.y * 32;
+#pragma unroll
+    for (int i = 0; i < 32; i += 8) {
+        const int64_t j = j0 + ty + i, k = k0 + tx;
+        if (j < h && k < d) tile[ty + i][tx] = a[j] * W1[j * d + k];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 32; i += 8) {
+        const int64_t k = k0 + ty + i, j = j0 + tx;
+        if (j < h && k < d) P[k * h + j] = tile[tx][ty + i];
+    }
+}
+
+__global__ void __launch_bounds__(256)
+f32_to_bf16_kernel(const float* __restrict__ src, bf16_t* __restrict__ dst, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) dst[i] = td_f32_to_bf16(src[i]);
+}
+
+// b'[r] = sum_j W2[r][j] * (c_j + a_j b1_j) + b2[r]; one block per output row,
+// fp64 accumulation.
+template <typename T>
+__global__ void __launch_bounds__(kBlock)
+fold_bias_kernel(const T* __restrict__ W2, const T* __restrict__ b1, const T* __restrict__ b2,
+                 const float* __restrict__ a, const float* __restrict__ c, float* __restrict__ bp, int64_t d,
+                 int64_t h) {
+    __shared__ double red[kBlock / TD_WAVE];
+    const int64_t r = blockIdx.x;
+    double acc = 0.0;
+    for (int64_t j = threadIdx.x; j < h; j += kBlock) {
+        double kj = (double)c[j];
+        if (b1) kj += (double)a[j] * (double)td_load<T>(b1 + j);
+        acc += (double)td_load<T>(W2 + r * h + j) * kj;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x / 64] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int w = 0; w < kBlock / TD_WAVE; ++w) t += red[w];
+        if (b2) t += (double)td_load<T>(b2 + r);
+        bp[r] = (float)t;
+    }
+}
+
+// ---------------------------------------------------------------- predictor
+// One block per neuron row: s = max|w| / 127 (fp64), q = rint(w / s) clamped,
+// bounds in code units.  All arithmetic is IEEE fp64 so the codes are a pure
+// function of the inputs.
+template <typename T>
+__global__ void __launch_bounds__(kBlock)
+sketch_kernel(const T* __restrict__ W1, const T* __restrict__ b1, const float* __restrict__ lo,
+              const float* __restrict__ hi, int64_t d, int8_t* __restrict__ Q, float* __restrict__ tlo,
+              float* __restrict__ thi) {
+    __shared__ float red[kBlock / TD_WAVE];
+    const int64_t j = blockIdx.x;
+    const T* row = W1 + j * d;
+    float m = 0.0f;
+    for (int64_t k = threadIdx.x; k < d; k += kBlock) m = fmaxf(m, fabsf(td_load<T>(row + k)));
+    m = td_wave_max(m);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x / 64] = m;
+    __syncthreads();
+    m = red[0];
+#pragma unroll
+    for (int w = 1; w < kBlock / TD_WAVE; ++w) m = fmaxf(m, red[w]);
+    const double s = (double)m / 127.0;
+    const double bj = b1 ? (double)td_load<T>(b1 + j) : 0.0;
+    if (m > 0.0f) {
+        for (int64_t k = threadIdx.x; k < d; k += kBlock) {
+            double q = rint((double)td_load<T>(row + k) / s);
+            q = fmin(fmax(q, -127.0), 127.0);
+            Q[j * d + k] = (int8_t)(int)q;
+        }
+        if (threadIdx.x == 0) {
+            tlo[j] = (float)(((double)lo[j] - bj) / s);
+            thi[j] = (float)(((double)hi[j] - bj) / s);
+        }
+    } else {
+        for (int64_t k = threadIdx.x; k < d; k += kBlock) Q[j * d + k] = 0;
+        if (threadIdx.x == 0) {
+            const bool inside = ((double)lo[j] <= bj) && (bj < (double)hi[j]);
+            tlo[j] = inside ? -INFINITY : INFINITY;
+            thi[j] = INFINITY;
+        }
+    }
+}
+
+// -------------------------------------------------------------- calibration
+// One block per neuron.  zt: that neuron's n calibration pre-activations.
+// Sort in LDS (bitonic, padded with +inf), read the two quantiles by linear
+// interpolation at q*(n-1), then fit sigma(z) ~ a z + c over lo <= z < hi.
+__device__ __forceinline__ double block_sum(double v, double* red) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x / 64] = v;
+    __syncthreads();
+    double t = 0.0;
+#pragma unroll
+    for (int w = 0; w < kBlock / TD_WAVE; ++w) t += red[w];
+    return t;
+}
+
+__device__ __forceinline__ double quantile_sorted(const float* v, int n, double q) {
+    const double pos = q * (double)(n - 1);
+    int i = (int)floor(pos);
+    i = min(max(i, 0), n - 1);
+    const double g = pos - (double)i;
+    const int i1 = min(i + 1, n - 1);
+    return (double)v[i] + g * ((double)v[i1] - (double)v[i]);
+}
+
+__global__ void __launch_bounds__(kBlock)
+calibrate_neuron_kernel(const float* __restrict__ Zt, int n, int npad, float coverage,
+                        const float* __restrict__ cov_pn, int act, float* __restrict__ lo, float* __restrict__ hi,
+                        float* __restrict__ a, float* __restrict__ c) {
+    extern __shared__ float vals[];
+    __shared__ double red[kBlock / TD_WAVE];
+    const int64_t j = blockIdx.x;
+    const float* z = Zt + j * (int64_t)n;
+    for (int i = threadIdx.x; i < npad; i += kBlock) vals[i] = i < n ? z[i] : INFINITY;
+    __syncthreads();
+    for (int k = 2; k <= npad; k <<= 1) {
+        for (int s = k >> 1; s > 0; s >>= 1) {
+            for (int t = threadIdx.x; t < npad / 2; t += kBlock) {
+                const int i = 2 * t - (t & (s - 1));  // index with bit `s` clear
+                const int p = i + s;
+                const bool up = (i & k) == 0;
+                const float x0 = vals[i], x1 = vals[p];
+                if ((x0 > x1) == up) {
+                    vals[i] = x1;
+                    vals[p] = x0;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    const double t = cov_pn ? (double)cov_pn[j] : (double)coverage;
+    const float lo32 = (float)quantile_sorted(vals, n, (1.0 - t) / 2.0);
+    const float hi32 = (float)quantile_sorted(vals, n, (1.0 + t) / 2.0);
+
+    double cnt = 0.0, sz = 0.0, sg = 0.0;
+    for (int i = threadIdx.x; i < n; i += kBlock) {
+        const float v = vals[i];
+        if (v >= lo32 && v < hi32) {
+            cnt += 1.0;
+            sz += (double)v;
+            sg += td_act_f64((double)v, act);
+        }
+    }
+    cnt = block_sum(cnt, red);
+    sz = block_sum(sz, red);
+    sg = block_sum(sg, red);
+    float aj, cj;
+    if (cnt < 0.5) {
+        aj = 0.0f;
+        cj = (float)td_act_f64((double)lo32, act);
+    } else {
+        const double zbar = sz / cnt, gbar = sg / cnt;
+        double var = 0.0, cov = 0.0;
+        for (int i = threadIdx.x; i < n; i += kBlock) {
+            const float v = vals[i];
+            if (v >= lo32 && v < hi32) {
+                const double dz = (double)v - zbar;
+                var += dz * dz;
+                cov += dz * (td_act_f64((double)v, act) - gbar);
+            }
+        }
+        var = block_sum(var, red);
+        cov = block_sum(cov, red);
+        if (cnt < 1.5 || !(var > 0.0)) {
+            aj = 0.0f;
+            cj = (float)gbar;
+        } else {
+            const double slope = cov / var;
+            aj = (float)slope;
+            cj = (float)(gbar - slope * zbar);
+        }
+    }
+    if (threadIdx.x == 0) {
+        lo[j] = lo32;
+        hi[j] = hi32;
+        a[j] = aj;
+        c[j] = cj;
+    }
+}
+
+struct DevBuf {  // frees on scope exit
+    void* p = nullptr;
+    ~DevBuf() {
+        if (p) (void)hipFree(p);
+    }
+    tardis_status_t alloc(size_t bytes) {
+        hipError_t e = hipMalloc(&p, bytes ? bytes : 16);
+        if (e != hipSuccess) {
+            p = nullptr;
+            (void)hipGetLastError();
+            return e == hipErrorOutOfMemory ? TARDIS_ERR_OOM : TARDIS_ERR_HIP;
+        }
+        return TARDIS_OK;
+    }
+};
+
+dim3 tile_grid(int64_t cols, int64_t rows) { return dim3((unsigned)((cols + 31) / 32), (unsigned)((rows + 31) / 32)); }
+
+}  // namespace
+
+tardis_status_t td_transpose(const void* src, void* dst, int64_t rows, int64_t cols, int32_t dtype, hipStream_t s) {
+    if ((rows + 31) / 32 > 65535) return TARDIS_ERR_SHAPE;
+    if (dtype == TARDIS_BF16)
+        hipLaunchKernelGGL(transpose_kernel<uint16_t>, tile_grid(cols, rows), dim3(256), 0, s,
+                           static_cast<const uint16_t*>(src), static_cast<uint16_t*>(dst), rows, cols);
+    else
+        hipLaunchKernelGGL(transpose_kernel<uint32_t>, tile_grid(cols, rows), dim3(256), 0, s,
+                           static_cast<const uint32_t*>(src), static_cast<uint32_t*>(dst), rows, cols);
+    TD_HIP(hipGetLastError());
+    return TARDIS_OK;
+}
+
+tardis_status_t td_build_sketch(const void* W1, const void* b1, const float* lo, const float* hi, int64_t h,
+                                int64_t d, int32_t dtype, int8_t* Q, float* tlo, float* thi, hipStream_t s) {
+    if (dtype == TARDIS_BF16)
+        hipLaunchKernelGGL(sketch_kernel<bf16_t>, dim3((unsigned)h), dim3(kBlock), 0, s,
+                           static_cast<const bf16_t*>(W1), static_cast<const bf16_t*>(b1), lo, hi, d, Q, tlo, thi);
+    else
+        hipLaunchKernelGGL(sketch_kernel<float>, dim3((unsigned)h), dim3(kBlock), 0, s,
+                           static_cast<const float*>(W1), static_cast<const float*>(b1), lo, hi, d, Q, tlo, thi);
+    TD_HIP(hipGetLastError());
+    return TARDIS_OK;
+}
+
+tardis_status_t td_fold(const tardis_ffn_desc* desc, const float* a, const float* c, void* Wp, float* bp,
+                        hipStream_t s) {
+    const int64_t d = desc->d, h = desc->h;
+    if ((h + 31) / 32 > 65535 || (d + 31) / 32 > 65535) return TARDIS_ERR_SHAPE;
+    if (desc->dtype == TARDIS_BF16) {
+        DevBuf phi, plo, acc;
+        TD_TRY(phi.alloc((size_t)d * h * 2));
+        TD_TRY(plo.alloc((size_t)d * h * 2));
+        TD_TRY(acc.alloc((size_t)d * d * 4));
+        hipLaunchKernelGGL(scale_transpose_bf16_kernel, tile_grid(d, h), dim3(256), 0, s,
+                           static_cast<const bf16_t*>(desc->W1), a, static_cast<bf16_t*>(phi.p),
+                           static_cast<bf16_t*>(plo.p), h, d);
+        TD_TRY(td_gemm_nt(desc->W2, phi.p, static_cast<float*>(acc.p), d, d, h, TARDIS_BF16, 0, nullptr, s));
+        TD_TRY(td_gemm_nt(desc->W2, plo.p, static_cast<float*>(acc.p), d, d, h, TARDIS_BF16, 1, nullptr, s));
+        const int64_t n = d * d;
+        hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                           static_cast<const float*>(acc.p), static_cast<bf16_t*>(Wp), n);
+        hipLaunchKernelGGL(fold_bias_kernel<bf16_t>, dim3((unsigned)d), dim3(kBlock), 0, s,
+                           static_cast<const bf16_t*>(desc->W2), static_cast<const bf16_t*>(desc->b1),
+                           static_cast<const bf16_t*>(desc->b2), a, c, bp, d, h);
+        TD_HIP(hipGetLastError());
+        TD_HIP(hipStreamSynchronize(s));  // temporaries are freed on return
+    } else {
+        DevBuf p;
+        TD_TRY(p.alloc((size_t)d * h * 4));
+        hipLaunchKernelGGL(scale_transpose_f32_kernel, tile_grid(d, h), dim3(256), 0, s,
+                           static_cast<const float*>(desc->W1), a, static_cast<float*>(p.p), h, d);
+        TD_TRY(td_gemm_nt(desc->W2, p.p, static_cast<float*>(Wp), d, d, h, TARDIS_F32, 0, nullptr, s));
+        hipLaunchKernelGGL(fold_bias_kernel<float>, dim3((unsigned)d), dim3(kBlock), 0, s,
+                           static_cast<const float*>(desc->W2), static_cast<const float*>(desc->b1),
+                           static_cast<const float*>(desc->b2), a, c, bp, d, h);
+        TD_HIP(hipGetLastError());
+        TD_HIP(hipStreamSynchronize(s));
+    }
+    return TARDIS_OK;
+}
+
+tardis_status_t td_calibrate(const tardis_ffn_desc* desc, const void* X, int64_t n, float coverage,
+                             const float* cov_pn, float* lo, float* hi, float* a, float* c, hipStream_t s) {
+    const int64_t d = desc->d, h = desc->h;
+    DevBuf zt;
+    TD_TRY(zt.alloc((size_t)h * n * 4));
+    TD_TRY(td_gemm_nt(desc->W1, X, static_cast<float*>(zt.p), h, n, d, desc->dtype, 0, desc->b1, s));
+    int npad = 2;
+    while (npad < n) npad <<= 1;
+    const size_t lds = (size_t)npad * sizeof(float);
+    if (lds > 48 * 1024)
+        TD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(calibrate_neuron_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(calibrate_neuron_kernel, dim3((unsigned)h), dim3(kBlock), lds, s,
+                       static_cast<const float*>(zt.p), (int)n, npad, coverage, cov_pn, (int)desc->act, lo, hi, a, c);
+    TD_HIP(hipGetLastError());
+    TD_HIP(hipStreamSynchronize(s));
+    return TARDIS_OK;
+}

@@ -1,0 +1,102 @@
+"""Host-only checks of the C ABI: the library loads, exports every function the
+header declares, and rejects bad arguments before touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2501_10054_amd import tardis as T
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "tardis.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(tardis_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_function():
+    lib = T.lib()
+    names = _declared()
+    assert len(names) >= 11
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(T.EXPORTS) == names
+
+
+def test_version_and_status_strings():
+    assert T.lib().tardis_version() == 1
+    seen = {T.status_string(s) for s in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+    assert T.status_string(99) == "unknown status"
+
+
+def _desc(**kw):
+    base = dict(d=64, h=256, dtype=T.F32, act=0, W1=0x1000, b1=None, W2=0x2000, b2=None)
+    base.update(kw)
+    return T.tardis_ffn_desc(**base)
+
+
+def test_fold_rejects_bad_arguments_without_a_gpu():
+    lib = T.lib()
+    h = C.c_void_p()
+    p = C.c_void_p(0x4000)
+    ok_opts = T.tardis_fold_opts(8, T.F32, 1, 0, 0)
+
+    def fold(desc, lo=p, opts=ok_opts, out=h):
+        return lib.tardis_fold(C.byref(desc) if desc is not None else None, lo, p, p, p,
+                               C.byref(opts) if opts is not None else None, None,
+                               C.byref(out) if out is not None else None)
+
+    assert fold(None) == T.ERR_INVALID_ARG
+    assert fold(_desc(), out=None) == T.ERR_INVALID_ARG
+    assert fold(_desc(W1=None)) == T.ERR_INVALID_ARG
+    assert fold(_desc(W2=None)) == T.ERR_INVALID_ARG
+    assert fold(_desc(W1=0x1004)) == T.ERR_INVALID_ARG          # misaligned
+    assert fold(_desc(d=0)) == T.ERR_SHAPE
+    assert fold(_desc(h=-3)) == T.ERR_SHAPE
+    assert fold(_desc(d=1 << 20)) == T.ERR_SHAPE
+    assert fold(_desc(dtype=7)) == T.ERR_DTYPE
+    assert fold(_desc(act=9)) == T.ERR_INVALID_ARG
+    assert fold(_desc(), lo=None) == T.ERR_INVALID_ARG
+    assert fold(_desc(), opts=T.tardis_fold_opts(4, T.F32, 1, 0, 0)) == T.ERR_INVALID_ARG
+    assert fold(_desc(), opts=T.tardis_fold_opts(8, T.BF16, 1, 0, 0)) == T.ERR_DTYPE
+    assert fold(_desc(), opts=T.tardis_fold_opts(8, T.F32, 0, 0, 0)) == T.ERR_SHAPE
+    assert fold(_desc(), opts=T.tardis_fold_opts(8, T.F32, 1, 1, 0)) == T.ERR_INVALID_ARG
+    assert h.value is None
+
+
+def test_calibrate_rejects_bad_arguments_without_a_gpu():
+    lib = T.lib()
+    p = C.c_void_p(0x4000)
+
+    def cal(desc, X=p, n=16, t=0.9, lo=p):
+        return lib.tardis_calibrate(C.byref(desc), X, n, t, None, lo, p, p, p, None)
+
+    assert cal(_desc(), X=None) == T.ERR_INVALID_ARG
+    assert cal(_desc(), lo=None) == T.ERR_INVALID_ARG
+    assert cal(_desc(), n=0) == T.ERR_SHAPE
+    assert cal(_desc(), n=1 << 20) == T.ERR_SHAPE
+    assert cal(_desc(), t=0.0) == T.ERR_INVALID_ARG
+    assert cal(_desc(), t=1.5) == T.ERR_INVALID_ARG
+    assert cal(_desc(h=0)) == T.ERR_SHAPE
+
+
+def test_online_calls_reject_null_handle():
+    lib = T.lib()
+    p = C.c_void_p(0x4000)
+    assert lib.tardis_ffn_forward(None, p, p, None) == T.ERR_STATE
+    assert lib.tardis_ffn_forward_batched(None, p, 1, p, None) == T.ERR_STATE
+    assert lib.tardis_dense_forward(None, p, 1, p, None) == T.ERR_STATE
+    assert lib.tardis_get_folded(None, p, p, None) == T.ERR_STATE
+    assert lib.tardis_get_predictor_state(None, p, p, p, None) == T.ERR_STATE
+    assert lib.tardis_get_last_outliers(None, 1, p, p, p, None) == T.ERR_STATE
+    assert lib.tardis_destroy(None) == T.OK
+
+
+def test_error_type_carries_status():
+    with pytest.raises(T.TardisError) as e:
+        T._check(T.ERR_SHAPE, "x")
+    assert e.value.status == T.ERR_SHAPE and "shape" in str(e.value)

@@ -1,0 +1,270 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU checker, element
+by element, on the same seeded inputs.
+
+Bars.  Integer work (predictor codes, masks, lists, counts): bit-exact.
+Floating point: relative L2 error of y <= 1e-2 for bf16 storage (fp32
+accumulation) and <= 1e-4 for fp32 storage; the folded matrix and the fitted
+lines have their own bounds stated at each test.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tardis_oracle as O
+from paper_2501_10054_amd import synth
+from paper_2501_10054_amd import tardis as T
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+Y_TOL = {"f32": 1e-4, "bf16": 1e-2}
+
+
+def dev(x, dtype):
+    """numpy float32 array (values representable in `dtype`) -> device tensor."""
+    if x is None:
+        return None
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
+    return t.to(torch.bfloat16 if dtype == "bf16" else torch.float32).to(DEV).contiguous()
+
+
+def host(t):
+    return t.detach().to("cpu").to(torch.float32).numpy().astype(np.float64)
+
+
+def rel_l2(got, want):
+    return float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30))
+
+
+def make_ffn(layer, act="gelu_erf"):
+    return T.FFN(dev(layer.W1, layer.dtype), dev(layer.W2, layer.dtype), dev(layer.b1, layer.dtype),
+                 dev(layer.b2, layer.dtype), act)
+
+
+def unpack_mask(mask_t, h):
+    w = mask_t.cpu().numpy().view(np.uint32)
+    bits = (w[:, :, None] >> np.arange(32, dtype=np.uint32)[None, None, :]) & 1
+    return bits.reshape(w.shape[0], -1)[:, :h].astype(bool)
+
+
+def custom_layer(d, h, dtype, seed, w1_std, bias):
+    return synth.make_layer(d, h, dtype, seed, w1_std=w1_std, w2_std=0.05, heavy_frac=0.02, with_bias=bias)
+
+
+def run_case(layer, X_cal, X_test, coverage, act="gelu_erf", batched=False, check_calibrate=True):
+    """Full pipeline on the GPU and in the checker; returns a dict of diagnostics."""
+    dt = layer.dtype
+    ffn = make_ffn(layer, act)
+    lo, hi, a, c = T.tardis_calibrate(ffn, dev(X_cal, dt), coverage)
+    torch.cuda.synchronize()
+    lo_h, hi_h, a_h, c_h = (t.cpu().numpy() for t in (lo, hi, a, c))
+
+    if check_calibrate:
+        olo, ohi, oa, oc = O.calibrate(layer.W1, layer.b1, X_cal, coverage, act)
+        scale = max(1e-6, float(np.abs(np.concatenate([olo, ohi])).max()))
+        assert np.abs(lo_h - olo).max() <= 2e-5 * scale
+        assert np.abs(hi_h - ohi).max() <= 2e-5 * scale
+        # a sample sitting within rounding distance of a range end may be in on one side and out
+        # on the other; that moves the fit by O(1/n)
+        n_cal = X_cal.shape[0]
+        assert np.abs(a_h - oa).max() <= 5.0 / n_cal + 1e-4
+        assert np.abs(c_h - oc).max() <= (5.0 / n_cal + 1e-4) * max(1.0, scale)
+
+    # from here on both sides use the SAME (lo, hi, a, c): the library's
+    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=max(1, X_test.shape[0]))
+    F = O.build(layer.W1, layer.b1, layer.W2, layer.b2, lo_h, hi_h, a_h, c_h, act)
+
+    Wp, bp = T.tardis_get_folded(L)
+    Q, tlo, thi = T.tardis_get_predictor_state(L)
+    torch.cuda.synchronize()
+    wp_err = rel_l2(host(Wp), F.Wp)
+    assert wp_err <= (3e-3 if dt == "bf16" else 1e-5), wp_err     # bf16: one rounding of W' (2^-9)
+    assert rel_l2(host(bp), F.bp) <= 1e-5 or np.abs(host(bp) - F.bp).max() <= 1e-6
+    np.testing.assert_array_equal(Q.cpu().numpy(), F.sk.Q)
+    np.testing.assert_array_equal(tlo.cpu().numpy(), F.sk.tlo)
+    np.testing.assert_array_equal(thi.cpu().numpy(), F.sk.thi)
+
+    n = X_test.shape[0]
+    Xd = dev(X_test, dt)
+    Yo, FLo = O.forward(F, X_test)
+    if batched:
+        Y = T.tardis_ffn_forward_batched(L, Xd)
+        mask, counts, lst = T.tardis_get_last_outliers(L, n)
+        torch.cuda.synchronize()
+        Yg = host(Y)
+        FLg = unpack_mask(mask, layer.h)
+        counts = counts.cpu().numpy()
+        lst = lst.cpu().numpy()
+        lists = [lst[t, :counts[t]] for t in range(n)]
+    else:
+        Yg = np.empty((n, layer.d))
+        FLg = np.empty((n, layer.h), bool)
+        counts = np.empty(n, np.int64)
+        lists = []
+        for t in range(n):
+            y = T.tardis_ffn_forward(L, Xd[t])
+            mask, cnt, lst = T.tardis_get_last_outliers(L, 1)
+            torch.cuda.synchronize()
+            Yg[t] = host(y)
+            FLg[t] = unpack_mask(mask, layer.h)[0]
+            counts[t] = int(cnt.item())
+            lists.append(lst.cpu().numpy()[0, :counts[t]])
+
+    np.testing.assert_array_equal(FLg, FLo)                         # mask: bit-exact
+    for t in range(n):
+        assert counts[t] == FLo[t].sum()
+        np.testing.assert_array_equal(np.sort(lists[t]), np.flatnonzero(FLo[t]))   # list: same set
+    err = rel_l2(Yg, Yo)
+    assert err <= Y_TOL[dt], err
+    per_tok = np.linalg.norm(Yg - Yo, axis=1) / np.linalg.norm(Yo, axis=1)
+    assert per_tok.max() <= 3 * Y_TOL[dt]
+
+    # dense baseline against the checker's dense FFN
+    Yd = host(T.tardis_dense_forward(L, Xd))
+    derr = rel_l2(Yd, O.dense(layer.W1, layer.b1, layer.W2, layer.b2, X_test, act))
+    assert derr <= Y_TOL[dt], derr
+    L.close()
+    return dict(y_err=err, wp_err=wp_err, dense_err=derr, rate=float(FLo.mean()))
+
+
+# ------------------------------------------------------------------ config 0
+def test_tiny_fp32_batch1():
+    w = synth.tiny()
+    r = run_case(w.layer, w.X_cal, w.X_test, w.coverage)
+    assert 0.03 < r["rate"] < 0.2
+
+
+def test_tiny_hard_fp32_with_bias():
+    w = synth.tiny(hard=True, with_bias=True)
+    r = run_case(w.layer, w.X_cal, w.X_test, w.coverage)
+    assert 0.03 < r["rate"] < 0.2
+
+
+@pytest.mark.parametrize("act", ["gelu_tanh", "relu", "identity"])
+def test_tiny_other_activations(act):
+    w = synth.tiny(hard=True, with_bias=True)
+    run_case(w.layer, w.X_cal, w.X_test[:8], 0.8, act=act)
+
+
+def test_tiny_batched_call():
+    w = synth.tiny(hard=True)
+    run_case(w.layer, w.X_cal, w.X_test, 0.85, batched=True)
+
+
+# ------------------------------------------------- ragged and several-tile shapes
+@pytest.mark.parametrize("d,h,dtype", [(72, 200, "f32"), (50, 77, "f32"), (200, 1000, "bf16"),
+                                       (136, 330, "bf16"), (70, 99, "bf16")])
+def test_ragged_shapes(d, h, dtype):
+    seed = synth.workload_seed(9, d)
+    layer = custom_layer(d, h, dtype, seed, w1_std=0.15, bias=True)
+    X_cal = synth.make_tokens(300, d, dtype, seed, synth.STREAM_CAL)
+    X_test = synth.make_tokens(6, d, dtype, seed, synth.STREAM_TEST)
+    run_case(layer, X_cal, X_test, 0.9)
+
+
+def test_mid_bf16_heavy_tail():
+    w = synth.decode(d=512, h=2048, n_cal=1024, n_test=16, coverage=0.95)
+    r = run_case(w.layer, w.X_cal, w.X_test, w.coverage)
+    assert 0.02 < r["rate"] < 0.12
+
+
+def test_mid_bf16_batched_high_fallback():
+    w = synth.decode(d=512, h=2048, n_cal=512, n_test=12, coverage=0.85)
+    r = run_case(w.layer, w.X_cal, w.X_test, w.coverage, batched=True)
+    assert 0.08 < r["rate"] < 0.25
+
+
+# ----------------------------------------------------------------- edge cases
+def test_degenerate_tokens_and_neurons():
+    d, h = 64, 96
+    seed = synth.workload_seed(9, 1)
+    layer = custom_layer(d, h, "f32", seed, w1_std=0.3, bias=True)
+    layer.W1[5] = 0.0                       # all-zero neuron: z = b1 for every token
+    layer.W1[6] = 0.0
+    layer.b1[6] = 100.0
+    X_cal = synth.make_tokens(200, d, "f32", seed, synth.STREAM_CAL)
+    X_test = synth.make_tokens(6, d, "f32", seed, synth.STREAM_TEST)
+    X_test[0] = 0.0                         # zero token
+    X_test[1] *= 1e-30                      # tiny token
+    X_test[2] *= 1e20                       # huge token: everything out of range
+    X_test[3, 1:] = 0.0                     # one-hot-like
+    run_case(layer, X_cal, X_test, 0.9)
+
+
+def test_all_flagged_equals_dense_and_none_flagged_equals_folded():
+    w = synth.tiny(hard=True)
+    layer = w.layer
+    ffn = make_ffn(layer)
+    lo, hi, a, c = T.tardis_calibrate(ffn, dev(w.X_cal, "f32"), 0.9)
+    Xd = dev(w.X_test[:4], "f32")
+    # empty ranges: every neuron is flagged, the result is the exact FFN
+    L = T.tardis_fold(ffn, hi.clone(), hi.clone(), a, c, max_batch=4)
+    Y = host(T.tardis_ffn_forward_batched(L, Xd))
+    _, counts, _ = T.tardis_get_last_outliers(L, 4)
+    assert (counts.cpu().numpy() == layer.h).all()
+    ref = O.dense(layer.W1, None, layer.W2, None, w.X_test[:4])
+    assert rel_l2(Y, ref) <= 1e-4
+    L.close()
+    # infinite ranges: nothing is flagged, the result is W'x + b'
+    inf = torch.full_like(lo, float("inf"))
+    L = T.tardis_fold(ffn, -inf, inf, a, c, max_batch=4)
+    Y = host(T.tardis_ffn_forward_batched(L, Xd))
+    _, counts, _ = T.tardis_get_last_outliers(L, 4)
+    assert (counts.cpu().numpy() == 0).all()
+    Wp, bp = O.fold(layer.W1, None, layer.W2, None, a.cpu().numpy(), c.cpu().numpy())
+    assert rel_l2(Y, w.X_test[:4].astype(np.float64) @ Wp.T + bp) <= 1e-4
+    L.close()
+
+
+def test_per_neuron_coverage_and_single_calibration_token():
+    w = synth.tiny(hard=True)
+    ffn = make_ffn(w.layer)
+    t = np.linspace(0.5, 0.99, w.layer.h).astype(np.float32)
+    lo, hi, a, c = T.tardis_calibrate(ffn, dev(w.X_cal, "f32"), 0.0, torch.from_numpy(t).to(DEV))
+    olo, ohi, oa, oc = O.calibrate(w.layer.W1, None, w.X_cal, t)
+    assert np.abs(lo.cpu().numpy() - olo).max() < 1e-5 and np.abs(hi.cpu().numpy() - ohi).max() < 1e-5
+    assert np.abs(a.cpu().numpy() - oa).max() < 2e-2
+    # n_cal = 1: lo = hi = z, no sample inside [lo, hi): slope 0, intercept sigma(lo)
+    lo, hi, a, c = T.tardis_calibrate(ffn, dev(w.X_cal[:1], "f32"), 0.9)
+    olo, ohi, oa, oc = O.calibrate(w.layer.W1, None, w.X_cal[:1], 0.9)
+    np.testing.assert_allclose(lo.cpu().numpy(), olo, atol=1e-6)
+    np.testing.assert_allclose(hi.cpu().numpy(), ohi, atol=1e-6)
+    np.testing.assert_array_equal(a.cpu().numpy(), 0.0)
+    np.testing.assert_allclose(c.cpu().numpy(), oc, atol=1e-6)
+
+
+def test_runtime_argument_errors():
+    w = synth.tiny()
+    ffn = make_ffn(w.layer)
+    lo, hi, a, c = T.tardis_calibrate(ffn, dev(w.X_cal, "f32"), 0.9)
+    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=2)
+    X = dev(w.X_test[:4], "f32")
+    with pytest.raises(T.TardisError) as e:
+        T.tardis_ffn_forward_batched(L, X)                       # n > max_batch
+    assert e.value.status == T.ERR_SHAPE
+    with pytest.raises(T.TardisError) as e:
+        T.tardis_ffn_forward(L, X[0], X[0])                      # aliasing
+    assert e.value.status == T.ERR_INVALID_ARG
+    T.tardis_ffn_forward_batched(L, X[:2])
+    with pytest.raises(T.TardisError) as e:
+        T.tardis_get_last_outliers(L, 1)                         # last call had 2 tokens
+    assert e.value.status == T.ERR_STATE
+    L.close()
+
+
+def test_repeated_calls_are_stable():
+    # the same token twice gives the same mask and (up to atomic ordering) the same y
+    w = synth.tiny(hard=True)
+    ffn = make_ffn(w.layer)
+    lo, hi, a, c = T.tardis_calibrate(ffn, dev(w.X_cal, "f32"), 0.9)
+    L = T.tardis_fold(ffn, lo, hi, a, c)
+    x = dev(w.X_test[3], "f32")
+    y1 = host(T.tardis_ffn_forward(L, x))
+    m1, c1, _ = T.tardis_get_last_outliers(L, 1)
+    m1 = m1.clone()
+    for _ in range(5):
+        y2 = host(T.tardis_ffn_forward(L, x))
+    m2, c2, _ = T.tardis_get_last_outliers(L, 1)
+    assert torch.equal(m1, m2) and int(c1.item()) == int(c2.item())
+    assert rel_l2(y2, y1) < 1e-6
+    L.close()
