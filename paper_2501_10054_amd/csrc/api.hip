@@ -1,5 +1,6 @@
 // C-ABI entry points of libtardis: argument validation, handle lifetime and
 // dispatch.  No kernel lives here.
+#include <cstdlib>
 #include <new>
 
 #include "common.h"
@@ -37,10 +38,18 @@ template <typename P> tardis_status_t dev_alloc(P** p, size_t bytes) {
     return TARDIS_OK;
 }
 
+// integer tuning knob from the environment (read when a layer is folded)
+int env_int(const char* name, int fallback, int lo, int hi) {
+    const char* v = std::getenv(name);
+    if (!v || !*v) return fallback;
+    const long x = std::strtol(v, nullptr, 10);
+    return (x < lo || x > hi) ? fallback : (int)x;
+}
+
 void free_layer(tardis_layer_s* L) {
     if (!L) return;
     void* owned[] = {L->W2T, L->W2, L->Wp, L->bp, L->Q, L->tlo, L->thi, L->a, L->c,
-                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync};
+                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix};
     for (void* p : owned)
         if (p) (void)hipFree(p);
     delete L;
@@ -77,6 +86,12 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     TD_TRY(dev_alloc(reinterpret_cast<char**>(&L->hidden), nb * h * es));
     TD_TRY(dev_alloc(&L->sync, 256));
     TD_HIP(hipMemsetAsync(L->sync, 0, 256, s));
+    L->dec_blocks = env_int("TARDIS_DECODE_BLOCKS", 256, 1, 4096);
+    L->dec_copies = env_int("TARDIS_DECODE_COPIES", 8, 1, 64);
+    L->dec_debug = env_int("TARDIS_DECODE_DEBUG", 0, 0, 255);
+    TD_TRY(dev_alloc(&L->yfix, (size_t)L->dec_copies * d * 4));
+    TD_HIP(hipMemsetAsync(L->yfix, 0, (size_t)L->dec_copies * d * 4, s));
+    L->use_fused = env_int("TARDIS_DECODE_FUSED", 1, 0, 1) && td_decode_fused_supported(L);
     TD_HIP(hipMemsetAsync(L->counts, 0, nb * 4, s));
     TD_HIP(hipMemsetAsync(L->mask, 0, nb * L->mask_words * 4, s));
     TD_HIP(hipMemsetAsync(L->yacc, 0, nb * d * 4, s));
@@ -172,8 +187,7 @@ tardis_status_t tardis_get_last_outliers(tardis_handle_t L, int64_t n, uint32_t*
     hipStream_t s = static_cast<hipStream_t>(stream);
     const size_t nn = (size_t)n;
     if (mask) TD_HIP(hipMemcpyAsync(mask, L->mask, nn * L->mask_words * 4, hipMemcpyDeviceToDevice, s));
-    if (counts) TD_HIP(hipMemcpyAsync(counts, L->counts, nn * 4, hipMemcpyDeviceToDevice, s));
-    if (list) TD_HIP(hipMemcpyAsync(list, L->list, nn * L->h * 4, hipMemcpyDeviceToDevice, s));
+    if (counts || list) TD_TRY(td_mask_to_list(L, n, counts, list, s));   // derived from the mask words
     return TARDIS_OK;
 }
 

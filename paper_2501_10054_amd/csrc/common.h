@@ -52,6 +52,11 @@ struct tardis_layer_s {
     int32_t* list;     // max_batch x h flagged indices
     float* hidden;     // max_batch x h activations for the dense baseline
     int32_t* sync;     // small block of device counters (zero between calls)
+    float* yfix;       // dec_copies x d fp32 repair accumulators of the fused decode kernel (zero between calls)
+    int32_t dec_blocks;   // grid of the fused decode kernel
+    int32_t dec_copies;   // number of repair accumulator copies
+    int32_t dec_debug;    // phase-skipping bits for timing experiments (0 in normal use)
+    int32_t use_fused;    // fused single-launch decode path available for this layer
     int64_t last_n;    // token count of the most recent online call
 };
 
@@ -145,6 +150,11 @@ tardis_status_t td_calibrate(const tardis_ffn_desc* desc, const void* X, int64_t
 // gemm.hip:  C[m][n] = sum_k A[m][k] * B[n][k]  (+ C if accumulate) (+ row_bias[m]); C fp32, ldc = N
 tardis_status_t td_gemm_nt(const void* A, const void* B, float* C, int64_t M, int64_t N, int64_t K,
                            int32_t dtype, int accumulate, const void* row_bias, hipStream_t s);
+// decode.hip
+bool td_decode_fused_supported(const tardis_layer_s* L);
+tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
+                                hipStream_t s);
+tardis_status_t td_mask_to_list(const tardis_layer_s* L, int64_t n, int32_t* counts, int32_t* list, hipStream_t s);
 // forward.hip
 tardis_status_t td_forward(tardis_layer_s* L, const void* x, int64_t n, void* y, hipStream_t s);
 tardis_status_t td_dense_forward(tardis_layer_s* L, const void* x, int64_t n, void* y, hipStream_t s);

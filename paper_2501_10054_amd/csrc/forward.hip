@@ -10,6 +10,7 @@
 // once with 16-byte loads per lane, one wavefront per row, the token staged in
 // LDS, and the per-row reduction done with cross-lane shuffles.
 #include "common.h"
+#include "rowdot.h"
 
 #include <hip/amd_detail/amd_hip_unsafe_atomics.h>
 
@@ -19,109 +20,6 @@ constexpr int kBlock = 256;                 // 4 wavefronts
 constexpr int kWaves = kBlock / TD_WAVE;
 constexpr int kPredRowsPerWave = 8;         // 4 waves x 8 rows = one 32-bit mask word per block
 constexpr int kGemvRowsPerWave = 4;
-
-// ------------------------------------------------------------------ row . x
-// 16-byte vector of T and its dot product with a 16-byte vector of x.
-template <typename T> struct RowVec;
-template <> struct RowVec<float> {
-    static constexpr int N = 4;
-    static __device__ __forceinline__ float dot(const td_u32x4& w, const td_u32x4& x, float acc) {
-        acc = fmaf(__uint_as_float(w.x), __uint_as_float(x.x), acc);
-        acc = fmaf(__uint_as_float(w.y), __uint_as_float(x.y), acc);
-        acc = fmaf(__uint_as_float(w.z), __uint_as_float(x.z), acc);
-        acc = fmaf(__uint_as_float(w.w), __uint_as_float(x.w), acc);
-        return acc;
-    }
-};
-__device__ __forceinline__ float dot2_bf16(uint32_t w, uint32_t x, float acc) {
-    acc = fmaf(__uint_as_float(w << 16), __uint_as_float(x << 16), acc);
-    acc = fmaf(__uint_as_float(w & 0xFFFF0000u), __uint_as_float(x & 0xFFFF0000u), acc);
-    return acc;
-}
-template <> struct RowVec<bf16_t> {
-    static constexpr int N = 8;
-    static __device__ __forceinline__ float dot(const td_u32x4& w, const td_u32x4& x, float acc) {
-        acc = dot2_bf16(w.x, x.x, acc);
-        acc = dot2_bf16(w.y, x.y, acc);
-        acc = dot2_bf16(w.z, x.z, acc);
-        acc = dot2_bf16(w.w, x.w, acc);
-        return acc;
-    }
-};
-
-// R rows at once (their loads are independent, so they overlap in flight).
-// rows[i] may be null for i past the end of the matrix; such rows return 0.
-// xs points at n values of x (LDS or global).  Result valid in every lane.
-template <typename T, int R>
-__device__ __forceinline__ void rows_dot(const T* const (&rows)[R], const T* xs, int n, int lane,
-                                         float (&out)[R]) {
-    constexpr int V = RowVec<T>::N;
-    float acc[R];
-#pragma unroll
-    for (int i = 0; i < R; ++i) acc[i] = 0.0f;
-    if (n % V == 0) {
-        const int nv = n / V;
-        const td_u32x4* xv = reinterpret_cast<const td_u32x4*>(xs);
-#pragma unroll 2
-        for (int v = lane; v < nv; v += TD_WAVE) {
-            td_u32x4 w[R];
-#pragma unroll
-            for (int i = 0; i < R; ++i)
-                w[i] = rows[i] ? td_load_stream16(reinterpret_cast<const td_u32x4*>(rows[i]) + v)
-                               : td_u32x4{0, 0, 0, 0};
-            const td_u32x4 xx = xv[v];
-#pragma unroll
-            for (int i = 0; i < R; ++i) acc[i] = RowVec<T>::dot(w[i], xx, acc[i]);
-        }
-    } else {
-        for (int k = lane; k < n; k += TD_WAVE) {
-            const float xx = td_load<T>(xs + k);
-#pragma unroll
-            for (int i = 0; i < R; ++i)
-                if (rows[i]) acc[i] = fmaf(td_load<T>(rows[i] + k), xx, acc[i]);
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < R; ++i) out[i] = td_wave_sum(acc[i]);
-}
-
-// int8 rows against the int8 token code: exact int32 sums.
-template <int R>
-__device__ __forceinline__ void rows_dot_i8(const int8_t* const (&rows)[R], const int8_t* xq, int n, int lane,
-                                            int (&out)[R]) {
-    int acc[R];
-#pragma unroll
-    for (int i = 0; i < R; ++i) acc[i] = 0;
-    if (n % 16 == 0) {
-        const int nv = n / 16;
-        const td_u32x4* xv = reinterpret_cast<const td_u32x4*>(xq);
-#pragma unroll 2
-        for (int v = lane; v < nv; v += TD_WAVE) {
-            td_u32x4 w[R];
-#pragma unroll
-            for (int i = 0; i < R; ++i)
-                w[i] = rows[i] ? td_load_stream16(reinterpret_cast<const td_u32x4*>(rows[i]) + v)
-                               : td_u32x4{0, 0, 0, 0};
-            const td_u32x4 xx = xv[v];
-#pragma unroll
-            for (int i = 0; i < R; ++i) {
-                acc[i] = __builtin_amdgcn_sdot4((int)w[i].x, (int)xx.x, acc[i], false);
-                acc[i] = __builtin_amdgcn_sdot4((int)w[i].y, (int)xx.y, acc[i], false);
-                acc[i] = __builtin_amdgcn_sdot4((int)w[i].z, (int)xx.z, acc[i], false);
-                acc[i] = __builtin_amdgcn_sdot4((int)w[i].w, (int)xx.w, acc[i], false);
-            }
-        }
-    } else {
-        for (int k = lane; k < n; k += TD_WAVE) {
-            const int xx = xq[k];
-#pragma unroll
-            for (int i = 0; i < R; ++i)
-                if (rows[i]) acc[i] += (int)rows[i][k] * xx;
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < R; ++i) out[i] = td_wave_sum_i(acc[i]);
-}
 
 // ------------------------------------------------------------ token staging
 // Copies x (d values) into LDS; returns max|x_k| over the block (all threads).
@@ -140,20 +38,6 @@ __device__ __forceinline__ float stage_token(const T* __restrict__ x, T* xs, int
 #pragma unroll
     for (int w = 1; w < kWaves; ++w) r = fmaxf(r, red[w]);
     return r;
-}
-
-// Exponent of the token's power-of-two quantisation step: floor(log2 m) - 6.
-__device__ __forceinline__ int token_exponent(float m) {
-    if (!(m > 0.0f)) return 0;
-    int ex;
-    (void)frexpf(m, &ex);  // m = f * 2^ex, 0.5 <= f < 1
-    return ex - 1 - 6;
-}
-
-__device__ __forceinline__ int8_t quantize_value(float v, int e) {
-    float q = rintf(ldexpf(v, -e));
-    q = fminf(fmaxf(q, -127.0f), 127.0f);
-    return (int8_t)(int)q;
 }
 
 // ----------------------------------------------- folded product + predictor
@@ -333,6 +217,13 @@ tardis_status_t forward_t(tardis_layer_s* L, const void* xv, int64_t n, void* yv
     const int gemv_blocks = div_up(d, kWaves * kGemvRowsPerWave);
     const int pred_blocks = div_up(h, 32);
     const int fix_blocks = 256;
+    if (L->use_fused) {
+        for (int64_t t = 0; t < n; ++t)
+            TD_TRY(td_decode_fused(L, static_cast<const T*>(xv) + t * d, static_cast<T*>(yv) + t * d,
+                                   L->yacc + t * d, L->mask + t * L->mask_words, s));
+        L->last_n = n;
+        return TARDIS_OK;
+    }
     // (a fill kernel, not a memset node, so that the call can be captured in a graph)
     hipLaunchKernelGGL(zero_i32_kernel, dim3(div_up(n, kBlock)), dim3(kBlock), 0, s, L->counts, (int)n);
     for (int64_t t = 0; t < n; ++t) {

@@ -26,6 +26,7 @@ evaluated on):
 """
 from __future__ import annotations
 
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 
 import numpy as np
@@ -33,22 +34,35 @@ import numpy as np
 BASE_SEED = 20250110
 
 
+def _round_chunk_bf16(u: np.ndarray) -> None:
+    """In place on the uint32 bit patterns: nearest bfloat16, ties to even."""
+    nan = (u & np.uint32(0x7FFFFFFF)) > np.uint32(0x7F800000)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    u += lsb
+    u += np.uint32(0x7FFF)
+    u &= np.uint32(0xFFFF0000)
+    if nan.any():
+        u[nan] |= np.uint32(0x7FC00000)
+
+
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
     """Round float32 values to the nearest bfloat16 (ties to even); result is
     float32 holding bf16-representable values."""
-    x = np.ascontiguousarray(x, dtype=np.float32)
-    u = x.view(np.uint32)
-    bias = np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
-    r = (u + bias) & np.uint32(0xFFFF0000)
-    # keep NaN/Inf bit patterns untouched in the exponent-all-ones case
-    special = (u & np.uint32(0x7F800000)) == np.uint32(0x7F800000)
-    r = np.where(special, u & np.uint32(0xFFFF0000), r)
-    return r.astype(np.uint32).view(np.float32).reshape(x.shape)
+    out = np.array(x, dtype=np.float32, order="C", copy=True)
+    u = out.reshape(-1).view(np.uint32)
+    n = u.shape[0]
+    step = 1 << 22
+    if n <= step:
+        _round_chunk_bf16(u)
+    else:
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            list(ex.map(lambda i: _round_chunk_bf16(u[i:i + step]), range(0, n, step)))
+    return out
 
 
-def _rng(seed: int, stream: int) -> np.random.Generator:
-    # Philox is counter based: (seed, stream) selects an independent sequence.
-    return np.random.Generator(np.random.Philox(key=[seed, stream]))
+def _rng(seed: int, stream: int, chunk: int = 0) -> np.random.Generator:
+    # Philox is counter based: (seed, stream, chunk) selects an independent sequence.
+    return np.random.Generator(np.random.Philox(key=[seed, (stream << 32) | chunk]))
 
 
 def _store(x: np.ndarray, dtype: str) -> np.ndarray:
@@ -60,13 +74,32 @@ def _store(x: np.ndarray, dtype: str) -> np.ndarray:
     raise ValueError(f"unknown storage dtype {dtype!r}")
 
 
+_CHUNK = 1 << 22          # elements per independently keyed chunk
+_POOL_THREADS = 8
+
+
 def normal(seed: int, stream: int, shape, std: float = 1.0, dtype: str = "f32") -> np.ndarray:
-    """N(0, std^2) samples of the given shape in the given storage dtype."""
-    g = _rng(seed, stream)
-    x = g.standard_normal(size=shape, dtype=np.float32)
-    if std != 1.0:
-        x *= np.float32(std)
-    return _store(x, dtype)
+    """N(0, std^2) samples of the given shape in the given storage dtype.  The
+    flat array is filled in fixed-size chunks, chunk i from the Philox sequence
+    keyed (seed, stream, i), so the values do not depend on how many threads
+    fill them."""
+    n = int(np.prod(shape))
+    flat = np.empty(n, np.float32)
+    nchunks = (n + _CHUNK - 1) // _CHUNK
+
+    def fill(i):
+        lo, hi = i * _CHUNK, min(n, (i + 1) * _CHUNK)
+        _rng(seed, stream, i).standard_normal(size=hi - lo, dtype=np.float32, out=flat[lo:hi])
+        if std != 1.0:
+            flat[lo:hi] *= np.float32(std)
+
+    if nchunks <= 1:
+        for i in range(nchunks):
+            fill(i)
+    else:
+        with ThreadPoolExecutor(max_workers=_POOL_THREADS) as ex:
+            list(ex.map(fill, range(nchunks)))
+    return _store(flat.reshape(shape), dtype)
 
 
 @dataclass
