@@ -49,7 +49,7 @@ int env_int(const char* name, int fallback, int lo, int hi) {
 void free_layer(tardis_layer_s* L) {
     if (!L) return;
     void* owned[] = {L->W2T, L->W2, L->Wp, L->bp, L->Q, L->tlo, L->thi, L->a, L->c,
-                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix};
+                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix, L->zeros_h};
     for (void* p : owned)
         if (p) (void)hipFree(p);
     delete L;
@@ -84,11 +84,13 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     TD_TRY(dev_alloc(&L->counts, nb * 4));
     TD_TRY(dev_alloc(&L->list, nb * h * 4));
     TD_TRY(dev_alloc(reinterpret_cast<char**>(&L->hidden), nb * h * es));
+    TD_TRY(dev_alloc(reinterpret_cast<char**>(&L->zeros_h), (size_t)h * es));
+    TD_HIP(hipMemsetAsync(L->zeros_h, 0, (size_t)h * es, s));
     TD_TRY(dev_alloc(&L->sync, 256));
     TD_HIP(hipMemsetAsync(L->sync, 0, 256, s));
-    L->dec_blocks = env_int("TARDIS_DECODE_BLOCKS", 256, 1, 4096);
-    L->dec_copies = env_int("TARDIS_DECODE_COPIES", 8, 1, 64);
-    L->dec_debug = env_int("TARDIS_DECODE_DEBUG", 0, 0, 255);
+    L->dec_threads = env_int("TARDIS_DECODE_THREADS", 1024, 512, 1024) == 512 ? 512 : 1024;
+    L->dec_blocks = env_int("TARDIS_DECODE_BLOCKS", L->dec_threads == 512 ? 512 : 256, 1, 4096);
+    L->dec_copies = env_int("TARDIS_DECODE_COPIES", 2, 1, 4);
     TD_TRY(dev_alloc(&L->yfix, (size_t)L->dec_copies * d * 4));
     TD_HIP(hipMemsetAsync(L->yfix, 0, (size_t)L->dec_copies * d * 4, s));
     L->use_fused = env_int("TARDIS_DECODE_FUSED", 1, 0, 1) && td_decode_fused_supported(L);

@@ -52,10 +52,11 @@ struct tardis_layer_s {
     int32_t* list;     // max_batch x h flagged indices
     float* hidden;     // max_batch x h activations for the dense baseline
     int32_t* sync;     // small block of device counters (zero between calls)
+    void* zeros_h;     // h zero elements of the layer dtype (stands in for a missing b1)
     float* yfix;       // dec_copies x d fp32 repair accumulators of the fused decode kernel (zero between calls)
     int32_t dec_blocks;   // grid of the fused decode kernel
+    int32_t dec_threads;  // block size of the fused decode kernel (512 or 1024)
     int32_t dec_copies;   // number of repair accumulator copies
-    int32_t dec_debug;    // phase-skipping bits for timing experiments (0 in normal use)
     int32_t use_fused;    // fused single-launch decode path available for this layer
     int64_t last_n;    // token count of the most recent online call
 };

@@ -22,6 +22,7 @@
 namespace {
 
 constexpr int kMaxNeuronsPerBlock = 512;
+constexpr int kMaxCopies = 4;                  // repair accumulator copies (blocks spread over them)
 
 __device__ __forceinline__ float load_coherent(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -42,9 +43,9 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                     const bf16_t* __restrict__ b1, const bf16_t* __restrict__ W2T, const float* __restrict__ a,
                     const float* __restrict__ c, const bf16_t* __restrict__ x, bf16_t* __restrict__ y,
                     float* __restrict__ yfold, float* __restrict__ yfix, int copies, uint32_t* __restrict__ mask,
-                    int32_t* __restrict__ done, int h, int npb, int rpb, int act, int dbg) {
+                    int32_t* __restrict__ done, int h, int npb, int rpb, int act) {
     static_assert(D % 1024 == 0, "rows must be whole multiples of 64 lanes x 16 bytes");
-    static_assert(D % BLOCK == 0 && BLOCK / TD_WAVE >= 8, "column ownership of the repair pass");
+    static_assert(D % BLOCK == 0 && BLOCK / TD_WAVE >= 4, "column ownership of the repair pass");
     constexpr int NW = BLOCK / TD_WAVE;
     constexpr int NVW = D / 8;                       // 16-byte vectors per bf16 row
     constexpr int IQ = D / 16 / TD_WAVE;             // per-lane vectors of an int8 row
@@ -67,19 +68,25 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     const int j0 = blk * npb;                        // first neuron of this block
     const int jn = min(npb, h - j0);                 // neurons owned (may be <= 0)
 
-    // ---- the token first (small), then the first batch of predictor rows, all in flight together
+    // ---- the token first (small), then the first batch of predictor rows and their range
+    //      bounds, all in flight together
     td_u32x4 xv[XI];
 #pragma unroll
     for (int it = 0; it < XI; ++it) {
         const int v = min(it * BLOCK + tid, NVW - 1);
         xv[it] = reinterpret_cast<const td_u32x4*>(x)[v];
     }
+    asm volatile("" ::: "memory");                   // keep the token's load ahead of the row loads
     td_u32x4 q[RQ][IQ];
+    float tl[RQ], th[RQ];
 #pragma unroll
     for (int i = 0; i < RQ; ++i) {   // rows past the end re-read a valid row; their result is ignored
         const int j = min(j0 + wave * RQ + i, h - 1);
         load_row<IQ>(q[i], Q + (size_t)j * D, lane);
+        tl[i] = tlo[j];
+        th[i] = thi[j];
     }
+    const float bias_out = bp[min(blk * rpb + wave, D - 1)];
 
     // ---- stage the token, its max and its int8 code
     if (tid < kMaxNeuronsPerBlock / 32) words[tid] = 0u;
@@ -120,11 +127,16 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
 
     // ---- predictor rows: exact int32 dot products, range test, block-local list
     const td_u32x4* xq4 = reinterpret_cast<const td_u32x4*>(xq) + lane;
-    for (int base = 0; base < ((dbg & 8) ? 0 : jn); base += NW * RQ) {
+    for (int base = 0; base < jn; base += NW * RQ) {
         const int jb = base + wave * RQ;
         if (base > 0) {
 #pragma unroll
-            for (int i = 0; i < RQ; ++i) load_row<IQ>(q[i], Q + (size_t)min(j0 + jb + i, h - 1) * D, lane);
+            for (int i = 0; i < RQ; ++i) {
+                const int j = min(j0 + jb + i, h - 1);
+                load_row<IQ>(q[i], Q + (size_t)j * D, lane);
+                tl[i] = tlo[j];
+                th[i] = thi[j];
+            }
         }
         int acc[RQ];
 #pragma unroll
@@ -146,7 +158,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
             const int jl = jb + i;
             if (jl < jn && lane == 0) {
                 const float v = ldexpf((float)s, e);
-                const bool inside = (v >= tlo[j0 + jl]) && (v < thi[j0 + jl]);
+                const bool inside = (v >= tl[i]) && (v < th[i]);
                 if (!inside) {
                     const int pos = atomicAdd(&nflag, 1);
                     flist[pos] = j0 + jl;
@@ -156,17 +168,15 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
         }
     }
 
-    // ---- request this wave's first row of the speculative product now; it is consumed
-    //      after the repair so that its latency hides the repair's dependent loads
     const td_u32x4* xs4 = reinterpret_cast<const td_u32x4*>(xs) + lane;
     const int r0 = blk * rpb;
-    const int rn = (dbg & 4) ? 0 : min(rpb, D - r0);  // W' rows owned (may be <= 0)
+    const int rn = min(rpb, D - r0);                 // W' rows owned (may be <= 0)
     td_u32x4 wp[IW];
-    load_row<IW>(wp, Wp + (size_t)min(r0 + wave, D - 1) * D, lane);
+    const void* wp_row = Wp + (size_t)min(r0 + wave, D - 1) * D;
 
     __syncthreads();
     if (jn > 0 && tid < (jn + 31) / 32) mask[(j0 >> 5) + tid] = words[tid];
-    const int nf = (dbg & 1) ? 0 : nflag;
+    const int nf = nflag;
 
     // ---- result fixing.  z_j and delta_j: one wavefront per flagged neuron (16-byte loads of
     //      W1[j], shuffle reduction).  y += delta_j * W2[:, j]: every thread owns the output
@@ -174,19 +184,24 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     //      wavefront reads 128 contiguous bytes), so the block's repair vector lives in
     //      registers and needs no LDS traffic.
     constexpr int CPT = D / BLOCK;                   // output columns per thread
-    constexpr int FCH = 8;                           // flagged neurons per pass
+    constexpr int FCH = (24 / CPT) < NW ? (24 / CPT) : NW;  // flagged neurons per pass (24 row registers)
     float yacc[CPT];
 #pragma unroll
     for (int u = 0; u < CPT; ++u) yacc[u] = 0.0f;
+    if (nf == 0) load_row<IW>(wp, wp_row, lane);
     for (int f0 = 0; f0 < nf; f0 += FCH) {
         asm volatile("" ::: "memory");   // re-read the token from LDS here instead of keeping it in registers
         const int fi = f0 + wave;
         const bool fixer = wave < FCH && fi < nf;
         td_u32x4 w1[IW];
         int jz = 0;
+        float aj = 0.0f, cj = 0.0f, bj = 0.0f;
         if (fixer) {
             jz = flist[fi];
             load_row<IW>(w1, W1 + (size_t)jz * D, lane);
+            aj = a[jz];
+            cj = c[jz];
+            bj = td_bf16_to_f32(b1[jz]);                // b1 is never null here (zeros if the layer has no bias)
         }
         uint16_t w2[FCH][CPT];                       // requested before z is known: one round trip in all
 #pragma unroll
@@ -196,13 +211,20 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
 #pragma unroll
             for (int u = 0; u < CPT; ++u) w2[i][u] = __builtin_nontemporal_load(row + u * BLOCK);
         }
+        // this wave's first row of the speculative product is requested BEHIND the repair's loads
+        // (loads return in order) and consumed after the repair, so that it streams in while the
+        // repair's dependent steps run
+        if (f0 == 0) {
+            asm volatile("" ::: "memory");
+            load_row<IW>(wp, wp_row, lane);
+        }
         if (fixer) {
             float z = 0.0f;
 #pragma unroll
             for (int it = 0; it < IW; ++it) z = RowVec<bf16_t>::dot(w1[it], xs4[it * TD_WAVE], z);
             z = td_wave_sum(z);
-            if (b1) z += td_bf16_to_f32(b1[jz]);
-            if (lane == 0) dl[wave] = td_act(z, act) - fmaf(a[jz], z, c[jz]);
+            z += bj;
+            if (lane == 0) dl[wave] = td_act(z, act) - fmaf(aj, z, cj);
         }
         __syncthreads();
 #pragma unroll
@@ -215,7 +237,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     }
 
     // ---- one coalesced atomic pass per block into an accumulator copy (fire and forget)
-    if (nf > 0 && !(dbg & 2)) {
+    if (nf > 0) {
         float* dst = yfix + (size_t)(blk % copies) * D + tid;
 #pragma unroll
         for (int u = 0; u < CPT; ++u)
@@ -232,7 +254,8 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
         s = td_wave_sum(s);
         // written through to memory so that the finishing block, on any XCD, reads it
         if (lane == 0)
-            __hip_atomic_store(yfold + r0 + ri, s + bp[r0 + ri], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(yfold + r0 + ri, s + (ri == wave ? bias_out : bp[r0 + ri]), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
     }
 
     // ---- signal completion; every store and atomic of this block has been acknowledged
@@ -242,17 +265,23 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     if (tid == 0)
         is_last = (__hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1);
     __syncthreads();
-    if (!is_last || (dbg & 16)) { if (is_last && tid == 0) __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); return; }
+    if (!is_last) return;
 
     // ---- the last block to finish assembles y and re-arms the scratch
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     typedef float f32x4 __attribute__((ext_vector_type(4)));
     for (int k4 = tid; k4 < D / 4; k4 += BLOCK) {
         f32x4 v = reinterpret_cast<const f32x4*>(yfold)[k4];
-        for (int cidx = 0; cidx < copies; ++cidx) {
-            f32x4* src = reinterpret_cast<f32x4*>(yfix + (size_t)cidx * D) + k4;
-            v += *src;
-            *src = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        f32x4 part[kMaxCopies];
+#pragma unroll
+        for (int cidx = 0; cidx < kMaxCopies; ++cidx)      // all copies requested before any is used
+            part[cidx] = cidx < copies ? reinterpret_cast<const f32x4*>(yfix + (size_t)cidx * D)[k4]
+                                       : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int cidx = 0; cidx < kMaxCopies; ++cidx) {
+            v += part[cidx];
+            if (cidx < copies)
+                reinterpret_cast<f32x4*>(yfix + (size_t)cidx * D)[k4] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         }
         uint2 o;
         o.x = (uint32_t)td_f32_to_bf16(v.x) | ((uint32_t)td_f32_to_bf16(v.y) << 16);
@@ -306,10 +335,10 @@ mask_to_list_kernel(const uint32_t* __restrict__ mask, int words, int h, int32_t
     if (threadIdx.x == 0 && counts) counts[t] = carry;
 }
 
-template <int D>
+template <int D, int BLOCK>
 tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
                               hipStream_t s) {
-    constexpr int BLOCK = 1024, RQ = 4;
+    constexpr int RQ = 4;
     const int G = L->dec_blocks;
     const int h = (int)L->h;
     int npb = (h + G - 1) / G;
@@ -317,10 +346,10 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
     const int rpb = (D + G - 1) / G;
     hipLaunchKernelGGL((decode_fused_kernel<D, BLOCK, RQ>), dim3(G), dim3(BLOCK), 0, s,
                        static_cast<const bf16_t*>(L->Wp), L->bp, L->Q, L->tlo, L->thi,
-                       static_cast<const bf16_t*>(L->W1), static_cast<const bf16_t*>(L->b1),
-                       static_cast<const bf16_t*>(L->W2T), L->a, L->c, static_cast<const bf16_t*>(x),
+                       static_cast<const bf16_t*>(L->W1),
+                       static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), static_cast<const bf16_t*>(L->W2T), L->a, L->c, static_cast<const bf16_t*>(x),
                        static_cast<bf16_t*>(y), yfold, L->yfix, L->dec_copies, mask, L->sync, h, npb, rpb,
-                       (int)L->act, L->dec_debug);
+                       (int)L->act);
     TD_HIP(hipGetLastError());
     return TARDIS_OK;
 }
@@ -339,10 +368,17 @@ bool td_decode_fused_supported(const tardis_layer_s* L) {
 
 tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
                                 hipStream_t s) {
+    if (L->dec_threads == 512) {
+        switch (L->d) {
+            case 1024: return launch_decode<1024, 512>(L, x, y, yfold, mask, s);
+            case 2048: return launch_decode<2048, 512>(L, x, y, yfold, mask, s);
+            case 4096: return launch_decode<4096, 512>(L, x, y, yfold, mask, s);
+        }
+    }
     switch (L->d) {
-        case 1024: return launch_decode<1024>(L, x, y, yfold, mask, s);
-        case 2048: return launch_decode<2048>(L, x, y, yfold, mask, s);
-        case 4096: return launch_decode<4096>(L, x, y, yfold, mask, s);
+        case 1024: return launch_decode<1024, 1024>(L, x, y, yfold, mask, s);
+        case 2048: return launch_decode<2048, 1024>(L, x, y, yfold, mask, s);
+        case 4096: return launch_decode<4096, 1024>(L, x, y, yfold, mask, s);
     }
     return TARDIS_ERR_SHAPE;
 }
