@@ -28,8 +28,8 @@ D, H = 4096, 16384
 TOKENS_PER_STEP = 1024
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of decode_fused_kernel from `rocprofv3 --pmc` (FETCH_SIZE and WRITE_SIZE runs,
-# scaled by a copy kernel of known size); see profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES = None
+# scaled by a copy kernel of known size); see profiles/*hbm-traffic.md.
+MEASURED_TRAFFIC_BYTES = 119069060
 
 
 def algorithmic_bytes(d: int, h: int, p: float) -> float:
@@ -47,6 +47,9 @@ def main() -> int:
     ap.add_argument("--coverage", type=float, default=0.95)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of a replayed HIP graph")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a 1 GiB device copy (known HBM traffic) so that profiler counters can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
@@ -107,19 +110,35 @@ def main() -> int:
             if st != 0:
                 raise RuntimeError(f"forward failed with status {st}")
 
-    def timed(hs, steps, warmup, **kw):
-        for _ in range(warmup):
+    def timed(hs, steps, warmup, graph=False, **kw):
+        """ms per step from HIP events on the launch stream, and host wall ms per step.  With
+        graph=True one step (1024 launches) is captured once and replayed."""
+        run = lambda: step(hs, **kw)
+        if graph:
             step(hs, **kw)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                cs = T._stream(torch.cuda.current_stream())     # the capture stream
+                nl = len(hs)
+                for t in range(TOKENS_PER_STEP):
+                    st = fwd(hs[t % nl], xp[t], yp[t], cs)
+                    if st != 0:
+                        raise RuntimeError(f"forward failed with status {st}")
+            run = g.replay
+        for _ in range(warmup):
+            run()
         torch.cuda.synchronize()
+        s_ = torch.cuda.current_stream()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t0 = time.time()
-        e0.record(stream)
+        e0.record(s_)
         for _ in range(steps):
-            step(hs, **kw)
-        e1.record(stream)
+            run()
+        e1.record(s_)
         torch.cuda.synchronize()
         wall = time.time() - t0
-        return e0.elapsed_time(e1) / steps, wall / steps * 1e3     # ms per step (GPU events, host wall)
+        return e0.elapsed_time(e1) / steps, wall / steps * 1e3
 
     # measured fallback rate of the timed tokens on layer 0
     step(handles[:1])
@@ -131,8 +150,12 @@ def main() -> int:
         rates.append(int(cnt.item()) / H)
     p = float(np.mean(rates))
 
-    cold_ms, cold_wall = timed(handles, args.steps, args.warmup)
-    hot_ms, _ = timed(handles[:1], max(2, args.steps // 2), 1)
+    use_graph = not args.no_graph
+    cold_ms, cold_wall = timed(handles, args.steps, args.warmup, graph=use_graph)
+    hot_ms, _ = timed(handles[:1], max(2, args.steps // 2), 1, graph=use_graph)
+    stream_ms = None
+    if use_graph:
+        stream_ms, _ = timed(handles, max(2, args.steps // 4), 1)
     res_dense = {}
     if not args.no_dense:
         dms, _ = timed(handles, max(2, args.steps // 4), 1, fn=dense, dense_call=True)
@@ -202,6 +225,8 @@ def main() -> int:
         "cpu_baseline": cpu,
         "hot": {"tokens_per_s": TOKENS_PER_STEP / (hot_ms * 1e-3),
                 "GBs": bytes_tok / (hot_ms * 1e-3 / TOKENS_PER_STEP) / 1e9},
+        "launch_mode": "hip graph replay (one graph = one 1024-token step)" if use_graph else "stream",
+        "stream_launch_tokens_per_s": (TOKENS_PER_STEP / (stream_ms * 1e-3)) if stream_ms else None,
         "host_wall_ms_per_step": cold_wall,
         "offline": offline,
         "setup_s": time.time() - t_setup,
@@ -209,6 +234,13 @@ def main() -> int:
     out.update(res_dense)
     if res_dense:
         out["speedup_vs_dense_own"] = tok_s / res_dense["dense_own_tokens_per_s"]
+    if args.copy_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_probe"] = "3 x torch copy_ of 1 GiB (reads 1 GiB, writes 1 GiB each)"
     print(json.dumps(out))
     for L in layers:
         L.close()

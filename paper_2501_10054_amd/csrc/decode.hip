@@ -172,7 +172,12 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     const int r0 = blk * rpb;
     const int rn = min(rpb, D - r0);                 // W' rows owned (may be <= 0)
     td_u32x4 wp[IW];
-    const void* wp_row = Wp + (size_t)min(r0 + wave, D - 1) * D;
+    const td_u32x4* wp_row = reinterpret_cast<const td_u32x4*>(Wp + (size_t)min(r0 + wave, D - 1) * D) + lane;
+    // first half of this wave's W' row: requested before the block meets at the barrier, so that
+    // the memory pipe stays busy while the flagged list is assembled
+    constexpr int IWA = IW / 2;
+#pragma unroll
+    for (int it = 0; it < IWA; ++it) wp[it] = td_load_stream16(wp_row + it * TD_WAVE);
 
     __syncthreads();
     if (jn > 0 && tid < (jn + 31) / 32) mask[(j0 >> 5) + tid] = words[tid];
@@ -188,7 +193,10 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     float yacc[CPT];
 #pragma unroll
     for (int u = 0; u < CPT; ++u) yacc[u] = 0.0f;
-    if (nf == 0) load_row<IW>(wp, wp_row, lane);
+    if (nf == 0) {
+#pragma unroll
+        for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * TD_WAVE);
+    }
     for (int f0 = 0; f0 < nf; f0 += FCH) {
         asm volatile("" ::: "memory");   // re-read the token from LDS here instead of keeping it in registers
         const int fi = f0 + wave;
@@ -211,12 +219,13 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
 #pragma unroll
             for (int u = 0; u < CPT; ++u) w2[i][u] = __builtin_nontemporal_load(row + u * BLOCK);
         }
-        // this wave's first row of the speculative product is requested BEHIND the repair's loads
-        // (loads return in order) and consumed after the repair, so that it streams in while the
+        // the second half of this wave's W' row is requested BEHIND the repair's loads (loads
+        // return in order) and consumed after the repair, so that it streams in while the
         // repair's dependent steps run
         if (f0 == 0) {
             asm volatile("" ::: "memory");
-            load_row<IW>(wp, wp_row, lane);
+#pragma unroll
+            for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * TD_WAVE);
         }
         if (fixer) {
             float z = 0.0f;
