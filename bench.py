@@ -195,7 +195,7 @@ def main() -> int:
             cores = os.cpu_count() or 1
         lay = w0.layer
         F = O.build(lay.W1, None, lay.W2, None, *(t.cpu().numpy() for t in cal0))
-        ns = 12
+        ns = 160
         t0 = time.time()
         O.forward(F, w0.X_test[:ns])
         dt = time.time() - t0
