@@ -147,6 +147,17 @@ tardis_status_t tardis_ffn_forward(tardis_handle_t L, const void* x, void* y, vo
 tardis_status_t tardis_ffn_forward_batched(tardis_handle_t L, const void* x, int64_t n, void* y,
                                            void* stream);
 
+/* A stack of folded layers of equal width d and dtype (FFN blocks chained
+ * without attention; the glue is this library's choice, the paper has none):
+ *     x_0 = x,  y_l = layer_l(x_l),  x_{l+1} = y_l / sqrt(mean(y_l^2) + 1e-6)
+ * per token, unit gain, no residual; the normalised activation is rounded to
+ * the layer dtype.  y receives the last layer's (un-normalised) output.
+ * `layers` is a HOST array of n_layers distinct handles; each layer's predictor
+ * output stays readable through tardis_get_last_outliers on its handle.
+ * 1 <= n <= every layer's max_batch.  x, y: n x d. */
+tardis_status_t tardis_stack_forward(const tardis_handle_t* layers, int32_t n_layers, const void* x,
+                                     int64_t n, void* y, void* stream);
+
 /* The unmodified FFN, y = W2 sigma(W1 x + b1) + b2, on the same streaming
  * kernels: the dense baseline the folded path is measured against.
  * 1 <= n <= max_batch.  x, y: n x d. */
@@ -172,6 +183,11 @@ tardis_status_t tardis_get_predictor_state(tardis_handle_t L, int8_t* Q, float* 
  * n must equal the token count of that call. */
 tardis_status_t tardis_get_last_outliers(tardis_handle_t L, int64_t n, uint32_t* mask,
                                          int32_t* counts, int32_t* list, void* stream);
+
+/* The normalised activation this layer handed to the next one in the most
+ * recent tardis_stack_forward (n x d, layer dtype; stream-ordered copy).  Only
+ * meaningful for a layer that was not last in that stack. */
+tardis_status_t tardis_get_handover(tardis_handle_t L, int64_t n, void* out, void* stream);
 
 /* Frees everything the handle owns.  The caller must have synchronised every
  * stream that used it.  NULL is accepted. */

@@ -49,7 +49,7 @@ int env_int(const char* name, int fallback, int lo, int hi) {
 void free_layer(tardis_layer_s* L) {
     if (!L) return;
     void* owned[] = {L->W2T, L->W2, L->Wp, L->bp, L->Q, L->tlo, L->thi, L->a, L->c,
-                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix, L->zeros_h};
+                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix, L->zeros_h, L->xnext};
     for (void* p : owned)
         if (p) (void)hipFree(p);
     delete L;
@@ -86,6 +86,7 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     TD_TRY(dev_alloc(reinterpret_cast<char**>(&L->hidden), nb * h * es));
     TD_TRY(dev_alloc(reinterpret_cast<char**>(&L->zeros_h), (size_t)h * es));
     TD_HIP(hipMemsetAsync(L->zeros_h, 0, (size_t)h * es, s));
+    TD_TRY(dev_alloc(reinterpret_cast<char**>(&L->xnext), nb * d * es));
     TD_TRY(dev_alloc(&L->sync, 256));
     TD_HIP(hipMemsetAsync(L->sync, 0, 256, s));
     L->dec_threads = env_int("TARDIS_DECODE_THREADS", 1024, 512, 1024) == 512 ? 512 : 1024;
@@ -155,7 +156,29 @@ tardis_status_t tardis_ffn_forward_batched(tardis_handle_t L, const void* x, int
     if (!L) return TARDIS_ERR_STATE;
     if (!x || !y || x == y) return TARDIS_ERR_INVALID_ARG;
     if (n < 1 || n > L->max_batch) return TARDIS_ERR_SHAPE;
-    return td_forward(L, x, n, y, static_cast<hipStream_t>(stream));
+    return td_forward(L, x, n, y, 0, static_cast<hipStream_t>(stream));
+}
+
+tardis_status_t tardis_stack_forward(const tardis_handle_t* layers, int32_t n_layers, const void* x, int64_t n,
+                                     void* y, void* stream) {
+    if (!layers || n_layers < 1 || n_layers > 4096) return TARDIS_ERR_INVALID_ARG;
+    if (!x || !y || x == y) return TARDIS_ERR_INVALID_ARG;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        if (!layers[l]) return TARDIS_ERR_STATE;
+        if (layers[l]->d != layers[0]->d || layers[l]->dtype != layers[0]->dtype) return TARDIS_ERR_SHAPE;
+        if (n < 1 || n > layers[l]->max_batch) return TARDIS_ERR_SHAPE;
+        for (int32_t m = 0; m < l; ++m)
+            if (layers[m] == layers[l]) return TARDIS_ERR_INVALID_ARG;   // each handle owns its hand-over buffer
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const void* cur = x;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const bool last = l == n_layers - 1;
+        void* out = last ? y : layers[l]->xnext;
+        TD_TRY(td_forward(layers[l], cur, n, out, last ? 0 : 1, s));
+        cur = out;
+    }
+    return TARDIS_OK;
 }
 
 tardis_status_t tardis_dense_forward(tardis_handle_t L, const void* x, int64_t n, void* y, void* stream) {
@@ -190,6 +213,15 @@ tardis_status_t tardis_get_last_outliers(tardis_handle_t L, int64_t n, uint32_t*
     const size_t nn = (size_t)n;
     if (mask) TD_HIP(hipMemcpyAsync(mask, L->mask, nn * L->mask_words * 4, hipMemcpyDeviceToDevice, s));
     if (counts || list) TD_TRY(td_mask_to_list(L, n, counts, list, s));   // derived from the mask words
+    return TARDIS_OK;
+}
+
+tardis_status_t tardis_get_handover(tardis_handle_t L, int64_t n, void* out, void* stream) {
+    if (!L) return TARDIS_ERR_STATE;
+    if (!out) return TARDIS_ERR_INVALID_ARG;
+    if (n < 1 || n > L->max_batch) return TARDIS_ERR_SHAPE;
+    TD_HIP(hipMemcpyAsync(out, L->xnext, (size_t)n * L->d * td_elem_size(L->dtype), hipMemcpyDeviceToDevice,
+                          static_cast<hipStream_t>(stream)));
     return TARDIS_OK;
 }
 

@@ -12,6 +12,8 @@ typedef unsigned int td_u32x4 __attribute__((ext_vector_type(4)));  // one 16-by
 
 #define TD_WAVE 64
 
+constexpr float kRmsEps = 1e-6f;
+
 #define TD_HIP(expr)                                                              \
     do {                                                                          \
         hipError_t e__ = (expr);                                                  \
@@ -53,6 +55,7 @@ struct tardis_layer_s {
     float* hidden;     // max_batch x h activations for the dense baseline
     int32_t* sync;     // small block of device counters (zero between calls)
     void* zeros_h;     // h zero elements of the layer dtype (stands in for a missing b1)
+    void* xnext;       // max_batch x d, layer dtype: normalised output handed to the next stacked layer
     float* yfix;       // dec_copies x d fp32 repair accumulators of the fused decode kernel (zero between calls)
     int32_t dec_blocks;   // grid of the fused decode kernel
     int32_t dec_threads;  // block size of the fused decode kernel (512 or 1024)
@@ -154,8 +157,9 @@ tardis_status_t td_gemm_nt(const void* A, const void* B, float* C, int64_t M, in
 // decode.hip
 bool td_decode_fused_supported(const tardis_layer_s* L);
 tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
-                                hipStream_t s);
+                                int norm_out, hipStream_t s);
 tardis_status_t td_mask_to_list(const tardis_layer_s* L, int64_t n, int32_t* counts, int32_t* list, hipStream_t s);
 // forward.hip
-tardis_status_t td_forward(tardis_layer_s* L, const void* x, int64_t n, void* y, hipStream_t s);
+// norm_out != 0: the output is y / sqrt(mean(y^2) + kRmsEps) per token (glue between stacked layers)
+tardis_status_t td_forward(tardis_layer_s* L, const void* x, int64_t n, void* y, int norm_out, hipStream_t s);
 tardis_status_t td_dense_forward(tardis_layer_s* L, const void* x, int64_t n, void* y, hipStream_t s);

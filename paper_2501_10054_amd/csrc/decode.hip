@@ -43,7 +43,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                     const bf16_t* __restrict__ b1, const bf16_t* __restrict__ W2T, const float* __restrict__ a,
                     const float* __restrict__ c, const bf16_t* __restrict__ x, bf16_t* __restrict__ y,
                     float* __restrict__ yfold, float* __restrict__ yfix, int copies, uint32_t* __restrict__ mask,
-                    int32_t* __restrict__ done, int h, int npb, int rpb, int act) {
+                    int32_t* __restrict__ done, int h, int npb, int rpb, int act, int norm_out, float eps) {
     static_assert(D % 1024 == 0, "rows must be whole multiples of 64 lanes x 16 bytes");
     static_assert(D % BLOCK == 0 && BLOCK / TD_WAVE >= 4, "column ownership of the repair pass");
     constexpr int NW = BLOCK / TD_WAVE;
@@ -279,23 +279,50 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     // ---- the last block to finish assembles y and re-arms the scratch
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     typedef float f32x4 __attribute__((ext_vector_type(4)));
-    for (int k4 = tid; k4 < D / 4; k4 += BLOCK) {
-        f32x4 v = reinterpret_cast<const f32x4*>(yfold)[k4];
-        f32x4 part[kMaxCopies];
+    constexpr int OI = (D / 4 + BLOCK - 1) / BLOCK;   // float4 pieces of y per thread
+    f32x4 out[OI];
+    float ss = 0.0f;
 #pragma unroll
-        for (int cidx = 0; cidx < kMaxCopies; ++cidx)      // all copies requested before any is used
-            part[cidx] = cidx < copies ? reinterpret_cast<const f32x4*>(yfix + (size_t)cidx * D)[k4]
-                                       : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int oi = 0; oi < OI; ++oi) {
+        const int k4 = oi * BLOCK + tid;
+        f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (k4 < D / 4) {
+            v = reinterpret_cast<const f32x4*>(yfold)[k4];
+            f32x4 part[kMaxCopies];
 #pragma unroll
-        for (int cidx = 0; cidx < kMaxCopies; ++cidx) {
-            v += part[cidx];
-            if (cidx < copies)
-                reinterpret_cast<f32x4*>(yfix + (size_t)cidx * D)[k4] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            for (int cidx = 0; cidx < kMaxCopies; ++cidx)      // all copies requested before any is used
+                part[cidx] = cidx < copies ? reinterpret_cast<const f32x4*>(yfix + (size_t)cidx * D)[k4]
+                                           : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int cidx = 0; cidx < kMaxCopies; ++cidx) {
+                v += part[cidx];
+                if (cidx < copies)
+                    reinterpret_cast<f32x4*>(yfix + (size_t)cidx * D)[k4] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            }
         }
-        uint2 o;
-        o.x = (uint32_t)td_f32_to_bf16(v.x) | ((uint32_t)td_f32_to_bf16(v.y) << 16);
-        o.y = (uint32_t)td_f32_to_bf16(v.z) | ((uint32_t)td_f32_to_bf16(v.w) << 16);
-        reinterpret_cast<uint2*>(y)[k4] = o;
+        out[oi] = v;
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+    float scale = 1.0f;
+    if (norm_out) {   // y / sqrt(mean(y^2) + eps): the glue between stacked layers
+        ss = td_wave_sum(ss);
+        if (lane == 0) red[wave] = ss;
+        __syncthreads();
+        float tot = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) tot += red[w];
+        scale = 1.0f / sqrtf(tot / (float)D + eps);
+    }
+#pragma unroll
+    for (int oi = 0; oi < OI; ++oi) {
+        const int k4 = oi * BLOCK + tid;
+        if (k4 < D / 4) {
+            const f32x4 v = out[oi] * scale;
+            uint2 o;
+            o.x = (uint32_t)td_f32_to_bf16(v.x) | ((uint32_t)td_f32_to_bf16(v.y) << 16);
+            o.y = (uint32_t)td_f32_to_bf16(v.z) | ((uint32_t)td_f32_to_bf16(v.w) << 16);
+            reinterpret_cast<uint2*>(y)[k4] = o;
+        }
     }
     if (tid == 0) __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -346,7 +373,7 @@ mask_to_list_kernel(const uint32_t* __restrict__ mask, int words, int h, int32_t
 
 template <int D, int BLOCK>
 tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
-                              hipStream_t s) {
+                              int norm_out, hipStream_t s) {
     constexpr int RQ = 4;
     const int G = L->dec_blocks;
     const int h = (int)L->h;
@@ -358,7 +385,7 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
                        static_cast<const bf16_t*>(L->W1),
                        static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), static_cast<const bf16_t*>(L->W2T), L->a, L->c, static_cast<const bf16_t*>(x),
                        static_cast<bf16_t*>(y), yfold, L->yfix, L->dec_copies, mask, L->sync, h, npb, rpb,
-                       (int)L->act);
+                       (int)L->act, norm_out, kRmsEps);
     TD_HIP(hipGetLastError());
     return TARDIS_OK;
 }
@@ -376,18 +403,18 @@ bool td_decode_fused_supported(const tardis_layer_s* L) {
 }
 
 tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
-                                hipStream_t s) {
+                                int norm_out, hipStream_t s) {
     if (L->dec_threads == 512) {
         switch (L->d) {
-            case 1024: return launch_decode<1024, 512>(L, x, y, yfold, mask, s);
-            case 2048: return launch_decode<2048, 512>(L, x, y, yfold, mask, s);
-            case 4096: return launch_decode<4096, 512>(L, x, y, yfold, mask, s);
+            case 1024: return launch_decode<1024, 512>(L, x, y, yfold, mask, norm_out, s);
+            case 2048: return launch_decode<2048, 512>(L, x, y, yfold, mask, norm_out, s);
+            case 4096: return launch_decode<4096, 512>(L, x, y, yfold, mask, norm_out, s);
         }
     }
     switch (L->d) {
-        case 1024: return launch_decode<1024, 1024>(L, x, y, yfold, mask, s);
-        case 2048: return launch_decode<2048, 1024>(L, x, y, yfold, mask, s);
-        case 4096: return launch_decode<4096, 1024>(L, x, y, yfold, mask, s);
+        case 1024: return launch_decode<1024, 1024>(L, x, y, yfold, mask, norm_out, s);
+        case 2048: return launch_decode<2048, 1024>(L, x, y, yfold, mask, norm_out, s);
+        case 4096: return launch_decode<4096, 1024>(L, x, y, yfold, mask, norm_out, s);
     }
     return TARDIS_ERR_SHAPE;
 }

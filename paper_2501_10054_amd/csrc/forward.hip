@@ -165,12 +165,24 @@ __global__ void __launch_bounds__(kBlock) zero_i32_kernel(int32_t* __restrict__ 
     if (i < n) p[i] = 0;
 }
 
-// fp32 accumulator -> output dtype
+// fp32 accumulator -> output dtype (one block; optionally y / sqrt(mean(y^2) + eps))
 template <typename T>
 __global__ void __launch_bounds__(kBlock)
-finish_kernel(const float* __restrict__ yacc, T* __restrict__ y, int d) {
-    const int k = (int)blockIdx.x * kBlock + threadIdx.x;
-    if (k < d) td_store<T>(y + k, yacc[k]);
+finish_kernel(const float* __restrict__ yacc, T* __restrict__ y, int d, int norm_out, float eps) {
+    __shared__ float red[kWaves];
+    float scale = 1.0f;
+    if (norm_out) {
+        float ss = 0.0f;
+        for (int k = threadIdx.x; k < d; k += kBlock) ss += yacc[k] * yacc[k];
+        ss = td_wave_sum(ss);
+        if ((threadIdx.x & (TD_WAVE - 1)) == 0) red[threadIdx.x / TD_WAVE] = ss;
+        __syncthreads();
+        float tot = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) tot += red[w];
+        scale = 1.0f / sqrtf(tot / (float)d + eps);
+    }
+    for (int k = threadIdx.x; k < d; k += kBlock) td_store<T>(y + k, yacc[k] * scale);
 }
 
 // -------------------------------------------------------------- dense FFN
@@ -211,7 +223,7 @@ dense_rows_kernel(const T* __restrict__ W, const T* __restrict__ bias, const T* 
 inline int div_up(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 template <typename T>
-tardis_status_t forward_t(tardis_layer_s* L, const void* xv, int64_t n, void* yv, hipStream_t s) {
+tardis_status_t forward_t(tardis_layer_s* L, const void* xv, int64_t n, void* yv, int norm_out, hipStream_t s) {
     const int d = (int)L->d, h = (int)L->h;
     const size_t xs_bytes = (((size_t)d * sizeof(T) + 15) & ~(size_t)15);
     const int gemv_blocks = div_up(d, kWaves * kGemvRowsPerWave);
@@ -220,7 +232,7 @@ tardis_status_t forward_t(tardis_layer_s* L, const void* xv, int64_t n, void* yv
     if (L->use_fused) {
         for (int64_t t = 0; t < n; ++t)
             TD_TRY(td_decode_fused(L, static_cast<const T*>(xv) + t * d, static_cast<T*>(yv) + t * d,
-                                   L->yacc + t * d, L->mask + t * L->mask_words, s));
+                                   L->yacc + t * d, L->mask + t * L->mask_words, norm_out, s));
         L->last_n = n;
         return TARDIS_OK;
     }
@@ -239,7 +251,7 @@ tardis_status_t forward_t(tardis_layer_s* L, const void* xv, int64_t n, void* yv
         hipLaunchKernelGGL(fix_kernel<T>, dim3(fix_blocks), dim3(kBlock), xs_bytes, s,
                            static_cast<const T*>(L->W1), static_cast<const T*>(L->b1),
                            static_cast<const T*>(L->W2T), L->a, L->c, x, count, list, yacc, d, h, (int)L->act);
-        hipLaunchKernelGGL(finish_kernel<T>, dim3(div_up(d, kBlock)), dim3(kBlock), 0, s, yacc, y, d);
+        hipLaunchKernelGGL(finish_kernel<T>, dim3(1), dim3(kBlock), 0, s, yacc, y, d, norm_out, kRmsEps);
     }
     TD_HIP(hipGetLastError());
     L->last_n = n;
@@ -269,8 +281,9 @@ tardis_status_t dense_t(tardis_layer_s* L, const void* xv, int64_t n, void* yv, 
 
 }  // namespace
 
-tardis_status_t td_forward(tardis_layer_s* L, const void* x, int64_t n, void* y, hipStream_t s) {
-    return L->dtype == TARDIS_BF16 ? forward_t<bf16_t>(L, x, n, y, s) : forward_t<float>(L, x, n, y, s);
+tardis_status_t td_forward(tardis_layer_s* L, const void* x, int64_t n, void* y, int norm_out, hipStream_t s) {
+    return L->dtype == TARDIS_BF16 ? forward_t<bf16_t>(L, x, n, y, norm_out, s)
+                                   : forward_t<float>(L, x, n, y, norm_out, s);
 }
 
 tardis_status_t td_dense_forward(tardis_layer_s* L, const void* x, int64_t n, void* y, hipStream_t s) {

@@ -23,8 +23,8 @@ _DTYPE_CODE = {torch.float32: F32, torch.bfloat16: BF16}
 
 EXPORTS = (
     "tardis_calibrate", "tardis_fold", "tardis_ffn_forward", "tardis_ffn_forward_batched",
-    "tardis_dense_forward", "tardis_get_folded", "tardis_get_predictor_state",
-    "tardis_get_last_outliers", "tardis_destroy", "tardis_status_string", "tardis_version",
+    "tardis_stack_forward", "tardis_dense_forward", "tardis_get_folded", "tardis_get_predictor_state",
+    "tardis_get_last_outliers", "tardis_get_handover", "tardis_destroy", "tardis_status_string", "tardis_version",
 )
 
 
@@ -61,9 +61,11 @@ def lib() -> C.CDLL:
         L.tardis_ffn_forward.argtypes = [vp, vp, vp, vp]
         L.tardis_ffn_forward_batched.argtypes = [vp, vp, i64, vp, vp]
         L.tardis_dense_forward.argtypes = [vp, vp, i64, vp, vp]
+        L.tardis_stack_forward.argtypes = [C.POINTER(vp), C.c_int32, vp, i64, vp, vp]
         L.tardis_get_folded.argtypes = [vp, vp, vp, vp]
         L.tardis_get_predictor_state.argtypes = [vp, vp, vp, vp, vp]
         L.tardis_get_last_outliers.argtypes = [vp, i64, vp, vp, vp, vp]
+        L.tardis_get_handover.argtypes = [vp, i64, vp, vp]
         L.tardis_destroy.argtypes = [vp]
         L.tardis_status_string.argtypes = [C.c_int]
         L.tardis_status_string.restype = C.c_char_p
@@ -169,6 +171,16 @@ def tardis_ffn_forward_batched(L: Layer, x, y=None, stream=None):
     return y
 
 
+def tardis_stack_forward(layers, x, y=None, stream=None):
+    """x: n x d through every layer in turn (RMS-normalised between layers)."""
+    if y is None:
+        y = torch.empty_like(x)
+    arr = (C.c_void_p * len(layers))(*[L.handle for L in layers])
+    n = 1 if x.dim() == 1 else x.shape[0]
+    _check(lib().tardis_stack_forward(arr, len(layers), _ptr(x), n, _ptr(y), _stream(stream)), "tardis_stack_forward")
+    return y
+
+
 def tardis_dense_forward(L: Layer, x, y=None, stream=None):
     if y is None:
         y = torch.empty_like(x)
@@ -191,6 +203,12 @@ def tardis_get_predictor_state(L: Layer, stream=None):
     _check(lib().tardis_get_predictor_state(L.handle, _ptr(Q), _ptr(tlo), _ptr(thi), _stream(stream)),
            "tardis_get_predictor_state")
     return Q, tlo, thi
+
+
+def tardis_get_handover(L: Layer, n: int, stream=None):
+    out = torch.empty(n, L.d, dtype=L.torch_dtype, device=L.device)
+    _check(lib().tardis_get_handover(L.handle, n, _ptr(out), _stream(stream)), "tardis_get_handover")
+    return out
 
 
 def tardis_get_last_outliers(L: Layer, n: int, want_list: bool = True, stream=None):

@@ -20,7 +20,7 @@ def _declared():
 def test_library_exports_every_declared_function():
     lib = T.lib()
     names = _declared()
-    assert len(names) >= 11
+    assert len(names) >= 13
     for n in names:
         assert hasattr(lib, n), n
     assert sorted(T.EXPORTS) == names
@@ -93,6 +93,11 @@ def test_online_calls_reject_null_handle():
     assert lib.tardis_get_folded(None, p, p, None) == T.ERR_STATE
     assert lib.tardis_get_predictor_state(None, p, p, p, None) == T.ERR_STATE
     assert lib.tardis_get_last_outliers(None, 1, p, p, p, None) == T.ERR_STATE
+    assert lib.tardis_get_handover(None, 1, p, None) == T.ERR_STATE
+    arr = (C.c_void_p * 2)(None, None)
+    assert lib.tardis_stack_forward(arr, 2, p, 1, C.c_void_p(0x8000), None) == T.ERR_STATE
+    assert lib.tardis_stack_forward(None, 2, p, 1, C.c_void_p(0x8000), None) == T.ERR_INVALID_ARG
+    assert lib.tardis_stack_forward(arr, 0, p, 1, C.c_void_p(0x8000), None) == T.ERR_INVALID_ARG
     assert lib.tardis_destroy(None) == T.OK
 
 

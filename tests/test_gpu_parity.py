@@ -270,6 +270,45 @@ def test_repeated_calls_are_stable():
     L.close()
 
 
+# ------------------------------------------------------------- stacked layers
+@pytest.mark.parametrize("d,h,dtype,n", [(1024, 4096, "bf16", 1), (1024, 4096, "bf16", 3), (64, 256, "f32", 2)])
+def test_stack_teacher_forced(d, h, dtype, n):
+    """Every layer is checked on the input the GPU itself handed to it: mask bit-exact, the
+    normalised hand-over and the final output within the y tolerance."""
+    nl = 3
+    layers, oracles = [], []
+    x0 = synth.make_tokens(n, d, dtype, synth.workload_seed(4, 99), synth.STREAM_TEST)
+    for li in range(nl):
+        seed = synth.workload_seed(4, li)
+        lay = synth.make_layer(d, h, dtype, seed, w1_std=0.03 if dtype == "bf16" else 0.2, w2_std=0.03,
+                               heavy_frac=0.01)
+        ffn = make_ffn(lay)
+        X_cal = synth.make_tokens(512, d, dtype, seed, synth.STREAM_CAL)
+        lo, hi, a, c = T.tardis_calibrate(ffn, dev(X_cal, dtype), 0.9)
+        layers.append(T.tardis_fold(ffn, lo, hi, a, c, max_batch=n))
+        oracles.append(O.build(lay.W1, None, lay.W2, None, *(t.cpu().numpy() for t in (lo, hi, a, c))))
+    y = T.tardis_stack_forward(layers, dev(x0, dtype))
+    torch.cuda.synchronize()
+    x_in = x0.astype(np.float64)
+    for li in range(nl):
+        Yo, FLo = O.forward(oracles[li], x_in)
+        mask, counts, _ = T.tardis_get_last_outliers(layers[li], n, want_list=False)
+        np.testing.assert_array_equal(unpack_mask(mask, h), FLo)
+        assert (counts.cpu().numpy() == FLo.sum(1)).all()
+        if li < nl - 1:
+            xn = host(T.tardis_get_handover(layers[li], n))
+            want = O.rmsnorm(Yo)
+            if dtype == "bf16":
+                want = O.to_bf16(want)
+            assert rel_l2(xn, want) <= Y_TOL[dtype]
+            x_in = xn                                   # teacher forcing: the GPU's own hand-over
+        else:
+            assert rel_l2(host(y), Yo) <= Y_TOL[dtype]
+    # one call per layer with host-side glue gives the same final result
+    for L in layers:
+        L.close()
+
+
 # ------------------------------------------------ config 1 at full size (d=4096, h=16384, bf16)
 @pytest.fixture(scope="module")
 def decode_full():
