@@ -49,7 +49,8 @@ int env_int(const char* name, int fallback, int lo, int hi) {
 void free_layer(tardis_layer_s* L) {
     if (!L) return;
     void* owned[] = {L->W2T, L->W2, L->Wp, L->bp, L->Q, L->tlo, L->thi, L->a, L->c,
-                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix, L->zeros_h, L->xnext};
+                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix, L->zeros_h, L->xnext,
+                     L->bt_xq, L->bt_e, L->bt_tokmask, L->bt_ulist, L->bt_ucount, L->bt_delta, L->bt_partial};
     for (void* p : owned)
         if (p) (void)hipFree(p);
     delete L;
@@ -95,6 +96,19 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     TD_TRY(dev_alloc(&L->yfix, (size_t)L->dec_copies * d * 4));
     TD_HIP(hipMemsetAsync(L->yfix, 0, (size_t)L->dec_copies * d * 4, s));
     L->use_fused = env_int("TARDIS_DECODE_FUSED", 1, 0, 1) && td_decode_fused_supported(L);
+    L->use_batched = env_int("TARDIS_BATCHED", 1, 0, 1) && td_batched_supported(L);
+    if (L->use_batched) {
+        TD_TRY(td_batched_init());
+        TD_TRY(dev_alloc(&L->bt_xq, (size_t)64 * d));
+        TD_TRY(dev_alloc(&L->bt_e, 64 * 4));
+        TD_TRY(dev_alloc(&L->bt_tokmask, (size_t)h * 8));
+        TD_TRY(dev_alloc(&L->bt_ulist, (size_t)h * 4));
+        TD_TRY(dev_alloc(&L->bt_ucount, 16));
+        TD_TRY(dev_alloc(&L->bt_delta, (size_t)64 * h * 2));
+        TD_TRY(dev_alloc(&L->bt_partial, td_batched_partial_floats(L) * 4));
+        TD_HIP(hipMemsetAsync(L->bt_delta, 0, (size_t)64 * h * 2, s));
+        TD_HIP(hipMemsetAsync(L->bt_ucount, 0, 16, s));
+    }
     TD_HIP(hipMemsetAsync(L->counts, 0, nb * 4, s));
     TD_HIP(hipMemsetAsync(L->mask, 0, nb * L->mask_words * 4, s));
     TD_HIP(hipMemsetAsync(L->yacc, 0, nb * d * 4, s));

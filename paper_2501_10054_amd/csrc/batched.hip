@@ -1,0 +1,496 @@
+// Batched online path (2..64 tokens per pass, bf16 storage): every weight matrix
+// is streamed ONCE per pass of up to 64 tokens instead of once per token.
+//
+// Steps per pass (Sec. "Inference Runtime", strictly per token):
+//   quantise     per token max|x|, exponent e_t and int8 code
+//   fold+predict W'X^T (bf16 MFMA) and QXq^T (int8 MFMA, exact int32) in one launch;
+//                flags -> per-token mask words, per-neuron token bitmask, and the
+//                list of neurons flagged by at least one token (the "union")
+//   delta        rows W1[j] of the union only (gathered): z, then
+//                delta = sigma(z) - (a z + c) for the (token, neuron) pairs that
+//                were flagged, 0 elsewhere
+//   scatter      y += Delta . W2: up to 16 tokens gather the union rows of W2^T
+//                (vector ALU, tokens in registers); more tokens run the masked
+//                dense product over W2 on the matrix cores (by then the union is
+//                most of the layer anyway)
+//   finish       sum of the partial products, optional RMS norm, conversion
+//
+// The streaming kernel is bandwidth bound: one wavefront owns 16 weight rows and
+// keeps 2 x 8 sixteen-byte loads per lane in flight; the token chunk is staged
+// through double-buffered LDS and shared by the block's four wavefronts.
+#include "common.h"
+#include "rowdot.h"
+
+namespace {
+
+constexpr int kTB = 64;                       // tokens per pass
+constexpr int kRowsPerBlock = 64;             // 4 wavefronts x 16 rows
+constexpr int kChunk = 512;                   // bytes of every weight row per pipeline stage
+constexpr int kXPitch = kChunk + 16;          // LDS pitch of a staged token row
+constexpr int kDownSplits = 8;                // split of the hidden axis in the masked dense scatter
+constexpr int kGatherSegs = 16;               // segments of the union list in the gather scatter
+constexpr int kGatherTok = 16;                // most tokens the gather scatter handles
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+
+enum { EPI_FOLD = 0, EPI_PRED = 1, EPI_DELTA = 2, EPI_DOWN = 3 };
+
+struct StreamArgs {
+    const unsigned char* W;        // weight rows
+    int64_t row_bytes;             // bytes per weight row (a multiple of kChunk * splits)
+    int M;                         // rows of W (capacity of the gather list when gathering)
+    const int32_t* gather;         // row indices, or null for rows 0..M-1
+    const int32_t* gather_count;   // device count of gather entries
+    const unsigned char* X;        // tokens: n_tok rows of row_bytes bytes
+    int n_tok;
+    // fold
+    const float* bp;
+    float* yfold;                  // [token][d]
+    int d;
+    // predict
+    const float* tlo;
+    const float* thi;
+    const int32_t* e_tok;
+    uint32_t* mask;                // [token][mask_words]
+    int mask_words;
+    unsigned long long* tokmask;   // [neuron]
+    int32_t* ulist;
+    int32_t* ucount;
+    // delta
+    const bf16_t* b1;
+    const float* a;
+    const float* c;
+    int act;
+    bf16_t* delta;                 // neuron-major [h][64] or token-major [64][h]
+    int delta_token_major;
+    int h;
+    // down
+    float* partial;                // [split][64][d]
+};
+
+template <bool I8> struct Acc;
+template <> struct Acc<false> { typedef f32x4_t type; };
+template <> struct Acc<true> { typedef i32x4_t type; };
+
+// D = A.B^T on one 16x16 tile: operand lanes hold 16 bytes of row (lane % 16) at k-group (lane / 16)
+template <bool I8>
+__device__ __forceinline__ typename Acc<I8>::type mma16(const td_u32x4& rowsA, const td_u32x4& rowsB,
+                                                        typename Acc<I8>::type acc);
+template <>
+__device__ __forceinline__ f32x4_t mma16<false>(const td_u32x4& ra, const td_u32x4& rb, f32x4_t acc) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ra), __builtin_bit_cast(bf16x8_t, rb),
+                                                   acc, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ i32x4_t mma16<true>(const td_u32x4& ra, const td_u32x4& rb, i32x4_t acc) {
+    return __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4_t, ra), __builtin_bit_cast(i32x4_t, rb), acc,
+                                                 0, 0, 0);
+}
+
+// One block: 64 weight rows (16 per wavefront) against NT*16 tokens over this block's K range.
+// TOKEN_ROWS: the tile is produced as D[token][weight row] (stores contiguous along the weight
+// rows) instead of D[weight row][token].
+template <bool I8, int NT, int EPI>
+__device__ __forceinline__ void stream_body(const StreamArgs& p, int row_block, int split, int chunks_per_split,
+                                            unsigned char* lds) {
+    constexpr bool TOKEN_ROWS = (EPI == EPI_FOLD || EPI == EPI_DOWN);
+    typedef typename Acc<I8>::type acc_t;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, g = lane >> 4;
+
+    int count = p.M;
+    if (p.gather) {
+        count = min(*p.gather_count, p.M);
+        if (row_block * kRowsPerBlock >= count) return;          // uniform: nothing gathered for this block
+    }
+    const int rw = row_block * kRowsPerBlock + wave * 16;        // first row (or list slot) of this wavefront
+    int my_row = min(rw + l16, count - 1);
+    if (p.gather) my_row = p.gather[my_row];
+    const unsigned char* wsrc = p.W + (size_t)my_row * p.row_bytes + (size_t)split * chunks_per_split * kChunk + g * 16;
+
+    // token staging map: piece q of this thread -> token (idx / 32), 16-byte piece (idx % 32)
+    constexpr int XP = NT * 2;
+    const unsigned char* xsrc[XP];
+    int xdst[XP];
+    bool xok[XP];
+#pragma unroll
+    for (int q = 0; q < XP; ++q) {
+        const int idx = tid + 256 * q;
+        const int t = idx >> 5, piece = idx & 31;
+        xok[q] = t < p.n_tok;
+        xsrc[q] = p.X + (size_t)min(t, p.n_tok - 1) * p.row_bytes + (size_t)split * chunks_per_split * kChunk + piece * 16;
+        xdst[q] = t * kXPitch + piece * 16;
+    }
+
+    acc_t acc[NT];
+#pragma unroll
+    for (int tt = 0; tt < NT; ++tt) acc[tt] = acc_t{0, 0, 0, 0};
+
+    td_u32x4 wa[8], wb[8], xr[XP];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) wa[s] = td_load_stream16(wsrc + s * 64);
+#pragma unroll
+    for (int q = 0; q < XP; ++q) {
+        xr[q] = xok[q] ? *reinterpret_cast<const td_u32x4*>(xsrc[q]) : td_u32x4{0, 0, 0, 0};
+        *reinterpret_cast<td_u32x4*>(lds + xdst[q]) = xr[q];
+    }
+    __syncthreads();
+
+    for (int ch = 0; ch < chunks_per_split; ++ch) {
+        const bool more = ch + 1 < chunks_per_split;
+        if (more) {
+#pragma unroll
+            for (int s = 0; s < 8; ++s) wb[s] = td_load_stream16(wsrc + (size_t)(ch + 1) * kChunk + s * 64);
+#pragma unroll
+            for (int q = 0; q < XP; ++q)
+                xr[q] = xok[q] ? *reinterpret_cast<const td_u32x4*>(xsrc[q] + (size_t)(ch + 1) * kChunk)
+                               : td_u32x4{0, 0, 0, 0};
+        }
+        const unsigned char* xb = lds + (ch & 1) * (kTB * kXPitch) + l16 * kXPitch + g * 16;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+#pragma unroll
+            for (int tt = 0; tt < NT; ++tt) {
+                const td_u32x4 xf = *reinterpret_cast<const td_u32x4*>(xb + tt * 16 * kXPitch + s * 64);
+                acc[tt] = TOKEN_ROWS ? mma16<I8>(xf, wa[s], acc[tt]) : mma16<I8>(wa[s], xf, acc[tt]);
+            }
+        }
+        if (more) {
+            unsigned char* nb = lds + ((ch + 1) & 1) * (kTB * kXPitch);
+#pragma unroll
+            for (int q = 0; q < XP; ++q) *reinterpret_cast<td_u32x4*>(nb + xdst[q]) = xr[q];
+#pragma unroll
+            for (int s = 0; s < 8; ++s) wa[s] = wb[s];
+        }
+        __syncthreads();
+    }
+
+    // ------------------------------------------------------------------ epilogues
+    // TOKEN_ROWS: acc[tt][i] = D[token tt*16 + 4g + i][weight row rw + l16]
+    // otherwise : acc[tt][i] = D[weight row rw + 4g + i][token tt*16 + l16]
+    if constexpr (EPI == EPI_FOLD) {
+        const int r = rw + l16;
+        if (r < p.M) {
+            const float b = p.bp[r];
+#pragma unroll
+            for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int t = tt * 16 + 4 * g + i;
+                    if (t < p.n_tok) p.yfold[(size_t)t * p.d + r] = acc[tt][i] + b;
+                }
+        }
+    } else if constexpr (EPI == EPI_DOWN) {
+        const int r = rw + l16;
+        if (r < p.M) {
+#pragma unroll
+            for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int t = tt * 16 + 4 * g + i;
+                    if (t < p.n_tok) p.partial[((size_t)split * kTB + t) * p.d + r] = acc[tt][i];
+                }
+        }
+    } else if constexpr (EPI == EPI_PRED) {
+        uint32_t* lmask = reinterpret_cast<uint32_t*>(lds + 2 * kTB * kXPitch);   // [64 tokens][2 words]
+        uint32_t* ltok = lmask + 128;                                           // [64 rows][2 words]
+        if (tid < 128) {
+            lmask[tid] = 0u;
+            ltok[tid] = 0u;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int rl = wave * 16 + 4 * g + i;                   // row within the block
+            const int r = row_block * kRowsPerBlock + rl;
+            if (r >= p.M) continue;
+            const float lo = p.tlo[r], hi = p.thi[r];
+#pragma unroll
+            for (int tt = 0; tt < NT; ++tt) {
+                const int t = tt * 16 + l16;
+                if (t >= p.n_tok) continue;
+                const float v = ldexpf((float)acc[tt][i], p.e_tok[t]);
+                const bool inside = (v >= lo) && (v < hi);
+                if (!inside) {
+                    atomicOr(&lmask[t * 2 + (rl >> 5)], 1u << (rl & 31));
+                    atomicOr(&ltok[rl * 2 + (t >> 5)], 1u << (t & 31));
+                }
+            }
+        }
+        __syncthreads();
+        if (tid < 128) {
+            const int t = tid >> 1, w = tid & 1;
+            const int word = row_block * 2 + w;
+            if (t < p.n_tok && word < p.mask_words) p.mask[(size_t)t * p.mask_words + word] = lmask[tid];
+        }
+        if (wave == 0) {
+            const int r = row_block * kRowsPerBlock + lane;
+            const unsigned long long tm = (unsigned long long)ltok[lane * 2] | ((unsigned long long)ltok[lane * 2 + 1] << 32);
+            const bool any = r < p.M && tm != 0ull;
+            if (r < p.M) p.tokmask[r] = tm;
+            const unsigned long long bal = __ballot(any);
+            int base = 0;
+            if (lane == 0 && bal) base = atomicAdd(p.ucount, __popcll(bal));
+            base = __shfl(base, 0, 64);
+            if (any) p.ulist[base + __popcll(bal & ((1ull << lane) - 1ull))] = r;
+        }
+    } else {  // EPI_DELTA
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int slot = rw + 4 * g + i;
+            if (slot >= count) continue;
+            const int j = p.gather[slot];
+            const unsigned long long tm = p.tokmask[j];
+            const float bj = td_bf16_to_f32(p.b1[j]), aj = p.a[j], cj = p.c[j];
+#pragma unroll
+            for (int tt = 0; tt < NT; ++tt) {
+                const int t = tt * 16 + l16;
+                float dv = 0.0f;
+                if (t < p.n_tok && ((tm >> t) & 1ull)) {
+                    const float z = acc[tt][i] + bj;
+                    dv = td_act(z, p.act) - fmaf(aj, z, cj);
+                }
+                if (p.delta_token_major) {
+                    if (dv != 0.0f) p.delta[(size_t)t * p.h + j] = td_f32_to_bf16(dv);
+                } else {
+                    p.delta[(size_t)j * kTB + t] = td_f32_to_bf16(dv);
+                }
+            }
+        }
+    }
+}
+
+constexpr int kStreamLds = 2 * kTB * kXPitch + 1024;
+
+// fold (bf16, blocks [0, fold_blocks)) and predictor (int8, the rest) in one launch
+template <int NT>
+__global__ void __launch_bounds__(256)
+fold_predict_batched_kernel(StreamArgs fold, StreamArgs pred, int fold_blocks, int fold_chunks, int pred_chunks) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    if ((int)blockIdx.x < fold_blocks)
+        stream_body<false, NT, EPI_FOLD>(fold, blockIdx.x, 0, fold_chunks, lds);
+    else
+        stream_body<true, NT, EPI_PRED>(pred, (int)blockIdx.x - fold_blocks, 0, pred_chunks, lds);
+}
+
+template <int NT, int EPI>
+__global__ void __launch_bounds__(256) stream_kernel(StreamArgs p, int chunks_per_split) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    stream_body<false, NT, EPI>(p, blockIdx.x, blockIdx.y, chunks_per_split, lds);
+}
+
+// per token: max|x|, exponent, int8 code (one block per token)
+__global__ void __launch_bounds__(256)
+quantize_tokens_kernel(const bf16_t* __restrict__ X, int d, int8_t* __restrict__ XQ, int32_t* __restrict__ E) {
+    __shared__ float red[4];
+    const int t = blockIdx.x;
+    const bf16_t* x = X + (size_t)t * d;
+    float m = 0.0f;
+    for (int k = threadIdx.x; k < d; k += 256) m = fmaxf(m, fabsf(td_bf16_to_f32(x[k])));
+    m = td_wave_max(m);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const int e = token_exponent(m);
+    for (int k = threadIdx.x; k < d; k += 256) XQ[(size_t)t * d + k] = quantize_value(td_bf16_to_f32(x[k]), e);
+    if (threadIdx.x == 0) E[t] = e;
+}
+
+__global__ void __launch_bounds__(256) fill_u32_kernel(uint32_t* __restrict__ p, size_t n, uint32_t v) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// gather scatter for up to 16 tokens: thread = one output column, tokens in registers;
+// blockIdx.y = segment of the union list.  partial[seg][t][c] = sum_i delta[j_i][t] * W2T[j_i][c]
+__global__ void __launch_bounds__(256)
+scatter_gather_kernel(const bf16_t* __restrict__ W2T, const bf16_t* __restrict__ delta, const int32_t* __restrict__ ulist,
+                      const int32_t* __restrict__ ucount, int h, int d, int n_tok, float* __restrict__ partial) {
+    const int c = (int)blockIdx.x * 256 + threadIdx.x;
+    const int count = min(*ucount, h);
+    const int len = (count + kGatherSegs - 1) / kGatherSegs;
+    const int i0 = (int)blockIdx.y * len, i1 = min(count, i0 + len);
+    float acc[kGatherTok];
+#pragma unroll
+    for (int t = 0; t < kGatherTok; ++t) acc[t] = 0.0f;
+    if (c < d) {
+#pragma unroll 4
+        for (int i = i0; i < i1; ++i) {
+            const int j = ulist[i];
+            const float w = td_bf16_to_f32(__builtin_nontemporal_load(W2T + (size_t)j * d + c));
+            const td_u32x4* dp = reinterpret_cast<const td_u32x4*>(delta + (size_t)j * kTB);
+            const td_u32x4 d0 = dp[0], d1 = dp[1];
+            const uint32_t dw[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                acc[2 * u] = fmaf(__uint_as_float(dw[u] << 16), w, acc[2 * u]);
+                acc[2 * u + 1] = fmaf(__uint_as_float(dw[u] & 0xFFFF0000u), w, acc[2 * u + 1]);
+            }
+        }
+        for (int t = 0; t < n_tok; ++t) partial[((size_t)blockIdx.y * kTB + t) * d + c] = acc[t];
+    }
+}
+
+// y[t] = yfold[t] + sum_s partial[s][t], optional RMS norm, conversion (one block per token)
+__global__ void __launch_bounds__(256)
+finish_batched_kernel(const float* __restrict__ yfold, const float* __restrict__ partial, int nparts, int d,
+                      bf16_t* __restrict__ y, int norm_out, float eps) {
+    __shared__ float red[4];
+    extern __shared__ float row[];
+    const int t = blockIdx.x;
+    float ss = 0.0f;
+    for (int k = threadIdx.x; k < d; k += 256) {
+        float v = yfold[(size_t)t * d + k];
+        for (int s = 0; s < nparts; ++s) v += partial[((size_t)s * kTB + t) * d + k];
+        row[k] = v;
+        ss += v * v;
+    }
+    float scale = 1.0f;
+    if (norm_out) {
+        ss = td_wave_sum(ss);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+        __syncthreads();
+        scale = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
+    }
+    for (int k = threadIdx.x; k < d; k += 256) y[(size_t)t * d + k] = td_f32_to_bf16(row[k] * scale);
+}
+
+inline int div_up(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+template <typename K> hipError_t allow_big_lds(K kernel) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               kStreamLds);
+}
+
+template <int NT>
+tardis_status_t pass_t(tardis_layer_s* L, const bf16_t* x, int nt, bf16_t* y, uint32_t* mask, float* yfold,
+                       int norm_out, hipStream_t s) {
+    const int d = (int)L->d, h = (int)L->h;
+    hipLaunchKernelGGL(quantize_tokens_kernel, dim3(nt), dim3(256), 0, s, x, d, L->bt_xq, L->bt_e);
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, s, reinterpret_cast<uint32_t*>(L->bt_ucount), (size_t)1, 0u);
+    const bool gather_scatter = nt <= kGatherTok;
+    if (!gather_scatter) {
+        const size_t words = (size_t)kTB * h / 2;
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(div_up(words, 256)), dim3(256), 0, s,
+                           reinterpret_cast<uint32_t*>(L->bt_delta), words, 0u);
+    }
+    StreamArgs base{};
+    base.n_tok = nt;
+    base.d = d;
+    base.h = h;
+    base.act = L->act;
+
+    StreamArgs fold = base;
+    fold.W = static_cast<const unsigned char*>(L->Wp);
+    fold.row_bytes = (int64_t)d * 2;
+    fold.M = d;
+    fold.X = reinterpret_cast<const unsigned char*>(x);
+    fold.bp = L->bp;
+    fold.yfold = yfold;
+    StreamArgs pred = base;
+    pred.W = reinterpret_cast<const unsigned char*>(L->Q);
+    pred.row_bytes = d;
+    pred.M = h;
+    pred.X = reinterpret_cast<const unsigned char*>(L->bt_xq);
+    pred.tlo = L->tlo;
+    pred.thi = L->thi;
+    pred.e_tok = L->bt_e;
+    pred.mask = mask;
+    pred.mask_words = (int)L->mask_words;
+    pred.tokmask = L->bt_tokmask;
+    pred.ulist = L->bt_ulist;
+    pred.ucount = L->bt_ucount;
+    const int fold_blocks = div_up(d, kRowsPerBlock), pred_blocks = div_up(h, kRowsPerBlock);
+    hipLaunchKernelGGL(fold_predict_batched_kernel<NT>, dim3(fold_blocks + pred_blocks), dim3(256), kStreamLds, s, fold,
+                       pred, fold_blocks, d * 2 / kChunk, d / kChunk);
+
+    StreamArgs del = base;
+    del.W = static_cast<const unsigned char*>(L->W1);
+    del.row_bytes = (int64_t)d * 2;
+    del.M = h;
+    del.gather = L->bt_ulist;
+    del.gather_count = L->bt_ucount;
+    del.X = reinterpret_cast<const unsigned char*>(x);
+    del.tokmask = L->bt_tokmask;
+    del.b1 = static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h);
+    del.a = L->a;
+    del.c = L->c;
+    del.delta = L->bt_delta;
+    del.delta_token_major = gather_scatter ? 0 : 1;
+    hipLaunchKernelGGL((stream_kernel<NT, EPI_DELTA>), dim3(pred_blocks, 1), dim3(256), kStreamLds, s, del,
+                       d * 2 / kChunk);
+
+    int nparts;
+    if (gather_scatter) {
+        nparts = kGatherSegs;
+        hipLaunchKernelGGL(scatter_gather_kernel, dim3(div_up(d, 256), kGatherSegs), dim3(256), 0, s,
+                           static_cast<const bf16_t*>(L->W2T), L->bt_delta, L->bt_ulist, L->bt_ucount, h, d, nt,
+                           L->bt_partial);
+    } else {
+        nparts = kDownSplits;
+        StreamArgs down = base;
+        down.W = static_cast<const unsigned char*>(L->W2);
+        down.row_bytes = (int64_t)h * 2;
+        down.M = d;
+        down.X = reinterpret_cast<const unsigned char*>(L->bt_delta);
+        down.partial = L->bt_partial;
+        hipLaunchKernelGGL((stream_kernel<NT, EPI_DOWN>), dim3(fold_blocks, kDownSplits), dim3(256), kStreamLds, s,
+                           down, h * 2 / kChunk / kDownSplits);
+    }
+    hipLaunchKernelGGL(finish_batched_kernel, dim3(nt), dim3(256), (size_t)d * sizeof(float), s, yfold, L->bt_partial,
+                       nparts, d, y, norm_out, kRmsEps);
+    TD_HIP(hipGetLastError());
+    return TARDIS_OK;
+}
+
+}  // namespace
+
+bool td_batched_supported(const tardis_layer_s* L) {
+    return L->dtype == TARDIS_BF16 && L->max_batch > 1 && L->d % kChunk == 0 && L->d <= 8192 &&
+           (L->h * 2) % ((int64_t)kChunk * kDownSplits) == 0;
+}
+
+size_t td_batched_partial_floats(const tardis_layer_s* L) {
+    return (size_t)(kGatherSegs > kDownSplits ? kGatherSegs : kDownSplits) * kTB * L->d;
+}
+
+// the streaming kernels use more than the default 64 KiB of dynamic LDS
+tardis_status_t td_batched_init() {
+    static bool done = false;
+    if (done) return TARDIS_OK;
+    TD_HIP(allow_big_lds(fold_predict_batched_kernel<1>));
+    TD_HIP(allow_big_lds(fold_predict_batched_kernel<2>));
+    TD_HIP(allow_big_lds(fold_predict_batched_kernel<4>));
+    TD_HIP(allow_big_lds(stream_kernel<1, EPI_DELTA>));
+    TD_HIP(allow_big_lds(stream_kernel<2, EPI_DELTA>));
+    TD_HIP(allow_big_lds(stream_kernel<4, EPI_DELTA>));
+    TD_HIP(allow_big_lds(stream_kernel<1, EPI_DOWN>));
+    TD_HIP(allow_big_lds(stream_kernel<2, EPI_DOWN>));
+    TD_HIP(allow_big_lds(stream_kernel<4, EPI_DOWN>));
+    done = true;
+    return TARDIS_OK;
+}
+
+tardis_status_t td_forward_batched(tardis_layer_s* L, const void* xv, int64_t n, void* yv, int norm_out,
+                                   hipStream_t s) {
+    const int d = (int)L->d;
+    for (int64_t t0 = 0; t0 < n; t0 += kTB) {
+        const int nt = (int)((n - t0 < kTB) ? n - t0 : kTB);
+        const bf16_t* x = static_cast<const bf16_t*>(xv) + t0 * d;
+        bf16_t* y = static_cast<bf16_t*>(yv) + t0 * d;
+        uint32_t* mask = L->mask + t0 * L->mask_words;
+        float* yfold = L->yacc + t0 * d;
+        tardis_status_t st;
+        if (nt <= 16)
+            st = pass_t<1>(L, x, nt, y, mask, yfold, norm_out, s);
+        else if (nt <= 32)
+            st = pass_t<2>(L, x, nt, y, mask, yfold, norm_out, s);
+        else
+            st = pass_t<4>(L, x, nt, y, mask, yfold, norm_out, s);
+        TD_TRY(st);
+    }
+    L->last_n = n;
+    return TARDIS_OK;
+}

@@ -61,6 +61,15 @@ struct tardis_layer_s {
     int32_t dec_threads;  // block size of the fused decode kernel (512 or 1024)
     int32_t dec_copies;   // number of repair accumulator copies
     int32_t use_fused;    // fused single-launch decode path available for this layer
+    // working memory of the batched path (one pass of up to 64 tokens); null if unused
+    int8_t* bt_xq;                 // 64 x d int8 token codes
+    int32_t* bt_e;                 // 64 token exponents
+    unsigned long long* bt_tokmask;  // h: which tokens of the pass flagged each neuron
+    int32_t* bt_ulist;             // h: neurons flagged by at least one token
+    int32_t* bt_ucount;            // 1
+    bf16_t* bt_delta;              // 64 x h repair factors
+    float* bt_partial;             // partial products of the scatter step
+    int32_t use_batched;
     int64_t last_n;    // token count of the most recent online call
 };
 
@@ -159,6 +168,11 @@ bool td_decode_fused_supported(const tardis_layer_s* L);
 tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
                                 int norm_out, hipStream_t s);
 tardis_status_t td_mask_to_list(const tardis_layer_s* L, int64_t n, int32_t* counts, int32_t* list, hipStream_t s);
+// batched.hip
+bool td_batched_supported(const tardis_layer_s* L);
+size_t td_batched_partial_floats(const tardis_layer_s* L);
+tardis_status_t td_batched_init();
+tardis_status_t td_forward_batched(tardis_layer_s* L, const void* x, int64_t n, void* y, int norm_out, hipStream_t s);
 // forward.hip
 // norm_out != 0: the output is y / sqrt(mean(y^2) + kRmsEps) per token (glue between stacked layers)
 tardis_status_t td_forward(tardis_layer_s* L, const void* x, int64_t n, void* y, int norm_out, hipStream_t s);

@@ -174,6 +174,22 @@ def test_mid_bf16_batched_high_fallback():
     assert 0.08 < r["rate"] < 0.25
 
 
+@pytest.mark.parametrize("n,coverage", [(2, 0.95), (16, 0.9), (20, 0.95), (48, 0.85), (64, 0.95), (70, 0.99), (150, 0.95)])
+def test_batched_passes_of_64_tokens(n, coverage):
+    """One weight stream per pass of up to 64 tokens: every tile count (1, 2, 4 token tiles), the
+    gather and the masked-dense scatter, a ragged last pass."""
+    w = synth.decode(d=1024, h=4096, n_cal=512, n_test=n, coverage=coverage, config=2)
+    run_case(w.layer, w.X_cal, w.X_test, coverage, batched=True, check_calibrate=False)
+
+
+def test_batched_with_bias_and_relu():
+    seed = synth.workload_seed(2, 7)
+    layer = synth.make_layer(512, 2048, "bf16", seed, w1_std=0.05, w2_std=0.05, heavy_frac=0.01, with_bias=True)
+    X_cal = synth.make_tokens(400, 512, "bf16", seed, synth.STREAM_CAL)
+    X_test = synth.make_tokens(33, 512, "bf16", seed, synth.STREAM_TEST)
+    run_case(layer, X_cal, X_test, 0.9, act="relu", batched=True, check_calibrate=False)
+
+
 # ----------------------------------------------------------------- edge cases
 def test_degenerate_tokens_and_neurons():
     d, h = 64, 96
