@@ -38,6 +38,56 @@ def algorithmic_bytes(d: int, h: int, p: float) -> float:
     return 2.0 * d * d + 1.0 * d * h + 4.0 * p * d * h
 
 
+def batched_sweep(T, synth, torch, np, to_dev, n_layers):
+    """Batched decode: tokens/s, algorithmic GB/s and union size per (batch, coverage), cold over
+    `n_layers` seeded layer copies, against the vendor-BLAS dense FFN at the same batch."""
+    rows = []
+    works = [synth.decode(layer=li, n_cal=4096, n_test=64, coverage=0.95) for li in range(n_layers)]
+    ffns = [T.FFN(to_dev(w.layer.W1), to_dev(w.layer.W2)) for w in works]
+    Xc = [to_dev(w.X_cal) for w in works]
+    X = to_dev(works[0].X_test)
+    stream = torch.cuda.current_stream()
+    for cov in (0.99, 0.95, 0.85):
+        layers = []
+        for ffn, xc in zip(ffns, Xc):
+            lo, hi, a, c = T.tardis_calibrate(ffn, xc, cov)
+            layers.append(T.tardis_fold(ffn, lo, hi, a, c, max_batch=64))
+        for B in (4, 16, 64):
+            xb = X[:B].contiguous()
+            yb = torch.empty_like(xb)
+            T.tardis_ffn_forward_batched(layers[0], xb, yb)
+            mask, counts, _ = T.tardis_get_last_outliers(layers[0], B, want_list=False)
+            union = int((mask.cpu().numpy().view(np.uint32)[:, None, :] >> np.arange(32, dtype=np.uint32)[None, :, None] & 1)
+                        .any(axis=0).sum())
+            p = float(counts.float().mean().item()) / H
+            reps = 60
+            for L in layers:
+                T.tardis_ffn_forward_batched(L, xb, yb)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for r in range(reps):
+                T.tardis_ffn_forward_batched(layers[r % len(layers)], xb, yb)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / reps
+            W1s, W2s = [f.W1 for f in ffns], [f.W2 for f in ffns]
+            e0.record(stream)
+            for r in range(reps):
+                i = r % len(ffns)
+                torch.nn.functional.linear(torch.nn.functional.gelu(torch.nn.functional.linear(xb, W1s[i])), W2s[i])
+            e1.record(stream)
+            torch.cuda.synchronize()
+            dus = e0.elapsed_time(e1) * 1e3 / reps
+            alg = 2.0 * D * D + D * H + union * 4.0 * D + B * 6.0 * D
+            rows.append({"batch": B, "coverage_t": cov, "fallback_rate": p, "union_neurons": union,
+                         "us_per_batch": us, "tokens_per_s": B / (us * 1e-6), "algorithmic_GBs": alg / us / 1e3,
+                         "dense_torch_us_per_batch": dus, "speedup_vs_dense_torch": dus / us})
+        for L in layers:
+            L.close()
+    return rows
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,6 +98,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of a replayed HIP graph")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also run the batched decode sweep: batch {4,16,64} x coverage {0.99,0.95,0.85}")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a 1 GiB device copy (known HBM traffic) so that profiler counters can be scaled")
     args = ap.parse_args()
@@ -234,6 +286,8 @@ def main() -> int:
     out.update(res_dense)
     if res_dense:
         out["speedup_vs_dense_own"] = tok_s / res_dense["dense_own_tokens_per_s"]
+    if args.sweep:
+        out["batched_sweep"] = batched_sweep(T, synth, torch, np, to_dev, args.layers)
     if args.copy_probe:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)

@@ -97,6 +97,7 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     TD_HIP(hipMemsetAsync(L->yfix, 0, (size_t)L->dec_copies * d * 4, s));
     L->use_fused = env_int("TARDIS_DECODE_FUSED", 1, 0, 1) && td_decode_fused_supported(L);
     L->use_batched = env_int("TARDIS_BATCHED", 1, 0, 1) && td_batched_supported(L);
+    L->batched_min_tokens = env_int("TARDIS_BATCHED_MIN", L->use_fused ? 4 : 1, 1, 64);
     if (L->use_batched) {
         TD_TRY(td_batched_init());
         TD_TRY(dev_alloc(&L->bt_xq, (size_t)64 * d));

@@ -92,9 +92,12 @@ __device__ __forceinline__ i32x4_t mma16<true>(const td_u32x4& ra, const td_u32x
 // One block: 64 weight rows (16 per wavefront) against NT*16 tokens over this block's K range.
 // TOKEN_ROWS: the tile is produced as D[token][weight row] (stores contiguous along the weight
 // rows) instead of D[weight row][token].
-template <bool I8, int NT, int EPI>
-__device__ __forceinline__ void stream_body(const StreamArgs& p, int row_block, int split, int chunks_per_split,
+template <bool I8, int NT, int EPI, int NCH>
+__device__ __forceinline__ void stream_body(const StreamArgs& p, int row_block, int split, int chunks_rt,
                                             unsigned char* lds) {
+    // NCH > 0: the chunk count is a compile-time constant and the pipeline below is fully unrolled
+    // (straight-line code lets the compiler count outstanding loads exactly); NCH == 0: run time.
+    const int chunks_per_split = NCH > 0 ? NCH : chunks_rt;
     constexpr bool TOKEN_ROWS = (EPI == EPI_FOLD || EPI == EPI_DOWN);
     typedef typename Acc<I8>::type acc_t;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -110,16 +113,17 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p, int row_block, 
     if (p.gather) my_row = p.gather[my_row];
     const unsigned char* wsrc = p.W + (size_t)my_row * p.row_bytes + (size_t)split * chunks_per_split * kChunk + g * 16;
 
-    // token staging map: piece q of this thread -> token (idx / 32), 16-byte piece (idx % 32)
+    // token staging map: piece q of this thread -> token (idx / 32), 16-byte piece (idx % 32).
+    // Token slots past n_tok re-read the last token: every load is unconditional (the in-order
+    // load counter stays statically known to the compiler) and the columns they produce are never
+    // stored (each token is an independent column of the product).
     constexpr int XP = NT * 2;
     const unsigned char* xsrc[XP];
     int xdst[XP];
-    bool xok[XP];
 #pragma unroll
     for (int q = 0; q < XP; ++q) {
         const int idx = tid + 256 * q;
         const int t = idx >> 5, piece = idx & 31;
-        xok[q] = t < p.n_tok;
         xsrc[q] = p.X + (size_t)min(t, p.n_tok - 1) * p.row_bytes + (size_t)split * chunks_per_split * kChunk + piece * 16;
         xdst[q] = t * kXPitch + piece * 16;
     }
@@ -128,43 +132,81 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p, int row_block, 
 #pragma unroll
     for (int tt = 0; tt < NT; ++tt) acc[tt] = acc_t{0, 0, 0, 0};
 
-    td_u32x4 wa[8], wb[8], xr[XP];
+    // Pipeline: while chunk ch is multiplied, the weights of chunks ch+1, ch+2 and the tokens of
+    // chunks ch+1 (on their way to LDS) and ch+2 are in flight.  The three weight buffers and the
+    // two token buffers are named statically (the loop is unrolled by six): a register copy would
+    // have to wait for the load it copies.  Past the last chunk the prefetches re-read chunk 0 (a
+    // cache hit) instead of being skipped, so that the in-order load counter stays statically
+    // known and no wait ever drains more than it needs.
+    const int last = chunks_per_split - 1;
+    td_u32x4 w0[8], w1[8], w2[8], xa[XP], xb[XP];
+    auto load_w = [&](td_u32x4 (&dst)[8], int ch) {
+        const unsigned char* src = wsrc + (size_t)(ch <= last ? ch : 0) * kChunk;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) wa[s] = td_load_stream16(wsrc + s * 64);
+        for (int s = 0; s < 8; ++s) dst[s] = td_load_stream16(src + s * 64);
+    };
+    auto load_x = [&](td_u32x4 (&dst)[XP], int ch) {
+        const size_t off = (size_t)(ch <= last ? ch : 0) * kChunk;
 #pragma unroll
-    for (int q = 0; q < XP; ++q) {
-        xr[q] = xok[q] ? *reinterpret_cast<const td_u32x4*>(xsrc[q]) : td_u32x4{0, 0, 0, 0};
-        *reinterpret_cast<td_u32x4*>(lds + xdst[q]) = xr[q];
-    }
+        for (int q = 0; q < XP; ++q) dst[q] = *reinterpret_cast<const td_u32x4*>(xsrc[q] + off);
+    };
+    auto stash_x = [&](const td_u32x4 (&src)[XP], int buf) {
+        unsigned char* nb = lds + buf * (kTB * kXPitch);
+#pragma unroll
+        for (int q = 0; q < XP; ++q) *reinterpret_cast<td_u32x4*>(nb + xdst[q]) = src[q];
+    };
+    load_x(xa, 0);
+    load_x(xb, 1);
+    asm volatile("" ::: "memory");   // issue order = program order from here on
+    load_w(w0, 0);
+    load_w(w1, 1);
+    asm volatile("" ::: "memory");
+    stash_x(xa, 0);
     __syncthreads();
 
-    for (int ch = 0; ch < chunks_per_split; ++ch) {
-        const bool more = ch + 1 < chunks_per_split;
-        if (more) {
-#pragma unroll
-            for (int s = 0; s < 8; ++s) wb[s] = td_load_stream16(wsrc + (size_t)(ch + 1) * kChunk + s * 64);
-#pragma unroll
-            for (int q = 0; q < XP; ++q)
-                xr[q] = xok[q] ? *reinterpret_cast<const td_u32x4*>(xsrc[q] + (size_t)(ch + 1) * kChunk)
-                               : td_u32x4{0, 0, 0, 0};
-        }
-        const unsigned char* xb = lds + (ch & 1) * (kTB * kXPitch) + l16 * kXPitch + g * 16;
+    // step ch: tokens of chunk ch+2 -> xl, weights of chunk ch+2 -> pre, multiply cur, tokens of
+    // chunk ch+1 (xs, requested one step ago) -> LDS
+    auto step = [&](td_u32x4 (&cur)[8], td_u32x4 (&pre)[8], td_u32x4 (&xl)[XP], td_u32x4 (&xs)[XP], int ch) {
+        load_x(xl, ch + 2);
+        asm volatile("" ::: "memory");
+        load_w(pre, ch + 2);
+        asm volatile("" ::: "memory");
+        const unsigned char* xf0 = lds + (ch & 1) * (kTB * kXPitch) + l16 * kXPitch + g * 16;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
 #pragma unroll
             for (int tt = 0; tt < NT; ++tt) {
-                const td_u32x4 xf = *reinterpret_cast<const td_u32x4*>(xb + tt * 16 * kXPitch + s * 64);
-                acc[tt] = TOKEN_ROWS ? mma16<I8>(xf, wa[s], acc[tt]) : mma16<I8>(wa[s], xf, acc[tt]);
+                const td_u32x4 xf = *reinterpret_cast<const td_u32x4*>(xf0 + tt * 16 * kXPitch + s * 64);
+                acc[tt] = TOKEN_ROWS ? mma16<I8>(xf, cur[s], acc[tt]) : mma16<I8>(cur[s], xf, acc[tt]);
             }
         }
-        if (more) {
-            unsigned char* nb = lds + ((ch + 1) & 1) * (kTB * kXPitch);
-#pragma unroll
-            for (int q = 0; q < XP; ++q) *reinterpret_cast<td_u32x4*>(nb + xdst[q]) = xr[q];
-#pragma unroll
-            for (int s = 0; s < 8; ++s) wa[s] = wb[s];
-        }
+        stash_x(xs, (ch + 1) & 1);
         __syncthreads();
+    };
+    if constexpr (NCH > 0) {
+#pragma unroll
+        for (int ch = 0; ch < NCH; ch += 6) {
+            step(w0, w2, xa, xb, ch);
+            if (ch + 1 < NCH) step(w1, w0, xb, xa, ch + 1);
+            if (ch + 2 < NCH) step(w2, w1, xa, xb, ch + 2);
+            if (ch + 3 < NCH) step(w0, w2, xb, xa, ch + 3);
+            if (ch + 4 < NCH) step(w1, w0, xa, xb, ch + 4);
+            if (ch + 5 < NCH) step(w2, w1, xb, xa, ch + 5);
+        }
+    } else {
+        for (int ch = 0; ch <= last; ch += 6) {   // chunk counts are uniform over the block
+            step(w0, w2, xa, xb, ch);
+            if (ch + 1 > last) break;
+            step(w1, w0, xb, xa, ch + 1);
+            if (ch + 2 > last) break;
+            step(w2, w1, xa, xb, ch + 2);
+            if (ch + 3 > last) break;
+            step(w0, w2, xb, xa, ch + 3);
+            if (ch + 4 > last) break;
+            step(w1, w0, xa, xb, ch + 4);
+            if (ch + 5 > last) break;
+            step(w2, w1, xb, xa, ch + 5);
+        }
     }
 
     // ------------------------------------------------------------------ epilogues
@@ -265,20 +307,21 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p, int row_block, 
 constexpr int kStreamLds = 2 * kTB * kXPitch + 1024;
 
 // fold (bf16, blocks [0, fold_blocks)) and predictor (int8, the rest) in one launch
-template <int NT>
+// FCH, PCH: compile-time chunk counts of the fold / predictor rows (0 = run time)
+template <int NT, int FCH, int PCH>
 __global__ void __launch_bounds__(256)
 fold_predict_batched_kernel(StreamArgs fold, StreamArgs pred, int fold_blocks, int fold_chunks, int pred_chunks) {
     extern __shared__ __align__(16) unsigned char lds[];
     if ((int)blockIdx.x < fold_blocks)
-        stream_body<false, NT, EPI_FOLD>(fold, blockIdx.x, 0, fold_chunks, lds);
+        stream_body<false, NT, EPI_FOLD, FCH>(fold, blockIdx.x, 0, fold_chunks, lds);
     else
-        stream_body<true, NT, EPI_PRED>(pred, (int)blockIdx.x - fold_blocks, 0, pred_chunks, lds);
+        stream_body<true, NT, EPI_PRED, PCH>(pred, (int)blockIdx.x - fold_blocks, 0, pred_chunks, lds);
 }
 
-template <int NT, int EPI>
+template <int NT, int EPI, int NCH>
 __global__ void __launch_bounds__(256) stream_kernel(StreamArgs p, int chunks_per_split) {
     extern __shared__ __align__(16) unsigned char lds[];
-    stream_body<false, NT, EPI>(p, blockIdx.x, blockIdx.y, chunks_per_split, lds);
+    stream_body<false, NT, EPI, NCH>(p, blockIdx.x, blockIdx.y, chunks_per_split, lds);
 }
 
 // per token: max|x|, exponent, int8 code (one block per token)
@@ -304,57 +347,93 @@ __global__ void __launch_bounds__(256) fill_u32_kernel(uint32_t* __restrict__ p,
 }
 
 // gather scatter for up to 16 tokens: thread = one output column, tokens in registers;
-// blockIdx.y = segment of the union list.  partial[seg][t][c] = sum_i delta[j_i][t] * W2T[j_i][c]
+// blockIdx.y = segment of the union list.  partial[seg][t][c] = sum_i delta[j_i][t] * W2T[j_i][c].
+// The segment is walked in batches of 64 neurons whose indices and 16 repair factors are staged
+// in LDS; the W2^T elements of all 64 neurons are requested back to back.
 __global__ void __launch_bounds__(256)
 scatter_gather_kernel(const bf16_t* __restrict__ W2T, const bf16_t* __restrict__ delta, const int32_t* __restrict__ ulist,
                       const int32_t* __restrict__ ucount, int h, int d, int n_tok, float* __restrict__ partial) {
-    const int c = (int)blockIdx.x * 256 + threadIdx.x;
+    __shared__ int js[64];
+    __shared__ __align__(16) bf16_t ds[64][kGatherTok];
+    const int c = min((int)blockIdx.x * 256 + (int)threadIdx.x, d - 1);
     const int count = min(*ucount, h);
     const int len = (count + kGatherSegs - 1) / kGatherSegs;
     const int i0 = (int)blockIdx.y * len, i1 = min(count, i0 + len);
     float acc[kGatherTok];
 #pragma unroll
     for (int t = 0; t < kGatherTok; ++t) acc[t] = 0.0f;
-    if (c < d) {
-#pragma unroll 4
-        for (int i = i0; i < i1; ++i) {
-            const int j = ulist[i];
-            const float w = td_bf16_to_f32(__builtin_nontemporal_load(W2T + (size_t)j * d + c));
-            const td_u32x4* dp = reinterpret_cast<const td_u32x4*>(delta + (size_t)j * kTB);
-            const td_u32x4 d0 = dp[0], d1 = dp[1];
-            const uint32_t dw[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+    for (int b0 = i0; b0 < i1; b0 += 64) {
+        const int nb = min(64, i1 - b0);
+        __syncthreads();
+        {   // 64 neurons x 32 bytes of repair factors: thread = (neuron tid/4, 8-byte piece tid%4)
+            const int r = threadIdx.x >> 2, piece = threadIdx.x & 3;
+            const int j = ulist[b0 + min(r, nb - 1)];
+            if (piece == 0) js[r] = j;
+            *reinterpret_cast<uint2*>(&ds[r][piece * 4]) =
+                *reinterpret_cast<const uint2*>(delta + (size_t)j * kTB + piece * 4);
+        }
+        __syncthreads();
+        // all 64 elements of this batch are requested before the first is used
+        uint16_t w[64];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                acc[2 * u] = fmaf(__uint_as_float(dw[u] << 16), w, acc[2 * u]);
-                acc[2 * u + 1] = fmaf(__uint_as_float(dw[u] & 0xFFFF0000u), w, acc[2 * u + 1]);
+        for (int k = 0; k < 64; ++k) w[k] = __builtin_nontemporal_load(W2T + (size_t)js[min(k, nb - 1)] * d + c);
+#pragma unroll
+        for (int k = 0; k < 64; ++k) {
+            if (k < nb) {
+                const float wf = td_bf16_to_f32(w[k]);
+                const td_u32x4 d0 = *reinterpret_cast<const td_u32x4*>(&ds[k][0]);
+                const td_u32x4 d1 = *reinterpret_cast<const td_u32x4*>(&ds[k][8]);
+                const uint32_t dw[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    acc[2 * u] = fmaf(__uint_as_float(dw[u] << 16), wf, acc[2 * u]);
+                    acc[2 * u + 1] = fmaf(__uint_as_float(dw[u] & 0xFFFF0000u), wf, acc[2 * u + 1]);
+                }
             }
         }
-        for (int t = 0; t < n_tok; ++t) partial[((size_t)blockIdx.y * kTB + t) * d + c] = acc[t];
     }
+    if ((int)blockIdx.x * 256 + (int)threadIdx.x < d)
+        for (int t = 0; t < n_tok; ++t) partial[((size_t)blockIdx.y * kTB + t) * d + c] = acc[t];
 }
 
-// y[t] = yfold[t] + sum_s partial[s][t], optional RMS norm, conversion (one block per token)
-__global__ void __launch_bounds__(256)
+// y[t] = yfold[t] + sum_s partial[s][t], optional RMS norm, conversion.  One block of 1024
+// threads per token, 4 columns per thread per step; d is a multiple of 4.
+__global__ void __launch_bounds__(1024)
 finish_batched_kernel(const float* __restrict__ yfold, const float* __restrict__ partial, int nparts, int d,
                       bf16_t* __restrict__ y, int norm_out, float eps) {
-    __shared__ float red[4];
-    extern __shared__ float row[];
+    __shared__ float red[16];
+    extern __shared__ __align__(16) float row[];
     const int t = blockIdx.x;
     float ss = 0.0f;
-    for (int k = threadIdx.x; k < d; k += 256) {
-        float v = yfold[(size_t)t * d + k];
-        for (int s = 0; s < nparts; ++s) v += partial[((size_t)s * kTB + t) * d + k];
-        row[k] = v;
-        ss += v * v;
+    for (int k4 = threadIdx.x; k4 < d / 4; k4 += 1024) {
+        f32x4_t v = reinterpret_cast<const f32x4_t*>(yfold + (size_t)t * d)[k4];
+        f32x4_t part[16];
+#pragma unroll
+        for (int s = 0; s < 16; ++s)
+            part[s] = s < nparts ? reinterpret_cast<const f32x4_t*>(partial + ((size_t)s * kTB + t) * d)[k4]
+                                 : f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int s = 0; s < 16; ++s) v += part[s];
+        reinterpret_cast<f32x4_t*>(row)[k4] = v;
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
     float scale = 1.0f;
     if (norm_out) {
         ss = td_wave_sum(ss);
         if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
         __syncthreads();
-        scale = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
+        float tot = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) tot += red[w];
+        scale = 1.0f / sqrtf(tot / (float)d + eps);
     }
-    for (int k = threadIdx.x; k < d; k += 256) y[(size_t)t * d + k] = td_f32_to_bf16(row[k] * scale);
+    for (int k4 = threadIdx.x; k4 < d / 4; k4 += 1024) {
+        const f32x4_t v = reinterpret_cast<const f32x4_t*>(row)[k4] * scale;
+        uint2 o;
+        o.x = (uint32_t)td_f32_to_bf16(v.x) | ((uint32_t)td_f32_to_bf16(v.y) << 16);
+        o.y = (uint32_t)td_f32_to_bf16(v.z) | ((uint32_t)td_f32_to_bf16(v.w) << 16);
+        reinterpret_cast<uint2*>(y + (size_t)t * d)[k4] = o;
+    }
 }
 
 inline int div_up(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
@@ -403,8 +482,12 @@ tardis_status_t pass_t(tardis_layer_s* L, const bf16_t* x, int nt, bf16_t* y, ui
     pred.ulist = L->bt_ulist;
     pred.ucount = L->bt_ucount;
     const int fold_blocks = div_up(d, kRowsPerBlock), pred_blocks = div_up(h, kRowsPerBlock);
-    hipLaunchKernelGGL(fold_predict_batched_kernel<NT>, dim3(fold_blocks + pred_blocks), dim3(256), kStreamLds, s, fold,
-                       pred, fold_blocks, d * 2 / kChunk, d / kChunk);
+    if (d == 4096)
+        hipLaunchKernelGGL((fold_predict_batched_kernel<NT, 16, 8>), dim3(fold_blocks + pred_blocks), dim3(256),
+                           kStreamLds, s, fold, pred, fold_blocks, 16, 8);
+    else
+        hipLaunchKernelGGL((fold_predict_batched_kernel<NT, 0, 0>), dim3(fold_blocks + pred_blocks), dim3(256),
+                           kStreamLds, s, fold, pred, fold_blocks, d * 2 / kChunk, d / kChunk);
 
     StreamArgs del = base;
     del.W = static_cast<const unsigned char*>(L->W1);
@@ -419,8 +502,11 @@ tardis_status_t pass_t(tardis_layer_s* L, const bf16_t* x, int nt, bf16_t* y, ui
     del.c = L->c;
     del.delta = L->bt_delta;
     del.delta_token_major = gather_scatter ? 0 : 1;
-    hipLaunchKernelGGL((stream_kernel<NT, EPI_DELTA>), dim3(pred_blocks, 1), dim3(256), kStreamLds, s, del,
-                       d * 2 / kChunk);
+    if (d == 4096)
+        hipLaunchKernelGGL((stream_kernel<NT, EPI_DELTA, 16>), dim3(pred_blocks, 1), dim3(256), kStreamLds, s, del, 16);
+    else
+        hipLaunchKernelGGL((stream_kernel<NT, EPI_DELTA, 0>), dim3(pred_blocks, 1), dim3(256), kStreamLds, s, del,
+                           d * 2 / kChunk);
 
     int nparts;
     if (gather_scatter) {
@@ -436,10 +522,14 @@ tardis_status_t pass_t(tardis_layer_s* L, const bf16_t* x, int nt, bf16_t* y, ui
         down.M = d;
         down.X = reinterpret_cast<const unsigned char*>(L->bt_delta);
         down.partial = L->bt_partial;
-        hipLaunchKernelGGL((stream_kernel<NT, EPI_DOWN>), dim3(fold_blocks, kDownSplits), dim3(256), kStreamLds, s,
-                           down, h * 2 / kChunk / kDownSplits);
+        if (h == 16384)
+            hipLaunchKernelGGL((stream_kernel<NT, EPI_DOWN, 8>), dim3(fold_blocks, kDownSplits), dim3(256), kStreamLds,
+                               s, down, 8);
+        else
+            hipLaunchKernelGGL((stream_kernel<NT, EPI_DOWN, 0>), dim3(fold_blocks, kDownSplits), dim3(256), kStreamLds,
+                               s, down, h * 2 / kChunk / kDownSplits);
     }
-    hipLaunchKernelGGL(finish_batched_kernel, dim3(nt), dim3(256), (size_t)d * sizeof(float), s, yfold, L->bt_partial,
+    hipLaunchKernelGGL(finish_batched_kernel, dim3(nt), dim3(1024), (size_t)d * sizeof(float), s, yfold, L->bt_partial,
                        nparts, d, y, norm_out, kRmsEps);
     TD_HIP(hipGetLastError());
     return TARDIS_OK;
@@ -460,15 +550,24 @@ size_t td_batched_partial_floats(const tardis_layer_s* L) {
 tardis_status_t td_batched_init() {
     static bool done = false;
     if (done) return TARDIS_OK;
-    TD_HIP(allow_big_lds(fold_predict_batched_kernel<1>));
-    TD_HIP(allow_big_lds(fold_predict_batched_kernel<2>));
-    TD_HIP(allow_big_lds(fold_predict_batched_kernel<4>));
-    TD_HIP(allow_big_lds(stream_kernel<1, EPI_DELTA>));
-    TD_HIP(allow_big_lds(stream_kernel<2, EPI_DELTA>));
-    TD_HIP(allow_big_lds(stream_kernel<4, EPI_DELTA>));
-    TD_HIP(allow_big_lds(stream_kernel<1, EPI_DOWN>));
-    TD_HIP(allow_big_lds(stream_kernel<2, EPI_DOWN>));
-    TD_HIP(allow_big_lds(stream_kernel<4, EPI_DOWN>));
+    TD_HIP((allow_big_lds(fold_predict_batched_kernel<1, 0, 0>)));
+    TD_HIP((allow_big_lds(fold_predict_batched_kernel<2, 0, 0>)));
+    TD_HIP((allow_big_lds(fold_predict_batched_kernel<4, 0, 0>)));
+    TD_HIP((allow_big_lds(fold_predict_batched_kernel<1, 16, 8>)));
+    TD_HIP((allow_big_lds(fold_predict_batched_kernel<2, 16, 8>)));
+    TD_HIP((allow_big_lds(fold_predict_batched_kernel<4, 16, 8>)));
+    TD_HIP((allow_big_lds(stream_kernel<1, EPI_DELTA, 0>)));
+    TD_HIP((allow_big_lds(stream_kernel<2, EPI_DELTA, 0>)));
+    TD_HIP((allow_big_lds(stream_kernel<4, EPI_DELTA, 0>)));
+    TD_HIP((allow_big_lds(stream_kernel<1, EPI_DELTA, 16>)));
+    TD_HIP((allow_big_lds(stream_kernel<2, EPI_DELTA, 16>)));
+    TD_HIP((allow_big_lds(stream_kernel<4, EPI_DELTA, 16>)));
+    TD_HIP((allow_big_lds(stream_kernel<1, EPI_DOWN, 0>)));
+    TD_HIP((allow_big_lds(stream_kernel<2, EPI_DOWN, 0>)));
+    TD_HIP((allow_big_lds(stream_kernel<4, EPI_DOWN, 0>)));
+    TD_HIP((allow_big_lds(stream_kernel<1, EPI_DOWN, 8>)));
+    TD_HIP((allow_big_lds(stream_kernel<2, EPI_DOWN, 8>)));
+    TD_HIP((allow_big_lds(stream_kernel<4, EPI_DOWN, 8>)));
     done = true;
     return TARDIS_OK;
 }

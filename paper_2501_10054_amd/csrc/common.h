@@ -70,6 +70,7 @@ struct tardis_layer_s {
     bf16_t* bt_delta;              // 64 x h repair factors
     float* bt_partial;             // partial products of the scatter step
     int32_t use_batched;
+    int32_t batched_min_tokens;    // token counts up to this go through the single-token path
     int64_t last_n;    // token count of the most recent online call
 };
 

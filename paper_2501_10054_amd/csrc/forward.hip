@@ -229,7 +229,8 @@ tardis_status_t forward_t(tardis_layer_s* L, const void* xv, int64_t n, void* yv
     const int gemv_blocks = div_up(d, kWaves * kGemvRowsPerWave);
     const int pred_blocks = div_up(h, 32);
     const int fix_blocks = 256;
-    if (n > 1 && L->use_batched) return td_forward_batched(L, xv, n, yv, norm_out, s);
+    // a handful of tokens is faster through the single-token kernel (one launch each)
+    if (n > L->batched_min_tokens && L->use_batched) return td_forward_batched(L, xv, n, yv, norm_out, s);
     if (L->use_fused) {
         for (int64_t t = 0; t < n; ++t)
             TD_TRY(td_decode_fused(L, static_cast<const T*>(xv) + t * d, static_cast<T*>(yv) + t * d,
