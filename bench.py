@@ -38,6 +38,87 @@ def algorithmic_bytes(d: int, h: int, p: float) -> float:
     return 2.0 * d * d + 1.0 * d * h + 4.0 * p * d * h
 
 
+def _time_us(torch, fn, reps, warm=2):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    st = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(st)
+    for _ in range(reps):
+        fn()
+    e1.record(st)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps
+
+
+def prefill_run(T, synth, torch, np, to_dev):
+    """2048 tokens x d=4096 through one layer (passes of 64 tokens) against the dense FFN as two
+    vendor-BLAS GEMMs; also the offline fold/calibration GEMM rate on the matrix cores."""
+    n = 2048
+    w = synth.decode(layer=0, n_cal=4096, n_test=n, coverage=0.95, config=3)
+    ffn = T.FFN(to_dev(w.layer.W1), to_dev(w.layer.W2))
+    Xc = to_dev(w.X_cal)
+    lo, hi, a, c = T.tardis_calibrate(ffn, Xc, w.coverage)
+    cal_us = _time_us(torch, lambda: T.tardis_calibrate(ffn, Xc, w.coverage), 3, 1)
+    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=n)
+    t0 = time.time()
+    L2 = T.tardis_fold(ffn, lo, hi, a, c, max_batch=1)
+    torch.cuda.synchronize()
+    fold_ms = (time.time() - t0) * 1e3
+    L2.close()
+    X = to_dev(w.X_test)
+    Y = torch.empty_like(X)
+    us = _time_us(torch, lambda: T.tardis_ffn_forward_batched(L, X, Y), 5, 1)
+    _, counts, _ = T.tardis_get_last_outliers(L, n, want_list=False)
+    p = float(counts.float().mean().item()) / H
+    W1, W2 = ffn.W1, ffn.W2
+    dus = _time_us(torch, lambda: torch.nn.functional.linear(
+        torch.nn.functional.gelu(torch.nn.functional.linear(X, W1)), W2), 5, 1)
+    L.close()
+    gemm_flop = 2.0 * D * D * H          # one of the two accumulating fold GEMMs, or the calibration GEMM
+    return {"tokens": n, "fallback_rate": p, "us": us, "tokens_per_s": n / (us * 1e-6),
+            "dense_torch_us": dus, "dense_torch_TFLOPs": (2.0 * 2 * n * D * H) / dus / 1e6,
+            "speedup_vs_dense_torch": dus / us,
+            "calibrate_us": cal_us, "fold_ms_incl_alloc": fold_ms,
+            "note": "fold = 2 bf16 MFMA GEMMs of %.0f GFLOP each (head + remainder of diag(a)W1); "
+                    "calibrate = 1 such GEMM + per-neuron sort/fit" % (gemm_flop / 1e9)}
+
+
+def stack_run(T, synth, torch, np, to_dev, n_layers):
+    """n_layers independent layers chained with RMS-norm glue, batch 1 and 32."""
+    layers = []
+    for li in range(n_layers):
+        w = synth.decode(layer=li, n_cal=2048, n_test=32, coverage=0.95, config=4)
+        ffn = T.FFN(to_dev(w.layer.W1), to_dev(w.layer.W2))
+        lo, hi, a, c = T.tardis_calibrate(ffn, to_dev(w.X_cal), w.coverage)
+        layers.append(T.tardis_fold(ffn, lo, hi, a, c, max_batch=32))
+        if li == 0:
+            X = to_dev(w.X_test)
+    out = {"layers": n_layers}
+    for B in (1, 32):
+        xb = X[:B].contiguous()
+        yb = torch.empty_like(xb)
+        us = _time_us(torch, lambda: T.tardis_stack_forward(layers, xb, yb), 10, 2)
+        rates = []
+        for L in layers:
+            _, cnt, _ = T.tardis_get_last_outliers(L, B, want_list=False)
+            rates.append(float(cnt.float().mean().item()) / H)
+        def dense_stack():
+            h_ = xb
+            for L in layers:
+                h_ = torch.nn.functional.linear(torch.nn.functional.gelu(torch.nn.functional.linear(h_, L.ffn.W1)), L.ffn.W2)
+                h_ = torch.nn.functional.rms_norm(h_, (D,), eps=1e-6)
+            return h_
+        dus = _time_us(torch, dense_stack, 10, 2)
+        out[f"batch{B}"] = {"us_per_step": us, "tokens_per_s": B / (us * 1e-6), "dense_torch_us_per_step": dus,
+                            "speedup_vs_dense_torch": dus / us,
+                            "per_layer_fallback_rate": [round(r, 4) for r in rates]}
+    for L in layers:
+        L.close()
+    return out
+
+
 def batched_sweep(T, synth, torch, np, to_dev, n_layers):
     """Batched decode: tokens/s, algorithmic GB/s and union size per (batch, coverage), cold over
     `n_layers` seeded layer copies, against the vendor-BLAS dense FFN at the same batch."""
@@ -100,6 +181,8 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of a replayed HIP graph")
     ap.add_argument("--sweep", action="store_true",
                     help="also run the batched decode sweep: batch {4,16,64} x coverage {0.99,0.95,0.85}")
+    ap.add_argument("--prefill", action="store_true", help="also run the 2048-token prefill shape")
+    ap.add_argument("--stack", type=int, default=0, help="also run a stack of this many layers (32 = the full configuration)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a 1 GiB device copy (known HBM traffic) so that profiler counters can be scaled")
     args = ap.parse_args()
@@ -288,6 +371,10 @@ def main() -> int:
         out["speedup_vs_dense_own"] = tok_s / res_dense["dense_own_tokens_per_s"]
     if args.sweep:
         out["batched_sweep"] = batched_sweep(T, synth, torch, np, to_dev, args.layers)
+    if args.prefill:
+        out["prefill"] = prefill_run(T, synth, torch, np, to_dev)
+    if args.stack > 0:
+        out["stack"] = stack_run(T, synth, torch, np, to_dev, args.stack)
     if args.copy_probe:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
