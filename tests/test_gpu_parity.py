@@ -249,6 +249,65 @@ def test_per_neuron_coverage_and_single_calibration_token():
     np.testing.assert_allclose(c.cpu().numpy(), oc, rtol=1e-5, atol=1e-5)
 
 
+def test_calibrate_many_samples_uses_large_lds():
+    # 20000 calibration tokens: the per-neuron sort needs 128 KiB of LDS (padded to 32768 samples)
+    seed = synth.workload_seed(9, 3)
+    layer = synth.make_layer(64, 128, "f32", seed, w1_std=0.2, w2_std=0.05)
+    X_cal = synth.make_tokens(20000, 64, "f32", seed, synth.STREAM_CAL)
+    ffn = make_ffn(layer)
+    lo, hi, a, c = T.tardis_calibrate(ffn, dev(X_cal, "f32"), 0.95)
+    olo, ohi, oa, oc = O.calibrate(layer.W1, None, X_cal, 0.95)
+    assert np.abs(lo.cpu().numpy() - olo).max() < 2e-5 and np.abs(hi.cpu().numpy() - ohi).max() < 2e-5
+    assert np.abs(a.cpu().numpy() - oa).max() < 1e-3 and np.abs(c.cpu().numpy() - oc).max() < 1e-3
+
+
+def test_fused_kernel_with_ragged_hidden_width_and_bias():
+    # d = 2048 takes the single-launch kernel; h = 1000 is neither a multiple of 32 nor of the
+    # per-block neuron count, and the layer has biases
+    seed = synth.workload_seed(9, 4)
+    layer = synth.make_layer(2048, 1000, "bf16", seed, w1_std=0.03, w2_std=0.03, heavy_frac=0.01, with_bias=True)
+    X_cal = synth.make_tokens(256, 2048, "bf16", seed, synth.STREAM_CAL)
+    X_test = synth.make_tokens(5, 2048, "bf16", seed, synth.STREAM_TEST)
+    run_case(layer, X_cal, X_test, 0.9, check_calibrate=False)
+
+
+def test_fused_kernel_many_flagged_per_block():
+    # 40 % fallback: every block repairs far more neurons than one pass holds
+    w = synth.decode(d=1024, h=4096, n_cal=256, n_test=4, coverage=0.6, config=9)
+    r = run_case(w.layer, w.X_cal, w.X_test, 0.6, check_calibrate=False)
+    assert r["rate"] > 0.3
+
+
+def test_graph_capture_and_replay_of_forward():
+    # the online call allocates nothing and records no memset: it can be captured and replayed
+    w = synth.decode(d=1024, h=4096, n_cal=256, n_test=6, coverage=0.9, config=9)
+    ffn = make_ffn(w.layer)
+    lo, hi, a, c = T.tardis_calibrate(ffn, dev(w.X_cal, "bf16"), 0.9)
+    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=8)
+    X = dev(w.X_test, "bf16")
+    y_eager = torch.stack([T.tardis_ffn_forward(L, X[t]).clone() for t in range(3)])
+    yb_eager = T.tardis_ffn_forward_batched(L, X).clone()
+    torch.cuda.synchronize()
+    y_g = torch.zeros_like(y_eager)
+    yb_g = torch.zeros_like(yb_eager)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for t in range(3):
+            T.tardis_ffn_forward(L, X[t], y_g[t])
+        T.tardis_ffn_forward_batched(L, X, yb_g)
+    for rep in range(3):
+        y_g.zero_()
+        yb_g.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert rel_l2(host(y_g), host(y_eager)) < 2e-3, rep       # atomic ordering only
+        assert rel_l2(host(yb_g), host(yb_eager)) < 2e-3, rep
+        T.tardis_ffn_forward(L, X[5])                              # eager work between replays
+        torch.cuda.synchronize()
+    L.close()
+
+
 def test_runtime_argument_errors():
     w = synth.tiny()
     ffn = make_ffn(w.layer)
