@@ -29,7 +29,7 @@ TOKENS_PER_STEP = 1024
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of decode_fused_kernel from `rocprofv3 --pmc` (FETCH_SIZE and WRITE_SIZE runs,
 # scaled by a copy kernel of known size); see profiles/*hbm-traffic.md.
-MEASURED_TRAFFIC_BYTES = 119069060
+MEASURED_TRAFFIC_BYTES = 119089537
 
 
 def algorithmic_bytes(d: int, h: int, p: float) -> float:
