@@ -150,19 +150,27 @@ gemm_nt_mfma_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict_
         if (kt + 1 < nk) fetch((int64_t)(kt + 1) * MK);
         const unsigned char* as = lds + (kt & 1) * MSTAGE + (wm * 128 + frow) * MSTRIDE + fk;
         const unsigned char* bs = lds + (kt & 1) * MSTAGE + MT * MSTRIDE + (wn * 128 + frow) * MSTRIDE + fk;
+        // fragments of slice ks+1 are read from LDS while the 16 MFMAs of slice ks run
+        bf16x8_t fa[2][4], fb[2][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            fa[0][i] = *reinterpret_cast<const bf16x8_t*>(as + i * 32 * MSTRIDE);
+            fb[0][i] = *reinterpret_cast<const bf16x8_t*>(bs + i * 32 * MSTRIDE);
+        }
 #pragma unroll
         for (int ks = 0; ks < MK / 16; ++ks) {
-            bf16x8_t fa[4], fb[4];
+            if (ks + 1 < MK / 16) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                fa[i] = *reinterpret_cast<const bf16x8_t*>(as + i * 32 * MSTRIDE + ks * 32);
-                fb[i] = *reinterpret_cast<const bf16x8_t*>(bs + i * 32 * MSTRIDE + ks * 32);
+                for (int i = 0; i < 4; ++i) {
+                    fa[(ks + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(as + i * 32 * MSTRIDE + (ks + 1) * 32);
+                    fb[(ks + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(bs + i * 32 * MSTRIDE + (ks + 1) * 32);
+                }
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
         }
         if (kt + 1 < nk) stash((kt + 1) & 1);
         __syncthreads();

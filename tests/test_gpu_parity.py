@@ -387,17 +387,24 @@ def test_stack_teacher_forced(d, h, dtype, n):
 # ------------------------------------------------ config 1 at full size (d=4096, h=16384, bf16)
 @pytest.fixture(scope="module")
 def decode_full():
-    w = synth.decode(n_cal=4096, n_test=24, coverage=0.95)
+    w = synth.decode(n_cal=4096, n_test=2048, coverage=0.95)
     ffn = make_ffn(w.layer)
     lo, hi, a, c = T.tardis_calibrate(ffn, dev(w.X_cal, "bf16"), w.coverage)
-    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=8)
+    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=2048)
     torch.cuda.synchronize()
-    yield w, ffn, (lo, hi, a, c), L
+    box = {}
+
+    def oracle():
+        if "F" not in box:      # built once: the fp64 fold of the full layer takes several seconds
+            box["F"] = O.build(w.layer.W1, None, w.layer.W2, None, *(t.cpu().numpy() for t in (lo, hi, a, c)))
+        return box["F"]
+
+    yield w, ffn, (lo, hi, a, c), L, oracle
     L.close()
 
 
 def test_full_size_calibrate_on_sampled_neurons(decode_full):
-    w, ffn, (lo, hi, a, c), L = decode_full
+    w, ffn, (lo, hi, a, c), L, _ = decode_full
     rng = np.random.default_rng(0)
     sub = np.sort(rng.choice(w.layer.h, 192, replace=False))
     sub[:4] = w.layer.heavy_neurons[:4]
@@ -413,9 +420,9 @@ def test_full_size_calibrate_on_sampled_neurons(decode_full):
 
 
 def test_full_size_decode_batch1(decode_full):
-    w, ffn, (lo, hi, a, c), L = decode_full
+    w, ffn, (lo, hi, a, c), L, oracle = decode_full
     layer = w.layer
-    F = O.build(layer.W1, None, layer.W2, None, *(t.cpu().numpy() for t in (lo, hi, a, c)))
+    F = oracle()
     Wp, bp = T.tardis_get_folded(L)
     Q, tlo, thi = T.tardis_get_predictor_state(L)
     assert rel_l2(host(Wp), F.Wp) <= 3e-3
@@ -448,7 +455,7 @@ def test_full_size_decode_batch1(decode_full):
 
 
 def test_full_size_batched_matches_per_token(decode_full):
-    w, ffn, _, L = decode_full
+    w, ffn, _, L, _ = decode_full
     Xd = dev(w.X_test[16:24], "bf16")
     Yb = T.tardis_ffn_forward_batched(L, Xd)
     mb, cb, _ = T.tardis_get_last_outliers(L, 8, want_list=False)
@@ -458,3 +465,80 @@ def test_full_size_batched_matches_per_token(decode_full):
         m1, c1, _ = T.tardis_get_last_outliers(L, 1, want_list=False)
         assert torch.equal(m1[0], mb[t]) and int(c1.item()) == int(cb[t].item())
         assert rel_l2(host(y), host(Yb[t])) <= 2e-3            # bf16 output, atomic ordering
+
+
+@pytest.mark.parametrize("B", [16, 64])
+def test_full_size_batched_decode_sampled_tokens(decode_full, B):
+    """Batched decode at the full layer size, in the configuration the sweep times: the checker
+    recomputes a sample of the batch's tokens one by one."""
+    w, ffn, _, L, oracle = decode_full
+    F = oracle()
+    X = w.X_test[100:100 + B]
+    Y = T.tardis_ffn_forward_batched(L, dev(X, "bf16"))
+    mask, counts, _ = T.tardis_get_last_outliers(L, B, want_list=False)
+    torch.cuda.synchronize()
+    FLg = unpack_mask(mask, w.layer.h)
+    for t in sorted({0, 1, B // 2, B - 1}):
+        yo, flo = O.forward_token(F, X[t])
+        np.testing.assert_array_equal(FLg[t], flo)
+        assert int(counts[t].item()) == flo.sum()
+        assert rel_l2(host(Y[t]), yo) <= 1e-2
+    union = FLg.any(axis=0).sum()
+    assert union >= FLg[0].sum()
+
+
+def test_full_size_prefill_sampled_tokens(decode_full):
+    """2048 tokens x d=4096 through the layer (32 passes of 64): sampled tokens against the checker,
+    and every token's flag count against the expected fallback rate."""
+    w, ffn, _, L, oracle = decode_full
+    F = oracle()
+    n = 2048
+    Y = T.tardis_ffn_forward_batched(L, dev(w.X_test, "bf16"))
+    mask, counts, _ = T.tardis_get_last_outliers(L, n, want_list=False)
+    torch.cuda.synchronize()
+    FLg = unpack_mask(mask, w.layer.h)
+    for t in (0, 63, 64, 1000, 2047):
+        yo, flo = O.forward_token(F, w.X_test[t])
+        np.testing.assert_array_equal(FLg[t], flo)
+        assert rel_l2(host(Y[t]), yo) <= 1e-2
+    cnt = counts.cpu().numpy()
+    assert (cnt == FLg.sum(1)).all()
+    assert abs(cnt.mean() / w.layer.h - 0.05) < 0.005
+    assert torch.isfinite(Y.float()).all()
+
+
+def test_full_size_stack_of_three_layers():
+    """Three independent full-size layers chained with the RMS-norm glue at batch 1 and 32; every
+    layer is checked on the input the GPU handed to it (sampled tokens for the batch)."""
+    d, h, nl = 4096, 16384, 3
+    layers, lays, cals = [], [], []
+    for li in range(nl):
+        w = synth.decode(layer=li, n_cal=1024, n_test=32, coverage=0.95, config=4)
+        ffn = make_ffn(w.layer)
+        lo, hi, a, c = T.tardis_calibrate(ffn, dev(w.X_cal, "bf16"), 0.95)
+        layers.append(T.tardis_fold(ffn, lo, hi, a, c, max_batch=32))
+        lays.append(w.layer)
+        cals.append(tuple(t.cpu().numpy() for t in (lo, hi, a, c)))
+        if li == 0:
+            X0 = w.X_test
+    for B, sample in ((1, [0]), (32, [0, 31])):
+        x0 = X0[:B]
+        y = T.tardis_stack_forward(layers, dev(x0, "bf16"))
+        torch.cuda.synchronize()
+        x_in = x0.astype(np.float64)
+        for li in range(nl):
+            F = O.build(lays[li].W1, None, lays[li].W2, None, *cals[li])
+            mask, counts, _ = T.tardis_get_last_outliers(layers[li], B, want_list=False)
+            FLg = unpack_mask(mask, h)
+            xn = host(T.tardis_get_handover(layers[li], B)) if li < nl - 1 else None
+            for t in sample:
+                yo, flo = O.forward_token(F, x_in[t])
+                np.testing.assert_array_equal(FLg[t], flo)
+                if li < nl - 1:
+                    assert rel_l2(xn[t], O.to_bf16(O.rmsnorm(yo[None])[0])) <= 1e-2
+                else:
+                    assert rel_l2(host(y)[t], yo) <= 1e-2
+            del F
+            x_in = xn
+    for L in layers:
+        L.close()
