@@ -93,11 +93,11 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     L->dec_threads = env_int("TARDIS_DECODE_THREADS", 1024, 512, 1024) == 512 ? 512 : 1024;
     L->dec_blocks = env_int("TARDIS_DECODE_BLOCKS", L->dec_threads == 512 ? 512 : 256, 1, 4096);
     L->dec_copies = env_int("TARDIS_DECODE_COPIES", 2, 1, 4);
-    TD_TRY(dev_alloc(&L->yfix, (size_t)L->dec_copies * d * 4));
-    TD_HIP(hipMemsetAsync(L->yfix, 0, (size_t)L->dec_copies * d * 4, s));
+    TD_TRY(dev_alloc(&L->yfix, (size_t)L->dec_copies * kDecodeMaxTokens * d * 4));
+    TD_HIP(hipMemsetAsync(L->yfix, 0, (size_t)L->dec_copies * kDecodeMaxTokens * d * 4, s));
     L->use_fused = env_int("TARDIS_DECODE_FUSED", 1, 0, 1) && td_decode_fused_supported(L);
     L->use_batched = env_int("TARDIS_BATCHED", 1, 0, 1) && td_batched_supported(L);
-    L->batched_min_tokens = env_int("TARDIS_BATCHED_MIN", L->use_fused ? 4 : 1, 1, 64);
+    L->batched_min_tokens = env_int("TARDIS_BATCHED_MIN", L->use_fused ? 8 : 1, 1, 64);
     if (L->use_batched) {
         TD_TRY(td_batched_init());
         TD_TRY(dev_alloc(&L->bt_xq, (size_t)64 * d));

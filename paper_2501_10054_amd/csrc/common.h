@@ -56,7 +56,7 @@ struct tardis_layer_s {
     int32_t* sync;     // small block of device counters (zero between calls)
     void* zeros_h;     // h zero elements of the layer dtype (stands in for a missing b1)
     void* xnext;       // max_batch x d, layer dtype: normalised output handed to the next stacked layer
-    float* yfix;       // dec_copies x d fp32 repair accumulators of the fused decode kernel (zero between calls)
+    float* yfix;       // dec_copies x kDecodeMaxTokens x d fp32 repair accumulators of the fused decode kernel (zero between calls)
     int32_t dec_blocks;   // grid of the fused decode kernel
     int32_t dec_threads;  // block size of the fused decode kernel (512 or 1024)
     int32_t dec_copies;   // number of repair accumulator copies
@@ -166,8 +166,9 @@ tardis_status_t td_gemm_nt(const void* A, const void* B, float* C, int64_t M, in
                            int32_t dtype, int accumulate, const void* row_bias, hipStream_t s);
 // decode.hip
 bool td_decode_fused_supported(const tardis_layer_s* L);
+constexpr int kDecodeMaxTokens = 4;   // tokens the single-launch kernel can share one weight pass between
 tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
-                                int norm_out, hipStream_t s);
+                                int tokens, int norm_out, hipStream_t s);
 tardis_status_t td_mask_to_list(const tardis_layer_s* L, int64_t n, int32_t* counts, int32_t* list, hipStream_t s);
 // batched.hip
 bool td_batched_supported(const tardis_layer_s* L);

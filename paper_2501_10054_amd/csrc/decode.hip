@@ -36,28 +36,34 @@ __device__ __forceinline__ void load_row(td_u32x4 (&dst)[N], const void* row, in
     for (int it = 0; it < N; ++it) dst[it] = td_load_stream16(p + it * TD_WAVE);
 }
 
-template <int D, int BLOCK, int RQ>
+// TB tokens (1, 2 or 4) share one pass over the weights: x, y, yfold are TB x D, mask has TB rows of
+// mask_words words, yfix is copies x TB x D.
+template <int D, int BLOCK, int RQ, int TB>
 __global__ void __launch_bounds__(BLOCK)
 decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp, const int8_t* __restrict__ Q,
                     const float* __restrict__ tlo, const float* __restrict__ thi, const bf16_t* __restrict__ W1,
                     const bf16_t* __restrict__ b1, const bf16_t* __restrict__ W2T, const float* __restrict__ a,
                     const float* __restrict__ c, const bf16_t* __restrict__ x, bf16_t* __restrict__ y,
                     float* __restrict__ yfold, float* __restrict__ yfix, int copies, uint32_t* __restrict__ mask,
-                    int32_t* __restrict__ done, int h, int npb, int rpb, int act, int norm_out, float eps) {
+                    int mask_words, int32_t* __restrict__ done, int h, int npb, int rpb, int act, int norm_out,
+                    float eps) {
     static_assert(D % 1024 == 0, "rows must be whole multiples of 64 lanes x 16 bytes");
     static_assert(D % BLOCK == 0 && BLOCK / TD_WAVE >= 4, "column ownership of the repair pass");
+    static_assert(TB == 1 || TB == 2 || TB == 4, "tokens per pass");
     constexpr int NW = BLOCK / TD_WAVE;
     constexpr int NVW = D / 8;                       // 16-byte vectors per bf16 row
     constexpr int IQ = D / 16 / TD_WAVE;             // per-lane vectors of an int8 row
     constexpr int IW = NVW / TD_WAVE;                // per-lane vectors of a bf16 row
-    constexpr int XI = (NVW + BLOCK - 1) / BLOCK;    // per-thread vectors of the token
+    constexpr int XI = (TB * NVW + BLOCK - 1) / BLOCK;  // per-thread vectors of the tokens
+    constexpr int MW = kMaxNeuronsPerBlock / 32;
 
-    __shared__ __align__(16) bf16_t xs[D];
-    __shared__ __align__(16) int8_t xq[D];
-    __shared__ float dl[NW];                         // delta_j of the neurons being repaired
-    __shared__ int flist[kMaxNeuronsPerBlock];
-    __shared__ uint32_t words[kMaxNeuronsPerBlock / 32];
-    __shared__ float red[NW];
+    __shared__ __align__(16) bf16_t xs[TB * D];
+    __shared__ __align__(16) int8_t xq[TB * D];
+    __shared__ float dl[NW][TB];                     // delta of the neurons being repaired, per token
+    __shared__ int flist[kMaxNeuronsPerBlock];       // neurons flagged by at least one token
+    __shared__ unsigned char fbits[kMaxNeuronsPerBlock];  // which tokens flagged them
+    __shared__ uint32_t words[TB][MW];
+    __shared__ int tmax[TB];                         // max |x| per token (bit pattern of a non-negative float)
     __shared__ int nflag;
     __shared__ int is_last;
 
@@ -68,15 +74,15 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     const int j0 = blk * npb;                        // first neuron of this block
     const int jn = min(npb, h - j0);                 // neurons owned (may be <= 0)
 
-    // ---- the token first (small), then the first batch of predictor rows and their range
+    // ---- the tokens first (small), then the first batch of predictor rows and their range
     //      bounds, all in flight together
     td_u32x4 xv[XI];
 #pragma unroll
     for (int it = 0; it < XI; ++it) {
-        const int v = min(it * BLOCK + tid, NVW - 1);
+        const int v = min(it * BLOCK + tid, TB * NVW - 1);
         xv[it] = reinterpret_cast<const td_u32x4*>(x)[v];
     }
-    asm volatile("" ::: "memory");                   // keep the token's load ahead of the row loads
+    asm volatile("" ::: "memory");                   // keep the tokens' loads ahead of the row loads
     td_u32x4 q[RQ][IQ];
     float tl[RQ], th[RQ];
 #pragma unroll
@@ -88,31 +94,36 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     }
     const float bias_out = bp[min(blk * rpb + wave, D - 1)];
 
-    // ---- stage the token, its max and its int8 code
-    if (tid < kMaxNeuronsPerBlock / 32) words[tid] = 0u;
+    // ---- stage the tokens, their maxima and their int8 codes
+    for (int k = tid; k < TB * MW; k += BLOCK) (&words[0][0])[k] = 0u;
+    if (tid < TB) tmax[tid] = 0;
     if (tid == 0) nflag = 0;
-    float m = 0.0f;
+    __syncthreads();
 #pragma unroll
     for (int it = 0; it < XI; ++it) {
         const int v = it * BLOCK + tid;
-        if (v < NVW) {
+        if (v < TB * NVW) {
             reinterpret_cast<td_u32x4*>(xs)[v] = xv[it];
             const bf16_t* e8 = reinterpret_cast<const bf16_t*>(&xv[it]);
+            float m = 0.0f;
 #pragma unroll
             for (int u = 0; u < 8; ++u) m = fmaxf(m, fabsf(td_bf16_to_f32(e8[u])));
+            m = td_wave_max(m);                      // a wavefront's 64 vectors belong to one token
+            if (lane == 0) atomicMax(&tmax[v / NVW], __float_as_int(m));
         }
     }
-    m = td_wave_max(m);
-    if (lane == 0) red[wave] = m;
     __syncthreads();
-    m = red[0];
+    int ex[TB];
 #pragma unroll
-    for (int w = 1; w < NW; ++w) m = fmaxf(m, red[w]);
-    const int e = token_exponent(m);
+    for (int t = 0; t < TB; ++t) ex[t] = token_exponent(__int_as_float(tmax[t]));
 #pragma unroll
     for (int it = 0; it < XI; ++it) {
         const int v = it * BLOCK + tid;
-        if (v < NVW) {
+        if (v < TB * NVW) {
+            const int tok = v / NVW;
+            int e = ex[0];
+#pragma unroll
+            for (int t = 1; t < TB; ++t) e = tok == t ? ex[t] : e;
             const bf16_t* e8 = reinterpret_cast<const bf16_t*>(&xv[it]);
             uint32_t lo = 0, hi = 0;
 #pragma unroll
@@ -125,7 +136,8 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     }
     __syncthreads();
 
-    // ---- predictor rows: exact int32 dot products, range test, block-local list
+    // ---- predictor rows: exact int32 dot products, range test per token, block-local list of
+    //      the neurons flagged by at least one token
     const td_u32x4* xq4 = reinterpret_cast<const td_u32x4*>(xq) + lane;
     for (int base = 0; base < jn; base += NW * RQ) {
         const int jb = base + wave * RQ;
@@ -138,32 +150,53 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                 th[i] = thi[j];
             }
         }
-        int acc[RQ];
+        // two tokens at a time against the rows held in registers (register budget)
+        constexpr int TP = TB < 2 ? TB : 2;
+        uint32_t bits[RQ];
 #pragma unroll
-        for (int i = 0; i < RQ; ++i) acc[i] = 0;
+        for (int i = 0; i < RQ; ++i) bits[i] = 0u;
 #pragma unroll
-        for (int it = 0; it < IQ; ++it) {
-            const td_u32x4 xx = xq4[it * TD_WAVE];
+        for (int t0 = 0; t0 < TB; t0 += TP) {
+            if (TB > 1) asm volatile("" ::: "memory");
+            int acc[RQ][TP];
+#pragma unroll
+            for (int i = 0; i < RQ; ++i)
+#pragma unroll
+                for (int t = 0; t < TP; ++t) acc[i][t] = 0;
+#pragma unroll
+            for (int it = 0; it < IQ; ++it) {
+#pragma unroll
+                for (int t = 0; t < TP; ++t) {
+                    const td_u32x4 xx = xq4[(t0 + t) * (D / 16) + it * TD_WAVE];
+#pragma unroll
+                    for (int i = 0; i < RQ; ++i) {
+                        acc[i][t] = __builtin_amdgcn_sdot4((int)q[i][it].x, (int)xx.x, acc[i][t], false);
+                        acc[i][t] = __builtin_amdgcn_sdot4((int)q[i][it].y, (int)xx.y, acc[i][t], false);
+                        acc[i][t] = __builtin_amdgcn_sdot4((int)q[i][it].z, (int)xx.z, acc[i][t], false);
+                        acc[i][t] = __builtin_amdgcn_sdot4((int)q[i][it].w, (int)xx.w, acc[i][t], false);
+                    }
+                }
+            }
 #pragma unroll
             for (int i = 0; i < RQ; ++i) {
-                acc[i] = __builtin_amdgcn_sdot4((int)q[i][it].x, (int)xx.x, acc[i], false);
-                acc[i] = __builtin_amdgcn_sdot4((int)q[i][it].y, (int)xx.y, acc[i], false);
-                acc[i] = __builtin_amdgcn_sdot4((int)q[i][it].z, (int)xx.z, acc[i], false);
-                acc[i] = __builtin_amdgcn_sdot4((int)q[i][it].w, (int)xx.w, acc[i], false);
+#pragma unroll
+                for (int t = 0; t < TP; ++t) {
+                    const float v = ldexpf((float)td_wave_sum_i(acc[i][t]), ex[t0 + t]);
+                    const bool inside = (v >= tl[i]) && (v < th[i]);
+                    bits[i] |= inside ? 0u : (1u << (t0 + t));
+                }
             }
         }
 #pragma unroll
         for (int i = 0; i < RQ; ++i) {
-            const int s = td_wave_sum_i(acc[i]);
             const int jl = jb + i;
-            if (jl < jn && lane == 0) {
-                const float v = ldexpf((float)s, e);
-                const bool inside = (v >= tl[i]) && (v < th[i]);
-                if (!inside) {
-                    const int pos = atomicAdd(&nflag, 1);
-                    flist[pos] = j0 + jl;
-                    atomicOr(&words[jl >> 5], 1u << (jl & 31));
-                }
+            if (jl < jn && lane == 0 && bits[i]) {
+#pragma unroll
+                for (int t = 0; t < TB; ++t)
+                    if ((bits[i] >> t) & 1u) atomicOr(&words[t][jl >> 5], 1u << (jl & 31));
+                const int pos = atomicAdd(&nflag, 1);
+                flist[pos] = j0 + jl;
+                fbits[pos] = (unsigned char)bits[i];
             }
         }
     }
@@ -180,93 +213,135 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     for (int it = 0; it < IWA; ++it) wp[it] = td_load_stream16(wp_row + it * TD_WAVE);
 
     __syncthreads();
-    if (jn > 0 && tid < (jn + 31) / 32) mask[(j0 >> 5) + tid] = words[tid];
+    if (jn > 0) {
+        const int nw = (jn + 31) / 32;
+        for (int k = tid; k < TB * nw; k += BLOCK) {
+            const int t = k / nw, w = k % nw;
+            mask[(size_t)t * mask_words + (j0 >> 5) + w] = words[t][w];
+        }
+    }
     const int nf = nflag;
 
-    // ---- result fixing.  z_j and delta_j: one wavefront per flagged neuron (16-byte loads of
-    //      W1[j], shuffle reduction).  y += delta_j * W2[:, j]: every thread owns the output
-    //      columns tid, tid + BLOCK, ... and reads them from W2^T[j] with 2-byte loads (a
-    //      wavefront reads 128 contiguous bytes), so the block's repair vector lives in
-    //      registers and needs no LDS traffic.
+    // ---- result fixing.  z and delta: one wavefront per flagged neuron (16-byte loads of
+    //      W1[j], shuffle reduction), for the tokens that flagged it.  y += delta * W2[:, j]:
+    //      every thread owns the output columns tid, tid + BLOCK, ... and reads them from
+    //      W2^T[j] with 2-byte loads (a wavefront reads 128 contiguous bytes), so the block's
+    //      repair vectors live in registers and need no LDS traffic.
     constexpr int CPT = D / BLOCK;                   // output columns per thread
-    constexpr int FCH = (24 / CPT) < NW ? (24 / CPT) : NW;  // flagged neurons per pass (24 row registers)
-    float yacc[CPT];
+    constexpr int WREG = TB == 1 ? 24 : 16;          // registers holding W2^T elements per pass
+    constexpr int FCH = (WREG / CPT) < NW ? (WREG / CPT) : NW;  // flagged neurons per pass
+    float yacc[TB][CPT];
 #pragma unroll
-    for (int u = 0; u < CPT; ++u) yacc[u] = 0.0f;
-    if (nf == 0) {
+    for (int t = 0; t < TB; ++t)
 #pragma unroll
-        for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * TD_WAVE);
-    }
-    for (int f0 = 0; f0 < nf; f0 += FCH) {
-        asm volatile("" ::: "memory");   // re-read the token from LDS here instead of keeping it in registers
+        for (int u = 0; u < CPT; ++u) yacc[t][u] = 0.0f;
+    // the columns a thread owns are rotated by a block-dependent number of wavefronts, so that
+    // the blocks' atomic passes do not all start on the same cache lines
+    const int ctid = (tid + TD_WAVE * (blk >> 3)) & (BLOCK - 1);
+    // one pass over up to FCH flagged neurons.  The first pass is straight-line code (no
+    // loop-carried register state), and it also requests the second half of this wave's W' row
+    // BEHIND the repair's loads (loads return in order): it is consumed after the repair and
+    // streams in while the repair's dependent steps run.
+    auto repair_pass = [&](auto first_tag, const int f0) {
+        constexpr bool kFirst = decltype(first_tag)::value;
+        asm volatile("" ::: "memory");   // re-read the tokens from LDS here instead of keeping them in registers
         const int fi = f0 + wave;
         const bool fixer = wave < FCH && fi < nf;
         td_u32x4 w1[IW];
-        int jz = 0;
-        float aj = 0.0f, cj = 0.0f, bj = 0.0f;
+        float aj = 0.0f, cj = 0.0f;
+        uint32_t bj_raw = 0;
         if (fixer) {
-            jz = flist[fi];
+            const int jz = flist[fi];
             load_row<IW>(w1, W1 + (size_t)jz * D, lane);
             aj = a[jz];
             cj = c[jz];
-            bj = td_bf16_to_f32(b1[jz]);                // b1 is never null here (zeros if the layer has no bias)
+            bj_raw = b1[jz];                         // b1 is never null here (zeros if the layer has no bias)
         }
         uint16_t w2[FCH][CPT];                       // requested before z is known: one round trip in all
 #pragma unroll
         for (int i = 0; i < FCH; ++i) {
             const int j = flist[min(f0 + i, nf - 1)];
-            const bf16_t* row = W2T + (size_t)j * D + tid;
+            const bf16_t* row = W2T + (size_t)j * D + ctid;
 #pragma unroll
             for (int u = 0; u < CPT; ++u) w2[i][u] = __builtin_nontemporal_load(row + u * BLOCK);
         }
-        // the second half of this wave's W' row is requested BEHIND the repair's loads (loads
-        // return in order) and consumed after the repair, so that it streams in while the
-        // repair's dependent steps run
-        if (f0 == 0) {
+        if (kFirst) {
             asm volatile("" ::: "memory");
 #pragma unroll
             for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * TD_WAVE);
         }
+        // nothing above may wait for a load: the conversion of b1 is pinned below this point
+        asm volatile("" : "+v"(bj_raw), "+v"(aj), "+v"(cj));
         if (fixer) {
-            float z = 0.0f;
+            const float bj = td_bf16_to_f32((bf16_t)bj_raw);
+            const uint32_t zbits = fbits[fi];
 #pragma unroll
-            for (int it = 0; it < IW; ++it) z = RowVec<bf16_t>::dot(w1[it], xs4[it * TD_WAVE], z);
-            z = td_wave_sum(z);
-            z += bj;
-            if (lane == 0) dl[wave] = td_act(z, act) - fmaf(aj, z, cj);
+            for (int t = 0; t < TB; ++t) {
+                if (TB > 1) asm volatile("" ::: "memory");   // one token's LDS reads at a time (register budget)
+                float z = 0.0f;
+#pragma unroll
+                for (int it = 0; it < IW; ++it) z = RowVec<bf16_t>::dot(w1[it], xs4[t * NVW + it * TD_WAVE], z);
+                z = td_wave_sum(z) + bj;
+                const float dv = ((zbits >> t) & 1u) ? td_act(z, act) - fmaf(aj, z, cj) : 0.0f;
+                if (lane == 0) dl[wave][t] = dv;
+            }
         }
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < FCH; ++i) {
-            const float delta = (f0 + i < nf) ? dl[i] : 0.0f;
+            if (f0 + i < nf) {
 #pragma unroll
-            for (int u = 0; u < CPT; ++u) yacc[u] = fmaf(delta, td_bf16_to_f32(w2[i][u]), yacc[u]);
+                for (int t = 0; t < TB; ++t) {
+                    const float delta = dl[i][t];
+#pragma unroll
+                    for (int u = 0; u < CPT; ++u)
+                        yacc[t][u] = fmaf(delta, td_bf16_to_f32(w2[i][u]), yacc[t][u]);
+                }
+            }
         }
         __syncthreads();
+    };
+    if (nf == 0) {
+#pragma unroll
+        for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * TD_WAVE);
+    } else {
+        repair_pass(std::true_type{}, 0);
+        for (int f0 = FCH; f0 < nf; f0 += FCH) repair_pass(std::false_type{}, f0);
     }
 
-    // ---- one coalesced atomic pass per block into an accumulator copy (fire and forget)
-    if (nf > 0) {
-        float* dst = yfix + (size_t)(blk % copies) * D + tid;
+    // ---- one coalesced atomic pass per block and token into an accumulator copy (fire and forget)
+    auto atomic_pass = [&]() {
+        if (nf > 0) {
 #pragma unroll
-        for (int u = 0; u < CPT; ++u)
-            __hip_atomic_fetch_add(dst + u * BLOCK, yacc[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+            for (int t = 0; t < TB; ++t) {
+                float* dst = yfix + ((size_t)(blk % copies) * TB + t) * D + ctid;
+#pragma unroll
+                for (int u = 0; u < CPT; ++u)
+                    if (TB == 1 || yacc[t][u] != 0.0f)
+                        __hip_atomic_fetch_add(dst + u * BLOCK, yacc[t][u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    };
+    atomic_pass();
 
     // ---- speculative product rows (the first one from the registers loaded above)
     for (int ri = wave; ri < rn; ri += NW) {
         asm volatile("" ::: "memory");
         if (ri != wave) load_row<IW>(wp, Wp + (size_t)(r0 + ri) * D, lane);
-        float s = 0.0f;
+        const float bias = ri == wave ? bias_out : bp[r0 + ri];
 #pragma unroll
-        for (int it = 0; it < IW; ++it) s = RowVec<bf16_t>::dot(wp[it], xs4[it * TD_WAVE], s);
-        s = td_wave_sum(s);
-        // written through to memory so that the finishing block, on any XCD, reads it
-        if (lane == 0)
-            __hip_atomic_store(yfold + r0 + ri, s + (ri == wave ? bias_out : bp[r0 + ri]), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
+        for (int t = 0; t < TB; ++t) {
+            if (TB > 1) asm volatile("" ::: "memory");
+            float s = 0.0f;
+#pragma unroll
+            for (int it = 0; it < IW; ++it) s = RowVec<bf16_t>::dot(wp[it], xs4[t * NVW + it * TD_WAVE], s);
+            s = td_wave_sum(s);
+            // written through to memory so that the finishing block, on any XCD, reads it
+            if (lane == 0)
+                __hip_atomic_store(yfold + (size_t)t * D + r0 + ri, s + bias, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
-
     // ---- signal completion; every store and atomic of this block has been acknowledged
     //      (vmcnt drained by the workgroup-scope release) before the counter moves
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -279,51 +354,73 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     // ---- the last block to finish assembles y and re-arms the scratch
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     typedef float f32x4 __attribute__((ext_vector_type(4)));
-    constexpr int OI = (D / 4 + BLOCK - 1) / BLOCK;   // float4 pieces of y per thread
-    f32x4 out[OI];
-    float ss = 0.0f;
+    constexpr int OI = (D / 4 + BLOCK - 1) / BLOCK;   // float4 pieces of one token's y per thread
+    const f32x4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    f32x4 out[TB][OI];
+    f32x4 part[TB][OI][kMaxCopies];
 #pragma unroll
-    for (int oi = 0; oi < OI; ++oi) {
-        const int k4 = oi * BLOCK + tid;
-        f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (k4 < D / 4) {
-            v = reinterpret_cast<const f32x4*>(yfold)[k4];
-            f32x4 part[kMaxCopies];
+    for (int t = 0; t < TB; ++t)                      // every load of every token requested before any is used
 #pragma unroll
-            for (int cidx = 0; cidx < kMaxCopies; ++cidx)      // all copies requested before any is used
-                part[cidx] = cidx < copies ? reinterpret_cast<const f32x4*>(yfix + (size_t)cidx * D)[k4]
-                                           : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        for (int oi = 0; oi < OI; ++oi) {
+            const int k4 = oi * BLOCK + tid;
+            const bool live = k4 < D / 4;
+            out[t][oi] = live ? reinterpret_cast<const f32x4*>(yfold + (size_t)t * D)[k4] : zero4;
+#pragma unroll
+            for (int cidx = 0; cidx < kMaxCopies; ++cidx)
+                part[t][oi][cidx] = (live && cidx < copies)
+                                        ? reinterpret_cast<const f32x4*>(yfix + ((size_t)cidx * TB + t) * D)[k4]
+                                        : zero4;
+        }
+    float ss[TB];
+#pragma unroll
+    for (int t = 0; t < TB; ++t) {
+        ss[t] = 0.0f;
+#pragma unroll
+        for (int oi = 0; oi < OI; ++oi) {
+            const int k4 = oi * BLOCK + tid;
+            f32x4 v = out[t][oi];
 #pragma unroll
             for (int cidx = 0; cidx < kMaxCopies; ++cidx) {
-                v += part[cidx];
-                if (cidx < copies)
-                    reinterpret_cast<f32x4*>(yfix + (size_t)cidx * D)[k4] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                v += part[t][oi][cidx];
+                if (k4 < D / 4 && cidx < copies)
+                    reinterpret_cast<f32x4*>(yfix + ((size_t)cidx * TB + t) * D)[k4] = zero4;
+            }
+            out[t][oi] = v;
+            ss[t] += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        }
+    }
+    float scale[TB];
+#pragma unroll
+    for (int t = 0; t < TB; ++t) scale[t] = 1.0f;
+    if (norm_out) {   // y / sqrt(mean(y^2) + eps): the glue between stacked layers
+        float* redt = &dl[0][0];                      // NW x TB floats, free by now
+#pragma unroll
+        for (int t = 0; t < TB; ++t) {
+            const float w = td_wave_sum(ss[t]);
+            if (lane == 0) redt[wave * TB + t] = w;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < TB; ++t) {
+            float tot = 0.0f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) tot += redt[w * TB + t];
+            scale[t] = 1.0f / sqrtf(tot / (float)D + eps);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < TB; ++t)
+#pragma unroll
+        for (int oi = 0; oi < OI; ++oi) {
+            const int k4 = oi * BLOCK + tid;
+            if (k4 < D / 4) {
+                const f32x4 v = out[t][oi] * scale[t];
+                uint2 o;
+                o.x = (uint32_t)td_f32_to_bf16(v.x) | ((uint32_t)td_f32_to_bf16(v.y) << 16);
+                o.y = (uint32_t)td_f32_to_bf16(v.z) | ((uint32_t)td_f32_to_bf16(v.w) << 16);
+                reinterpret_cast<uint2*>(y + (size_t)t * D)[k4] = o;
             }
         }
-        out[oi] = v;
-        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-    }
-    float scale = 1.0f;
-    if (norm_out) {   // y / sqrt(mean(y^2) + eps): the glue between stacked layers
-        ss = td_wave_sum(ss);
-        if (lane == 0) red[wave] = ss;
-        __syncthreads();
-        float tot = 0.0f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) tot += red[w];
-        scale = 1.0f / sqrtf(tot / (float)D + eps);
-    }
-#pragma unroll
-    for (int oi = 0; oi < OI; ++oi) {
-        const int k4 = oi * BLOCK + tid;
-        if (k4 < D / 4) {
-            const f32x4 v = out[oi] * scale;
-            uint2 o;
-            o.x = (uint32_t)td_f32_to_bf16(v.x) | ((uint32_t)td_f32_to_bf16(v.y) << 16);
-            o.y = (uint32_t)td_f32_to_bf16(v.z) | ((uint32_t)td_f32_to_bf16(v.w) << 16);
-            reinterpret_cast<uint2*>(y)[k4] = o;
-        }
-    }
     if (tid == 0) __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
@@ -371,7 +468,7 @@ mask_to_list_kernel(const uint32_t* __restrict__ mask, int words, int h, int32_t
     if (threadIdx.x == 0 && counts) counts[t] = carry;
 }
 
-template <int D, int BLOCK>
+template <int D, int BLOCK, int TB>
 tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
                               int norm_out, hipStream_t s) {
     constexpr int RQ = 4;
@@ -380,14 +477,25 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
     int npb = (h + G - 1) / G;
     npb = (npb + 31) / 32 * 32;
     const int rpb = (D + G - 1) / G;
-    hipLaunchKernelGGL((decode_fused_kernel<D, BLOCK, RQ>), dim3(G), dim3(BLOCK), 0, s,
+    hipLaunchKernelGGL((decode_fused_kernel<D, BLOCK, RQ, TB>), dim3(G), dim3(BLOCK), 0, s,
                        static_cast<const bf16_t*>(L->Wp), L->bp, L->Q, L->tlo, L->thi,
                        static_cast<const bf16_t*>(L->W1),
-                       static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), static_cast<const bf16_t*>(L->W2T), L->a, L->c, static_cast<const bf16_t*>(x),
-                       static_cast<bf16_t*>(y), yfold, L->yfix, L->dec_copies, mask, L->sync, h, npb, rpb,
-                       (int)L->act, norm_out, kRmsEps);
+                       static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), static_cast<const bf16_t*>(L->W2T),
+                       L->a, L->c, static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), yfold, L->yfix,
+                       L->dec_copies, mask, (int)L->mask_words, L->sync, h, npb, rpb, (int)L->act, norm_out, kRmsEps);
     TD_HIP(hipGetLastError());
     return TARDIS_OK;
+}
+
+template <int D, int BLOCK>
+tardis_status_t launch_tb(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask, int tokens,
+                          int norm_out, hipStream_t s) {
+    switch (tokens) {
+        case 1: return launch_decode<D, BLOCK, 1>(L, x, y, yfold, mask, norm_out, s);
+        case 2: return launch_decode<D, BLOCK, 2>(L, x, y, yfold, mask, norm_out, s);
+        case 4: return launch_decode<D, BLOCK, 4>(L, x, y, yfold, mask, norm_out, s);
+    }
+    return TARDIS_ERR_INVALID_ARG;
 }
 
 }  // namespace
@@ -402,19 +510,20 @@ bool td_decode_fused_supported(const tardis_layer_s* L) {
     return npb <= kMaxNeuronsPerBlock;
 }
 
+// `tokens` (1, 2 or 4) consecutive tokens in one launch
 tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
-                                int norm_out, hipStream_t s) {
+                                int tokens, int norm_out, hipStream_t s) {
     if (L->dec_threads == 512) {
         switch (L->d) {
-            case 1024: return launch_decode<1024, 512>(L, x, y, yfold, mask, norm_out, s);
-            case 2048: return launch_decode<2048, 512>(L, x, y, yfold, mask, norm_out, s);
-            case 4096: return launch_decode<4096, 512>(L, x, y, yfold, mask, norm_out, s);
+            case 1024: return launch_tb<1024, 512>(L, x, y, yfold, mask, tokens, norm_out, s);
+            case 2048: return launch_tb<2048, 512>(L, x, y, yfold, mask, tokens, norm_out, s);
+            case 4096: return launch_tb<4096, 512>(L, x, y, yfold, mask, tokens, norm_out, s);
         }
     }
     switch (L->d) {
-        case 1024: return launch_decode<1024, 1024>(L, x, y, yfold, mask, norm_out, s);
-        case 2048: return launch_decode<2048, 1024>(L, x, y, yfold, mask, norm_out, s);
-        case 4096: return launch_decode<4096, 1024>(L, x, y, yfold, mask, norm_out, s);
+        case 1024: return launch_tb<1024, 1024>(L, x, y, yfold, mask, tokens, norm_out, s);
+        case 2048: return launch_tb<2048, 1024>(L, x, y, yfold, mask, tokens, norm_out, s);
+        case 4096: return launch_tb<4096, 1024>(L, x, y, yfold, mask, tokens, norm_out, s);
     }
     return TARDIS_ERR_SHAPE;
 }

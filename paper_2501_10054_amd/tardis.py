@@ -13,7 +13,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libtardis.so")
+LIB_PATH = os.environ.get("TARDIS_LIB") or os.path.join(_HERE, "libtardis.so")
 
 OK, ERR_INVALID_ARG, ERR_SHAPE, ERR_DTYPE, ERR_STATE, ERR_OOM, ERR_HIP = range(7)
 ACT = {"gelu_erf": 0, "gelu_tanh": 1, "relu": 2, "identity": 3}

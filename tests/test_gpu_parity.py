@@ -174,10 +174,12 @@ def test_mid_bf16_batched_high_fallback():
     assert 0.08 < r["rate"] < 0.25
 
 
-@pytest.mark.parametrize("n,coverage", [(2, 0.95), (16, 0.9), (20, 0.95), (48, 0.85), (64, 0.95), (70, 0.99), (150, 0.95)])
+@pytest.mark.parametrize("n,coverage", [(2, 0.95), (3, 0.95), (4, 0.9), (7, 0.85), (8, 0.95), (9, 0.95), (16, 0.9),
+                                        (20, 0.95), (48, 0.85), (64, 0.95), (70, 0.99), (150, 0.95)])
 def test_batched_passes_of_64_tokens(n, coverage):
-    """One weight stream per pass of up to 64 tokens: every tile count (1, 2, 4 token tiles), the
-    gather and the masked-dense scatter, a ragged last pass."""
+    """Up to 8 tokens: groups of 4, 2 and 1 tokens sharing one single-launch weight pass.  More: one
+    weight stream per pass of up to 64 tokens, every tile count (1, 2, 4 token tiles), the gather
+    and the masked-dense scatter, a ragged last pass."""
     w = synth.decode(d=1024, h=4096, n_cal=512, n_test=n, coverage=coverage, config=2)
     run_case(w.layer, w.X_cal, w.X_test, coverage, batched=True, check_calibrate=False)
 
@@ -267,14 +269,17 @@ def test_fused_kernel_with_ragged_hidden_width_and_bias():
     seed = synth.workload_seed(9, 4)
     layer = synth.make_layer(2048, 1000, "bf16", seed, w1_std=0.03, w2_std=0.03, heavy_frac=0.01, with_bias=True)
     X_cal = synth.make_tokens(256, 2048, "bf16", seed, synth.STREAM_CAL)
-    X_test = synth.make_tokens(5, 2048, "bf16", seed, synth.STREAM_TEST)
-    run_case(layer, X_cal, X_test, 0.9, check_calibrate=False)
+    X_test = synth.make_tokens(7, 2048, "bf16", seed, synth.STREAM_TEST)
+    run_case(layer, X_cal, X_test[:5], 0.9, check_calibrate=False)
+    run_case(layer, X_cal, X_test, 0.9, check_calibrate=False, batched=True)     # groups of 4 + 2 + 1 tokens
 
 
 def test_fused_kernel_many_flagged_per_block():
     # 40 % fallback: every block repairs far more neurons than one pass holds
     w = synth.decode(d=1024, h=4096, n_cal=256, n_test=4, coverage=0.6, config=9)
     r = run_case(w.layer, w.X_cal, w.X_test, 0.6, check_calibrate=False)
+    assert r["rate"] > 0.3
+    r = run_case(w.layer, w.X_cal, w.X_test, 0.6, check_calibrate=False, batched=True)   # four tokens per launch
     assert r["rate"] > 0.3
 
 
@@ -467,7 +472,7 @@ def test_full_size_batched_matches_per_token(decode_full):
         assert rel_l2(host(y), host(Yb[t])) <= 2e-3            # bf16 output, atomic ordering
 
 
-@pytest.mark.parametrize("B", [16, 64])
+@pytest.mark.parametrize("B", [2, 4, 7, 16, 64])
 def test_full_size_batched_decode_sampled_tokens(decode_full, B):
     """Batched decode at the full layer size, in the configuration the sweep times: the checker
     recomputes a sample of the batch's tokens one by one."""
