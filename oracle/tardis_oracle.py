@@ -24,7 +24,8 @@ fp32 because the library interface carries it as fp32.
 Pins (tests/test_oracle_pins.py): the paper's printed two-neuron example, its
 2x2 folding example, the standard normal CDF table for GELU, closed forms for
 the least-squares fit, a literal per-neuron rank-1 fold, brute-force integer
-dot products, and the all-flagged / none-flagged identities.
+dot products, hand-worked 4-bit group codes, the reconstruction error bound of
+both sketches, and the all-flagged / none-flagged identities.
 
 parity unpinned: nothing on the gated path.  (The integer predictor below is a
 reading of "a quantised copy of W1", Sec. "Predictor Generation"; the paper
@@ -173,33 +174,30 @@ def fold(W1, b1, W2, b2, a, c):
 # ---------------------------------------------------------------------------
 @dataclass
 class Sketch:
-    Q: np.ndarray      # h x d int8, round-to-nearest symmetric per-row codes of W1
-    s: np.ndarray      # h fp64 row scales, W1[j] ~ s[j] * Q[j]
+    Q: np.ndarray      # h x d int8 codes of W1: W1[j] ~ s[j] * Q[j]
+    s: np.ndarray      # h fp64 row scales
     tlo: np.ndarray    # h fp32, (lo - b1) / s
     thi: np.ndarray    # h fp32, (hi - b1) / s
+    bits: int = 8
+    group: int = 0     # columns per group (4-bit sketch), 0 for the ungrouped 8-bit sketch
+    m: np.ndarray | None = None   # h x ceil(d/group) uint8 group multipliers (4-bit sketch)
+    q4: np.ndarray | None = None  # h x d int8 4-bit codes in [-7, 7]; Q = m (per group) * q4
 
 
-def sketch(W1, b1, lo, hi) -> Sketch:
-    """int8 sketch of W1 and the range bounds expressed in sketch units.
+SKETCH4_QMAX = 7       # largest 4-bit code magnitude (symmetric: -8 is not used)
+SKETCH4_MMAX = 15      # largest group multiplier (4 bits, 1..15)
+SKETCH4_GROUP = 32     # consecutive columns that share one multiplier
 
-    s_j = max_k |W1[j,k]| / 127 ; q_jk = rint(W1[j,k] / s_j) (ties to even),
-    clamped to [-127, 127].  The test lo <= s_j*(q_j . x) + b1_j < hi becomes
-    tlo_j <= q_j . x < thi_j with tlo = (lo-b1)/s, thi = (hi-b1)/s, both rounded
-    once to fp32.  A neuron whose weights are all zero has z = b1_j for every
-    token: it is never flagged if b1_j lies in its range and always otherwise.
-    """
-    W1 = _f64(W1)
-    h, d = W1.shape
-    lo = _f64(lo); hi = _f64(hi)
-    b = np.zeros(h) if b1 is None else _f64(b1)
-    s = np.abs(W1).max(axis=1) / 127.0
-    Q = np.zeros((h, d), np.int8)
+
+def _thresholds(lo, hi, b, s):
+    """Range bounds in sketch units, rounded once to fp32.  A neuron whose weights
+    are all zero (s = 0) has z = b1_j for every token: it is never flagged if
+    b1_j lies in its range and always otherwise."""
+    h = s.shape[0]
     tlo = np.empty(h, np.float32)
     thi = np.empty(h, np.float32)
     for j in range(h):
         if s[j] > 0.0:
-            q = np.rint(W1[j] / s[j])
-            Q[j] = np.clip(q, -127, 127).astype(np.int8)
             tlo[j] = np.float32((lo[j] - b[j]) / s[j])
             thi[j] = np.float32((hi[j] - b[j]) / s[j])
         elif lo[j] <= b[j] < hi[j]:
@@ -208,7 +206,61 @@ def sketch(W1, b1, lo, hi) -> Sketch:
         else:                       # empty interval: the neuron is always flagged
             tlo[j] = np.inf
             thi[j] = np.inf
-    return Sketch(Q=Q, s=s, tlo=tlo, thi=thi)
+    return tlo, thi
+
+
+def sketch(W1, b1, lo, hi, bits: int = 8) -> Sketch:
+    """Integer sketch of W1 (the "quantised copy of W1" of Sec. "Predictor
+    Generation", round-to-nearest) and the range bounds in sketch units.
+
+    bits = 8:  s_j = max_k |W1[j,k]| / 127 ; q_jk = rint(W1[j,k] / s_j) (ties to
+    even), clamped to [-127, 127].
+
+    bits = 4:  the row is cut into groups of 32 consecutive columns (the last one
+    may be shorter).  With g_jG = max_{k in G} |W1[j,k]| and r_j = max_G g_jG,
+        s_j  = r_j / (7 * 15)
+        m_jG = ceil(g_jG / (7 s_j))  clamped to [1, 15]        (4-bit multiplier)
+        q_jk = rint(W1[j,k] / (m_jG s_j))  clamped to [-7, 7]  (4-bit code)
+    and the code the predictor multiplies with is the integer Q_jk = m_jG q_jk
+    (|Q_jk| <= 105), so that W1[j,k] ~ s_j Q_jk exactly as in the 8-bit case and
+    the dot product stays one exact integer sum.  Storage: 4 bits per weight plus
+    4 bits per group of 32.
+
+    Either way the test lo <= s_j*(Q_j . x) + b1_j < hi becomes
+    tlo_j <= Q_j . x < thi_j with tlo = (lo-b1)/s, thi = (hi-b1)/s.
+    """
+    W1 = _f64(W1)
+    h, d = W1.shape
+    lo = _f64(lo); hi = _f64(hi)
+    b = np.zeros(h) if b1 is None else _f64(b1)
+    if bits == 8:
+        Q = np.zeros((h, d), np.int8)
+        s = np.abs(W1).max(axis=1) / 127.0
+        for j in range(h):
+            if s[j] > 0.0:
+                Q[j] = np.clip(np.rint(W1[j] / s[j]), -127, 127).astype(np.int8)
+        tlo, thi = _thresholds(lo, hi, b, s)
+        return Sketch(Q=Q, s=s, tlo=tlo, thi=thi)
+    if bits != 4:
+        raise ValueError("sketch bits must be 8 or 4")
+    G = SKETCH4_GROUP
+    ng = (d + G - 1) // G
+    Wg = np.zeros((h, ng * G))                     # zero padding changes no maximum and no code
+    Wg[:, :d] = W1
+    Wg = Wg.reshape(h, ng, G)
+    gmax = np.abs(Wg).max(axis=2)                  # h x ng
+    s = gmax.max(axis=1) / float(SKETCH4_QMAX * SKETCH4_MMAX)
+    live = s > 0.0
+    s_safe = np.where(live, s, 1.0)
+    m = np.clip(np.ceil(gmax / (SKETCH4_QMAX * s_safe)[:, None]), 1, SKETCH4_MMAX)
+    m = np.where(live[:, None], m, 1.0)
+    q = np.clip(np.rint(Wg / (m * s_safe[:, None])[:, :, None]), -SKETCH4_QMAX, SKETCH4_QMAX)
+    q = np.where(live[:, None, None], q, 0.0)
+    q4 = q.reshape(h, ng * G)[:, :d].astype(np.int8)
+    Q = (m[:, :, None] * q).reshape(h, ng * G)[:, :d].astype(np.int8)
+    m = m.astype(np.uint8)
+    tlo, thi = _thresholds(lo, hi, b, s)
+    return Sketch(Q=Q, s=s, tlo=tlo, thi=thi, bits=4, group=G, m=m, q4=q4)
 
 
 def quantize_token(x):
@@ -260,7 +312,7 @@ class Folded:
     sk: Sketch
 
 
-def build(W1, b1, W2, b2, lo, hi, a, c, kind: str = "gelu_erf", wp_round=None) -> Folded:
+def build(W1, b1, W2, b2, lo, hi, a, c, kind: str = "gelu_erf", wp_round=None, sketch_bits: int = 8) -> Folded:
     """Everything the online path needs.  `wp_round`, if given, is applied to W'
     once (e.g. rounding to the storage dtype) for the storage-matched variant."""
     Wp, bp = fold(W1, b1, W2, b2, a, c)
@@ -268,7 +320,7 @@ def build(W1, b1, W2, b2, lo, hi, a, c, kind: str = "gelu_erf", wp_round=None) -
         Wp = np.asarray(wp_round(Wp), dtype=np.float64)
     h, d = np.shape(W1)
     return Folded(d=d, h=h, kind=kind, W1=_f64(W1), b1=_f64(b1), W2=_f64(W2),
-                  a=_f64(a), c=_f64(c), Wp=Wp, bp=bp, sk=sketch(W1, b1, lo, hi))
+                  a=_f64(a), c=_f64(c), Wp=Wp, bp=bp, sk=sketch(W1, b1, lo, hi, sketch_bits))
 
 
 def fix_terms(F: Folded, x, flags):

@@ -354,6 +354,127 @@ def test_sketch_codes_brute_force():
     assert not O.predict(sk, rng.normal(size=10))[3]
 
 
+def test_sketch4_hand_worked_groups():
+    # one row of 5 groups of 32 columns, numbers chosen so that every step can be done by hand:
+    # r = 105 => s = 105 / (7 * 15) = 1
+    row = np.zeros(160)
+    # group 0 holds the row maximum: m = ceil(105 / 7) = 15, q = rint(w / 15) (ties to even)
+    row[0:6] = [105.0, 52.5, 22.5, 7.5, -37.5, 30.0]
+    # group 1: largest 14 => m = 2, q = rint(w / 2)
+    row[32:37] = [14.0, 13.0, 3.0, 1.0, -5.0]
+    # group 2: largest 7 => m = 1 exactly; q = rint(w)
+    row[64:68] = [7.0, -6.5, 2.5, 0.4]
+    # group 3: largest just above 7 => m = 2
+    row[96:98] = [7.0001, -7.0]
+    # group 4: all zero => m = 1, q = 0
+    sk = O.sketch(row[None, :], None, np.array([-10.0]), np.array([21.0]), bits=4)
+    assert sk.bits == 4 and sk.group == 32 and sk.s[0] == 1.0
+    np.testing.assert_array_equal(sk.m[0], [15, 2, 1, 2, 1])
+    np.testing.assert_array_equal(sk.q4[0, 0:6], [7, 4, 2, 0, -2, 2])
+    np.testing.assert_array_equal(sk.q4[0, 32:37], [7, 6, 2, 0, -2])
+    np.testing.assert_array_equal(sk.q4[0, 64:68], [7, -6, 2, 0])
+    np.testing.assert_array_equal(sk.q4[0, 96:98], [4, -4])
+    np.testing.assert_array_equal(sk.Q[0, 0:6], [105, 60, 30, 0, -30, 30])
+    np.testing.assert_array_equal(sk.Q[0, 32:37], [14, 12, 4, 0, -4])
+    np.testing.assert_array_equal(sk.Q[0, 96:98], [8, -8])
+    assert (sk.Q[0, 128:] == 0).all() and (sk.Q[0, 6:32] == 0).all()
+    assert sk.tlo[0] == np.float32(-10.0) and sk.thi[0] == np.float32(21.0)
+    # the predictor sees the integer sum_k Q_k xq_k: x = e_0 + e_32 (scaled by 64 in the int8 code)
+    x = np.zeros(160); x[0] = 1.0; x[32] = 1.0
+    xq, e = O.quantize_token(x)
+    assert e == -6 and xq[0] == 64
+    assert O.predict(sk, x)[0]                     # v = (105 + 14) * 64 * 2^-6 = 119, outside [-10, 21)
+    sk2 = O.sketch(row[None, :], None, np.array([-10.0]), np.array([119.0]), bits=4)
+    assert O.predict(sk2, x)[0]                    # v = 119 is not < 119
+    sk3 = O.sketch(row[None, :], None, np.array([119.0]), np.array([119.5]), bits=4)
+    assert not O.predict(sk3, x)[0]                # 119 <= v < 119.5
+
+
+def test_sketch4_brute_force_and_error_bound():
+    rng = np.random.default_rng(21)
+    h, d = 9, 70                                   # 3 groups, the last one of 6 columns
+    W1 = rng.normal(0, 0.3, (h, d))
+    W1[:, 5] = 4.0 * np.sign(W1[:, 5])             # a heavy column: its group gets the largest multiplier
+    W1[2] = 0.0
+    W1[4, 32:64] = 0.0                             # a zero group inside a non-zero row
+    b1 = rng.normal(0, 0.1, h)
+    lo = rng.normal(-1, 0.1, h)
+    hi = lo + 1.5
+    sk = O.sketch(W1, b1, lo, hi, bits=4)
+    assert sk.m.shape == (h, 3)
+    for j in range(h):
+        r = max(abs(v) for v in W1[j])
+        if r == 0:
+            assert (sk.Q[j] == 0).all() and (sk.m[j] == 1).all()
+            continue
+        s = r / 105.0
+        assert sk.s[j] == s
+        assert sk.tlo[j] == np.float32((lo[j] - b1[j]) / s) and sk.thi[j] == np.float32((hi[j] - b1[j]) / s)
+        seen15 = False
+        for g in range(3):
+            cols = range(32 * g, min(32 * g + 32, d))
+            gmax = max(abs(W1[j, k]) for k in cols)
+            m = 1
+            while m < 15 and 7 * m * s < gmax:     # smallest multiplier whose range covers the group
+                m += 1
+            assert sk.m[j, g] == m
+            seen15 |= m == 15
+            for k in cols:
+                q = max(-7, min(7, round(W1[j, k] / (m * s))))     # python round: ties to even
+                assert sk.q4[j, k] == q and sk.Q[j, k] == m * q
+                # no code is ever clipped, and the dequantised weight is within half a group step
+                assert abs(W1[j, k] / (m * s)) <= 7 * (1 + 1e-12)
+                assert abs(s * sk.Q[j, k] - W1[j, k]) <= 0.5 * m * s * (1 + 1e-12)
+        assert seen15 and np.abs(sk.Q[j]).max() == 105
+    # the heavy column's group is coarser than the others (that is the point of grouping)
+    assert (sk.m[[0, 1, 3], 0] == 15).all() and (sk.m[[0, 1, 3], 1] < 8).all() and (sk.m[4, 1] == 1)
+    with pytest.raises(ValueError):
+        O.sketch(W1, b1, lo, hi, bits=2)
+
+
+def test_predict_with_sketch4_is_the_grouped_integer_sum():
+    rng = np.random.default_rng(22)
+    h, d = 11, 96
+    W1 = rng.normal(0, 0.4, (h, d))
+    lo = rng.normal(-1.0, 0.5, h)
+    hi = lo + rng.uniform(0.5, 3.0, h)
+    sk = O.sketch(W1, None, lo, hi, bits=4)
+    for _ in range(10):
+        x = rng.normal(size=d) * rng.choice([0.01, 1.0, 30.0])
+        xq, e = O.quantize_token(x)
+        flags = O.predict(sk, x)
+        for j in range(h):
+            acc = 0
+            for g in range(3):
+                acc += int(sk.m[j, g]) * sum(int(sk.q4[j, k]) * int(xq[k]) for k in range(32 * g, 32 * g + 32))
+            assert abs(acc) < 2 ** 31
+            v = np.float32(acc) * np.float32(2.0 ** e)
+            assert bool(flags[j]) == (not (v >= sk.tlo[j] and v < sk.thi[j]))
+
+
+def test_sketch4_tracks_true_preactivation_less_tightly_than_sketch8():
+    w = synth.tiny(hard=True, with_bias=True)
+    W1 = w.layer.W1.astype(np.float64)
+    b1 = w.layer.b1.astype(np.float64)
+    lo, hi, a, c = O.calibrate(W1, b1, w.X_cal, 0.9)
+    sk4, sk8 = O.sketch(W1, b1, lo, hi, bits=4), O.sketch(W1, b1, lo, hi, bits=8)
+    step = sk4.s[:, None] * np.repeat(sk4.m, 32, axis=1)[:, :W1.shape[1]]          # per-weight code step
+    agree4 = agree8 = total = 0
+    for x in w.X_test.astype(np.float64):
+        xq, e = O.quantize_token(x)
+        z = W1 @ x + b1
+        acc = (sk4.Q.astype(np.int64) @ xq.astype(np.int64)).astype(np.float64)
+        zhat = sk4.s * acc * 2.0 ** e + b1
+        bound = (0.5 * 2.0 ** e) * np.abs(W1).sum(1) + 0.5 * (step * np.abs(xq)[None, :]).sum(1) * 2.0 ** e
+        assert (np.abs(zhat - z) <= bound * (1 + 1e-9) + 1e-12).all()
+        truth = ~((z >= lo) & (z < hi))
+        f4, f8 = O.predict(sk4, x), O.predict(sk8, x)
+        safe = np.minimum(np.abs(z - lo), np.abs(z - hi)) > bound * (1 + 1e-6) + 1e-6
+        assert (f4[safe] == truth[safe]).all()
+        agree4 += (f4 == truth).sum(); agree8 += (f8 == truth).sum(); total += truth.size
+    assert agree8 >= agree4 and agree4 / total > 0.85
+
+
 def test_ties_round_to_even_in_codes():
     W1 = np.array([[127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 63.5]])
     sk = O.sketch(W1, None, np.array([-1.0]), np.array([1.0]))
