@@ -32,10 +32,12 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = 119089537
 
 
-def algorithmic_bytes(d: int, h: int, p: float) -> float:
-    """Bytes the method itself must move per token at batch 1: folded matrix (bf16) + int8 sketch
-    + the W1 and W2 rows of the flagged neurons (bf16)."""
-    return 2.0 * d * d + 1.0 * d * h + 4.0 * p * d * h
+def algorithmic_bytes(d: int, h: int, p: float, sketch_bits: int = 8) -> float:
+    """Bytes the method itself must move per token at batch 1: folded matrix (bf16) + sketch (one
+    byte per weight, or 4 bits per weight plus one multiplier byte per 32) + the W1 and W2 rows
+    of the flagged neurons (bf16)."""
+    sketch = 1.0 * d * h if sketch_bits == 8 else 0.5 * d * h + d * h / 32.0
+    return 2.0 * d * d + sketch + 4.0 * p * d * h
 
 
 def _time_us(torch, fn, reps, warm=2):
@@ -179,6 +181,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--layers", type=int, default=6, help="independently seeded layer copies for the cold loop")
     ap.add_argument("--coverage", type=float, default=0.95)
+    ap.add_argument("--sketch-bits", type=int, default=8, choices=(8, 4),
+                    help="predictor code width of the timed layers (8 = the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of a replayed HIP graph")
@@ -218,7 +222,7 @@ def main() -> int:
         lo, hi, a, c = T.tardis_calibrate(ffn, Xc, w.coverage)
         torch.cuda.synchronize()
         t1 = time.time()
-        L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=1)
+        L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=1, sketch_bits=args.sketch_bits)
         torch.cuda.synchronize()
         t2 = time.time()
         if li == 0:
@@ -318,7 +322,7 @@ def main() -> int:
         }
 
     tok_s = TOKENS_PER_STEP / (cold_ms * 1e-3)
-    bytes_tok = algorithmic_bytes(D, H, p)
+    bytes_tok = algorithmic_bytes(D, H, p, args.sketch_bits)
     launch_s = cold_ms * 1e-3 / TOKENS_PER_STEP          # one kernel launch per token
     achieved = bytes_tok / launch_s / 1e9
 
@@ -332,7 +336,7 @@ def main() -> int:
         except Exception:
             cores = os.cpu_count() or 1
         lay = w0.layer
-        F = O.build(lay.W1, None, lay.W2, None, *(t.cpu().numpy() for t in cal0))
+        F = O.build(lay.W1, None, lay.W2, None, *(t.cpu().numpy() for t in cal0), sketch_bits=args.sketch_bits)
         ns = 160
         t0 = time.time()
         O.forward(F, w0.X_test[:ns])
@@ -355,9 +359,11 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "decode single layer d=4096 ffn=16384 bf16, batch 1, 1024 tokens/step, "
                                f"cold over {args.layers} seeded layer copies", "coverage_t": args.coverage,
-                   "measured_fallback_rate": p, "tokens_per_step": TOKENS_PER_STEP},
+                   "measured_fallback_rate": p, "tokens_per_step": TOKENS_PER_STEP,
+                   "sketch_bits": args.sketch_bits},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES if args.sketch_bits == 8 else None,
                      "kernel": "decode_fused_kernel", "algorithmic_bytes_per_launch": bytes_tok,
                      "avg_launch_us": launch_s * 1e6},
         "cpu_baseline": cpu,

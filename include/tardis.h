@@ -82,7 +82,7 @@ typedef struct {
 } tardis_ffn_desc;
 
 typedef struct {
-    int32_t sketch_bits;   /* predictor code width; 8 is the only supported value */
+    int32_t sketch_bits;   /* predictor code width: 8, or 4 (grouped, see tardis_fold) */
     int32_t folded_dtype;  /* storage of W'; must equal desc.dtype */
     int64_t max_batch;     /* largest n accepted by the batched online calls (>= 1) */
     int32_t deterministic; /* reserved, must be 0 */
@@ -117,6 +117,16 @@ tardis_status_t tardis_calibrate(const tardis_ffn_desc* desc, const void* X_cal,
  * and the predictor: an int8 round-to-nearest per-row symmetric code Q of W1
  * (s_j = max_k|W1[j,k]|/127, q_jk = rint(W1[j,k]/s_j)) with the range bounds in
  * code units, tlo_j = fp32((lo_j-b1_j)/s_j), thi_j = fp32((hi_j-b1_j)/s_j).
+ * With opts->sketch_bits = 4 the code is grouped instead (the paper's predictor is
+ * a low-bit quantised W1; this is its round-to-nearest form with 4-bit codes): each
+ * row is cut into groups G of 32 consecutive columns (the last may be shorter),
+ *     g_jG = max_{k in G}|W1[j,k]|,  s_j = max_G g_jG / (7*15),
+ *     m_jG = ceil(g_jG / (7 s_j)) clamped to [1,15],
+ *     q_jk = rint(W1[j,k] / (m_jG s_j)) clamped to [-7,7],
+ * all in fp64, and the predictor uses the integer code Q_jk = m_jG q_jk (|Q| <= 105)
+ * exactly as it uses the 8-bit code; tlo, thi as above with this s_j.  Storage is
+ * 4 bits per weight plus one multiplier per group where the decode kernel reads the
+ * packed form (bf16, d = 2048 or 4096), one byte per weight elsewhere.
  *
  * W1, b1, b2 are BORROWED: they must stay valid and unchanged until
  * tardis_destroy (the repair step reads W1 in place).  W2 is copied into a
@@ -170,9 +180,14 @@ tardis_status_t tardis_dense_forward(tardis_handle_t L, const void* x, int64_t n
  * floats.  Either may be NULL. */
 tardis_status_t tardis_get_folded(tardis_handle_t L, void* Wp, float* bp, void* stream);
 
-/* Q: h x d int8; tlo, thi: h floats.  Any may be NULL. */
+/* Q: h x d int8, the integer codes the predictor multiplies with (for a 4-bit
+ * sketch the products m_jG q_jk); tlo, thi: h floats.  Any may be NULL. */
 tardis_status_t tardis_get_predictor_state(tardis_handle_t L, int8_t* Q, float* tlo, float* thi,
                                            void* stream);
+
+/* Group multipliers of a 4-bit sketch: M is h x ceil(d/32) bytes, M[j][G] = m_jG.
+ * TARDIS_ERR_STATE for a layer folded with an 8-bit sketch. */
+tardis_status_t tardis_get_sketch_groups(tardis_handle_t L, uint8_t* M, void* stream);
 
 /* Predictor output of the most recent online call on this handle, for its n
  * tokens (stream-ordered copies into caller buffers; any may be NULL):

@@ -48,7 +48,7 @@ int env_int(const char* name, int fallback, int lo, int hi) {
 
 void free_layer(tardis_layer_s* L) {
     if (!L) return;
-    void* owned[] = {L->W2T, L->W2, L->Wp, L->bp, L->Q, L->tlo, L->thi, L->a, L->c,
+    void* owned[] = {L->W2T, L->W2, L->Wp, L->bp, L->Q, L->Q4, L->M4, L->tlo, L->thi, L->a, L->c,
                      L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix, L->zeros_h, L->xnext,
                      L->bt_xq, L->bt_e, L->bt_tokmask, L->bt_ulist, L->bt_ucount, L->bt_delta, L->bt_partial};
     for (void* p : owned)
@@ -65,6 +65,7 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     L->dtype = desc->dtype;
     L->act = desc->act;
     L->max_batch = opts ? opts->max_batch : 1;
+    L->sketch_bits = opts ? opts->sketch_bits : 8;
     L->mask_words = (h + 31) / 32;
     L->W1 = desc->W1;
     L->b1 = desc->b1;
@@ -75,7 +76,6 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     TD_TRY(dev_alloc(reinterpret_cast<char**>(&L->W2), (size_t)h * d * es));
     TD_TRY(dev_alloc(reinterpret_cast<char**>(&L->Wp), (size_t)d * d * es));
     TD_TRY(dev_alloc(&L->bp, (size_t)d * 4));
-    TD_TRY(dev_alloc(&L->Q, (size_t)h * d));
     TD_TRY(dev_alloc(&L->tlo, (size_t)h * 4));
     TD_TRY(dev_alloc(&L->thi, (size_t)h * 4));
     TD_TRY(dev_alloc(&L->a, (size_t)h * 4));
@@ -98,6 +98,13 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     L->use_fused = env_int("TARDIS_DECODE_FUSED", 1, 0, 1) && td_decode_fused_supported(L);
     L->use_batched = env_int("TARDIS_BATCHED", 1, 0, 1) && td_batched_supported(L);
     L->batched_min_tokens = env_int("TARDIS_BATCHED_MIN", L->use_fused ? 8 : 1, 1, 64);
+    // 4-bit sketch: the decode kernel reads the packed form (d = 2048, 4096); every other path
+    // reads one-byte effective codes, kept only where such a path can run
+    const bool packed4 = L->sketch_bits == 4 && L->use_fused && (d == 2048 || d == 4096);
+    const bool byte_codes = !packed4 || (L->use_batched && L->max_batch > L->batched_min_tokens);
+    if (byte_codes) TD_TRY(dev_alloc(&L->Q, (size_t)h * d));
+    if (packed4) TD_TRY(dev_alloc(&L->Q4, (size_t)h * d / 2));
+    if (L->sketch_bits == 4) TD_TRY(dev_alloc(&L->M4, (size_t)h * ((d + 31) / 32)));
     if (L->use_batched) {
         TD_TRY(td_batched_init());
         TD_TRY(dev_alloc(&L->bt_xq, (size_t)64 * d));
@@ -117,7 +124,8 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     TD_HIP(hipMemcpyAsync(L->c, c, (size_t)h * 4, hipMemcpyDeviceToDevice, s));
     TD_HIP(hipMemcpyAsync(L->W2, desc->W2, (size_t)h * d * es, hipMemcpyDeviceToDevice, s));
     TD_TRY(td_transpose(desc->W2, L->W2T, d, h, desc->dtype, s));
-    TD_TRY(td_build_sketch(desc->W1, desc->b1, lo, hi, h, d, desc->dtype, L->Q, L->tlo, L->thi, s));
+    TD_TRY(td_build_sketch(desc->W1, desc->b1, lo, hi, h, d, desc->dtype, L->sketch_bits, L->Q, L->Q4, L->M4, L->tlo,
+                           L->thi, s));
     TD_TRY(td_fold(desc, L->a, L->c, L->Wp, L->bp, s));
     TD_HIP(hipStreamSynchronize(s));
     return TARDIS_OK;
@@ -146,7 +154,7 @@ tardis_status_t tardis_fold(const tardis_ffn_desc* desc, const float* lo, const 
     TD_TRY(check_desc(desc));
     if (!lo || !hi || !a || !c) return TARDIS_ERR_INVALID_ARG;
     if (opts) {
-        if (opts->sketch_bits != 8) return TARDIS_ERR_INVALID_ARG;
+        if (opts->sketch_bits != 8 && opts->sketch_bits != 4) return TARDIS_ERR_INVALID_ARG;
         if (opts->folded_dtype != desc->dtype) return TARDIS_ERR_DTYPE;
         if (opts->max_batch < 1 || opts->max_batch > kMaxBatch) return TARDIS_ERR_SHAPE;
         if (opts->deterministic != 0) return TARDIS_ERR_INVALID_ARG;
@@ -214,9 +222,22 @@ tardis_status_t tardis_get_folded(tardis_handle_t L, void* Wp, float* bp, void* 
 tardis_status_t tardis_get_predictor_state(tardis_handle_t L, int8_t* Q, float* tlo, float* thi, void* stream) {
     if (!L) return TARDIS_ERR_STATE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (Q) TD_HIP(hipMemcpyAsync(Q, L->Q, (size_t)L->h * L->d, hipMemcpyDeviceToDevice, s));
+    if (Q) {
+        if (L->Q)
+            TD_HIP(hipMemcpyAsync(Q, L->Q, (size_t)L->h * L->d, hipMemcpyDeviceToDevice, s));
+        else
+            TD_TRY(td_unpack_sketch4(L->Q4, L->M4, L->h, L->d, Q, s));
+    }
     if (tlo) TD_HIP(hipMemcpyAsync(tlo, L->tlo, (size_t)L->h * 4, hipMemcpyDeviceToDevice, s));
     if (thi) TD_HIP(hipMemcpyAsync(thi, L->thi, (size_t)L->h * 4, hipMemcpyDeviceToDevice, s));
+    return TARDIS_OK;
+}
+
+tardis_status_t tardis_get_sketch_groups(tardis_handle_t L, uint8_t* M, void* stream) {
+    if (!L || L->sketch_bits != 4) return TARDIS_ERR_STATE;
+    if (!M) return TARDIS_ERR_INVALID_ARG;
+    TD_HIP(hipMemcpyAsync(M, L->M4, (size_t)L->h * ((L->d + 31) / 32), hipMemcpyDeviceToDevice,
+                          static_cast<hipStream_t>(stream)));
     return TARDIS_OK;
 }
 

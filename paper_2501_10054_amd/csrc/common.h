@@ -42,7 +42,10 @@ struct tardis_layer_s {
     void* W2;      // d x h, copy of W2 as given (dense baseline)
     void* Wp;      // d x d folded matrix
     float* bp;     // d folded bias
-    int8_t* Q;     // h x d predictor codes
+    int8_t* Q;     // h x d predictor codes, one byte each (absent when only the packed 4-bit form is kept)
+    uint8_t* Q4;   // packed 4-bit sketch, h x d/2 bytes: one 16-byte vector per group of 32 columns (or null)
+    uint8_t* M4;   // 4-bit sketch: h x ceil(d/32) group multipliers, one byte each (or null)
+    int32_t sketch_bits;
     float* tlo;    // h
     float* thi;    // h
     float* a;      // h
@@ -155,8 +158,14 @@ __device__ __forceinline__ double td_act_f64(double z, int act) {
 
 // offline.hip
 tardis_status_t td_transpose(const void* src, void* dst, int64_t rows, int64_t cols, int32_t dtype, hipStream_t s);
+// bits = 8: Q (required).  bits = 4: M4 (required), Q (effective one-byte codes, optional) and Q4
+// (packed, optional, needs d % 32 == 0).
 tardis_status_t td_build_sketch(const void* W1, const void* b1, const float* lo, const float* hi, int64_t h,
-                                int64_t d, int32_t dtype, int8_t* Q, float* tlo, float* thi, hipStream_t s);
+                                int64_t d, int32_t dtype, int32_t bits, int8_t* Q, uint8_t* Q4, uint8_t* M4,
+                                float* tlo, float* thi, hipStream_t s);
+// one-byte effective codes (multiplier * 4-bit code) from the packed 4-bit sketch
+tardis_status_t td_unpack_sketch4(const uint8_t* Q4, const uint8_t* M4, int64_t h, int64_t d, int8_t* Q,
+                                  hipStream_t s);
 tardis_status_t td_fold(const tardis_ffn_desc* desc, const float* a, const float* c, void* Wp, float* bp,
                         hipStream_t s);
 tardis_status_t td_calibrate(const tardis_ffn_desc* desc, const void* X, int64_t n, float coverage,

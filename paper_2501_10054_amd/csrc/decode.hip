@@ -38,10 +38,16 @@ __device__ __forceinline__ void load_row(td_u32x4 (&dst)[N], const void* row, in
 
 // TB tokens (1, 2 or 4) share one pass over the weights: x, y, yfold are TB x D, mask has TB rows of
 // mask_words words, yfix is copies x TB x D.
-template <int D, int BLOCK, int RQ, int TB>
+//
+// SK = 8: Q holds one int8 code per weight.  SK = 4: Q holds the packed 4-bit sketch, one 16-byte
+// vector per group of 32 columns (byte b of dword w = code of column 4w+b in the low nibble, of column
+// 16+4w+b in the high nibble), M4 one multiplier byte per group; the integer the range test sees is
+// sum over groups of multiplier * (code . token code), the same number an int8 row of
+// multiplier*code would give.
+template <int D, int BLOCK, int RQ, int TB, int SK>
 __global__ void __launch_bounds__(BLOCK)
 decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp, const int8_t* __restrict__ Q,
-                    const float* __restrict__ tlo, const float* __restrict__ thi, const bf16_t* __restrict__ W1,
+                    const uint8_t* __restrict__ M4, const float* __restrict__ tlo, const float* __restrict__ thi, const bf16_t* __restrict__ W1,
                     const bf16_t* __restrict__ b1, const bf16_t* __restrict__ W2T, const float* __restrict__ a,
                     const float* __restrict__ c, const bf16_t* __restrict__ x, bf16_t* __restrict__ y,
                     float* __restrict__ yfold, float* __restrict__ yfix, int copies, uint32_t* __restrict__ mask,
@@ -50,9 +56,11 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     static_assert(D % 1024 == 0, "rows must be whole multiples of 64 lanes x 16 bytes");
     static_assert(D % BLOCK == 0 && BLOCK / TD_WAVE >= 4, "column ownership of the repair pass");
     static_assert(TB == 1 || TB == 2 || TB == 4, "tokens per pass");
+    static_assert(SK == 8 || (SK == 4 && D % 2048 == 0), "a packed 4-bit row must fill whole wavefront loads");
     constexpr int NW = BLOCK / TD_WAVE;
     constexpr int NVW = D / 8;                       // 16-byte vectors per bf16 row
-    constexpr int IQ = D / 16 / TD_WAVE;             // per-lane vectors of an int8 row
+    constexpr int QROW = SK == 8 ? D : D / 2;        // bytes of one predictor row
+    constexpr int IQ = QROW / 16 / TD_WAVE;          // per-lane vectors of a predictor row
     constexpr int IW = NVW / TD_WAVE;                // per-lane vectors of a bf16 row
     constexpr int XI = (TB * NVW + BLOCK - 1) / BLOCK;  // per-thread vectors of the tokens
     constexpr int MW = kMaxNeuronsPerBlock / 32;
@@ -84,14 +92,22 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     }
     asm volatile("" ::: "memory");                   // keep the tokens' loads ahead of the row loads
     td_u32x4 q[RQ][IQ];
+    uint32_t mg[RQ][IQ];                             // group multipliers (4-bit sketch only)
     float tl[RQ], th[RQ];
+    auto load_pred_rows = [&](const int jfirst) {    // rows past the end re-read a valid row; their result is ignored
 #pragma unroll
-    for (int i = 0; i < RQ; ++i) {   // rows past the end re-read a valid row; their result is ignored
-        const int j = min(j0 + wave * RQ + i, h - 1);
-        load_row<IQ>(q[i], Q + (size_t)j * D, lane);
-        tl[i] = tlo[j];
-        th[i] = thi[j];
-    }
+        for (int i = 0; i < RQ; ++i) {
+            const int j = min(jfirst + i, h - 1);
+            load_row<IQ>(q[i], Q + (size_t)j * QROW, lane);
+            if (SK == 4) {
+#pragma unroll
+                for (int it = 0; it < IQ; ++it) mg[i][it] = M4[(size_t)j * (D / 32) + it * TD_WAVE + lane];
+            }
+            tl[i] = tlo[j];
+            th[i] = thi[j];
+        }
+    };
+    load_pred_rows(j0 + wave * RQ);
     const float bias_out = bp[min(blk * rpb + wave, D - 1)];
 
     // ---- stage the tokens, their maxima and their int8 codes
@@ -131,7 +147,13 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                 lo |= ((uint32_t)(uint8_t)quantize_value(td_bf16_to_f32(e8[u]), e)) << (8 * u);
                 hi |= ((uint32_t)(uint8_t)quantize_value(td_bf16_to_f32(e8[u + 4]), e)) << (8 * u);
             }
-            reinterpret_cast<uint2*>(xq)[v] = make_uint2(lo, hi);
+            if (SK == 8) {
+                reinterpret_cast<uint2*>(xq)[v] = make_uint2(lo, hi);
+            } else {   // columns 0..15 of every group of 32 in the first half of the token's codes, 16..31 in the second
+                const int i8 = v - tok * NVW, g = i8 >> 2, part = i8 & 3;
+                const int at = tok * (D / 8) + (part < 2 ? 0 : D / 16) + g * 2 + (part & 1);
+                reinterpret_cast<uint2*>(xq)[at] = make_uint2(lo, hi);
+            }
         }
     }
     __syncthreads();
@@ -141,15 +163,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     const td_u32x4* xq4 = reinterpret_cast<const td_u32x4*>(xq) + lane;
     for (int base = 0; base < jn; base += NW * RQ) {
         const int jb = base + wave * RQ;
-        if (base > 0) {
-#pragma unroll
-            for (int i = 0; i < RQ; ++i) {
-                const int j = min(j0 + jb + i, h - 1);
-                load_row<IQ>(q[i], Q + (size_t)j * D, lane);
-                tl[i] = tlo[j];
-                th[i] = thi[j];
-            }
-        }
+        if (base > 0) load_pred_rows(j0 + jb);
         // two tokens at a time against the rows held in registers (register budget)
         constexpr int TP = TB < 2 ? TB : 2;
         uint32_t bits[RQ];
@@ -165,15 +179,43 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                 for (int t = 0; t < TP; ++t) acc[i][t] = 0;
 #pragma unroll
             for (int it = 0; it < IQ; ++it) {
+                if (SK == 8) {
 #pragma unroll
-                for (int t = 0; t < TP; ++t) {
-                    const td_u32x4 xx = xq4[(t0 + t) * (D / 16) + it * TD_WAVE];
+                    for (int t = 0; t < TP; ++t) {
+                        const td_u32x4 xx = xq4[(t0 + t) * (D / 16) + it * TD_WAVE];
+#pragma unroll
+                        for (int i = 0; i < RQ; ++i) {
+                            acc[i][t] = __builtin_amdgcn_sdot4((int)q[i][it].x, (int)xx.x, acc[i][t], false);
+                            acc[i][t] = __builtin_amdgcn_sdot4((int)q[i][it].y, (int)xx.y, acc[i][t], false);
+                            acc[i][t] = __builtin_amdgcn_sdot4((int)q[i][it].z, (int)xx.z, acc[i][t], false);
+                            acc[i][t] = __builtin_amdgcn_sdot4((int)q[i][it].w, (int)xx.w, acc[i][t], false);
+                        }
+                    }
+                } else {
+                    // a nibble moved to the top of its byte is 16 * code as a signed byte: the group
+                    // sums below are 16 times the true ones, taken out after the reduction
+                    td_u32x4 xl[TP], xh[TP];
+#pragma unroll
+                    for (int t = 0; t < TP; ++t) {
+                        xl[t] = xq4[(t0 + t) * (D / 16) + it * TD_WAVE];
+                        xh[t] = xq4[(t0 + t) * (D / 16) + D / 32 + it * TD_WAVE];
+                    }
 #pragma unroll
                     for (int i = 0; i < RQ; ++i) {
-                        acc[i][t] = __builtin_amdgcn_sdot4((int)q[i][it].x, (int)xx.x, acc[i][t], false);
-                        acc[i][t] = __builtin_amdgcn_sdot4((int)q[i][it].y, (int)xx.y, acc[i][t], false);
-                        acc[i][t] = __builtin_amdgcn_sdot4((int)q[i][it].z, (int)xx.z, acc[i][t], false);
-                        acc[i][t] = __builtin_amdgcn_sdot4((int)q[i][it].w, (int)xx.w, acc[i][t], false);
+                        const td_u32x4 w = q[i][it];
+                        const td_u32x4 wl = (w << 4) & 0xF0F0F0F0u, wh = w & 0xF0F0F0F0u;
+#pragma unroll
+                        for (int t = 0; t < TP; ++t) {
+                            int g = __builtin_amdgcn_sdot4((int)wl.x, (int)xl[t].x, 0, false);
+                            g = __builtin_amdgcn_sdot4((int)wl.y, (int)xl[t].y, g, false);
+                            g = __builtin_amdgcn_sdot4((int)wl.z, (int)xl[t].z, g, false);
+                            g = __builtin_amdgcn_sdot4((int)wl.w, (int)xl[t].w, g, false);
+                            g = __builtin_amdgcn_sdot4((int)wh.x, (int)xh[t].x, g, false);
+                            g = __builtin_amdgcn_sdot4((int)wh.y, (int)xh[t].y, g, false);
+                            g = __builtin_amdgcn_sdot4((int)wh.z, (int)xh[t].z, g, false);
+                            g = __builtin_amdgcn_sdot4((int)wh.w, (int)xh[t].w, g, false);
+                            acc[i][t] += (int)mg[i][it] * g;
+                        }
                     }
                 }
             }
@@ -181,7 +223,8 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
             for (int i = 0; i < RQ; ++i) {
 #pragma unroll
                 for (int t = 0; t < TP; ++t) {
-                    const float v = ldexpf((float)td_wave_sum_i(acc[i][t]), ex[t0 + t]);
+                    const int total = td_wave_sum_i(acc[i][t]);
+                    const float v = ldexpf((float)(SK == 8 ? total : total >> 4), ex[t0 + t]);
                     const bool inside = (v >= tl[i]) && (v < th[i]);
                     bits[i] |= inside ? 0u : (1u << (t0 + t));
                 }
@@ -468,7 +511,7 @@ mask_to_list_kernel(const uint32_t* __restrict__ mask, int words, int h, int32_t
     if (threadIdx.x == 0 && counts) counts[t] = carry;
 }
 
-template <int D, int BLOCK, int TB>
+template <int D, int BLOCK, int TB, int SK>
 tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
                               int norm_out, hipStream_t s) {
     constexpr int RQ = 4;
@@ -477,8 +520,9 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
     int npb = (h + G - 1) / G;
     npb = (npb + 31) / 32 * 32;
     const int rpb = (D + G - 1) / G;
-    hipLaunchKernelGGL((decode_fused_kernel<D, BLOCK, RQ, TB>), dim3(G), dim3(BLOCK), 0, s,
-                       static_cast<const bf16_t*>(L->Wp), L->bp, L->Q, L->tlo, L->thi,
+    const int8_t* codes = SK == 8 ? L->Q : reinterpret_cast<const int8_t*>(L->Q4);
+    hipLaunchKernelGGL((decode_fused_kernel<D, BLOCK, RQ, TB, SK>), dim3(G), dim3(BLOCK), 0, s,
+                       static_cast<const bf16_t*>(L->Wp), L->bp, codes, L->M4, L->tlo, L->thi,
                        static_cast<const bf16_t*>(L->W1),
                        static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), static_cast<const bf16_t*>(L->W2T),
                        L->a, L->c, static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), yfold, L->yfix,
@@ -487,13 +531,13 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
     return TARDIS_OK;
 }
 
-template <int D, int BLOCK>
+template <int D, int BLOCK, int SK>
 tardis_status_t launch_tb(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask, int tokens,
                           int norm_out, hipStream_t s) {
     switch (tokens) {
-        case 1: return launch_decode<D, BLOCK, 1>(L, x, y, yfold, mask, norm_out, s);
-        case 2: return launch_decode<D, BLOCK, 2>(L, x, y, yfold, mask, norm_out, s);
-        case 4: return launch_decode<D, BLOCK, 4>(L, x, y, yfold, mask, norm_out, s);
+        case 1: return launch_decode<D, BLOCK, 1, SK>(L, x, y, yfold, mask, norm_out, s);
+        case 2: return launch_decode<D, BLOCK, 2, SK>(L, x, y, yfold, mask, norm_out, s);
+        case 4: return launch_decode<D, BLOCK, 4, SK>(L, x, y, yfold, mask, norm_out, s);
     }
     return TARDIS_ERR_INVALID_ARG;
 }
@@ -513,17 +557,27 @@ bool td_decode_fused_supported(const tardis_layer_s* L) {
 // `tokens` (1, 2 or 4) consecutive tokens in one launch
 tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
                                 int tokens, int norm_out, hipStream_t s) {
+    if (L->Q4) {   // packed 4-bit sketch (d = 2048 or 4096 only)
+        if (L->dec_threads == 512) {
+            if (L->d == 2048) return launch_tb<2048, 512, 4>(L, x, y, yfold, mask, tokens, norm_out, s);
+            if (L->d == 4096) return launch_tb<4096, 512, 4>(L, x, y, yfold, mask, tokens, norm_out, s);
+        } else {
+            if (L->d == 2048) return launch_tb<2048, 1024, 4>(L, x, y, yfold, mask, tokens, norm_out, s);
+            if (L->d == 4096) return launch_tb<4096, 1024, 4>(L, x, y, yfold, mask, tokens, norm_out, s);
+        }
+        return TARDIS_ERR_SHAPE;
+    }
     if (L->dec_threads == 512) {
         switch (L->d) {
-            case 1024: return launch_tb<1024, 512>(L, x, y, yfold, mask, tokens, norm_out, s);
-            case 2048: return launch_tb<2048, 512>(L, x, y, yfold, mask, tokens, norm_out, s);
-            case 4096: return launch_tb<4096, 512>(L, x, y, yfold, mask, tokens, norm_out, s);
+            case 1024: return launch_tb<1024, 512, 8>(L, x, y, yfold, mask, tokens, norm_out, s);
+            case 2048: return launch_tb<2048, 512, 8>(L, x, y, yfold, mask, tokens, norm_out, s);
+            case 4096: return launch_tb<4096, 512, 8>(L, x, y, yfold, mask, tokens, norm_out, s);
         }
     }
     switch (L->d) {
-        case 1024: return launch_tb<1024, 1024>(L, x, y, yfold, mask, tokens, norm_out, s);
-        case 2048: return launch_tb<2048, 1024>(L, x, y, yfold, mask, tokens, norm_out, s);
-        case 4096: return launch_tb<4096, 1024>(L, x, y, yfold, mask, tokens, norm_out, s);
+        case 1024: return launch_tb<1024, 1024, 8>(L, x, y, yfold, mask, tokens, norm_out, s);
+        case 2048: return launch_tb<2048, 1024, 8>(L, x, y, yfold, mask, tokens, norm_out, s);
+        case 4096: return launch_tb<4096, 1024, 8>(L, x, y, yfold, mask, tokens, norm_out, s);
     }
     return TARDIS_ERR_SHAPE;
 }

@@ -151,6 +151,103 @@ sketch_kernel(const T* __restrict__ W1, const T* __restrict__ b1, const float* _
     }
 }
 
+// 4-bit grouped sketch (groups of 32 consecutive columns): group maxima g, row maximum r,
+// s = r / (7*15), multiplier m = ceil(g / (7 s)) in [1, 15], code q = rint(w / (m s)) in [-7, 7];
+// all in fp64, each step one IEEE operation, so every output is a function of the inputs.
+// Outputs: M4 (one byte per group); Q (optional) the effective one-byte code m*q; Q4 (optional,
+// d % 32 == 0) the packed form read by the decode kernel: group G is the 16-byte vector G of the
+// row, byte b of its dword w holds column 4w+b in the low nibble and column 16+4w+b in the high one.
+template <typename T>
+__global__ void __launch_bounds__(kBlock)
+sketch4_kernel(const T* __restrict__ W1, const T* __restrict__ b1, const float* __restrict__ lo,
+               const float* __restrict__ hi, int64_t d, int ng, int8_t* __restrict__ Q, uint8_t* __restrict__ Q4,
+               uint8_t* __restrict__ M4, float* __restrict__ tlo, float* __restrict__ thi) {
+    extern __shared__ int gval[];                    // group maxima (bit patterns), then multipliers
+    __shared__ float red[kBlock / TD_WAVE];
+    const int64_t j = blockIdx.x;
+    const T* row = W1 + j * d;
+    for (int g = threadIdx.x; g < ng; g += kBlock) gval[g] = 0;
+    __syncthreads();
+    for (int64_t k = threadIdx.x; k < d; k += kBlock)   // non-negative floats order like their bit patterns
+        atomicMax(&gval[k >> 5], __float_as_int(fabsf(td_load<T>(row + k))));
+    __syncthreads();
+    float r = 0.0f;
+    for (int g = threadIdx.x; g < ng; g += kBlock) r = fmaxf(r, __int_as_float(gval[g]));
+    r = td_wave_max(r);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x / 64] = r;
+    __syncthreads();
+    r = red[0];
+#pragma unroll
+    for (int w = 1; w < kBlock / TD_WAVE; ++w) r = fmaxf(r, red[w]);
+    const double s = (double)r / 105.0;
+    const double bj = b1 ? (double)td_load<T>(b1 + j) : 0.0;
+    const bool live = r > 0.0f;
+    for (int g = threadIdx.x; g < ng; g += kBlock) {
+        int m = 1;
+        if (live) {
+            const double t = ceil((double)__int_as_float(gval[g]) / (7.0 * s));
+            m = (int)fmin(fmax(t, 1.0), 15.0);
+        }
+        gval[g] = m;
+        M4[j * ng + g] = (uint8_t)m;
+    }
+    __syncthreads();
+    auto code = [&](int64_t k) -> int {              // 4-bit code of column k
+        if (!live) return 0;
+        const double q = rint((double)td_load<T>(row + k) / ((double)gval[k >> 5] * s));
+        return (int)fmin(fmax(q, -7.0), 7.0);
+    };
+    if (Q4) {   // d is a multiple of 32 here
+        uint32_t* out = reinterpret_cast<uint32_t*>(Q4 + j * (d / 2));
+        for (int64_t idx = threadIdx.x; idx < d / 8; idx += kBlock) {
+            const int64_t g = idx >> 2, w = idx & 3;
+            uint32_t word = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int64_t klo = 32 * g + 4 * w + b, khi = klo + 16;
+                const int qlo = code(klo), qhi = code(khi);
+                word |= (uint32_t)((qlo & 0xF) | ((qhi & 0xF) << 4)) << (8 * b);
+                if (Q) {
+                    Q[j * d + klo] = (int8_t)(gval[g] * qlo);
+                    Q[j * d + khi] = (int8_t)(gval[g] * qhi);
+                }
+            }
+            out[idx] = word;
+        }
+    } else if (Q) {
+        for (int64_t k = threadIdx.x; k < d; k += kBlock) Q[j * d + k] = (int8_t)(gval[k >> 5] * code(k));
+    }
+    if (threadIdx.x == 0) {
+        if (live) {
+            tlo[j] = (float)(((double)lo[j] - bj) / s);
+            thi[j] = (float)(((double)hi[j] - bj) / s);
+        } else {
+            const bool inside = ((double)lo[j] <= bj) && (bj < (double)hi[j]);
+            tlo[j] = inside ? -INFINITY : INFINITY;
+            thi[j] = INFINITY;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(kBlock)
+unpack_sketch4_kernel(const uint8_t* __restrict__ Q4, const uint8_t* __restrict__ M4, int64_t d,
+                      int8_t* __restrict__ Q) {
+    const int64_t j = blockIdx.x;
+    const uint32_t* in = reinterpret_cast<const uint32_t*>(Q4 + j * (d / 2));
+    for (int64_t idx = threadIdx.x; idx < d / 8; idx += kBlock) {
+        const int64_t g = idx >> 2, w = idx & 3;
+        const int m = M4[j * (d / 32) + g];
+        const uint32_t word = in[idx];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int byte = (int)((word >> (8 * b)) & 0xFFu);
+            const int qlo = ((byte & 0xF) ^ 8) - 8, qhi = ((byte >> 4) ^ 8) - 8;   // sign-extend 4 bits
+            Q[j * d + 32 * g + 4 * w + b] = (int8_t)(m * qlo);
+            Q[j * d + 32 * g + 16 + 4 * w + b] = (int8_t)(m * qhi);
+        }
+    }
+}
+
 // -------------------------------------------------------------- calibration
 // One block per neuron.  zt: that neuron's n calibration pre-activations.
 // Sort in LDS (bitonic, padded with +inf), read the two quantiles by linear
@@ -284,13 +381,36 @@ tardis_status_t td_transpose(const void* src, void* dst, int64_t rows, int64_t c
 }
 
 tardis_status_t td_build_sketch(const void* W1, const void* b1, const float* lo, const float* hi, int64_t h,
-                                int64_t d, int32_t dtype, int8_t* Q, float* tlo, float* thi, hipStream_t s) {
+                                int64_t d, int32_t dtype, int32_t bits, int8_t* Q, uint8_t* Q4, uint8_t* M4,
+                                float* tlo, float* thi, hipStream_t s) {
+    if (bits == 4) {
+        const int64_t ng = (d + 31) / 32;
+        if (!M4 || (Q4 && d % 32 != 0) || ng * 4 > 64 * 1024) return TARDIS_ERR_SHAPE;
+        if (dtype == TARDIS_BF16)
+            hipLaunchKernelGGL(sketch4_kernel<bf16_t>, dim3((unsigned)h), dim3(kBlock), (size_t)ng * 4, s,
+                               static_cast<const bf16_t*>(W1), static_cast<const bf16_t*>(b1), lo, hi, d, (int)ng,
+                               Q, Q4, M4, tlo, thi);
+        else
+            hipLaunchKernelGGL(sketch4_kernel<float>, dim3((unsigned)h), dim3(kBlock), (size_t)ng * 4, s,
+                               static_cast<const float*>(W1), static_cast<const float*>(b1), lo, hi, d, (int)ng,
+                               Q, Q4, M4, tlo, thi);
+        TD_HIP(hipGetLastError());
+        return TARDIS_OK;
+    }
+    if (bits != 8 || !Q) return TARDIS_ERR_INVALID_ARG;
     if (dtype == TARDIS_BF16)
         hipLaunchKernelGGL(sketch_kernel<bf16_t>, dim3((unsigned)h), dim3(kBlock), 0, s,
                            static_cast<const bf16_t*>(W1), static_cast<const bf16_t*>(b1), lo, hi, d, Q, tlo, thi);
     else
         hipLaunchKernelGGL(sketch_kernel<float>, dim3((unsigned)h), dim3(kBlock), 0, s,
                            static_cast<const float*>(W1), static_cast<const float*>(b1), lo, hi, d, Q, tlo, thi);
+    TD_HIP(hipGetLastError());
+    return TARDIS_OK;
+}
+
+tardis_status_t td_unpack_sketch4(const uint8_t* Q4, const uint8_t* M4, int64_t h, int64_t d, int8_t* Q,
+                                  hipStream_t s) {
+    hipLaunchKernelGGL(unpack_sketch4_kernel, dim3((unsigned)h), dim3(kBlock), 0, s, Q4, M4, d, Q);
     TD_HIP(hipGetLastError());
     return TARDIS_OK;
 }

@@ -24,7 +24,7 @@ _DTYPE_CODE = {torch.float32: F32, torch.bfloat16: BF16}
 EXPORTS = (
     "tardis_calibrate", "tardis_fold", "tardis_ffn_forward", "tardis_ffn_forward_batched",
     "tardis_stack_forward", "tardis_dense_forward", "tardis_get_folded", "tardis_get_predictor_state",
-    "tardis_get_last_outliers", "tardis_get_handover", "tardis_destroy", "tardis_status_string", "tardis_version",
+    "tardis_get_sketch_groups", "tardis_get_last_outliers", "tardis_get_handover", "tardis_destroy", "tardis_status_string", "tardis_version",
 )
 
 
@@ -64,6 +64,7 @@ def lib() -> C.CDLL:
         L.tardis_stack_forward.argtypes = [C.POINTER(vp), C.c_int32, vp, i64, vp, vp]
         L.tardis_get_folded.argtypes = [vp, vp, vp, vp]
         L.tardis_get_predictor_state.argtypes = [vp, vp, vp, vp, vp]
+        L.tardis_get_sketch_groups.argtypes = [vp, vp, vp]
         L.tardis_get_last_outliers.argtypes = [vp, i64, vp, vp, vp, vp]
         L.tardis_get_handover.argtypes = [vp, i64, vp, vp]
         L.tardis_destroy.argtypes = [vp]
@@ -145,10 +146,10 @@ class Layer:
             pass
 
 
-def tardis_fold(ffn: FFN, lo, hi, a, c, max_batch: int = 1, stream=None) -> Layer:
+def tardis_fold(ffn: FFN, lo, hi, a, c, max_batch: int = 1, sketch_bits: int = 8, stream=None) -> Layer:
     for t in (lo, hi, a, c):
         assert t.is_cuda and t.is_contiguous() and t.dtype == torch.float32 and t.numel() == ffn.h
-    opts = tardis_fold_opts(8, ffn.dtype, max_batch, 0, 0)
+    opts = tardis_fold_opts(sketch_bits, ffn.dtype, max_batch, 0, 0)
     handle = C.c_void_p()
     st = lib().tardis_fold(C.byref(ffn.desc), _ptr(lo), _ptr(hi), _ptr(a), _ptr(c), C.byref(opts),
                            _stream(stream), C.byref(handle))
@@ -203,6 +204,12 @@ def tardis_get_predictor_state(L: Layer, stream=None):
     _check(lib().tardis_get_predictor_state(L.handle, _ptr(Q), _ptr(tlo), _ptr(thi), _stream(stream)),
            "tardis_get_predictor_state")
     return Q, tlo, thi
+
+
+def tardis_get_sketch_groups(L: Layer, stream=None):
+    M = torch.empty(L.h, (L.d + 31) // 32, dtype=torch.uint8, device=L.device)
+    _check(lib().tardis_get_sketch_groups(L.handle, _ptr(M), _stream(stream)), "tardis_get_sketch_groups")
+    return M
 
 
 def tardis_get_handover(L: Layer, n: int, stream=None):

@@ -61,7 +61,8 @@ def test_fold_rejects_bad_arguments_without_a_gpu():
     assert fold(_desc(dtype=7)) == T.ERR_DTYPE
     assert fold(_desc(act=9)) == T.ERR_INVALID_ARG
     assert fold(_desc(), lo=None) == T.ERR_INVALID_ARG
-    assert fold(_desc(), opts=T.tardis_fold_opts(4, T.F32, 1, 0, 0)) == T.ERR_INVALID_ARG
+    assert fold(_desc(), opts=T.tardis_fold_opts(2, T.F32, 1, 0, 0)) == T.ERR_INVALID_ARG       # 8 and 4 only
+    assert fold(_desc(), opts=T.tardis_fold_opts(16, T.F32, 1, 0, 0)) == T.ERR_INVALID_ARG
     assert fold(_desc(), opts=T.tardis_fold_opts(8, T.BF16, 1, 0, 0)) == T.ERR_DTYPE
     assert fold(_desc(), opts=T.tardis_fold_opts(8, T.F32, 0, 0, 0)) == T.ERR_SHAPE
     assert fold(_desc(), opts=T.tardis_fold_opts(8, T.F32, 1, 1, 0)) == T.ERR_INVALID_ARG
@@ -94,6 +95,7 @@ def test_online_calls_reject_null_handle():
     assert lib.tardis_get_predictor_state(None, p, p, p, None) == T.ERR_STATE
     assert lib.tardis_get_last_outliers(None, 1, p, p, p, None) == T.ERR_STATE
     assert lib.tardis_get_handover(None, 1, p, None) == T.ERR_STATE
+    assert lib.tardis_get_sketch_groups(None, p, None) == T.ERR_STATE
     arr = (C.c_void_p * 2)(None, None)
     assert lib.tardis_stack_forward(arr, 2, p, 1, C.c_void_p(0x8000), None) == T.ERR_STATE
     assert lib.tardis_stack_forward(None, 2, p, 1, C.c_void_p(0x8000), None) == T.ERR_INVALID_ARG

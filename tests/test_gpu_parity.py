@@ -51,7 +51,7 @@ def custom_layer(d, h, dtype, seed, w1_std, bias):
     return synth.make_layer(d, h, dtype, seed, w1_std=w1_std, w2_std=0.05, heavy_frac=0.02, with_bias=bias)
 
 
-def run_case(layer, X_cal, X_test, coverage, act="gelu_erf", batched=False, check_calibrate=True):
+def run_case(layer, X_cal, X_test, coverage, act="gelu_erf", batched=False, check_calibrate=True, sketch_bits=8):
     """Full pipeline on the GPU and in the checker; returns a dict of diagnostics."""
     dt = layer.dtype
     ffn = make_ffn(layer, act)
@@ -71,8 +71,8 @@ def run_case(layer, X_cal, X_test, coverage, act="gelu_erf", batched=False, chec
         assert np.abs(c_h - oc).max() <= (5.0 / n_cal + 1e-4) * max(1.0, scale)
 
     # from here on both sides use the SAME (lo, hi, a, c): the library's
-    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=max(1, X_test.shape[0]))
-    F = O.build(layer.W1, layer.b1, layer.W2, layer.b2, lo_h, hi_h, a_h, c_h, act)
+    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=max(1, X_test.shape[0]), sketch_bits=sketch_bits)
+    F = O.build(layer.W1, layer.b1, layer.W2, layer.b2, lo_h, hi_h, a_h, c_h, act, sketch_bits=sketch_bits)
 
     Wp, bp = T.tardis_get_folded(L)
     Q, tlo, thi = T.tardis_get_predictor_state(L)
@@ -83,6 +83,8 @@ def run_case(layer, X_cal, X_test, coverage, act="gelu_erf", batched=False, chec
     np.testing.assert_array_equal(Q.cpu().numpy(), F.sk.Q)
     np.testing.assert_array_equal(tlo.cpu().numpy(), F.sk.tlo)
     np.testing.assert_array_equal(thi.cpu().numpy(), F.sk.thi)
+    if sketch_bits == 4:
+        np.testing.assert_array_equal(T.tardis_get_sketch_groups(L).cpu().numpy(), F.sk.m)
 
     n = X_test.shape[0]
     Xd = dev(X_test, dt)
@@ -190,6 +192,41 @@ def test_batched_with_bias_and_relu():
     X_cal = synth.make_tokens(400, 512, "bf16", seed, synth.STREAM_CAL)
     X_test = synth.make_tokens(33, 512, "bf16", seed, synth.STREAM_TEST)
     run_case(layer, X_cal, X_test, 0.9, act="relu", batched=True, check_calibrate=False)
+
+
+# ------------------------------------------------------------- 4-bit grouped sketch
+def test_sketch4_tiny_fp32_and_ragged_groups():
+    w = synth.tiny(hard=True, with_bias=True)                    # d = 64: two whole groups
+    run_case(w.layer, w.X_cal, w.X_test, w.coverage, sketch_bits=4)
+    seed = synth.workload_seed(9, 11)
+    layer = synth.make_layer(50, 77, "f32", seed, w1_std=0.2, w2_std=0.05, heavy_frac=0.05)   # last group: 18 columns
+    run_case(layer, synth.make_tokens(300, 50, "f32", seed, synth.STREAM_CAL),
+             synth.make_tokens(6, 50, "f32", seed, synth.STREAM_TEST), 0.9, sketch_bits=4, batched=True)
+
+
+def test_sketch4_zero_rows_and_zero_groups():
+    seed = synth.workload_seed(9, 12)
+    layer = custom_layer(96, 64, "f32", seed, w1_std=0.3, bias=True)
+    layer.W1[5] = 0.0                                            # zero row, bias inside or outside its range
+    layer.W1[6] = 0.0
+    layer.b1[6] = 100.0
+    layer.W1[7, 32:64] = 0.0                                     # a zero group in a live row
+    layer.W1[8, :] = 0.0
+    layer.W1[8, 70] = 0.25                                       # one non-zero weight in the whole row
+    run_case(layer, synth.make_tokens(200, 96, "f32", seed, synth.STREAM_CAL),
+             synth.make_tokens(5, 96, "f32", seed, synth.STREAM_TEST), 0.9, sketch_bits=4)
+
+
+@pytest.mark.parametrize("d,h,n,batched", [(1024, 2048, 3, False), (2048, 1000, 3, False), (2048, 1000, 7, True),
+                                           (2048, 4096, 20, True), (4096, 2048, 5, True)])
+def test_sketch4_bf16_paths(d, h, n, batched):
+    """d = 1024: the single-launch kernel on one-byte effective codes.  d = 2048, 4096: the packed
+    4-bit rows (1, 2 and 4 tokens per launch); 20 tokens: the 64-token-pass path on effective codes."""
+    seed = synth.workload_seed(9, 13)
+    layer = synth.make_layer(d, h, "bf16", seed, w1_std=0.03, w2_std=0.03, heavy_frac=0.01, with_bias=True)
+    X_cal = synth.make_tokens(256, d, "bf16", seed, synth.STREAM_CAL)
+    X_test = synth.make_tokens(n, d, "bf16", seed, synth.STREAM_TEST)
+    run_case(layer, X_cal, X_test, 0.9, check_calibrate=False, batched=batched, sketch_bits=4)
 
 
 # ----------------------------------------------------------------- edge cases
@@ -510,6 +547,35 @@ def test_full_size_prefill_sampled_tokens(decode_full):
     assert (cnt == FLg.sum(1)).all()
     assert abs(cnt.mean() / w.layer.h - 0.05) < 0.005
     assert torch.isfinite(Y.float()).all()
+
+
+def test_full_size_sketch4_decode(decode_full):
+    """The full layer folded with the 4-bit sketch: codes and multipliers bit-exact, masks bit-exact
+    and y within the bar for single tokens and a group of four; the flag rate rises a little
+    because the coarser predictor errs on both sides."""
+    w, ffn, (lo, hi, a, c), _, _ = decode_full
+    L4 = T.tardis_fold(ffn, lo, hi, a, c, max_batch=8, sketch_bits=4)
+    sk = O.sketch(w.layer.W1, None, lo.cpu().numpy(), hi.cpu().numpy(), bits=4)
+    Q, tlo, thi = T.tardis_get_predictor_state(L4)
+    assert torch.equal(Q.cpu(), torch.from_numpy(sk.Q))
+    np.testing.assert_array_equal(T.tardis_get_sketch_groups(L4).cpu().numpy(), sk.m)
+    np.testing.assert_array_equal(tlo.cpu().numpy(), sk.tlo)
+    np.testing.assert_array_equal(thi.cpu().numpy(), sk.thi)
+    F = O.build(w.layer.W1, None, w.layer.W2, None, *(t.cpu().numpy() for t in (lo, hi, a, c)), sketch_bits=4)
+    X = w.X_test[300:306]
+    Yo, FLo = O.forward(F, X)
+    Xd = dev(X, "bf16")
+    for t in range(2):
+        y = T.tardis_ffn_forward(L4, Xd[t])
+        mask, cnt, _ = T.tardis_get_last_outliers(L4, 1, want_list=False)
+        np.testing.assert_array_equal(unpack_mask(mask, w.layer.h)[0], FLo[t])
+        assert rel_l2(host(y), Yo[t]) <= 1e-2
+    Y = T.tardis_ffn_forward_batched(L4, Xd)                     # 4 + 2 tokens per launch
+    mask, counts, _ = T.tardis_get_last_outliers(L4, 6, want_list=False)
+    np.testing.assert_array_equal(unpack_mask(mask, w.layer.h), FLo)
+    assert rel_l2(host(Y), Yo) <= 1e-2
+    assert 0.04 < FLo.mean() < 0.09
+    L4.close()
 
 
 def test_full_size_stack_of_three_layers():
