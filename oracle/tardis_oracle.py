@@ -181,12 +181,11 @@ class Sketch:
     bits: int = 8
     group: int = 0     # columns per group (4-bit sketch), 0 for the ungrouped 8-bit sketch
     m: np.ndarray | None = None   # h x ceil(d/group) uint8 group multipliers (4-bit sketch)
-    q4: np.ndarray | None = None  # h x d int8 4-bit codes in [-7, 7]; Q = m (per group) * q4
+    q4: np.ndarray | None = None  # h x d int8 low-bit codes (in [-7, 7] for 4 bits); Q = m (per group) * q4
 
 
-SKETCH4_QMAX = 7       # largest 4-bit code magnitude (symmetric: -8 is not used)
-SKETCH4_MMAX = 15      # largest group multiplier (4 bits, 1..15)
-SKETCH4_GROUP = 32     # consecutive columns that share one multiplier
+SKETCH_MMAX = 15       # largest group multiplier (4 bits, 1..15)
+SKETCH_GROUP = 32      # consecutive columns that share one multiplier
 
 
 def _thresholds(lo, hi, b, s):
@@ -226,6 +225,10 @@ def sketch(W1, b1, lo, hi, bits: int = 8) -> Sketch:
     the dot product stays one exact integer sum.  Storage: 4 bits per weight plus
     4 bits per group of 32.
 
+    bits = 3, 2 (checker only, for the predictor-width study of Sec. "Predictor
+    Size"; the library builds 8 and 4): the same grouped form with the largest
+    code 2^(bits-1) - 1 in place of 7.
+
     Either way the test lo <= s_j*(Q_j . x) + b1_j < hi becomes
     tlo_j <= Q_j . x < thi_j with tlo = (lo-b1)/s, thi = (hi-b1)/s.
     """
@@ -241,26 +244,27 @@ def sketch(W1, b1, lo, hi, bits: int = 8) -> Sketch:
                 Q[j] = np.clip(np.rint(W1[j] / s[j]), -127, 127).astype(np.int8)
         tlo, thi = _thresholds(lo, hi, b, s)
         return Sketch(Q=Q, s=s, tlo=tlo, thi=thi)
-    if bits != 4:
-        raise ValueError("sketch bits must be 8 or 4")
-    G = SKETCH4_GROUP
+    if bits not in (4, 3, 2):
+        raise ValueError("sketch bits must be 8, 4, 3 or 2")
+    qmax = 2 ** (bits - 1) - 1
+    G = SKETCH_GROUP
     ng = (d + G - 1) // G
     Wg = np.zeros((h, ng * G))                     # zero padding changes no maximum and no code
     Wg[:, :d] = W1
     Wg = Wg.reshape(h, ng, G)
     gmax = np.abs(Wg).max(axis=2)                  # h x ng
-    s = gmax.max(axis=1) / float(SKETCH4_QMAX * SKETCH4_MMAX)
+    s = gmax.max(axis=1) / float(qmax * SKETCH_MMAX)
     live = s > 0.0
     s_safe = np.where(live, s, 1.0)
-    m = np.clip(np.ceil(gmax / (SKETCH4_QMAX * s_safe)[:, None]), 1, SKETCH4_MMAX)
+    m = np.clip(np.ceil(gmax / (qmax * s_safe)[:, None]), 1, SKETCH_MMAX)
     m = np.where(live[:, None], m, 1.0)
-    q = np.clip(np.rint(Wg / (m * s_safe[:, None])[:, :, None]), -SKETCH4_QMAX, SKETCH4_QMAX)
+    q = np.clip(np.rint(Wg / (m * s_safe[:, None])[:, :, None]), -qmax, qmax)
     q = np.where(live[:, None, None], q, 0.0)
     q4 = q.reshape(h, ng * G)[:, :d].astype(np.int8)
     Q = (m[:, :, None] * q).reshape(h, ng * G)[:, :d].astype(np.int8)
     m = m.astype(np.uint8)
     tlo, thi = _thresholds(lo, hi, b, s)
-    return Sketch(Q=Q, s=s, tlo=tlo, thi=thi, bits=4, group=G, m=m, q4=q4)
+    return Sketch(Q=Q, s=s, tlo=tlo, thi=thi, bits=bits, group=G, m=m, q4=q4)
 
 
 def quantize_token(x):

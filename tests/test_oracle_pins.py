@@ -429,7 +429,7 @@ def test_sketch4_brute_force_and_error_bound():
     # the heavy column's group is coarser than the others (that is the point of grouping)
     assert (sk.m[[0, 1, 3], 0] == 15).all() and (sk.m[[0, 1, 3], 1] < 8).all() and (sk.m[4, 1] == 1)
     with pytest.raises(ValueError):
-        O.sketch(W1, b1, lo, hi, bits=2)
+        O.sketch(W1, b1, lo, hi, bits=5)
 
 
 def test_predict_with_sketch4_is_the_grouped_integer_sum():
@@ -473,6 +473,30 @@ def test_sketch4_tracks_true_preactivation_less_tightly_than_sketch8():
         assert (f4[safe] == truth[safe]).all()
         agree4 += (f4 == truth).sum(); agree8 += (f8 == truth).sum(); total += truth.size
     assert agree8 >= agree4 and agree4 / total > 0.85
+
+
+def test_predictor_quality_falls_with_code_width():
+    """Flag precision / recall against the exact pre-activation by code width, on the scaled-down
+    decode layer (heavy-tailed weights): the study the paper makes of its predictor's size
+    (Sec. "Predictor Size"), here for round-to-nearest codes.  8 and 4 bits are usable; 2-bit
+    round-to-nearest codes are not (the paper's 2-bit predictor is error-compensated)."""
+    w = synth.decode(d=512, h=1024, n_cal=512, n_test=24, coverage=0.95)
+    W1 = w.layer.W1.astype(np.float64)
+    lo, hi, a, c = O.calibrate(W1, None, w.X_cal, 0.95)
+    res = {}
+    for bits in (8, 4, 3, 2):
+        sk = O.sketch(W1, None, lo, hi, bits=bits)
+        tp = fp = fn = 0
+        for x in w.X_test.astype(np.float64):
+            z = W1 @ x
+            truth = ~((z >= lo) & (z < hi))
+            f = O.predict(sk, x)
+            tp += (f & truth).sum(); fp += (f & ~truth).sum(); fn += (~f & truth).sum()
+        res[bits] = (tp / (tp + fp), tp / (tp + fn))
+    assert res[8][0] > 0.95 and res[8][1] > 0.95
+    assert res[4][0] > 0.75 and res[4][1] > 0.80
+    assert res[8] > res[4] > res[3] > res[2]
+    assert res[2][1] < 0.6
 
 
 def test_ties_round_to_even_in_codes():
