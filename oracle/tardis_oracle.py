@@ -27,7 +27,11 @@ the least-squares fit, a literal per-neuron rank-1 fold, brute-force integer
 dot products, hand-worked 4-bit group codes, the reconstruction error bound of
 both sketches, and the all-flagged / none-flagged identities.
 
-parity unpinned: nothing on the gated path.  (The integer predictor below is a
+parity unpinned: kde_centroid / range_search (the paper prints no worked
+example of its range search and leaves the density estimate, the error
+aggregation and the end of the growth loop open; they are pinned only by an
+independent brute-force re-implementation and by invariants).  Nothing on the
+gated path.  (The integer predictor below is a
 reading of "a quantised copy of W1", Sec. "Predictor Generation"; the paper
 prints no numbers for it, so it is pinned by brute force and by the printed
 example's flag set, not by a published value.)
@@ -141,6 +145,110 @@ def calibrate(W1, b1, X_cal, coverage, kind: str = "gelu_erf"):
         zs = np.sort(zj)
         lo[j] = np.float32(quantile_linear(zs, (1.0 - t[j]) / 2.0))
         hi[j] = np.float32(quantile_linear(zs, (1.0 + t[j]) / 2.0))
+        sel = (zj >= np.float64(lo[j])) & (zj < np.float64(hi[j]))
+        aj, cj = fit_line(zj[sel], act(zj[sel], kind), float(lo[j]), kind)
+        a[j] = np.float32(aj)
+        c[j] = np.float32(cj)
+    return lo, hi, a, c
+
+
+# ---------------------------------------------------------------------------
+# range search  (Sec. "Non-linear Function Approximation", paragraph "Range
+# Searching" and the inner loop of Algorithm 1: start at the centroid of the
+# neuron's input distribution, grow the range by a step s to the left or to
+# the right, whichever candidate is approximated with the smaller error, until
+# the range holds the portion t of the calibration inputs)
+# ---------------------------------------------------------------------------
+KDE_GRID = 256            # points at which the density estimate is evaluated
+SEARCH_MAX_STEPS = 65536  # growth steps after which the whole sample range is taken
+
+
+def kde_centroid(zs: np.ndarray) -> float:
+    """Mode of a Gaussian kernel density estimate of the samples `zs` (sorted).
+
+    The paper names kernel density estimation and nothing more.  Reading:
+    Gaussian kernel, bandwidth 1.06 * std * N^(-1/5) (std with N-1 in the
+    denominator), density evaluated at KDE_GRID equally spaced points from the
+    smallest to the largest sample (both included); the centroid is the grid
+    point of largest density, the leftmost one among equals.  All samples equal
+    (or one sample): that value.
+    """
+    n = zs.shape[0]
+    zmin, zmax = float(zs[0]), float(zs[-1])
+    if n < 2 or not zmax > zmin:
+        return zmin
+    mean = zs.sum() / n
+    std = math.sqrt(((zs - mean) ** 2).sum() / (n - 1))
+    bw = 1.06 * std * n ** (-0.2)
+    grid = zmin + np.arange(KDE_GRID) * ((zmax - zmin) / (KDE_GRID - 1))
+    u = (grid[:, None] - zs[None, :]) / bw
+    dens = np.exp(-0.5 * u * u).sum(axis=1)
+    return float(grid[int(np.argmax(dens))])       # argmax returns the first maximum
+
+
+def approx_error(z_in: np.ndarray, kind: str) -> float:
+    """Error of approximating sigma by its least-squares line over the samples
+    `z_in` of a candidate range: the sum over the samples of |sigma(z) - (a z + c)|
+    (the per-input L2 distance err_n(x) of one neuron's contribution, without the
+    factor ||W2[:, n]|| that both candidates of a step share)."""
+    if z_in.shape[0] == 0:
+        return 0.0
+    g = act(z_in, kind)
+    a, c = fit_line(z_in, g, 0.0, kind)
+    return float(np.abs(g - (a * z_in + c)).sum())
+
+
+def range_search(z: np.ndarray, t: float, step: float, kind: str = "gelu_erf"):
+    """Greedy range of one neuron.  Returns (lo, hi) in fp64.
+
+    R = [centroid, centroid); while the portion of the samples with lo <= z < hi
+    is below t: the two candidates are (lo - s, hi) and (lo, hi + s); the one
+    with the smaller approx_error is taken, the right one when they are equal.
+    Readings where the listing is silent or garbled: both candidates keep the
+    other end of R; a side whose end already lies beyond every sample (lo <=
+    min z, resp. hi > max z) is not offered again - the listing would otherwise
+    keep choosing an extension that adds no sample and never end; after
+    SEARCH_MAX_STEPS steps the whole sample range is taken.
+    """
+    zs = np.sort(_f64(z))
+    n = zs.shape[0]
+    lo = hi = kde_centroid(zs)
+    zmin, zmax = float(zs[0]), float(zs[-1])
+    for _ in range(SEARCH_MAX_STEPS):
+        inside = (zs >= lo) & (zs < hi)
+        if inside.sum() / n >= t:
+            return lo, hi
+        left_open, right_open = lo > zmin, not hi > zmax
+        if not left_open and not right_open:
+            return lo, hi
+        if left_open and right_open:
+            e_l = approx_error(zs[(zs >= lo - step) & (zs < hi)], kind)
+            e_r = approx_error(zs[(zs >= lo) & (zs < hi + step)], kind)
+            go_left = e_l < e_r
+        else:
+            go_left = left_open
+        if go_left:
+            lo = lo - step
+        else:
+            hi = hi + step
+    return zmin, float(np.nextafter(zmax, np.inf))
+
+
+def calibrate_search(W1, b1, X_cal, coverage, step, kind: str = "gelu_erf"):
+    """As `calibrate`, with the range of every neuron found by `range_search`
+    instead of central quantiles.  Returns four float32 arrays of length h."""
+    Z = preact(W1, b1, X_cal)
+    n, h = Z.shape
+    t = np.broadcast_to(np.asarray(coverage, dtype=np.float64), (h,))
+    lo = np.empty(h, np.float32)
+    hi = np.empty(h, np.float32)
+    a = np.empty(h, np.float32)
+    c = np.empty(h, np.float32)
+    for j in range(h):
+        zj = Z[:, j]
+        l, r = range_search(zj, float(t[j]), float(step), kind)
+        lo[j] = np.float32(l)
+        hi[j] = np.float32(r)
         sel = (zj >= np.float64(lo[j])) & (zj < np.float64(hi[j]))
         aj, cj = fit_line(zj[sel], act(zj[sel], kind), float(lo[j]), kind)
         a[j] = np.float32(aj)

@@ -323,6 +323,128 @@ def test_batched_forward_is_per_token():
     assert FL.any() and not FL.all()
 
 
+# ---------------------------------------------------------------- range search
+def _brute_centroid(zs):
+    n = len(zs)
+    if n < 2 or zs[-1] == zs[0]:
+        return zs[0]
+    mean = sum(zs) / n
+    std = math.sqrt(sum((v - mean) ** 2 for v in zs) / (n - 1))
+    bw = 1.06 * std * n ** (-0.2)
+    best, best_d = None, -1.0
+    for g in range(256):
+        u = zs[0] + g * ((zs[-1] - zs[0]) / 255)
+        dsum = sum(math.exp(-0.5 * ((u - v) / bw) ** 2) for v in zs)
+        if dsum > best_d:
+            best, best_d = u, dsum
+    return best
+
+
+def _brute_error(sel, kind):
+    if len(sel) == 0:
+        return 0.0
+    zz = np.array(sel)
+    g = O.act(zz, kind)
+    if len(sel) < 2 or zz.max() == zz.min():
+        return float(np.abs(g - g.mean()).sum())
+    coef, *_ = np.linalg.lstsq(np.stack([zz, np.ones_like(zz)], 1), g, rcond=None)   # library least squares
+    return float(np.abs(g - (coef[0] * zz + coef[1])).sum())
+
+
+def _brute_search(z, t, step, kind):
+    zs = sorted(float(v) for v in z)
+    lo = hi = _brute_centroid(zs)
+    trace = []
+    while sum(1 for v in zs if lo <= v < hi) / len(zs) < t:
+        can_l, can_r = lo > zs[0], not hi > zs[-1]
+        if can_l and can_r:
+            e_l = _brute_error([v for v in zs if lo - step <= v < hi], kind)
+            e_r = _brute_error([v for v in zs if lo <= v < hi + step], kind)
+            left = e_l < e_r - 1e-9 * max(e_l, e_r)        # a clear win only; exact ties go right
+            near_tie = abs(e_l - e_r) <= 1e-9 * max(e_l, e_r, 1e-300)
+        else:
+            left, near_tie = can_l, False
+        trace.append(("L" if left else "R", near_tie))
+        if left:
+            lo -= step
+        else:
+            hi += step
+    return lo, hi, trace
+
+
+def test_kde_centroid_against_brute_force_and_shape():
+    rng = np.random.default_rng(31)
+    z = np.sort(np.concatenate([rng.normal(-2.0, 0.3, 40), rng.normal(1.5, 0.5, 160)]))
+    assert O.kde_centroid(z) == pytest.approx(_brute_centroid(list(z)), abs=1e-12)
+    assert abs(O.kde_centroid(z) - 1.5) < 0.3                     # the heavier of the two modes
+    z = np.sort(rng.normal(0.7, 1.0, 4000))
+    assert abs(O.kde_centroid(z) - 0.7) < 0.15
+    assert O.kde_centroid(np.array([2.5, 2.5, 2.5])) == 2.5 and O.kde_centroid(np.array([-1.0])) == -1.0
+
+
+@pytest.mark.parametrize("kind,t,step", [("gelu_erf", 0.9, 0.1), ("gelu_erf", 0.6, 0.25), ("gelu_tanh", 0.8, 0.07),
+                                         ("relu", 0.85, 0.2)])
+def test_range_search_against_brute_force(kind, t, step):
+    rng = np.random.default_rng(32)
+    z = rng.normal(0.2, 1.3, 150)
+    lo, hi = O.range_search(z, t, step, kind)
+    blo, bhi, trace = _brute_search(z, t, step, kind)
+    if not any(tie for _, tie in trace):                          # no step was decided by rounding noise
+        assert lo == pytest.approx(blo, abs=1e-9) and hi == pytest.approx(bhi, abs=1e-9)
+    cen = O.kde_centroid(np.sort(z))
+    kl, kr = (cen - lo) / step, (hi - cen) / step
+    assert abs(kl - round(kl)) < 1e-6 and abs(kr - round(kr)) < 1e-6 and round(kl) + round(kr) == len(trace)
+    cover = ((z >= lo) & (z < hi)).mean()
+    assert cover >= t
+    # minimal: undoing the last step falls below the target
+    last = trace[-1][0]
+    plo, phi = (lo + step, hi) if last == "L" else (lo, hi - step)
+    assert ((z >= plo) & (z < phi)).mean() < t
+
+
+def test_range_search_tie_rule_and_exhausted_sides():
+    z = np.array([1.0, 1.2, 1.4, 1.5, 1.6, 1.8, 2.0, 3.0])
+    # identity: every candidate is fitted exactly, all errors are 0, ties go right until the right
+    # end passes the largest sample, then the left side is the only one offered
+    lo, hi = O.range_search(z, 1.0, 0.5, "identity")
+    cen = O.kde_centroid(np.sort(z))
+    assert hi > 3.0 and hi - 0.5 <= 3.0 and lo <= 1.0 and lo + 0.5 > 1.0
+    lo2, hi2 = O.range_search(z, 0.5, 0.5, "identity")             # reached before the right side is exhausted
+    assert lo2 == cen and ((z >= lo2) & (z < hi2)).mean() >= 0.5
+    # relu, samples on both sides of the kink, centroid on the positive side: growing right costs
+    # nothing, growing left across 0 does, so the range grows right first
+    z = np.concatenate([np.linspace(-3, -0.5, 30), np.linspace(0.5, 2.0, 70)])
+    cen = O.kde_centroid(np.sort(z))
+    assert cen > 0.5
+    lo3, hi3 = O.range_search(z, 0.7, 0.25, "relu")
+    assert hi3 > 2.0 and lo3 >= 0.25 - 1e-12                       # 70 % of the samples are the positive ones
+    lo4, hi4 = O.range_search(z, 0.8, 0.25, "relu")
+    assert hi4 > 2.0 and lo4 < -0.5                                # now it has to cross the kink
+
+
+def test_range_search_step_cap_takes_everything(monkeypatch):
+    monkeypatch.setattr(O, "SEARCH_MAX_STEPS", 5)
+    z = np.linspace(-1, 1, 50)
+    lo, hi = O.range_search(z, 0.99, 0.01, "gelu_erf")
+    assert lo == -1.0 and hi > 1.0 and ((z >= lo) & (z < hi)).all()
+
+
+def test_calibrate_search_covers_and_fits():
+    w = synth.tiny(hard=True, with_bias=True)
+    W1, b1 = w.layer.W1[:24], w.layer.b1[:24]
+    lo, hi, a, c = O.calibrate_search(W1, b1, w.X_cal[:200], 0.85, 0.05)
+    Z = O.preact(W1, b1, w.X_cal[:200])
+    qlo, qhi, _, _ = O.calibrate(W1, b1, w.X_cal[:200], 0.85)
+    for j in range(24):
+        sel = (Z[:, j] >= np.float64(lo[j])) & (Z[:, j] < np.float64(hi[j]))
+        assert 0.85 <= sel.mean() < 0.85 + 0.2
+        aj, cj = O.fit_line(Z[sel, j], O.act(Z[sel, j]), float(lo[j]), "gelu_erf")
+        assert a[j] == np.float32(aj) and c[j] == np.float32(cj)
+    # GELU is nearly linear far from 0 on either side, so the greedy ranges lean outwards: each one
+    # reaches farther than the central-quantile range on one side and stops short on the other
+    assert (((hi > qhi) & (lo > qlo)) | ((hi < qhi) & (lo < qlo))).mean() > 0.8
+
+
 # ------------------------------------------------------------------- predictor
 def test_sketch_codes_brute_force():
     rng = np.random.default_rng(12)
