@@ -183,6 +183,8 @@ def main() -> int:
     ap.add_argument("--coverage", type=float, default=0.95)
     ap.add_argument("--sketch-bits", type=int, default=8, choices=(8, 4),
                     help="predictor code width of the timed layers (8 = the headline configuration)")
+    ap.add_argument("--search-step", type=float, default=0.0,
+                    help="also time the greedy range search with this increment on the first layer (offline figure)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of a replayed HIP graph")
@@ -227,6 +229,12 @@ def main() -> int:
         t2 = time.time()
         if li == 0:
             offline = {"calibrate_ms": (t1 - t0) * 1e3, "fold_ms": (t2 - t1) * 1e3}
+            if args.search_step > 0:   # the greedy range search over the same calibration tokens (ranges not used below)
+                t3 = time.time()
+                T.tardis_calibrate_search(ffn, Xc, w.coverage, args.search_step)
+                torch.cuda.synchronize()
+                offline["calibrate_search_ms"] = (time.time() - t3) * 1e3
+                offline["search_step"] = args.search_step
             works.append((w, (lo, hi, a, c)))
         layers.append(L)
         del Xc

@@ -110,6 +110,25 @@ tardis_status_t tardis_calibrate(const tardis_ffn_desc* desc, const void* X_cal,
                                  float coverage, const float* coverage_per_neuron,
                                  float* lo, float* hi, float* a, float* c, void* stream);
 
+/* As tardis_calibrate, with the range of every neuron found by the greedy search
+ * of Algorithm 1 (its inner loop; Sec. "Non-linear Function Approximation",
+ * "Range Searching") instead of central quantiles: the range starts empty at the
+ * centroid of the neuron's calibration inputs (mode of a Gaussian kernel density
+ * estimate, bandwidth 1.06 std n^(-1/5), evaluated at 256 equally spaced points
+ * from the smallest to the largest sample) and grows by `step` at a time, to the
+ * left or to the right, whichever candidate range is approximated by its own
+ * least-squares line with the smaller sum of |sigma(z) - (a z + c)| over its
+ * samples (the right one on equality), until it holds the portion t of the
+ * samples.  A side whose end lies beyond every sample is not grown further;
+ * after 4096 steps the whole sample range is taken.  The layer-level and
+ * neuron-level threshold assignment of Algorithm 1 is not part of this call:
+ * pass its result through coverage_per_neuron.
+ *   step   range increment s > 0, in units of the pre-activation.
+ *   1 <= n_cal <= 8192.  Other arguments and behaviour as tardis_calibrate. */
+tardis_status_t tardis_calibrate_search(const tardis_ffn_desc* desc, const void* X_cal, int64_t n_cal,
+                                        float coverage, const float* coverage_per_neuron, float step,
+                                        float* lo, float* hi, float* a, float* c, void* stream);
+
 /* Constant folding and predictor construction (Sec. "Constant Folded Matrix
  * Generation" and Sec. "Predictor Generation").  Builds
  *     W' = W2 diag(a) W1            (d x d, stored in desc->dtype, rounded once)

@@ -160,7 +160,7 @@ def calibrate(W1, b1, X_cal, coverage, kind: str = "gelu_erf"):
 # the range holds the portion t of the calibration inputs)
 # ---------------------------------------------------------------------------
 KDE_GRID = 256            # points at which the density estimate is evaluated
-SEARCH_MAX_STEPS = 65536  # growth steps after which the whole sample range is taken
+SEARCH_MAX_STEPS = 4096   # growth steps after which the whole sample range is taken
 
 
 def kde_centroid(zs: np.ndarray) -> float:

@@ -1,5 +1,6 @@
 // C-ABI entry points of libtardis: argument validation, handle lifetime and
 // dispatch.  No kernel lives here.
+#include <cmath>
 #include <cstdlib>
 #include <new>
 
@@ -10,6 +11,7 @@ namespace {
 constexpr int64_t kMaxD = 32768;          // token + its int8 code must fit in LDS
 constexpr int64_t kMaxH = 1 << 22;
 constexpr int64_t kMaxCal = 32768;        // one neuron's samples are sorted in LDS
+constexpr int64_t kMaxSearchCal = 8192;   // range search also keeps sigma of every sample there, in fp64
 constexpr int64_t kMaxBatch = 4096;
 constexpr size_t kTokenLdsCap = 60 * 1024;
 
@@ -143,7 +145,20 @@ tardis_status_t tardis_calibrate(const tardis_ffn_desc* desc, const void* X_cal,
     if (!aligned16(X_cal)) return TARDIS_ERR_INVALID_ARG;
     if (n_cal < 1 || n_cal > kMaxCal) return TARDIS_ERR_SHAPE;
     if (!coverage_per_neuron && !(coverage > 0.0f && coverage <= 1.0f)) return TARDIS_ERR_INVALID_ARG;
-    return td_calibrate(desc, X_cal, n_cal, coverage, coverage_per_neuron, lo, hi, a, c,
+    return td_calibrate(desc, X_cal, n_cal, coverage, coverage_per_neuron, 0.0f, lo, hi, a, c,
+                        static_cast<hipStream_t>(stream));
+}
+
+tardis_status_t tardis_calibrate_search(const tardis_ffn_desc* desc, const void* X_cal, int64_t n_cal,
+                                        float coverage, const float* coverage_per_neuron, float step, float* lo,
+                                        float* hi, float* a, float* c, void* stream) {
+    TD_TRY(check_desc(desc));
+    if (!X_cal || !lo || !hi || !a || !c) return TARDIS_ERR_INVALID_ARG;
+    if (!aligned16(X_cal)) return TARDIS_ERR_INVALID_ARG;
+    if (n_cal < 1 || n_cal > kMaxSearchCal) return TARDIS_ERR_SHAPE;
+    if (!coverage_per_neuron && !(coverage > 0.0f && coverage <= 1.0f)) return TARDIS_ERR_INVALID_ARG;
+    if (!(step > 0.0f) || !(step < INFINITY)) return TARDIS_ERR_INVALID_ARG;
+    return td_calibrate(desc, X_cal, n_cal, coverage, coverage_per_neuron, step, lo, hi, a, c,
                         static_cast<hipStream_t>(stream));
 }
 

@@ -168,8 +168,10 @@ tardis_status_t td_unpack_sketch4(const uint8_t* Q4, const uint8_t* M4, int64_t 
                                   hipStream_t s);
 tardis_status_t td_fold(const tardis_ffn_desc* desc, const float* a, const float* c, void* Wp, float* bp,
                         hipStream_t s);
+// step > 0: greedy range search with that increment; step <= 0: central quantile ranges
 tardis_status_t td_calibrate(const tardis_ffn_desc* desc, const void* X, int64_t n, float coverage,
-                             const float* cov_pn, float* lo, float* hi, float* a, float* c, hipStream_t s);
+                             const float* cov_pn, float step, float* lo, float* hi, float* a, float* c,
+                             hipStream_t s);
 // gemm.hip:  C[m][n] = sum_k A[m][k] * B[n][k]  (+ C if accumulate) (+ row_bias[m]); C fp32, ldc = N
 tardis_status_t td_gemm_nt(const void* A, const void* B, float* C, int64_t M, int64_t N, int64_t K,
                            int32_t dtype, int accumulate, const void* row_bias, hipStream_t s);

@@ -273,16 +273,8 @@ __device__ __forceinline__ double quantile_sorted(const float* v, int n, double 
     return (double)v[i] + g * ((double)v[i1] - (double)v[i]);
 }
 
-__global__ void __launch_bounds__(kBlock)
-calibrate_neuron_kernel(const float* __restrict__ Zt, int n, int npad, float coverage,
-                        const float* __restrict__ cov_pn, int act, float* __restrict__ lo, float* __restrict__ hi,
-                        float* __restrict__ a, float* __restrict__ c) {
-    extern __shared__ float vals[];
-    __shared__ double red[kBlock / TD_WAVE];
-    const int64_t j = blockIdx.x;
-    const float* z = Zt + j * (int64_t)n;
-    for (int i = threadIdx.x; i < npad; i += kBlock) vals[i] = i < n ? z[i] : INFINITY;
-    __syncthreads();
+// sorts vals[0..npad) ascending (npad a power of two, padded with +inf)
+__device__ __forceinline__ void sort_lds(float* vals, int npad) {
     for (int k = 2; k <= npad; k <<= 1) {
         for (int s = k >> 1; s > 0; s >>= 1) {
             for (int t = threadIdx.x; t < npad / 2; t += kBlock) {
@@ -298,10 +290,11 @@ calibrate_neuron_kernel(const float* __restrict__ Zt, int n, int npad, float cov
             __syncthreads();
         }
     }
-    const double t = cov_pn ? (double)cov_pn[j] : (double)coverage;
-    const float lo32 = (float)quantile_sorted(vals, n, (1.0 - t) / 2.0);
-    const float hi32 = (float)quantile_sorted(vals, n, (1.0 + t) / 2.0);
+}
 
+// least-squares line of sigma(z) on z over the samples with lo32 <= z < hi32, and the four outputs
+__device__ __forceinline__ void fit_and_store(const float* vals, int n, float lo32, float hi32, int act, double* red,
+                                              int64_t j, float* lo, float* hi, float* a, float* c) {
     double cnt = 0.0, sz = 0.0, sg = 0.0;
     for (int i = threadIdx.x; i < n; i += kBlock) {
         const float v = vals[i];
@@ -346,6 +339,173 @@ calibrate_neuron_kernel(const float* __restrict__ Zt, int n, int npad, float cov
         a[j] = aj;
         c[j] = cj;
     }
+}
+
+__global__ void __launch_bounds__(kBlock)
+calibrate_neuron_kernel(const float* __restrict__ Zt, int n, int npad, float coverage,
+                        const float* __restrict__ cov_pn, int act, float* __restrict__ lo, float* __restrict__ hi,
+                        float* __restrict__ a, float* __restrict__ c) {
+    extern __shared__ float vals[];
+    __shared__ double red[kBlock / TD_WAVE];
+    const int64_t j = blockIdx.x;
+    const float* z = Zt + j * (int64_t)n;
+    for (int i = threadIdx.x; i < npad; i += kBlock) vals[i] = i < n ? z[i] : INFINITY;
+    __syncthreads();
+    sort_lds(vals, npad);
+    const double t = cov_pn ? (double)cov_pn[j] : (double)coverage;
+    const float lo32 = (float)quantile_sorted(vals, n, (1.0 - t) / 2.0);
+    const float hi32 = (float)quantile_sorted(vals, n, (1.0 + t) / 2.0);
+    fit_and_store(vals, n, lo32, hi32, act, red, j, lo, hi, a, c);
+}
+
+// ------------------------------------------------------------- range search
+// Greedy range of Algorithm 1 (inner loop), one block per neuron: centroid = mode of a Gaussian
+// kernel density estimate on a grid of 256 points (bandwidth 1.06 std n^-1/5), then the range
+// grows by `step` to the left or to the right, whichever candidate's least-squares line leaves
+// the smaller sum of |sigma(z) - (a z + c)| over its samples (right on equality), until it holds
+// the portion t of the samples.  A side whose end lies beyond every sample is not offered again.
+constexpr int kKdeGrid = 256;
+constexpr int kSearchMaxSteps = 4096;
+static_assert(kKdeGrid == kBlock, "one grid point per thread");
+
+// four block-wide sums at once
+__device__ __forceinline__ void block_sum4(double (&v)[4], double (*red4)[4]) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v[q] += __shfl_xor(v[q], o, 64);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) red4[threadIdx.x / 64][q] = v[q];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < kBlock / TD_WAVE; ++w) t += red4[w][q];
+        v[q] = t;
+    }
+}
+
+// first index i in [0, n) with vals[i] >= x (n if none)
+__device__ __forceinline__ int lower_bound_lds(const float* vals, int n, double x) {
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if ((double)vals[mid] >= x) hi = mid; else lo = mid + 1;
+    }
+    return lo;
+}
+
+__global__ void __launch_bounds__(kBlock)
+range_search_kernel(const float* __restrict__ Zt, int n, int npad, float coverage, const float* __restrict__ cov_pn,
+                    float step32, int act, float* __restrict__ lo, float* __restrict__ hi, float* __restrict__ a,
+                    float* __restrict__ c) {
+    extern __shared__ double gv[];                   // sigma of the sorted samples, then the samples
+    float* vals = reinterpret_cast<float*>(gv + ((n + 1) & ~1));
+    __shared__ double red[kBlock / TD_WAVE];
+    __shared__ double red4[kBlock / TD_WAVE][4];
+    __shared__ double dens[kKdeGrid];
+    const int64_t j = blockIdx.x;
+    const float* z = Zt + j * (int64_t)n;
+    for (int i = threadIdx.x; i < npad; i += kBlock) vals[i] = i < n ? z[i] : INFINITY;
+    __syncthreads();
+    sort_lds(vals, npad);
+    for (int i = threadIdx.x; i < n; i += kBlock) gv[i] = td_act_f64((double)vals[i], act);
+    const double zmin = (double)vals[0], zmax = (double)vals[n - 1];
+    const double t = cov_pn ? (double)cov_pn[j] : (double)coverage;
+    const double step = (double)step32;
+
+    // ---- centroid
+    double cen = zmin;
+    if (n >= 2 && zmax > zmin) {
+        double sz = 0.0;
+        for (int i = threadIdx.x; i < n; i += kBlock) sz += (double)vals[i];
+        const double mean = block_sum(sz, red) / (double)n;
+        double sv = 0.0;
+        for (int i = threadIdx.x; i < n; i += kBlock) {
+            const double dz = (double)vals[i] - mean;
+            sv += dz * dz;
+        }
+        const double sd = sqrt(block_sum(sv, red) / (double)(n - 1));
+        const double bw = 1.06 * sd * pow((double)n, -0.2);
+        const double delta = (zmax - zmin) / (double)(kKdeGrid - 1);
+        const double u = zmin + (double)threadIdx.x * delta;
+        double dsum = 0.0;
+        for (int k = 0; k < n; ++k) {
+            const double q = (u - (double)vals[k]) / bw;
+            dsum += exp(-0.5 * q * q);
+        }
+        dens[threadIdx.x] = dsum;
+        __syncthreads();
+        int best = 0;
+        double best_d = dens[0];
+        for (int g = 1; g < kKdeGrid; ++g)           // the leftmost among equal maxima
+            if (dens[g] > best_d) {
+                best_d = dens[g];
+                best = g;
+            }
+        cen = zmin + (double)best * delta;
+    }
+    __syncthreads();
+
+    // ---- growth (every thread carries the same scalars)
+    double rlo = cen, rhi = cen;
+    bool done = false;
+    for (int it = 0; it < kSearchMaxSteps && !done; ++it) {
+        const int il = lower_bound_lds(vals, n, rlo), ih = lower_bound_lds(vals, n, rhi);
+        if ((double)(ih - il) / (double)n >= t) {
+            done = true;
+            break;
+        }
+        const bool left_open = rlo > zmin, right_open = !(rhi > zmax);
+        if (!left_open && !right_open) {
+            done = true;
+            break;
+        }
+        bool go_left = left_open;
+        if (left_open && right_open) {
+            // candidate 0: [rlo - step, rhi) = samples [cl, ih); candidate 1: [rlo, rhi + step) = samples [il, ch)
+            const int cl = lower_bound_lds(vals, n, rlo - step), ch = lower_bound_lds(vals, n, rhi + step);
+            const int n0 = ih - cl, n1 = ch - il;
+            double sums[4] = {0.0, 0.0, 0.0, 0.0};   // sum z, sum g of both candidates
+            for (int i = cl + (int)threadIdx.x; i < ch; i += kBlock) {
+                const double zi = (double)vals[i], gi = gv[i];
+                if (i < ih) { sums[0] += zi; sums[1] += gi; }
+                if (i >= il) { sums[2] += zi; sums[3] += gi; }
+            }
+            block_sum4(sums, red4);
+            const double zb0 = n0 ? sums[0] / n0 : 0.0, gb0 = n0 ? sums[1] / n0 : 0.0;
+            const double zb1 = n1 ? sums[2] / n1 : 0.0, gb1 = n1 ? sums[3] / n1 : 0.0;
+            double vc[4] = {0.0, 0.0, 0.0, 0.0};     // var, cov of both candidates
+            for (int i = cl + (int)threadIdx.x; i < ch; i += kBlock) {
+                const double zi = (double)vals[i], gi = gv[i];
+                if (i < ih) { vc[0] += (zi - zb0) * (zi - zb0); vc[1] += (zi - zb0) * (gi - gb0); }
+                if (i >= il) { vc[2] += (zi - zb1) * (zi - zb1); vc[3] += (zi - zb1) * (gi - gb1); }
+            }
+            block_sum4(vc, red4);
+            double a0 = 0.0, c0 = gb0, a1 = 0.0, c1 = gb1;
+            if (n0 >= 2 && vc[0] > 0.0) { a0 = vc[1] / vc[0]; c0 = gb0 - a0 * zb0; }
+            if (n1 >= 2 && vc[2] > 0.0) { a1 = vc[3] / vc[2]; c1 = gb1 - a1 * zb1; }
+            double er[4] = {0.0, 0.0, 0.0, 0.0};
+            for (int i = cl + (int)threadIdx.x; i < ch; i += kBlock) {
+                const double zi = (double)vals[i], gi = gv[i];
+                if (i < ih) er[0] += fabs(gi - (a0 * zi + c0));
+                if (i >= il) er[1] += fabs(gi - (a1 * zi + c1));
+            }
+            block_sum4(er, red4);
+            go_left = er[0] < er[1];
+        }
+        if (go_left) rlo = rlo - step; else rhi = rhi + step;
+    }
+    if (!done) {   // step cap reached: the whole sample range
+        rlo = zmin;
+        rhi = nextafter(zmax, INFINITY);
+    }
+    __syncthreads();
+    fit_and_store(vals, n, (float)rlo, (float)rhi, act, red, j, lo, hi, a, c);
 }
 
 struct DevBuf {  // frees on scope exit
@@ -453,13 +613,26 @@ tardis_status_t td_fold(const tardis_ffn_desc* desc, const float* a, const float
 }
 
 tardis_status_t td_calibrate(const tardis_ffn_desc* desc, const void* X, int64_t n, float coverage,
-                             const float* cov_pn, float* lo, float* hi, float* a, float* c, hipStream_t s) {
+                             const float* cov_pn, float step, float* lo, float* hi, float* a, float* c,
+                             hipStream_t s) {
     const int64_t d = desc->d, h = desc->h;
     DevBuf zt;
     TD_TRY(zt.alloc((size_t)h * n * 4));
     TD_TRY(td_gemm_nt(desc->W1, X, static_cast<float*>(zt.p), h, n, d, desc->dtype, 0, desc->b1, s));
     int npad = 2;
     while (npad < n) npad <<= 1;
+    if (step > 0.0f) {   // greedy range search instead of central quantiles
+        const size_t lds = (size_t)((n + 1) & ~(int64_t)1) * sizeof(double) + (size_t)npad * sizeof(float);
+        if (lds > 48 * 1024)
+            TD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(range_search_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(range_search_kernel, dim3((unsigned)h), dim3(kBlock), lds, s,
+                           static_cast<const float*>(zt.p), (int)n, npad, coverage, cov_pn, step, (int)desc->act, lo,
+                           hi, a, c);
+        TD_HIP(hipGetLastError());
+        TD_HIP(hipStreamSynchronize(s));
+        return TARDIS_OK;
+    }
     const size_t lds = (size_t)npad * sizeof(float);
     if (lds > 48 * 1024)
         TD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(calibrate_neuron_kernel),

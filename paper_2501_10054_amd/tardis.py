@@ -22,7 +22,7 @@ _TORCH_DTYPE = {F32: torch.float32, BF16: torch.bfloat16}
 _DTYPE_CODE = {torch.float32: F32, torch.bfloat16: BF16}
 
 EXPORTS = (
-    "tardis_calibrate", "tardis_fold", "tardis_ffn_forward", "tardis_ffn_forward_batched",
+    "tardis_calibrate", "tardis_calibrate_search", "tardis_fold", "tardis_ffn_forward", "tardis_ffn_forward_batched",
     "tardis_stack_forward", "tardis_dense_forward", "tardis_get_folded", "tardis_get_predictor_state",
     "tardis_get_sketch_groups", "tardis_get_last_outliers", "tardis_get_handover", "tardis_destroy", "tardis_status_string", "tardis_version",
 )
@@ -56,6 +56,7 @@ def lib() -> C.CDLL:
         L = C.CDLL(LIB_PATH)
         vp, i64, f32 = C.c_void_p, C.c_int64, C.c_float
         L.tardis_calibrate.argtypes = [C.POINTER(tardis_ffn_desc), vp, i64, f32, vp, vp, vp, vp, vp, vp]
+        L.tardis_calibrate_search.argtypes = [C.POINTER(tardis_ffn_desc), vp, i64, f32, vp, f32, vp, vp, vp, vp, vp]
         L.tardis_fold.argtypes = [C.POINTER(tardis_ffn_desc), vp, vp, vp, vp, C.POINTER(tardis_fold_opts), vp,
                                   C.POINTER(vp)]
         L.tardis_ffn_forward.argtypes = [vp, vp, vp, vp]
@@ -121,6 +122,18 @@ def tardis_calibrate(ffn: FFN, X_cal, coverage: float = 0.95, coverage_per_neuro
     st = lib().tardis_calibrate(C.byref(ffn.desc), _ptr(X_cal), X_cal.shape[0], float(coverage),
                                 _ptr(coverage_per_neuron), *[_ptr(t) for t in out], _stream(stream))
     _check(st, "tardis_calibrate")
+    return tuple(out)
+
+
+def tardis_calibrate_search(ffn: FFN, X_cal, coverage: float = 0.95, step: float = 0.05, coverage_per_neuron=None,
+                            stream=None):
+    """-> (lo, hi, a, c) with greedily searched ranges."""
+    assert X_cal.is_cuda and X_cal.is_contiguous() and X_cal.dtype == ffn.W1.dtype and X_cal.shape[1] == ffn.d
+    out = [torch.empty(ffn.h, dtype=torch.float32, device=X_cal.device) for _ in range(4)]
+    st = lib().tardis_calibrate_search(C.byref(ffn.desc), _ptr(X_cal), X_cal.shape[0], float(coverage),
+                                       _ptr(coverage_per_neuron), float(step), *[_ptr(t) for t in out],
+                                       _stream(stream))
+    _check(st, "tardis_calibrate_search")
     return tuple(out)
 
 

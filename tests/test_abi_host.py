@@ -84,6 +84,19 @@ def test_calibrate_rejects_bad_arguments_without_a_gpu():
     assert cal(_desc(), t=1.5) == T.ERR_INVALID_ARG
     assert cal(_desc(h=0)) == T.ERR_SHAPE
 
+    def search(desc, X=p, n=16, t=0.9, step=0.1, lo=p):
+        return lib.tardis_calibrate_search(C.byref(desc), X, n, t, None, step, lo, p, p, p, None)
+
+    assert search(_desc(), X=None) == T.ERR_INVALID_ARG
+    assert search(_desc(), lo=None) == T.ERR_INVALID_ARG
+    assert search(_desc(), n=0) == T.ERR_SHAPE
+    assert search(_desc(), n=8193) == T.ERR_SHAPE                # the search keeps more per sample in LDS
+    assert search(_desc(), t=1.5) == T.ERR_INVALID_ARG
+    assert search(_desc(), step=0.0) == T.ERR_INVALID_ARG
+    assert search(_desc(), step=-1.0) == T.ERR_INVALID_ARG
+    assert search(_desc(), step=float("inf")) == T.ERR_INVALID_ARG
+    assert search(_desc(), step=float("nan")) == T.ERR_INVALID_ARG
+
 
 def test_online_calls_reject_null_handle():
     lib = T.lib()

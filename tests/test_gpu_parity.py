@@ -194,6 +194,61 @@ def test_batched_with_bias_and_relu():
     run_case(layer, X_cal, X_test, 0.9, act="relu", batched=True, check_calibrate=False)
 
 
+# ------------------------------------------------------------- greedy range search
+@pytest.mark.parametrize("dtype,d,h,n_cal,t,step,act", [("f32", 64, 96, 400, 0.9, 0.05, "gelu_erf"),
+                                                       ("bf16", 256, 64, 1000, 0.85, 0.1, "gelu_erf"),
+                                                       ("f32", 64, 48, 300, 0.8, 0.08, "relu"),
+                                                       ("f32", 48, 40, 257, 1.0, 0.25, "gelu_tanh")])
+def test_calibrate_search_against_checker(dtype, d, h, n_cal, t, step, act):
+    """The two sides see pre-activations that differ in the last bits (fp32 against fp64 dot
+    products), and every growth step is a comparison of two error sums: a step decided by less than
+    that noise may go the other way, so a few neurons may end a whole number of steps apart.  Nearly
+    all neurons must agree to rounding, every neuron must satisfy what defines the search."""
+    t, step = float(np.float32(t)), float(np.float32(step))     # the interface carries both as fp32
+    seed = synth.workload_seed(9, 21)
+    layer = synth.make_layer(d, h, dtype, seed, w1_std=0.2 if d < 128 else 0.1, w2_std=0.05, heavy_frac=0.02,
+                             with_bias=True)
+    X_cal = synth.make_tokens(n_cal, d, dtype, seed, synth.STREAM_CAL)
+    ffn = make_ffn(layer, act)
+    lo, hi, a, c = (v.cpu().numpy() for v in T.tardis_calibrate_search(ffn, dev(X_cal, dtype), t, step))
+    olo, ohi, oa, oc = O.calibrate_search(layer.W1, layer.b1, X_cal, t, step, act)
+    scale = float(np.abs(np.concatenate([olo, ohi])).max())
+    same = (np.abs(lo - olo) <= 1e-4 * scale) & (np.abs(hi - ohi) <= 1e-4 * scale)
+    assert same.mean() >= 0.95, same.mean()
+    assert np.abs(a - oa)[same].max() <= 5.0 / n_cal + 1e-4
+    assert np.abs(c - oc)[same].max() <= (5.0 / n_cal + 1e-4) * max(1.0, scale)
+    Z = O.preact(layer.W1, layer.b1, X_cal)
+    for j in range(h):
+        inside = (Z[:, j] >= np.float64(lo[j])) & (Z[:, j] < np.float64(hi[j]))
+        assert inside.mean() >= t - 2.0 / n_cal                   # reached the target (up to samples on the edge)
+        # the range is the centroid grown by whole steps on either side
+        cen = O.kde_centroid(np.sort(Z[:, j]))
+        kl, kr = (cen - lo[j]) / step, (hi[j] - cen) / step
+        if inside.mean() < 1.0:
+            assert abs(kl - round(kl)) < 2e-2 and abs(kr - round(kr)) < 2e-2
+        if not same[j]:                                           # a different but valid sequence of steps
+            assert abs((lo[j] - olo[j]) / step - round((lo[j] - olo[j]) / step)) < 2e-2
+        # and its line is the least-squares line of its own samples
+        aj, cj = O.fit_line(Z[inside, j], O.act(Z[inside, j], act), float(lo[j]), act)
+        assert abs(a[j] - aj) <= 5.0 / n_cal + 1e-4 and abs(c[j] - cj) <= (5.0 / n_cal + 1e-4) * max(1.0, scale)
+
+
+def test_calibrate_search_feeds_the_online_path():
+    # ranges from the search go through fold and forward like any others
+    w = synth.decode(d=1024, h=512, n_cal=512, n_test=4, coverage=0.9)
+    ffn = make_ffn(w.layer)
+    lo, hi, a, c = T.tardis_calibrate_search(ffn, dev(w.X_cal, "bf16"), 0.9, 0.1)
+    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=4)
+    F = O.build(w.layer.W1, None, w.layer.W2, None, *(v.cpu().numpy() for v in (lo, hi, a, c)))
+    Yo, FLo = O.forward(F, w.X_test)
+    Y = T.tardis_ffn_forward_batched(L, dev(w.X_test, "bf16"))
+    mask, _, _ = T.tardis_get_last_outliers(L, 4, want_list=False)
+    np.testing.assert_array_equal(unpack_mask(mask, 512), FLo)
+    assert rel_l2(host(Y), Yo) <= 1e-2
+    assert 0.05 < FLo.mean() < 0.2
+    L.close()
+
+
 # ------------------------------------------------------------- 4-bit grouped sketch
 def test_sketch4_tiny_fp32_and_ragged_groups():
     w = synth.tiny(hard=True, with_bias=True)                    # d = 64: two whole groups
@@ -459,6 +514,24 @@ def test_full_size_calibrate_on_sampled_neurons(decode_full):
     Z = O.preact(w.layer.W1[sub], None, w.X_cal)
     frac = ((Z >= glo[None, :].astype(np.float64)) & (Z < ghi[None, :].astype(np.float64))).mean(0)
     assert np.abs(frac - w.coverage).max() <= 3.0 / w.X_cal.shape[0]
+
+
+def test_full_size_calibrate_search_on_sampled_neurons(decode_full):
+    w, ffn, _, _, _ = decode_full
+    t, step = float(np.float32(0.95)), float(np.float32(0.05))
+    lo, hi, a, c = (v.cpu().numpy() for v in T.tardis_calibrate_search(ffn, dev(w.X_cal, "bf16"), t, step))
+    rng = np.random.default_rng(1)
+    sub = np.sort(rng.choice(w.layer.h, 48, replace=False))
+    sub[:3] = w.layer.heavy_neurons[:3]
+    olo, ohi, oa, oc = O.calibrate_search(w.layer.W1[sub], None, w.X_cal, t, step)
+    scale = float(np.abs(np.concatenate([olo, ohi])).max())
+    same = (np.abs(lo[sub] - olo) <= 1e-4 * scale) & (np.abs(hi[sub] - ohi) <= 1e-4 * scale)
+    assert same.mean() >= 0.9, same.mean()
+    assert np.abs(a[sub] - oa)[same].max() <= 2e-3 and np.abs(c[sub] - oc)[same].max() <= 2e-3 * max(1.0, scale)
+    Z = O.preact(w.layer.W1[sub], None, w.X_cal)
+    frac = ((Z >= lo[sub][None, :].astype(np.float64)) & (Z < hi[sub][None, :].astype(np.float64))).mean(0)
+    assert (frac >= t - 2.0 / w.X_cal.shape[0]).all() and (frac < t + 0.05).all()
+    assert np.isfinite(lo).all() and np.isfinite(hi).all() and (hi > lo).all()
 
 
 def test_full_size_decode_batch1(decode_full):
