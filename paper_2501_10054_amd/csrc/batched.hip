@@ -449,7 +449,7 @@ tardis_status_t pass_t(tardis_layer_s* L, const bf16_t* x, int nt, bf16_t* y, ui
     const int d = (int)L->d, h = (int)L->h;
     hipLaunchKernelGGL(quantize_tokens_kernel, dim3(nt), dim3(256), 0, s, x, d, L->bt_xq, L->bt_e);
     hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, s, reinterpret_cast<uint32_t*>(L->bt_ucount), (size_t)1, 0u);
-    const bool gather_scatter = nt <= kGatherTok;
+    const bool gather_scatter = nt <= L->gather_max_tokens;
     if (!gather_scatter) {
         const size_t words = (size_t)kTB * h / 2;
         hipLaunchKernelGGL(fill_u32_kernel, dim3(div_up(words, 256)), dim3(256), 0, s,

@@ -73,6 +73,11 @@ struct tardis_layer_s {
     bf16_t* bt_delta;              // 64 x h repair factors
     float* bt_partial;             // partial products of the scatter step
     int32_t use_batched;
+    int32_t* rec_count;            // two-kernel path: flagged neurons per predictor block,
+    uint32_t* rec_jb;              //   neuron index | token bits << 24 (dec_blocks x neurons per block),
+    float* rec_delta;              //   and 8 deltas per record
+    int32_t defer_min_tokens;      // groups of at least this many tokens take the two-kernel path (4, 8; 99 = never)
+    int32_t gather_max_tokens;     // passes of up to this many tokens scatter through the union rows of W2^T
     int32_t batched_min_tokens;    // token counts up to this go through the single-token path
     int64_t last_n;    // token count of the most recent online call
 };
@@ -177,7 +182,7 @@ tardis_status_t td_gemm_nt(const void* A, const void* B, float* C, int64_t M, in
                            int32_t dtype, int accumulate, const void* row_bias, hipStream_t s);
 // decode.hip
 bool td_decode_fused_supported(const tardis_layer_s* L);
-constexpr int kDecodeMaxTokens = 4;   // tokens the single-launch kernel can share one weight pass between
+constexpr int kDecodeMaxTokens = 8;   // tokens one weight pass of the decode kernel can be shared between
 tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
                                 int tokens, int norm_out, hipStream_t s);
 tardis_status_t td_mask_to_list(const tardis_layer_s* L, int64_t n, int32_t* counts, int32_t* list, hipStream_t s);

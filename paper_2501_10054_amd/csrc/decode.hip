@@ -44,7 +44,26 @@ __device__ __forceinline__ void load_row(td_u32x4 (&dst)[N], const void* row, in
 // 16+4w+b in the high nibble), M4 one multiplier byte per group; the integer the range test sees is
 // sum over groups of multiplier * (code . token code), the same number an int8 row of
 // multiplier*code would give.
-template <int D, int BLOCK, int RQ, int TB, int SK>
+//
+// DEFER = true: the block stops after computing delta for its flagged neurons and writes one record
+// per flagged neuron (index, token bits, TB deltas) instead of applying W2^T; the speculative rows
+// go to yfold with plain stores and a second kernel (down_project_kernel) finishes the tokens.
+// With many tokens per launch this replaces TB x d atomics per block by a column-sliced pass.
+struct DeferOut {
+    int32_t* count;    // flagged neurons of every block
+    uint32_t* jb;      // blocks x cap: neuron index | token bits << 24
+    float* delta;      // blocks x cap x TB
+    int cap;           // record slots per block (= neurons per block)
+};
+
+//
+// NG > 0 (8 tokens): the predictor rows go through the int8 matrix cores instead of packed dot
+// products: the block's rows form NG groups of 16, each group is shared by NW/NG wavefronts that
+// split the columns, a wavefront multiplies its 16 rows x K-slice with the 8 tokens by
+// v_mfma_i32_16x16x64_i8 (tokens 8..15 of the tile repeat tokens 0..7 and are ignored), and the
+// partial sums meet in LDS.  Eight tokens of packed dot products would keep the vector ALUs busy
+// for longer than the rows take to arrive.
+template <int D, int BLOCK, int RQ, int TB, int SK, bool DEFER, int NG>
 __global__ void __launch_bounds__(BLOCK)
 decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp, const int8_t* __restrict__ Q,
                     const uint8_t* __restrict__ M4, const float* __restrict__ tlo, const float* __restrict__ thi, const bf16_t* __restrict__ W1,
@@ -52,12 +71,18 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                     const float* __restrict__ c, const bf16_t* __restrict__ x, bf16_t* __restrict__ y,
                     float* __restrict__ yfold, float* __restrict__ yfix, int copies, uint32_t* __restrict__ mask,
                     int mask_words, int32_t* __restrict__ done, int h, int npb, int rpb, int act, int norm_out,
-                    float eps) {
+                    float eps, DeferOut rec) {
     static_assert(D % 1024 == 0, "rows must be whole multiples of 64 lanes x 16 bytes");
     static_assert(D % BLOCK == 0 && BLOCK / TD_WAVE >= 4, "column ownership of the repair pass");
-    static_assert(TB == 1 || TB == 2 || TB == 4, "tokens per pass");
+    static_assert(TB == 1 || TB == 2 || TB == 4 || (TB == 8 && DEFER), "tokens per pass");
     static_assert(SK == 8 || (SK == 4 && D % 2048 == 0), "a packed 4-bit row must fill whole wavefront loads");
+    static_assert(NG == 0 || (SK == 8 && TB == 8 && DEFER && (BLOCK / TD_WAVE) % NG == 0), "matrix-core predictor");
     constexpr int NW = BLOCK / TD_WAVE;
+    constexpr int KQ = NG > 0 ? NW / NG : 1;         // wavefronts sharing a group of 16 rows
+    constexpr int KS = D / KQ;                       // columns of one wavefront's slice
+    constexpr int NL = NG > 0 ? KS / 64 : 1;         // 16-byte vectors per lane of that slice
+    constexpr int XP = NG > 0 ? D + 16 : D;          // LDS pitch of a token's int8 code (bank spread for the tile reads)
+    static_assert(NG == 0 || (KS % 64 == 0 && NL >= 1), "slice of whole 64-column steps");
     constexpr int NVW = D / 8;                       // 16-byte vectors per bf16 row
     constexpr int QROW = SK == 8 ? D : D / 2;        // bytes of one predictor row
     constexpr int IQ = QROW / 16 / TD_WAVE;          // per-lane vectors of a predictor row
@@ -65,8 +90,9 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     constexpr int XI = (TB * NVW + BLOCK - 1) / BLOCK;  // per-thread vectors of the tokens
     constexpr int MW = kMaxNeuronsPerBlock / 32;
 
-    __shared__ __align__(16) bf16_t xs[TB * D];
-    __shared__ __align__(16) int8_t xq[TB * D];
+    extern __shared__ __align__(16) unsigned char token_lds[];   // TB x D bf16 tokens, then their TB x D int8 codes
+    bf16_t* xs = reinterpret_cast<bf16_t*>(token_lds);
+    int8_t* xq = reinterpret_cast<int8_t*>(token_lds + (size_t)TB * D * 2);
     __shared__ float dl[NW][TB];                     // delta of the neurons being repaired, per token
     __shared__ int flist[kMaxNeuronsPerBlock];       // neurons flagged by at least one token
     __shared__ unsigned char fbits[kMaxNeuronsPerBlock];  // which tokens flagged them
@@ -74,6 +100,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     __shared__ int tmax[TB];                         // max |x| per token (bit pattern of a non-negative float)
     __shared__ int nflag;
     __shared__ int is_last;
+    __shared__ int pacc[NG > 0 ? NW : 1][16][NG > 0 ? TB : 1];   // partial sums of the matrix-core predictor
 
     const int tid = threadIdx.x;
     const int lane = tid & (TD_WAVE - 1);
@@ -107,7 +134,20 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
             th[i] = thi[j];
         }
     };
-    load_pred_rows(j0 + wave * RQ);
+    td_u32x4 qm[NL];                                 // matrix-core path: row (lane % 16) of the group, 16 bytes per step
+    float tl_own = 0.0f, th_own = 0.0f;              // ... and the bounds of neuron `tid` of the block
+    if constexpr (NG > 0) {
+        const int grp = wave % NG, kq = wave / NG;
+        const int j = min(j0 + grp * 16 + (lane & 15), h - 1);
+        const td_u32x4* p = reinterpret_cast<const td_u32x4*>(Q + (size_t)j * D + kq * KS) + (lane >> 4);
+#pragma unroll
+        for (int m = 0; m < NL; ++m) qm[m] = td_load_stream16(p + m * 4);
+        const int jt = min(j0 + tid, h - 1);
+        tl_own = tlo[jt];
+        th_own = thi[jt];
+    } else {
+        load_pred_rows(j0 + wave * RQ);
+    }
     const float bias_out = bp[min(blk * rpb + wave, D - 1)];
 
     // ---- stage the tokens, their maxima and their int8 codes
@@ -147,7 +187,9 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                 lo |= ((uint32_t)(uint8_t)quantize_value(td_bf16_to_f32(e8[u]), e)) << (8 * u);
                 hi |= ((uint32_t)(uint8_t)quantize_value(td_bf16_to_f32(e8[u + 4]), e)) << (8 * u);
             }
-            if (SK == 8) {
+            if (NG > 0) {
+                reinterpret_cast<uint2*>(xq + (size_t)tok * XP)[v - tok * NVW] = make_uint2(lo, hi);
+            } else if (SK == 8) {
                 reinterpret_cast<uint2*>(xq)[v] = make_uint2(lo, hi);
             } else {   // columns 0..15 of every group of 32 in the first half of the token's codes, 16..31 in the second
                 const int i8 = v - tok * NVW, g = i8 >> 2, part = i8 & 3;
@@ -161,7 +203,24 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     // ---- predictor rows: exact int32 dot products, range test per token, block-local list of
     //      the neurons flagged by at least one token
     const td_u32x4* xq4 = reinterpret_cast<const td_u32x4*>(xq) + lane;
-    for (int base = 0; base < jn; base += NW * RQ) {
+    if constexpr (NG > 0) {
+        typedef int i32x4 __attribute__((ext_vector_type(4)));
+        const int grp = wave % NG, kq = wave / NG;
+        const int8_t* xrow = xq + (size_t)((lane & 15) & (TB - 1)) * XP + kq * KS + (lane >> 4) * 16;
+        i32x4 acc4 = {0, 0, 0, 0};
+#pragma unroll
+        for (int m = 0; m < NL; ++m) {
+            const td_u32x4 xb = *reinterpret_cast<const td_u32x4*>(xrow + m * 64);
+            acc4 = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, qm[m]),
+                                                         __builtin_bit_cast(i32x4, xb), acc4, 0, 0, 0);
+        }
+        if ((lane & 15) < TB) {   // lane: token lane % 16, rows 4 * (lane / 16) + i of the group
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pacc[wave][4 * (lane >> 4) + i][lane & 15] = acc4[i];
+        }
+        (void)grp;
+    }
+    for (int base = 0; NG == 0 && base < jn; base += NW * RQ) {
         const int jb = base + wave * RQ;
         if (base > 0) load_pred_rows(j0 + jb);
         // two tokens at a time against the rows held in registers (register budget)
@@ -255,6 +314,30 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
 #pragma unroll
     for (int it = 0; it < IWA; ++it) wp[it] = td_load_stream16(wp_row + it * TD_WAVE);
 
+    if constexpr (NG > 0) {
+        __syncthreads();                             // the partial sums of every wavefront are in LDS
+        if (tid < jn) {
+            const int grp = tid >> 4, row = tid & 15;
+            uint32_t bits = 0;
+#pragma unroll
+            for (int t = 0; t < TB; ++t) {
+                int total = 0;
+#pragma unroll
+                for (int kq = 0; kq < KQ; ++kq) total += pacc[kq * NG + grp][row][t];
+                const float v = ldexpf((float)total, ex[t]);
+                const bool inside = (v >= tl_own) && (v < th_own);
+                bits |= inside ? 0u : (1u << t);
+            }
+            if (bits) {
+#pragma unroll
+                for (int t = 0; t < TB; ++t)
+                    if ((bits >> t) & 1u) atomicOr(&words[t][tid >> 5], 1u << (tid & 31));
+                const int pos = atomicAdd(&nflag, 1);
+                flist[pos] = j0 + tid;
+                fbits[pos] = (unsigned char)bits;
+            }
+        }
+    }
     __syncthreads();
     if (jn > 0) {
         const int nw = (jn + 31) / 32;
@@ -278,6 +361,71 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     for (int t = 0; t < TB; ++t)
 #pragma unroll
         for (int u = 0; u < CPT; ++u) yacc[t][u] = 0.0f;
+    if constexpr (DEFER) {
+        // ---- one wavefront per flagged neuron: exact z and delta for the tokens that flagged it
+        if (tid == 0) rec.count[blk] = nf;
+        if (nf == 0) {
+#pragma unroll
+            for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * TD_WAVE);
+        }
+        for (int f0 = 0; f0 < nf; f0 += NW) {
+            asm volatile("" ::: "memory");
+            const int fi = f0 + wave;
+            const bool fixer = fi < nf;
+            td_u32x4 w1[IW];
+            float aj = 0.0f, cj = 0.0f;
+            uint32_t bj_raw = 0;
+            int jz = 0;
+            if (fixer) {
+                jz = flist[fi];
+                load_row<IW>(w1, W1 + (size_t)jz * D, lane);
+                aj = a[jz];
+                cj = c[jz];
+                bj_raw = b1[jz];
+            }
+            if (f0 == 0) {   // the rest of this wave's W' row streams in behind the first batch of W1 rows
+                asm volatile("" ::: "memory");
+#pragma unroll
+                for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * TD_WAVE);
+            }
+            asm volatile("" : "+v"(bj_raw), "+v"(aj), "+v"(cj));
+            if (fixer) {
+                const float bj = td_bf16_to_f32((bf16_t)bj_raw);
+                const uint32_t zbits = fbits[fi];
+                const size_t slot = (size_t)blk * rec.cap + fi;
+#pragma unroll
+                for (int t = 0; t < TB; ++t) {
+                    asm volatile("" ::: "memory");
+                    float dv = 0.0f;
+                    if ((zbits >> t) & 1u) {
+                        float z = 0.0f;
+#pragma unroll
+                        for (int it = 0; it < IW; ++it) z = RowVec<bf16_t>::dot(w1[it], xs4[t * NVW + it * TD_WAVE], z);
+                        z = td_wave_sum(z) + bj;
+                        dv = td_act(z, act) - fmaf(aj, z, cj);
+                    }
+                    if (lane == 0) rec.delta[slot * TB + t] = dv;
+                }
+                if (lane == 0) rec.jb[slot] = (uint32_t)jz | (zbits << 24);
+            }
+        }
+        for (int ri = wave; ri < rn; ri += NW) {
+            asm volatile("" ::: "memory");
+            if (ri != wave) load_row<IW>(wp, Wp + (size_t)(r0 + ri) * D, lane);
+            const float bias = ri == wave ? bias_out : bp[r0 + ri];
+#pragma unroll
+            for (int t = 0; t < TB; ++t) {
+                asm volatile("" ::: "memory");
+                float s = 0.0f;
+#pragma unroll
+                for (int it = 0; it < IW; ++it) s = RowVec<bf16_t>::dot(wp[it], xs4[t * NVW + it * TD_WAVE], s);
+                s = td_wave_sum(s);
+                if (lane == 0) yfold[(size_t)t * D + r0 + ri] = s + bias;
+            }
+        }
+        return;
+    }
+
     // the columns a thread owns are rotated by a block-dependent number of wavefronts, so that
     // the blocks' atomic passes do not all start on the same cache lines
     const int ctid = (tid + TD_WAVE * (blk >> 3)) & (BLOCK - 1);
@@ -467,6 +615,145 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     if (tid == 0) __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Second kernel of the deferred path: y_t = yfold_t + sum over the records of delta_t * W2^T[j].
+// A block owns one slice of 256 output columns and the records of 16 predictor blocks, one
+// wavefront per predictor block: a lane owns 4 columns (8-byte loads, 512 contiguous bytes per
+// wavefront and row), eight rows in flight; each wavefront accumulates into its own TB x 256 floats
+// of LDS (read-modify-write by the owning wavefront only, for the tokens whose bit is set), the
+// block reduces over its wavefronts and adds TB x 256 floats to the accumulators in memory - 16
+// times fewer atomics than one d-vector per predictor block and token.  The last block to finish
+// assembles the tokens.
+template <int TB>
+__global__ void __launch_bounds__(1024)
+down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, const float* __restrict__ yfold,
+                    float* __restrict__ yfix, bf16_t* __restrict__ y, int32_t* __restrict__ done, int D, int nslices,
+                    int norm_out, float eps) {
+    constexpr int NW = 16, SL = 256, U = 16;         // rows in flight per wavefront
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    extern __shared__ __align__(16) float accL[];    // NW x TB x SL
+    __shared__ int is_last;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int slice = blockIdx.x % nslices, group = blockIdx.x / nslices;
+    float* acc = accL + (size_t)wave * TB * SL + lane * 4;
+    const f32x4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int t = 0; t < TB; ++t) *reinterpret_cast<f32x4*>(acc + t * SL) = zero4;
+    const int pb = __builtin_amdgcn_readfirstlane(group * NW + wave);
+    const int pbc = min(pb, nblk - 1);
+    const uint32_t* jb = rec.jb + (size_t)pbc * rec.cap;
+    const float* dl = rec.delta + (size_t)pbc * rec.cap * TB;
+    const bf16_t* base = W2T + (size_t)slice * SL + lane * 4;
+    // the count and the first 64 records are requested together (a slot past the count holds stale
+    // but in-bounds data and is never applied); lane r keeps record r and hands it out by readlane
+    const int cnt = pb < nblk ? rec.count[pb] : 0;
+    for (int c0 = 0; c0 < rec.cap; c0 += TD_WAVE) {
+        const int mine = min(c0 + lane, rec.cap - 1);
+        const uint32_t myj = jb[mine];
+        float myd[TB];
+#pragma unroll
+        for (int t = 0; t < TB; ++t) myd[t] = dl[(size_t)mine * TB + t];
+        const int here = min(cnt - c0, TD_WAVE);     // records of this batch of 64 (<= 0: none)
+        if (here <= 0) break;
+        for (int r0 = 0; r0 < here; r0 += U) {
+            uint2 w[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {   // slots past the end re-read the last record; they are not applied
+                const uint32_t j = __builtin_amdgcn_readlane(myj, min(r0 + u, here - 1)) & 0xFFFFFFu;
+                const unsigned long long* p = reinterpret_cast<const unsigned long long*>(base + (size_t)j * D);
+                const unsigned long long v = __builtin_nontemporal_load(p);
+                w[u] = make_uint2((uint32_t)v, (uint32_t)(v >> 32));
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (r0 + u < here) {
+                    const int r = r0 + u;
+                    const uint32_t bits = __builtin_amdgcn_readlane(myj, r) >> 24;
+                    const f32x4 wf = {__uint_as_float(w[u].x << 16), __uint_as_float(w[u].x & 0xFFFF0000u),
+                                      __uint_as_float(w[u].y << 16), __uint_as_float(w[u].y & 0xFFFF0000u)};
+#pragma unroll
+                    for (int t = 0; t < TB; ++t) {
+                        if ((bits >> t) & 1u) {
+                            const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, myd[t]), r));
+                            f32x4* a4 = reinterpret_cast<f32x4*>(acc + t * SL);
+                            *a4 = *a4 + wf * d;
+                        }
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    // ---- reduce over the wavefronts; one atomic per (token, column) of the slice
+    for (int k = tid; k < TB * SL; k += 1024) {
+        const int t = k / SL, col = k % SL;
+        float sum = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) sum += accL[((size_t)w * TB + t) * SL + col];
+        if (sum != 0.0f)
+            __hip_atomic_fetch_add(yfix + (size_t)t * D + slice * SL + col, sum, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (tid == 0)
+        is_last = (__hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1);
+    __syncthreads();
+    if (!is_last) return;
+
+    // ---- the last block assembles the tokens and re-arms the scratch
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    float* redt = accL;                              // NW x TB floats, free by now
+    constexpr int TH = TB < 4 ? TB : 4;              // tokens assembled together
+    for (int t0 = 0; t0 < TB; t0 += TH) {
+        for (int k0 = 0; k0 < D / 4; k0 += 1024) {   // one pass when d = 4096
+            const int k4 = k0 + tid;
+            const bool live = k4 < D / 4;
+            f32x4 v[TH];
+#pragma unroll
+            for (int t = 0; t < TH; ++t) {
+                const f32x4 f = live ? reinterpret_cast<const f32x4*>(yfold + (size_t)(t0 + t) * D)[k4] : zero4;
+                const f32x4 g = live ? reinterpret_cast<const f32x4*>(yfix + (size_t)(t0 + t) * D)[k4] : zero4;
+                v[t] = f + g;
+            }
+            if (live) {
+#pragma unroll
+                for (int t = 0; t < TH; ++t) reinterpret_cast<f32x4*>(yfix + (size_t)(t0 + t) * D)[k4] = zero4;
+            }
+            float scale[TH];
+#pragma unroll
+            for (int t = 0; t < TH; ++t) scale[t] = 1.0f;
+            if (norm_out) {   // whole rows are needed: the host only asks for it when d <= 4096 (one pass)
+                __syncthreads();
+#pragma unroll
+                for (int t = 0; t < TH; ++t) {
+                    const float ss =
+                        td_wave_sum(v[t].x * v[t].x + v[t].y * v[t].y + v[t].z * v[t].z + v[t].w * v[t].w);
+                    if (lane == 0) redt[wave * TH + t] = ss;
+                }
+                __syncthreads();
+#pragma unroll
+                for (int t = 0; t < TH; ++t) {
+                    float tot = 0.0f;
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) tot += redt[w * TH + t];
+                    scale[t] = 1.0f / sqrtf(tot / (float)D + eps);
+                }
+            }
+            if (live) {
+#pragma unroll
+                for (int t = 0; t < TH; ++t) {
+                    const f32x4 o4 = v[t] * scale[t];
+                    uint2 o;
+                    o.x = (uint32_t)td_f32_to_bf16(o4.x) | ((uint32_t)td_f32_to_bf16(o4.y) << 16);
+                    o.y = (uint32_t)td_f32_to_bf16(o4.z) | ((uint32_t)td_f32_to_bf16(o4.w) << 16);
+                    reinterpret_cast<uint2*>(y + (size_t)(t0 + t) * D)[k4] = o;
+                }
+            }
+        }
+    }
+    if (tid == 0) __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // flagged indices of every token, ascending, and their counts, from the mask words
 __global__ void __launch_bounds__(256)
 mask_to_list_kernel(const uint32_t* __restrict__ mask, int words, int h, int32_t* __restrict__ counts,
@@ -511,7 +798,7 @@ mask_to_list_kernel(const uint32_t* __restrict__ mask, int words, int h, int32_t
     if (threadIdx.x == 0 && counts) counts[t] = carry;
 }
 
-template <int D, int BLOCK, int TB, int SK>
+template <int D, int BLOCK, int TB, int SK, bool DEFER, int NG = 0>
 tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
                               int norm_out, hipStream_t s) {
     constexpr int RQ = 4;
@@ -521,23 +808,65 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
     npb = (npb + 31) / 32 * 32;
     const int rpb = (D + G - 1) / G;
     const int8_t* codes = SK == 8 ? L->Q : reinterpret_cast<const int8_t*>(L->Q4);
-    hipLaunchKernelGGL((decode_fused_kernel<D, BLOCK, RQ, TB, SK>), dim3(G), dim3(BLOCK), 0, s,
+    const size_t lds = (size_t)TB * D * 3 + (NG > 0 ? TB * 16 : 0);   // the tokens (bf16) and their int8 codes
+    auto kernel = decode_fused_kernel<D, BLOCK, RQ, TB, SK, DEFER, NG>;
+    if (lds > 60 * 1024) {
+        static bool allowed = false;                 // per instantiation
+        if (!allowed) {
+            TD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            allowed = true;
+        }
+    }
+    const DeferOut rec{L->rec_count, L->rec_jb, L->rec_delta, npb};
+    hipLaunchKernelGGL(kernel, dim3(G), dim3(BLOCK), lds, s,
                        static_cast<const bf16_t*>(L->Wp), L->bp, codes, L->M4, L->tlo, L->thi,
                        static_cast<const bf16_t*>(L->W1),
                        static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), static_cast<const bf16_t*>(L->W2T),
                        L->a, L->c, static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), yfold, L->yfix,
-                       L->dec_copies, mask, (int)L->mask_words, L->sync, h, npb, rpb, (int)L->act, norm_out, kRmsEps);
+                       L->dec_copies, mask, (int)L->mask_words, L->sync, h, npb, rpb, (int)L->act, norm_out, kRmsEps,
+                       rec);
     TD_HIP(hipGetLastError());
+    if (DEFER) {
+        constexpr size_t lds2 = (size_t)16 * TB * 256 * sizeof(float);
+        auto k2 = down_project_kernel<TB>;
+        static bool allowed2 = false;
+        if (!allowed2) {
+            TD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k2), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds2));
+            allowed2 = true;
+        }
+        const int nslices = D / 256, ngroups = (G + 15) / 16;
+        hipLaunchKernelGGL(k2, dim3(nslices * ngroups), dim3(1024), lds2, s, static_cast<const bf16_t*>(L->W2T), rec,
+                           G, yfold, L->yfix, static_cast<bf16_t*>(y), L->sync, D, nslices, norm_out, kRmsEps);
+        TD_HIP(hipGetLastError());
+    }
     return TARDIS_OK;
 }
 
 template <int D, int BLOCK, int SK>
 tardis_status_t launch_tb(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask, int tokens,
                           int norm_out, hipStream_t s) {
+    if (BLOCK == 1024 && L->defer_min_tokens <= tokens) {   // two kernels: records, then the column-sliced pass
+        if (tokens == 4) return launch_decode<D, 1024, 4, SK, true>(L, x, y, yfold, mask, norm_out, s);
+        if (tokens == 8) {
+            // eight tokens need one-byte codes and 32 or 64 neurons per block (the matrix-core tiling);
+            // otherwise two groups of four
+            const int npb = (((int)L->h + L->dec_blocks - 1) / L->dec_blocks + 31) / 32 * 32;
+            if constexpr (SK == 8) {
+                if (npb == 64 && D >= 1024) return launch_decode<D, 1024, 8, 8, true, 4>(L, x, y, yfold, mask, norm_out, s);
+                if (npb == 32 && D >= 1024) return launch_decode<D, 1024, 8, 8, true, 2>(L, x, y, yfold, mask, norm_out, s);
+            }
+            TD_TRY((launch_decode<D, 1024, 4, SK, true>(L, x, y, yfold, mask, norm_out, s)));
+            return launch_decode<D, 1024, 4, SK, true>(L, static_cast<const bf16_t*>(x) + 4 * (size_t)D,
+                                                       static_cast<bf16_t*>(y) + 4 * (size_t)D, yfold + 4 * (size_t)D,
+                                                       mask + 4 * L->mask_words, norm_out, s);
+        }
+    }
     switch (tokens) {
-        case 1: return launch_decode<D, BLOCK, 1, SK>(L, x, y, yfold, mask, norm_out, s);
-        case 2: return launch_decode<D, BLOCK, 2, SK>(L, x, y, yfold, mask, norm_out, s);
-        case 4: return launch_decode<D, BLOCK, 4, SK>(L, x, y, yfold, mask, norm_out, s);
+        case 1: return launch_decode<D, BLOCK, 1, SK, false>(L, x, y, yfold, mask, norm_out, s);
+        case 2: return launch_decode<D, BLOCK, 2, SK, false>(L, x, y, yfold, mask, norm_out, s);
+        case 4: return launch_decode<D, BLOCK, 4, SK, false>(L, x, y, yfold, mask, norm_out, s);
     }
     return TARDIS_ERR_INVALID_ARG;
 }
@@ -554,7 +883,7 @@ bool td_decode_fused_supported(const tardis_layer_s* L) {
     return npb <= kMaxNeuronsPerBlock;
 }
 
-// `tokens` (1, 2 or 4) consecutive tokens in one launch
+// `tokens` (1, 2, 4, or 8 on the two-kernel path) consecutive tokens
 tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
                                 int tokens, int norm_out, hipStream_t s) {
     if (L->Q4) {   // packed 4-bit sketch (d = 2048 or 4096 only)
