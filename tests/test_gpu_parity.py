@@ -179,9 +179,9 @@ def test_mid_bf16_batched_high_fallback():
 @pytest.mark.parametrize("n,coverage", [(2, 0.95), (3, 0.95), (4, 0.9), (7, 0.85), (8, 0.95), (9, 0.95), (16, 0.9),
                                         (20, 0.95), (48, 0.85), (64, 0.95), (70, 0.99), (150, 0.95)])
 def test_batched_passes_of_64_tokens(n, coverage):
-    """Up to 8 tokens: groups of 4, 2 and 1 tokens sharing one single-launch weight pass.  More: one
-    weight stream per pass of up to 64 tokens, every tile count (1, 2, 4 token tiles), the gather
-    and the masked-dense scatter, a ragged last pass."""
+    """Up to 16 tokens: groups of 8, 4 (two kernels: records, then the column-sliced down projection),
+    2 and 1 tokens (one kernel).  More: one weight stream per pass of up to 64 tokens, every tile
+    count (1, 2, 4 token tiles), the masked-dense scatter, a ragged last pass."""
     w = synth.decode(d=1024, h=4096, n_cal=512, n_test=n, coverage=coverage, config=2)
     run_case(w.layer, w.X_cal, w.X_test, coverage, batched=True, check_calibrate=False)
 
