@@ -121,16 +121,15 @@ def stack_run(T, synth, torch, np, to_dev, n_layers):
     return out
 
 
-def batched_sweep(T, synth, torch, np, to_dev, n_layers):
+def batched_sweep(T, synth, torch, np, to_dev, pre, X, coverages):
     """Batched decode: tokens/s, algorithmic GB/s and union size per (batch, coverage), cold over
-    `n_layers` seeded layer copies, against the vendor-BLAS dense FFN at the same batch."""
+    the given layer copies (`pre`: FFN and device calibration tokens of each), against the
+    vendor-BLAS dense FFN at the same batch."""
     rows = []
-    works = [synth.decode(layer=li, n_cal=4096, n_test=64, coverage=0.95) for li in range(n_layers)]
-    ffns = [T.FFN(to_dev(w.layer.W1), to_dev(w.layer.W2)) for w in works]
-    Xc = [to_dev(w.X_cal) for w in works]
-    X = to_dev(works[0].X_test)
+    ffns = [f for f, _ in pre]
+    Xc = [x for _, x in pre]
     stream = torch.cuda.current_stream()
-    for cov in (0.99, 0.95, 0.85):
+    for cov in coverages:
         layers = []
         for ffn, xc in zip(ffns, Xc):
             lo, hi, a, c = T.tardis_calibrate(ffn, xc, cov)
@@ -187,6 +186,8 @@ def main() -> int:
                     help="also time the greedy range search with this increment on the first layer (offline figure)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the figures beside the headline one (batched decode at the headline coverage, 4-bit sketch)")
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of a replayed HIP graph")
     ap.add_argument("--sweep", action="store_true",
                     help="also run the batched decode sweep: batch {2,4,8,16,64} x coverage {0.99,0.95,0.85}")
@@ -213,7 +214,7 @@ def main() -> int:
 
     # ------------------------------------------------------------ set-up (untimed)
     t_setup = time.time()
-    layers, works = [], []
+    layers, works, pre, cals = [], [], [], []
     offline = {}
     for li in range(args.layers):
         w = synth.decode(layer=li, n_cal=4096, n_test=TOKENS_PER_STEP if li == 0 else 8, coverage=args.coverage)
@@ -237,6 +238,9 @@ def main() -> int:
                 offline["search_step"] = args.search_step
             works.append((w, (lo, hi, a, c)))
         layers.append(L)
+        cals.append((lo, hi, a, c))
+        if li < 4 and not args.no_extras:
+            pre.append((ffn, Xc))            # kept for the batched figures below
         del Xc
     w0, cal0 = works[0]
     X = to_dev(w0.X_test)                      # 1024 x d, resident in HBM before timing starts
@@ -386,8 +390,27 @@ def main() -> int:
     out.update(res_dense)
     if res_dense:
         out["speedup_vs_dense_own"] = tok_s / res_dense["dense_own_tokens_per_s"]
-    if args.sweep:
-        out["batched_sweep"] = batched_sweep(T, synth, torch, np, to_dev, args.layers)
+    if not args.no_extras:
+        # the same decode loop with the 4-bit sketch (same layers, same ranges and lines)
+        l4 = [T.tardis_fold(L.ffn, *cal, max_batch=1, sketch_bits=4) for L, cal in zip(layers, cals)]
+        h4 = [L.handle for L in l4]
+        step(h4[:1])
+        torch.cuda.synchronize()
+        r4 = []
+        for t in range(0, TOKENS_PER_STEP, 64):
+            lib.tardis_ffn_forward(h4[0], xp[t], yp[t], sptr)
+            _, cnt, _ = T.tardis_get_last_outliers(l4[0], 1, want_list=False)
+            r4.append(int(cnt.item()) / H)
+        p4 = float(np.mean(r4))
+        ms4, _ = timed(h4, max(2, args.steps // 2), 1, graph=use_graph)
+        b4 = algorithmic_bytes(D, H, p4, 4)
+        out["sketch4"] = {"tokens_per_s": TOKENS_PER_STEP / (ms4 * 1e-3), "us_per_token": ms4 * 1e3 / TOKENS_PER_STEP,
+                          "measured_fallback_rate": p4, "algorithmic_bytes_per_token": b4,
+                          "algorithmic_GBs": b4 / (ms4 * 1e-3 / TOKENS_PER_STEP) / 1e9}
+        for L in l4:
+            L.close()
+        covs = (0.99, 0.95, 0.85) if args.sweep else (args.coverage,)
+        out["batched_sweep"] = batched_sweep(T, synth, torch, np, to_dev, pre, X, covs)
     if args.prefill:
         out["prefill"] = prefill_run(T, synth, torch, np, to_dev)
     if args.stack > 0:

@@ -90,9 +90,14 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     constexpr int XI = (TB * NVW + BLOCK - 1) / BLOCK;  // per-thread vectors of the tokens
     constexpr int MW = kMaxNeuronsPerBlock / 32;
 
-    extern __shared__ __align__(16) unsigned char token_lds[];   // TB x D bf16 tokens, then their TB x D int8 codes
-    bf16_t* xs = reinterpret_cast<bf16_t*>(token_lds);
-    int8_t* xq = reinterpret_cast<int8_t*>(token_lds + (size_t)TB * D * 2);
+    // TB x D bf16 tokens and their int8 codes: static LDS while they fit the 64 KiB a kernel may
+    // declare, the dynamic segment for the larger groups
+    constexpr bool kStaticTokens = !DEFER && (size_t)TB * D * 3 <= 56 * 1024;
+    extern __shared__ __align__(16) unsigned char token_lds[];
+    __shared__ __align__(16) bf16_t xs_fixed[kStaticTokens ? TB * D : 8];
+    __shared__ __align__(16) int8_t xq_fixed[kStaticTokens ? TB * D : 16];
+    bf16_t* xs = kStaticTokens ? xs_fixed : reinterpret_cast<bf16_t*>(token_lds);
+    int8_t* xq = kStaticTokens ? xq_fixed : reinterpret_cast<int8_t*>(token_lds + (size_t)TB * D * 2);
     __shared__ float dl[NW][TB];                     // delta of the neurons being repaired, per token
     __shared__ int flist[kMaxNeuronsPerBlock];       // neurons flagged by at least one token
     __shared__ unsigned char fbits[kMaxNeuronsPerBlock];  // which tokens flagged them
@@ -808,7 +813,8 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
     npb = (npb + 31) / 32 * 32;
     const int rpb = (D + G - 1) / G;
     const int8_t* codes = SK == 8 ? L->Q : reinterpret_cast<const int8_t*>(L->Q4);
-    const size_t lds = (size_t)TB * D * 3 + (NG > 0 ? TB * 16 : 0);   // the tokens (bf16) and their int8 codes
+    const bool static_tokens = !DEFER && (size_t)TB * D * 3 <= 56 * 1024;    // as in the kernel
+    const size_t lds = static_tokens ? 0 : (size_t)TB * D * 3 + (NG > 0 ? TB * 16 : 0);
     auto kernel = decode_fused_kernel<D, BLOCK, RQ, TB, SK, DEFER, NG>;
     if (lds > 60 * 1024) {
         static bool allowed = false;                 // per instantiation
