@@ -29,7 +29,7 @@ TOKENS_PER_STEP = 1024
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of decode_fused_kernel from `rocprofv3 --pmc` (FETCH_SIZE and WRITE_SIZE runs,
 # scaled by a copy kernel of known size); see profiles/*hbm-traffic.md.
-MEASURED_TRAFFIC_BYTES = 119089537
+MEASURED_TRAFFIC_BYTES = {8: 119086884, 4: 88680345}     # by sketch width
 
 
 def algorithmic_bytes(d: int, h: int, p: float, sketch_bits: int = 8) -> float:
@@ -375,7 +375,7 @@ def main() -> int:
                    "sketch_bits": args.sketch_bits},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES if args.sketch_bits == 8 else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES[args.sketch_bits],
                      "kernel": "decode_fused_kernel", "algorithmic_bytes_per_launch": bytes_tok,
                      "avg_launch_us": launch_s * 1e6},
         "cpu_baseline": cpu,
