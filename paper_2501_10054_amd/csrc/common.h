@@ -181,6 +181,7 @@ tardis_status_t td_calibrate(const tardis_ffn_desc* desc, const void* X, int64_t
 tardis_status_t td_gemm_nt(const void* A, const void* B, float* C, int64_t M, int64_t N, int64_t K,
                            int32_t dtype, int accumulate, const void* row_bias, hipStream_t s);
 // decode.hip
+tardis_status_t td_decode_init();
 bool td_decode_fused_supported(const tardis_layer_s* L);
 constexpr int kDecodeMaxTokens = 8;   // tokens one weight pass of the decode kernel can be shared between
 tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,

@@ -816,14 +816,6 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
     const bool static_tokens = !DEFER && (size_t)TB * D * 3 <= 56 * 1024;    // as in the kernel
     const size_t lds = static_tokens ? 0 : (size_t)TB * D * 3 + (NG > 0 ? TB * 16 : 0);
     auto kernel = decode_fused_kernel<D, BLOCK, RQ, TB, SK, DEFER, NG>;
-    if (lds > 60 * 1024) {
-        static bool allowed = false;                 // per instantiation
-        if (!allowed) {
-            TD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            allowed = true;
-        }
-    }
     const DeferOut rec{L->rec_count, L->rec_jb, L->rec_delta, npb};
     hipLaunchKernelGGL(kernel, dim3(G), dim3(BLOCK), lds, s,
                        static_cast<const bf16_t*>(L->Wp), L->bp, codes, L->M4, L->tlo, L->thi,
@@ -836,12 +828,6 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
     if (DEFER) {
         constexpr size_t lds2 = (size_t)16 * TB * 256 * sizeof(float);
         auto k2 = down_project_kernel<TB>;
-        static bool allowed2 = false;
-        if (!allowed2) {
-            TD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k2), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)lds2));
-            allowed2 = true;
-        }
         const int nslices = D / 256, ngroups = (G + 15) / 16;
         hipLaunchKernelGGL(k2, dim3(nslices * ngroups), dim3(1024), lds2, s, static_cast<const bf16_t*>(L->W2T), rec,
                            G, yfold, L->yfix, static_cast<bf16_t*>(y), L->sync, D, nslices, norm_out, kRmsEps);
@@ -877,7 +863,25 @@ tardis_status_t launch_tb(tardis_layer_s* L, const void* x, void* y, float* yfol
     return TARDIS_ERR_INVALID_ARG;
 }
 
+template <typename K> hipError_t allow_lds(K kernel, size_t bytes) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)bytes);
+}
+
 }  // namespace
+
+// Kernels whose dynamic LDS exceeds the default limit are enabled once, when the first layer is
+// folded (not at launch: a launch may be under stream capture).
+tardis_status_t td_decode_init() {
+    static bool done = false;
+    if (done) return TARDIS_OK;
+    TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 4>, (size_t)8 * 4096 * 3 + 128));
+    TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 2>, (size_t)8 * 4096 * 3 + 128));
+    TD_HIP(allow_lds(down_project_kernel<4>, (size_t)16 * 4 * 256 * sizeof(float)));
+    TD_HIP(allow_lds(down_project_kernel<8>, (size_t)16 * 8 * 256 * sizeof(float)));
+    done = true;
+    return TARDIS_OK;
+}
 
 bool td_decode_fused_supported(const tardis_layer_s* L) {
     if (L->dtype != TARDIS_BF16) return false;

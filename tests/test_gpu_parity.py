@@ -377,10 +377,11 @@ def test_fused_kernel_many_flagged_per_block():
 
 def test_graph_capture_and_replay_of_forward():
     # the online call allocates nothing and records no memset: it can be captured and replayed
-    w = synth.decode(d=1024, h=4096, n_cal=256, n_test=6, coverage=0.9, config=9)
+    # (one-, two-, four- and eight-token groups: the last two run as two kernels each)
+    w = synth.decode(d=1024, h=4096, n_cal=256, n_test=15, coverage=0.9, config=9)
     ffn = make_ffn(w.layer)
     lo, hi, a, c = T.tardis_calibrate(ffn, dev(w.X_cal, "bf16"), 0.9)
-    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=8)
+    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=16)
     X = dev(w.X_test, "bf16")
     y_eager = torch.stack([T.tardis_ffn_forward(L, X[t]).clone() for t in range(3)])
     yb_eager = T.tardis_ffn_forward_batched(L, X).clone()
@@ -443,7 +444,8 @@ def test_repeated_calls_are_stable():
 
 
 # ------------------------------------------------------------- stacked layers
-@pytest.mark.parametrize("d,h,dtype,n", [(1024, 4096, "bf16", 1), (1024, 4096, "bf16", 3), (64, 256, "f32", 2)])
+@pytest.mark.parametrize("d,h,dtype,n", [(1024, 4096, "bf16", 1), (1024, 4096, "bf16", 3), (64, 256, "f32", 2),
+                                         (1024, 4096, "bf16", 12), (2048, 2048, "bf16", 8)])
 def test_stack_teacher_forced(d, h, dtype, n):
     """Every layer is checked on the input the GPU itself handed to it: mask bit-exact, the
     normalised hand-over and the final output within the y tolerance."""
