@@ -97,8 +97,9 @@ def stack_run(T, synth, torch, np, to_dev, n_layers):
         layers.append(T.tardis_fold(ffn, lo, hi, a, c, max_batch=32))
         if li == 0:
             X = to_dev(w.X_test)
+        print(f"bench.py: stack layer {li + 1}/{n_layers} folded", file=sys.stderr, flush=True)
     out = {"layers": n_layers}
-    for B in (1, 32):
+    for B in (1, 4, 8, 32):
         xb = X[:B].contiguous()
         yb = torch.empty_like(xb)
         us = _time_us(torch, lambda: T.tardis_stack_forward(layers, xb, yb), 10, 2)
