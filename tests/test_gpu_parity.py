@@ -375,6 +375,17 @@ def test_fused_kernel_many_flagged_per_block():
     assert r["rate"] > 0.3
 
 
+def test_two_kernel_groups_with_many_records_per_block():
+    # h = 20000 gives 96 neurons per block: more record slots than a wavefront holds at once, and no
+    # matrix-core tiling (eight tokens run as two groups of four); 80 % fallback fills most slots
+    seed = synth.workload_seed(9, 31)
+    layer = synth.make_layer(1024, 20000, "bf16", seed, w1_std=0.03, w2_std=0.01, heavy_frac=0.01)
+    X_cal = synth.make_tokens(256, 1024, "bf16", seed, synth.STREAM_CAL)
+    X_test = synth.make_tokens(8, 1024, "bf16", seed, synth.STREAM_TEST)
+    r = run_case(layer, X_cal, X_test, 0.2, check_calibrate=False, batched=True)
+    assert r["rate"] > 0.7
+
+
 def test_graph_capture_and_replay_of_forward():
     # the online call allocates nothing and records no memset: it can be captured and replayed
     # (one-, two-, four- and eight-token groups: the last two run as two kernels each)
