@@ -78,15 +78,18 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     static_assert(SK == 8 || (SK == 4 && D % 2048 == 0), "a packed 4-bit row must fill whole wavefront loads");
     static_assert(NG == 0 || (SK == 8 && TB == 8 && DEFER && (BLOCK / TD_WAVE) % NG == 0), "matrix-core predictor");
     constexpr int NW = BLOCK / TD_WAVE;
-    constexpr int KQ = NG > 0 ? NW / NG : 1;         // wavefronts sharing a group of 16 rows
+    constexpr int KQ = NW / (NG > 0 ? NG : 1);       // wavefronts sharing a group of 16 rows
     constexpr int KS = D / KQ;                       // columns of one wavefront's slice
     constexpr int NL = NG > 0 ? KS / 64 : 1;         // 16-byte vectors per lane of that slice
     constexpr int XP = NG > 0 ? D + 16 : D;          // LDS pitch of a token's int8 code (bank spread for the tile reads)
+    constexpr int XSP = DEFER ? D + 8 : D;           // LDS pitch of a token in elements (same reason, W' tiles)
+    constexpr int KW = D / NW;                       // columns of W' one wavefront multiplies on the deferred path
     static_assert(NG == 0 || (KS % 64 == 0 && NL >= 1), "slice of whole 64-column steps");
     constexpr int NVW = D / 8;                       // 16-byte vectors per bf16 row
     constexpr int QROW = SK == 8 ? D : D / 2;        // bytes of one predictor row
     constexpr int IQ = QROW / 16 / TD_WAVE;          // per-lane vectors of a predictor row
     constexpr int IW = NVW / TD_WAVE;                // per-lane vectors of a bf16 row
+    static_assert(!DEFER || (KW % 32 == 0 && KW * 2 / 64 == IW), "W' slices of whole 32-column steps, IW vectors per lane");
     constexpr int XI = (TB * NVW + BLOCK - 1) / BLOCK;  // per-thread vectors of the tokens
     constexpr int MW = kMaxNeuronsPerBlock / 32;
 
@@ -97,7 +100,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     __shared__ __align__(16) bf16_t xs_fixed[kStaticTokens ? TB * D : 8];
     __shared__ __align__(16) int8_t xq_fixed[kStaticTokens ? TB * D : 16];
     bf16_t* xs = kStaticTokens ? xs_fixed : reinterpret_cast<bf16_t*>(token_lds);
-    int8_t* xq = kStaticTokens ? xq_fixed : reinterpret_cast<int8_t*>(token_lds + (size_t)TB * D * 2);
+    int8_t* xq = kStaticTokens ? xq_fixed : reinterpret_cast<int8_t*>(token_lds + (size_t)TB * XSP * 2);
     __shared__ float dl[NW][TB];                     // delta of the neurons being repaired, per token
     __shared__ int flist[kMaxNeuronsPerBlock];       // neurons flagged by at least one token
     __shared__ unsigned char fbits[kMaxNeuronsPerBlock];  // which tokens flagged them
@@ -106,6 +109,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     __shared__ int nflag;
     __shared__ int is_last;
     __shared__ int pacc[NG > 0 ? NW : 1][16][NG > 0 ? TB : 1];   // partial sums of the matrix-core predictor
+    __shared__ float wpart[DEFER ? NW : 1][16][DEFER ? TB : 1];  // ... and of the matrix-core W' product
 
     const int tid = threadIdx.x;
     const int lane = tid & (TD_WAVE - 1);
@@ -164,7 +168,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     for (int it = 0; it < XI; ++it) {
         const int v = it * BLOCK + tid;
         if (v < TB * NVW) {
-            reinterpret_cast<td_u32x4*>(xs)[v] = xv[it];
+            reinterpret_cast<td_u32x4*>(xs + (size_t)(v / NVW) * XSP)[v % NVW] = xv[it];
             const bf16_t* e8 = reinterpret_cast<const bf16_t*>(&xv[it]);
             float m = 0.0f;
 #pragma unroll
@@ -308,16 +312,25 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
         }
     }
 
-    const td_u32x4* xs4 = reinterpret_cast<const td_u32x4*>(xs) + lane;
+    auto xsv = [&](int t, int it) -> td_u32x4 {       // vector it*64 + lane of token t
+        return reinterpret_cast<const td_u32x4*>(xs + (size_t)t * XSP)[it * TD_WAVE + lane];
+    };
     const int r0 = blk * rpb;
     const int rn = min(rpb, D - r0);                 // W' rows owned (may be <= 0)
     td_u32x4 wp[IW];
-    const td_u32x4* wp_row = reinterpret_cast<const td_u32x4*>(Wp + (size_t)min(r0 + wave, D - 1) * D) + lane;
+    // one kernel: wavefront w holds row r0 + w whole.  Deferred path: the block's (up to 16) rows are one
+    // matrix-core tile, wavefront w holds columns [w*KW, (w+1)*KW) of all of them - lane: row lane % 16,
+    // 16 bytes at step it, k-group lane / 16 - so the tokens are read from LDS once per block, not per row
+    const td_u32x4* wp_row =
+        DEFER ? reinterpret_cast<const td_u32x4*>(Wp + (size_t)min(r0 + (lane & 15), D - 1) * D + wave * KW) + (lane >> 4)
+              : reinterpret_cast<const td_u32x4*>(Wp + (size_t)min(r0 + wave, D - 1) * D) + lane;
+    constexpr int WSTEP = DEFER ? 4 : TD_WAVE;       // vectors between a lane's consecutive loads
+    const float bias_own = DEFER ? bp[min(r0 + tid / TB, D - 1)] : 0.0f;   // thread (row, token) of the final sum
     // first half of this wave's W' row: requested before the block meets at the barrier, so that
     // the memory pipe stays busy while the flagged list is assembled
     constexpr int IWA = IW / 2;
 #pragma unroll
-    for (int it = 0; it < IWA; ++it) wp[it] = td_load_stream16(wp_row + it * TD_WAVE);
+    for (int it = 0; it < IWA; ++it) wp[it] = td_load_stream16(wp_row + it * WSTEP);
 
     if constexpr (NG > 0) {
         __syncthreads();                             // the partial sums of every wavefront are in LDS
@@ -371,7 +384,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
         if (tid == 0) rec.count[blk] = nf;
         if (nf == 0) {
 #pragma unroll
-            for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * TD_WAVE);
+            for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * WSTEP);
         }
         for (int f0 = 0; f0 < nf; f0 += NW) {
             asm volatile("" ::: "memory");
@@ -391,7 +404,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
             if (f0 == 0) {   // the rest of this wave's W' row streams in behind the first batch of W1 rows
                 asm volatile("" ::: "memory");
 #pragma unroll
-                for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * TD_WAVE);
+                for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * WSTEP);
             }
             asm volatile("" : "+v"(bj_raw), "+v"(aj), "+v"(cj));
             if (fixer) {
@@ -405,7 +418,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                     if ((zbits >> t) & 1u) {
                         float z = 0.0f;
 #pragma unroll
-                        for (int it = 0; it < IW; ++it) z = RowVec<bf16_t>::dot(w1[it], xs4[t * NVW + it * TD_WAVE], z);
+                        for (int it = 0; it < IW; ++it) z = RowVec<bf16_t>::dot(w1[it], xsv(t, it), z);
                         z = td_wave_sum(z) + bj;
                         dv = td_act(z, act) - fmaf(aj, z, cj);
                     }
@@ -414,18 +427,30 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                 if (lane == 0) rec.jb[slot] = (uint32_t)jz | (zbits << 24);
             }
         }
-        for (int ri = wave; ri < rn; ri += NW) {
+        {   // speculative rows: 16 x KW slice of W' against the tokens on the matrix cores
+            typedef float f32x4m __attribute__((ext_vector_type(4)));
+            typedef __bf16 bf16x8m __attribute__((ext_vector_type(8)));
             asm volatile("" ::: "memory");
-            if (ri != wave) load_row<IW>(wp, Wp + (size_t)(r0 + ri) * D, lane);
-            const float bias = ri == wave ? bias_out : bp[r0 + ri];
+            const unsigned char* xb = reinterpret_cast<const unsigned char*>(xs) +
+                                      (size_t)((lane & 15) & (TB - 1)) * XSP * 2 + (size_t)wave * KW * 2 + (lane >> 4) * 16;
+            f32x4m accw = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int t = 0; t < TB; ++t) {
-                asm volatile("" ::: "memory");
-                float s = 0.0f;
+            for (int it = 0; it < IW; ++it) {
+                const td_u32x4 tk = *reinterpret_cast<const td_u32x4*>(xb + it * 64);
+                accw = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8m, wp[it]),
+                                                               __builtin_bit_cast(bf16x8m, tk), accw, 0, 0, 0);
+            }
+            if ((lane & 15) < TB) {   // lane: token lane % 16, rows 4 * (lane / 16) + i
 #pragma unroll
-                for (int it = 0; it < IW; ++it) s = RowVec<bf16_t>::dot(wp[it], xs4[t * NVW + it * TD_WAVE], s);
-                s = td_wave_sum(s);
-                if (lane == 0) yfold[(size_t)t * D + r0 + ri] = s + bias;
+                for (int i = 0; i < 4; ++i) wpart[wave][4 * (lane >> 4) + i][lane & 15] = accw[i];
+            }
+            __syncthreads();
+            if (tid < 16 * TB && tid / TB < rn) {
+                const int row = tid / TB, t = tid % TB;
+                float s = bias_own;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) s += wpart[w][row][t];
+                yfold[(size_t)t * D + r0 + row] = s;
             }
         }
         return;
@@ -464,7 +489,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
         if (kFirst) {
             asm volatile("" ::: "memory");
 #pragma unroll
-            for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * TD_WAVE);
+            for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * WSTEP);
         }
         // nothing above may wait for a load: the conversion of b1 is pinned below this point
         asm volatile("" : "+v"(bj_raw), "+v"(aj), "+v"(cj));
@@ -476,7 +501,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                 if (TB > 1) asm volatile("" ::: "memory");   // one token's LDS reads at a time (register budget)
                 float z = 0.0f;
 #pragma unroll
-                for (int it = 0; it < IW; ++it) z = RowVec<bf16_t>::dot(w1[it], xs4[t * NVW + it * TD_WAVE], z);
+                for (int it = 0; it < IW; ++it) z = RowVec<bf16_t>::dot(w1[it], xsv(t, it), z);
                 z = td_wave_sum(z) + bj;
                 const float dv = ((zbits >> t) & 1u) ? td_act(z, act) - fmaf(aj, z, cj) : 0.0f;
                 if (lane == 0) dl[wave][t] = dv;
@@ -499,7 +524,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     };
     if (nf == 0) {
 #pragma unroll
-        for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * TD_WAVE);
+        for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * WSTEP);
     } else {
         repair_pass(std::true_type{}, 0);
         for (int f0 = FCH; f0 < nf; f0 += FCH) repair_pass(std::false_type{}, f0);
@@ -530,7 +555,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
             if (TB > 1) asm volatile("" ::: "memory");
             float s = 0.0f;
 #pragma unroll
-            for (int it = 0; it < IW; ++it) s = RowVec<bf16_t>::dot(wp[it], xs4[t * NVW + it * TD_WAVE], s);
+            for (int it = 0; it < IW; ++it) s = RowVec<bf16_t>::dot(wp[it], xsv(t, it), s);
             s = td_wave_sum(s);
             // written through to memory so that the finishing block, on any XCD, reads it
             if (lane == 0)
@@ -700,12 +725,35 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, cons
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
+    if (!norm_out) {
+        // ---- no row-wide quantity is needed: the last of the blocks that share this slice of
+        //      columns assembles the slice (counter 1 + slice), all slices in parallel
+        const int ngroups = (int)gridDim.x / nslices;
+        if (tid == 0)
+            is_last = (__hip_atomic_fetch_add(done + 1 + slice, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                       ngroups - 1);
+        __syncthreads();
+        if (!is_last) return;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        for (int k = tid; k < TB * (SL / 4); k += 1024) {
+            const int t = k / (SL / 4), c4 = k % (SL / 4);
+            const size_t at = (size_t)t * D + slice * SL + c4 * 4;
+            const f32x4 o4 = *reinterpret_cast<const f32x4*>(yfold + at) + *reinterpret_cast<const f32x4*>(yfix + at);
+            *reinterpret_cast<f32x4*>(yfix + at) = zero4;
+            uint2 o;
+            o.x = (uint32_t)td_f32_to_bf16(o4.x) | ((uint32_t)td_f32_to_bf16(o4.y) << 16);
+            o.y = (uint32_t)td_f32_to_bf16(o4.z) | ((uint32_t)td_f32_to_bf16(o4.w) << 16);
+            *reinterpret_cast<uint2*>(y + at) = o;
+        }
+        if (tid == 0) __hip_atomic_store(done + 1 + slice, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
     if (tid == 0)
         is_last = (__hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1);
     __syncthreads();
     if (!is_last) return;
 
-    // ---- the last block assembles the tokens and re-arms the scratch
+    // ---- the last block assembles the tokens (with their row-wide norm) and re-arms the scratch
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     float* redt = accL;                              // NW x TB floats, free by now
     constexpr int TH = TB < 4 ? TB : 4;              // tokens assembled together
@@ -814,7 +862,7 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
     const int rpb = (D + G - 1) / G;
     const int8_t* codes = SK == 8 ? L->Q : reinterpret_cast<const int8_t*>(L->Q4);
     const bool static_tokens = !DEFER && (size_t)TB * D * 3 <= 56 * 1024;    // as in the kernel
-    const size_t lds = static_tokens ? 0 : (size_t)TB * D * 3 + (NG > 0 ? TB * 16 : 0);
+    const size_t lds = static_tokens ? 0 : (size_t)TB * (DEFER ? D + 8 : D) * 2 + (size_t)TB * (NG > 0 ? D + 16 : D);
     auto kernel = decode_fused_kernel<D, BLOCK, RQ, TB, SK, DEFER, NG>;
     const DeferOut rec{L->rec_count, L->rec_jb, L->rec_delta, npb};
     hipLaunchKernelGGL(kernel, dim3(G), dim3(BLOCK), lds, s,
@@ -839,7 +887,8 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
 template <int D, int BLOCK, int SK>
 tardis_status_t launch_tb(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask, int tokens,
                           int norm_out, hipStream_t s) {
-    if (BLOCK == 1024 && L->defer_min_tokens <= tokens) {   // two kernels: records, then the column-sliced pass
+    // two kernels: records, then the column-sliced pass (the block's W' rows must fit one 16-row tile)
+    if (BLOCK == 1024 && L->defer_min_tokens <= tokens && (D + L->dec_blocks - 1) / L->dec_blocks <= 16) {
         if (tokens == 4) return launch_decode<D, 1024, 4, SK, true>(L, x, y, yfold, mask, norm_out, s);
         if (tokens == 8) {
             // eight tokens need one-byte codes and 32 or 64 neurons per block (the matrix-core tiling);
@@ -875,8 +924,8 @@ template <typename K> hipError_t allow_lds(K kernel, size_t bytes) {
 tardis_status_t td_decode_init() {
     static bool done = false;
     if (done) return TARDIS_OK;
-    TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 4>, (size_t)8 * 4096 * 3 + 128));
-    TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 2>, (size_t)8 * 4096 * 3 + 128));
+    TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 4>, (size_t)8 * 4096 * 3 + 256));
+    TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 2>, (size_t)8 * 4096 * 3 + 256));
     TD_HIP(allow_lds(down_project_kernel<4>, (size_t)16 * 4 * 256 * sizeof(float)));
     TD_HIP(allow_lds(down_project_kernel<8>, (size_t)16 * 8 * 256 * sizeof(float)));
     done = true;

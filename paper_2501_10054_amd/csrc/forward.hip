@@ -233,7 +233,8 @@ tardis_status_t forward_t(tardis_layer_s* L, const void* xv, int64_t n, void* yv
     if (n > L->batched_min_tokens && L->use_batched) return td_forward_batched(L, xv, n, yv, norm_out, s);
     if (L->use_fused) {   // groups of 4, 2, 1 tokens share one pass over the weights
         for (int64_t t = 0; t < n;) {
-            const int g = (n - t >= 8 && L->dec_threads == 1024 && L->defer_min_tokens <= 8) ? 8
+            const int g = (n - t >= 8 && L->dec_threads == 1024 && L->defer_min_tokens <= 8 &&
+                           (d + L->dec_blocks - 1) / L->dec_blocks <= 16) ? 8
                           : (n - t >= 4) ? 4 : (n - t >= 2) ? 2 : 1;
             TD_TRY(td_decode_fused(L, static_cast<const T*>(xv) + t * d, static_cast<T*>(yv) + t * d,
                                    L->yacc + t * d, L->mask + t * L->mask_words, g, norm_out, s));
