@@ -51,7 +51,7 @@ int env_int(const char* name, int fallback, int lo, int hi) {
 void free_layer(tardis_layer_s* L) {
     if (!L) return;
     void* owned[] = {L->W2T, L->W2, L->Wp, L->bp, L->Q, L->Q4, L->M4, L->tlo, L->thi, L->a, L->c,
-                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix, L->zeros_h, L->xnext, L->rec_count, L->rec_jb, L->rec_delta,
+                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix, L->zeros_h, L->xnext, L->rec_count, L->rec_jb, L->rec_tb, L->rec_delta,
                      L->bt_xq, L->bt_e, L->bt_tokmask, L->bt_ulist, L->bt_ucount, L->bt_delta, L->bt_partial};
     for (void* p : owned)
         if (p) (void)hipFree(p);
@@ -104,6 +104,7 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
         const int64_t npb = ((h + L->dec_blocks - 1) / L->dec_blocks + 31) / 32 * 32;
         TD_TRY(dev_alloc(&L->rec_count, (size_t)L->dec_blocks * 4));
         TD_TRY(dev_alloc(&L->rec_jb, (size_t)L->dec_blocks * npb * 4));
+        TD_TRY(dev_alloc(&L->rec_tb, (size_t)L->dec_blocks * npb * 4));
         TD_TRY(dev_alloc(&L->rec_delta, (size_t)L->dec_blocks * npb * kDecodeMaxTokens * 4));
     }
     L->use_batched = env_int("TARDIS_BATCHED", 1, 0, 1) && td_batched_supported(L);

@@ -74,8 +74,9 @@ struct tardis_layer_s {
     float* bt_partial;             // partial products of the scatter step
     int32_t use_batched;
     int32_t* rec_count;            // two-kernel path: flagged neurons per predictor block,
-    uint32_t* rec_jb;              //   neuron index | token bits << 24 (dec_blocks x neurons per block),
-    float* rec_delta;              //   and 8 deltas per record
+    uint32_t* rec_jb;              //   neuron index and
+    uint32_t* rec_tb;              //   token bits of each record (dec_blocks x neurons per block),
+    float* rec_delta;              //   and kDecodeMaxTokens deltas per record
     int32_t defer_min_tokens;      // groups of at least this many tokens take the two-kernel path (4, 8; 99 = never)
     int32_t gather_max_tokens;     // passes of up to this many tokens scatter through the union rows of W2^T
     int32_t batched_min_tokens;    // token counts up to this go through the single-token path
@@ -183,7 +184,7 @@ tardis_status_t td_gemm_nt(const void* A, const void* B, float* C, int64_t M, in
 // decode.hip
 tardis_status_t td_decode_init();
 bool td_decode_fused_supported(const tardis_layer_s* L);
-constexpr int kDecodeMaxTokens = 8;   // tokens one weight pass of the decode kernel can be shared between
+constexpr int kDecodeMaxTokens = 16;  // tokens one weight pass of the decode kernel can be shared between
 tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
                                 int tokens, int norm_out, hipStream_t s);
 tardis_status_t td_mask_to_list(const tardis_layer_s* L, int64_t n, int32_t* counts, int32_t* list, hipStream_t s);

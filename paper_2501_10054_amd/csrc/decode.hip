@@ -51,7 +51,8 @@ __device__ __forceinline__ void load_row(td_u32x4 (&dst)[N], const void* row, in
 // With many tokens per launch this replaces TB x d atomics per block by a column-sliced pass.
 struct DeferOut {
     int32_t* count;    // flagged neurons of every block
-    uint32_t* jb;      // blocks x cap: neuron index | token bits << 24
+    uint32_t* jb;      // blocks x cap: neuron index
+    uint32_t* tb;      // blocks x cap: bit t set iff token t flagged the neuron
     float* delta;      // blocks x cap x TB
     int cap;           // record slots per block (= neurons per block)
 };
@@ -74,9 +75,11 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                     float eps, DeferOut rec) {
     static_assert(D % 1024 == 0, "rows must be whole multiples of 64 lanes x 16 bytes");
     static_assert(D % BLOCK == 0 && BLOCK / TD_WAVE >= 4, "column ownership of the repair pass");
-    static_assert(TB == 1 || TB == 2 || TB == 4 || (TB == 8 && DEFER), "tokens per pass");
+    static_assert(TB == 1 || TB == 2 || TB == 4 || ((TB == 8 || TB == 16) && DEFER), "tokens per pass");
     static_assert(SK == 8 || (SK == 4 && D % 2048 == 0), "a packed 4-bit row must fill whole wavefront loads");
-    static_assert(NG == 0 || (SK == 8 && TB == 8 && DEFER && (BLOCK / TD_WAVE) % NG == 0), "matrix-core predictor");
+    static_assert(NG == 0 || (SK == 8 && (TB == 8 || TB == 16) && DEFER && (BLOCK / TD_WAVE) % NG == 0),
+                  "matrix-core predictor");
+    static_assert(TB < 16 || NG > 0, "sixteen tokens only with the matrix-core predictor");
     constexpr int NW = BLOCK / TD_WAVE;
     constexpr int KQ = NW / (NG > 0 ? NG : 1);       // wavefronts sharing a group of 16 rows
     constexpr int KS = D / KQ;                       // columns of one wavefront's slice
@@ -100,16 +103,21 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     __shared__ __align__(16) bf16_t xs_fixed[kStaticTokens ? TB * D : 8];
     __shared__ __align__(16) int8_t xq_fixed[kStaticTokens ? TB * D : 16];
     bf16_t* xs = kStaticTokens ? xs_fixed : reinterpret_cast<bf16_t*>(token_lds);
-    int8_t* xq = kStaticTokens ? xq_fixed : reinterpret_cast<int8_t*>(token_lds + (size_t)TB * XSP * 2);
+    // sixteen tokens: the int8 codes live where the tokens will go once the predictor is done with
+    // them (the tokens wait in registers meanwhile); both do not fit the LDS at once
+    constexpr bool kAlias = TB == 16;
+    int8_t* xq = kStaticTokens ? xq_fixed
+                               : reinterpret_cast<int8_t*>(token_lds + (kAlias ? (size_t)0 : (size_t)TB * XSP * 2));
     __shared__ float dl[NW][TB];                     // delta of the neurons being repaired, per token
     __shared__ int flist[kMaxNeuronsPerBlock];       // neurons flagged by at least one token
-    __shared__ unsigned char fbits[kMaxNeuronsPerBlock];  // which tokens flagged them
+    __shared__ unsigned short fbits[kMaxNeuronsPerBlock];  // which tokens flagged them
     __shared__ uint32_t words[TB][MW];
     __shared__ int tmax[TB];                         // max |x| per token (bit pattern of a non-negative float)
     __shared__ int nflag;
     __shared__ int is_last;
-    __shared__ int pacc[NG > 0 ? NW : 1][16][NG > 0 ? TB : 1];   // partial sums of the matrix-core predictor
-    __shared__ float wpart[DEFER ? NW : 1][16][DEFER ? TB : 1];  // ... and of the matrix-core W' product
+    // partial sums of the matrix-core predictor (int32) and, later, of the matrix-core W' product (fp32)
+    __shared__ int pacc[DEFER ? NW : 1][16][DEFER ? TB : 1];
+    float (*wpart)[16][DEFER ? TB : 1] = reinterpret_cast<float (*)[16][DEFER ? TB : 1]>(pacc);
 
     const int tid = threadIdx.x;
     const int lane = tid & (TD_WAVE - 1);
@@ -145,12 +153,16 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     };
     td_u32x4 qm[NL];                                 // matrix-core path: row (lane % 16) of the group, 16 bytes per step
     float tl_own = 0.0f, th_own = 0.0f;              // ... and the bounds of neuron `tid` of the block
-    if constexpr (NG > 0) {
+    auto load_pred_tile = [&]() {
         const int grp = wave % NG, kq = wave / NG;
         const int j = min(j0 + grp * 16 + (lane & 15), h - 1);
         const td_u32x4* p = reinterpret_cast<const td_u32x4*>(Q + (size_t)j * D + kq * KS) + (lane >> 4);
 #pragma unroll
         for (int m = 0; m < NL; ++m) qm[m] = td_load_stream16(p + m * 4);
+    };
+    if constexpr (NG > 0) {
+        // (sixteen tokens occupy 32 registers until they are staged: their rows are requested after that)
+        if (!kAlias) load_pred_tile();
         const int jt = min(j0 + tid, h - 1);
         tl_own = tlo[jt];
         th_own = thi[jt];
@@ -168,7 +180,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     for (int it = 0; it < XI; ++it) {
         const int v = it * BLOCK + tid;
         if (v < TB * NVW) {
-            reinterpret_cast<td_u32x4*>(xs + (size_t)(v / NVW) * XSP)[v % NVW] = xv[it];
+            if (!kAlias) reinterpret_cast<td_u32x4*>(xs + (size_t)(v / NVW) * XSP)[v % NVW] = xv[it];
             const bf16_t* e8 = reinterpret_cast<const bf16_t*>(&xv[it]);
             float m = 0.0f;
 #pragma unroll
@@ -178,17 +190,24 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
         }
     }
     __syncthreads();
-    int ex[TB];
+    int ex[NG > 0 ? 1 : TB];                         // the matrix-core path reads them from LDS where needed
+    if constexpr (NG == 0) {
 #pragma unroll
-    for (int t = 0; t < TB; ++t) ex[t] = token_exponent(__int_as_float(tmax[t]));
+        for (int t = 0; t < TB; ++t) ex[t] = token_exponent(__int_as_float(tmax[t]));
+    }
 #pragma unroll
     for (int it = 0; it < XI; ++it) {
         const int v = it * BLOCK + tid;
         if (v < TB * NVW) {
             const int tok = v / NVW;
-            int e = ex[0];
+            int e;
+            if constexpr (NG > 0) {
+                e = token_exponent(__int_as_float(tmax[tok]));
+            } else {
+                e = ex[0];
 #pragma unroll
-            for (int t = 1; t < TB; ++t) e = tok == t ? ex[t] : e;
+                for (int t = 1; t < TB; ++t) e = tok == t ? ex[t] : e;
+            }
             const bf16_t* e8 = reinterpret_cast<const bf16_t*>(&xv[it]);
             uint32_t lo = 0, hi = 0;
 #pragma unroll
@@ -207,6 +226,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
             }
         }
     }
+    if constexpr (NG > 0 && kAlias) load_pred_tile();
     __syncthreads();
 
     // ---- predictor rows: exact int32 dot products, range test per token, block-local list of
@@ -228,6 +248,14 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
             for (int i = 0; i < 4; ++i) pacc[wave][4 * (lane >> 4) + i][lane & 15] = acc4[i];
         }
         (void)grp;
+        if constexpr (kAlias) {   // the tokens again (from cache), now that the predictor rows' registers are free
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int it = 0; it < XI; ++it) {
+                const int v = min(it * BLOCK + tid, TB * NVW - 1);
+                xv[it] = reinterpret_cast<const td_u32x4*>(x)[v];
+            }
+        }
     }
     for (int base = 0; NG == 0 && base < jn; base += NW * RQ) {
         const int jb = base + wave * RQ;
@@ -292,7 +320,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
 #pragma unroll
                 for (int t = 0; t < TP; ++t) {
                     const int total = td_wave_sum_i(acc[i][t]);
-                    const float v = ldexpf((float)(SK == 8 ? total : total >> 4), ex[t0 + t]);
+                    const float v = ldexpf((float)(SK == 8 ? total : total >> 4), ex[NG > 0 ? 0 : t0 + t]);
                     const bool inside = (v >= tl[i]) && (v < th[i]);
                     bits[i] |= inside ? 0u : (1u << (t0 + t));
                 }
@@ -307,7 +335,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                     if ((bits[i] >> t) & 1u) atomicOr(&words[t][jl >> 5], 1u << (jl & 31));
                 const int pos = atomicAdd(&nflag, 1);
                 flist[pos] = j0 + jl;
-                fbits[pos] = (unsigned char)bits[i];
+                fbits[pos] = (unsigned short)bits[i];
             }
         }
     }
@@ -342,7 +370,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                 int total = 0;
 #pragma unroll
                 for (int kq = 0; kq < KQ; ++kq) total += pacc[kq * NG + grp][row][t];
-                const float v = ldexpf((float)total, ex[t]);
+                const float v = ldexpf((float)total, token_exponent(__int_as_float(tmax[t])));
                 const bool inside = (v >= tl_own) && (v < th_own);
                 bits |= inside ? 0u : (1u << t);
             }
@@ -352,7 +380,14 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                     if ((bits >> t) & 1u) atomicOr(&words[t][tid >> 5], 1u << (tid & 31));
                 const int pos = atomicAdd(&nflag, 1);
                 flist[pos] = j0 + tid;
-                fbits[pos] = (unsigned char)bits;
+                fbits[pos] = (unsigned short)bits;
+            }
+        }
+        if constexpr (kAlias) {   // every wavefront is past its last read of the int8 codes: the tokens take their place
+#pragma unroll
+            for (int it = 0; it < XI; ++it) {
+                const int v = it * BLOCK + tid;
+                if (v < TB * NVW) reinterpret_cast<td_u32x4*>(xs + (size_t)(v / NVW) * XSP)[v % NVW] = xv[it];
             }
         }
     }
@@ -424,7 +459,10 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                     }
                     if (lane == 0) rec.delta[slot * TB + t] = dv;
                 }
-                if (lane == 0) rec.jb[slot] = (uint32_t)jz | (zbits << 24);
+                if (lane == 0) {
+                    rec.jb[slot] = (uint32_t)jz;
+                    rec.tb[slot] = zbits;
+                }
             }
         }
         {   // speculative rows: 16 x KW slice of W' against the tokens on the matrix cores
@@ -653,59 +691,92 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
 // block reduces over its wavefronts and adds TB x 256 floats to the accumulators in memory - 16
 // times fewer atomics than one d-vector per predictor block and token.  The last block to finish
 // assembles the tokens.
-template <int TB>
+template <int TB, int SL>
 __global__ void __launch_bounds__(1024)
-down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, const float* __restrict__ yfold,
+down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int pbw, const float* __restrict__ yfold,
                     float* __restrict__ yfix, bf16_t* __restrict__ y, int32_t* __restrict__ done, int D, int nslices,
                     int norm_out, float eps) {
-    constexpr int NW = 16, SL = 256, U = 16;         // rows in flight per wavefront
+    constexpr int NW = 16, U = SL == 128 ? 48 : 16;  // wavefronts; rows in flight per wavefront (4- or 8-byte loads)
+    constexpr int CPL = SL / TD_WAVE;                // columns per lane: 4 (8-byte loads) or 2 (4-byte loads)
+    static_assert(CPL == 4 || CPL == 2, "slice width");
     typedef float f32x4 __attribute__((ext_vector_type(4)));
+    typedef float f32xc __attribute__((ext_vector_type(CPL)));
     extern __shared__ __align__(16) float accL[];    // NW x TB x SL
     __shared__ int is_last;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int slice = blockIdx.x % nslices, group = blockIdx.x / nslices;
-    float* acc = accL + (size_t)wave * TB * SL + lane * 4;
+    float* acc = accL + (size_t)wave * TB * SL + lane * CPL;
     const f32x4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-    for (int t = 0; t < TB; ++t) *reinterpret_cast<f32x4*>(acc + t * SL) = zero4;
-    const int pb = __builtin_amdgcn_readfirstlane(group * NW + wave);
-    const int pbc = min(pb, nblk - 1);
-    const uint32_t* jb = rec.jb + (size_t)pbc * rec.cap;
-    const float* dl = rec.delta + (size_t)pbc * rec.cap * TB;
-    const bf16_t* base = W2T + (size_t)slice * SL + lane * 4;
-    // the count and the first 64 records are requested together (a slot past the count holds stale
-    // but in-bounds data and is never applied); lane r keeps record r and hands it out by readlane
-    const int cnt = pb < nblk ? rec.count[pb] : 0;
-    for (int c0 = 0; c0 < rec.cap; c0 += TD_WAVE) {
-        const int mine = min(c0 + lane, rec.cap - 1);
-        const uint32_t myj = jb[mine];
-        float myd[TB];
+    for (int t = 0; t < TB; ++t) {
 #pragma unroll
-        for (int t = 0; t < TB; ++t) myd[t] = dl[(size_t)mine * TB + t];
-        const int here = min(cnt - c0, TD_WAVE);     // records of this batch of 64 (<= 0: none)
-        if (here <= 0) break;
-        for (int r0 = 0; r0 < here; r0 += U) {
-            uint2 w[U];
+        for (int q = 0; q < CPL; ++q) acc[t * SL + q] = 0.0f;
+    }
+    const bf16_t* base = W2T + (size_t)slice * SL + lane * CPL;
+    // a wavefront takes `pbw` predictor blocks in turn
+    for (int pi = 0; pi < pbw; ++pi) {
+        const int pb = __builtin_amdgcn_readfirstlane((group * NW + wave) * pbw + pi);
+        if (pb >= nblk) break;
+        const uint32_t* jb = rec.jb + (size_t)pb * rec.cap;
+        const uint32_t* tbp = rec.tb + (size_t)pb * rec.cap;
+        const float* dl = rec.delta + (size_t)pb * rec.cap * TB;
+        // the count and the first 64 records are requested together (a slot past the count holds stale
+        // but in-bounds data and is never applied); lane r keeps record r and hands it out by readlane
+        const int cnt = rec.count[pb];
+        for (int c0 = 0; c0 < rec.cap; c0 += TD_WAVE) {
+            const int mine = min(c0 + lane, rec.cap - 1);
+            const uint32_t myj = jb[mine];
+            const uint32_t myb = tbp[mine];
+            float myd[TB];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {   // slots past the end re-read the last record; they are not applied
-                const uint32_t j = __builtin_amdgcn_readlane(myj, min(r0 + u, here - 1)) & 0xFFFFFFu;
-                const unsigned long long* p = reinterpret_cast<const unsigned long long*>(base + (size_t)j * D);
-                const unsigned long long v = __builtin_nontemporal_load(p);
-                w[u] = make_uint2((uint32_t)v, (uint32_t)(v >> 32));
-            }
+            for (int t = 0; t < TB; ++t) myd[t] = dl[(size_t)mine * TB + t];
+            const int here = min(cnt - c0, TD_WAVE);     // records of this batch of 64 (<= 0: none)
+            if (here <= 0) break;
+            for (int r0 = 0; r0 < here; r0 += U) {
+                uint32_t w[U][CPL / 2];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (r0 + u < here) {
-                    const int r = r0 + u;
-                    const uint32_t bits = __builtin_amdgcn_readlane(myj, r) >> 24;
-                    const f32x4 wf = {__uint_as_float(w[u].x << 16), __uint_as_float(w[u].x & 0xFFFF0000u),
-                                      __uint_as_float(w[u].y << 16), __uint_as_float(w[u].y & 0xFFFF0000u)};
+                for (int u = 0; u < U; ++u) {   // slots past the end re-read the last record; they are not applied
+                    const uint32_t j = __builtin_amdgcn_readlane(myj, min(r0 + u, here - 1));
+                    if constexpr (CPL == 4) {
+                        const unsigned long long v = __builtin_nontemporal_load(
+                            reinterpret_cast<const unsigned long long*>(base + (size_t)j * D));
+                        w[u][0] = (uint32_t)v;
+                        w[u][1] = (uint32_t)(v >> 32);
+                    } else {
+                        w[u][0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(base + (size_t)j * D));
+                    }
+                }
 #pragma unroll
-                    for (int t = 0; t < TB; ++t) {
-                        if ((bits >> t) & 1u) {
-                            const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, myd[t]), r));
-                            f32x4* a4 = reinterpret_cast<f32x4*>(acc + t * SL);
-                            *a4 = *a4 + wf * d;
+                for (int u = 0; u < U; ++u) {
+                    if (r0 + u < here) {
+                        const int r = r0 + u;
+                        const uint32_t bits = __builtin_amdgcn_readlane(myb, r);
+                        f32xc wf;
+#pragma unroll
+                        for (int q = 0; q < CPL / 2; ++q) {
+                            wf[2 * q] = __uint_as_float(w[u][q] << 16);
+                            wf[2 * q + 1] = __uint_as_float(w[u][q] & 0xFFFF0000u);
+                        }
+                        if constexpr (TB <= 8) {
+#pragma unroll
+                            for (int t = 0; t < TB; ++t) {
+                                if ((bits >> t) & 1u) {
+                                    const float d = __builtin_bit_cast(
+                                        float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, myd[t]), r));
+                                    f32xc* a4 = reinterpret_cast<f32xc*>(acc + t * SL);
+                                    *a4 = *a4 + wf * d;
+                                }
+                            }
+                        } else {   // many tokens, one or two of them set: walk the set bits (all scalar)
+                            uint32_t left = bits;
+                            while (left) {
+                                const int t = __builtin_ctz(left);
+                                left &= left - 1;
+                                const float d = __builtin_bit_cast(
+                                    float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, myd[t]), r));
+                                f32xc* a4 = reinterpret_cast<f32xc*>(acc + t * SL);
+                                *a4 = *a4 + wf * d;
+                            }
                         }
                     }
                 }
@@ -862,9 +933,11 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
     const int rpb = (D + G - 1) / G;
     const int8_t* codes = SK == 8 ? L->Q : reinterpret_cast<const int8_t*>(L->Q4);
     const bool static_tokens = !DEFER && (size_t)TB * D * 3 <= 56 * 1024;    // as in the kernel
-    const size_t lds = static_tokens ? 0 : (size_t)TB * (DEFER ? D + 8 : D) * 2 + (size_t)TB * (NG > 0 ? D + 16 : D);
+    const size_t lds = static_tokens ? 0
+                       : TB == 16    ? (size_t)TB * (D + 8) * 2      // the int8 codes share the tokens' place
+                                     : (size_t)TB * (DEFER ? D + 8 : D) * 2 + (size_t)TB * (NG > 0 ? D + 16 : D);
     auto kernel = decode_fused_kernel<D, BLOCK, RQ, TB, SK, DEFER, NG>;
-    const DeferOut rec{L->rec_count, L->rec_jb, L->rec_delta, npb};
+    const DeferOut rec{L->rec_count, L->rec_jb, L->rec_tb, L->rec_delta, npb};
     hipLaunchKernelGGL(kernel, dim3(G), dim3(BLOCK), lds, s,
                        static_cast<const bf16_t*>(L->Wp), L->bp, codes, L->M4, L->tlo, L->thi,
                        static_cast<const bf16_t*>(L->W1),
@@ -874,11 +947,14 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
                        rec);
     TD_HIP(hipGetLastError());
     if (DEFER) {
-        constexpr size_t lds2 = (size_t)16 * TB * 256 * sizeof(float);
-        auto k2 = down_project_kernel<TB>;
-        const int nslices = D / 256, ngroups = (G + 15) / 16;
+        constexpr int SL = TB >= 16 ? 128 : 256;     // slice width: 16 wavefronts x TB x SL floats of LDS
+        constexpr size_t lds2 = (size_t)16 * TB * SL * sizeof(float);
+        auto k2 = down_project_kernel<TB, SL>;
+        const int nslices = D / SL;
+        const int ngroups = nslices >= 256 ? 1 : 256 / nslices;          // about one block per CU
+        const int pbw = (G + 16 * ngroups - 1) / (16 * ngroups);         // predictor blocks per wavefront
         hipLaunchKernelGGL(k2, dim3(nslices * ngroups), dim3(1024), lds2, s, static_cast<const bf16_t*>(L->W2T), rec,
-                           G, yfold, L->yfix, static_cast<bf16_t*>(y), L->sync, D, nslices, norm_out, kRmsEps);
+                           G, pbw, yfold, L->yfix, static_cast<bf16_t*>(y), L->sync, D, nslices, norm_out, kRmsEps);
         TD_HIP(hipGetLastError());
     }
     return TARDIS_OK;
@@ -890,6 +966,17 @@ tardis_status_t launch_tb(tardis_layer_s* L, const void* x, void* y, float* yfol
     // two kernels: records, then the column-sliced pass (the block's W' rows must fit one 16-row tile)
     if (BLOCK == 1024 && L->defer_min_tokens <= tokens && (D + L->dec_blocks - 1) / L->dec_blocks <= 16) {
         if (tokens == 4) return launch_decode<D, 1024, 4, SK, true>(L, x, y, yfold, mask, norm_out, s);
+        if (tokens == 16) {
+            const int npb = (((int)L->h + L->dec_blocks - 1) / L->dec_blocks + 31) / 32 * 32;
+            if constexpr (SK == 8) {
+                if (npb == 64 && D >= 1024) return launch_decode<D, 1024, 16, 8, true, 4>(L, x, y, yfold, mask, norm_out, s);
+                if (npb == 32 && D >= 1024) return launch_decode<D, 1024, 16, 8, true, 2>(L, x, y, yfold, mask, norm_out, s);
+            }
+            TD_TRY((launch_tb<D, BLOCK, SK>(L, x, y, yfold, mask, 8, norm_out, s)));
+            return launch_tb<D, BLOCK, SK>(L, static_cast<const bf16_t*>(x) + 8 * (size_t)D,
+                                           static_cast<bf16_t*>(y) + 8 * (size_t)D, yfold + 8 * (size_t)D,
+                                           mask + 8 * L->mask_words, 8, norm_out, s);
+        }
         if (tokens == 8) {
             // eight tokens need one-byte codes and 32 or 64 neurons per block (the matrix-core tiling);
             // otherwise two groups of four
@@ -926,8 +1013,13 @@ tardis_status_t td_decode_init() {
     if (done) return TARDIS_OK;
     TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 4>, (size_t)8 * 4096 * 3 + 256));
     TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 2>, (size_t)8 * 4096 * 3 + 256));
-    TD_HIP(allow_lds(down_project_kernel<4>, (size_t)16 * 4 * 256 * sizeof(float)));
-    TD_HIP(allow_lds(down_project_kernel<8>, (size_t)16 * 8 * 256 * sizeof(float)));
+    TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 4>, (size_t)16 * (4096 + 8) * 2));
+    TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 2>, (size_t)16 * (4096 + 8) * 2));
+    TD_HIP(allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 4>, (size_t)16 * (2048 + 8) * 2));
+    TD_HIP(allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 2>, (size_t)16 * (2048 + 8) * 2));
+    TD_HIP(allow_lds((down_project_kernel<4, 256>), (size_t)16 * 4 * 256 * sizeof(float)));
+    TD_HIP(allow_lds((down_project_kernel<8, 256>), (size_t)16 * 8 * 256 * sizeof(float)));
+    TD_HIP(allow_lds((down_project_kernel<16, 128>), (size_t)16 * 16 * 128 * sizeof(float)));
     done = true;
     return TARDIS_OK;
 }

@@ -231,11 +231,12 @@ tardis_status_t forward_t(tardis_layer_s* L, const void* xv, int64_t n, void* yv
     const int fix_blocks = 256;
     // a handful of tokens is faster through the single-token kernel (one launch each)
     if (n > L->batched_min_tokens && L->use_batched) return td_forward_batched(L, xv, n, yv, norm_out, s);
-    if (L->use_fused) {   // groups of 4, 2, 1 tokens share one pass over the weights
+    if (L->use_fused) {   // groups of 16, 8, 4, 2, 1 tokens share one pass over the weights
+        const bool wide = L->dec_threads == 1024 && L->defer_min_tokens <= 8 &&
+                          (d + L->dec_blocks - 1) / L->dec_blocks <= 16;   // the two-kernel groups of 8 and 16
         for (int64_t t = 0; t < n;) {
-            const int g = (n - t >= 8 && L->dec_threads == 1024 && L->defer_min_tokens <= 8 &&
-                           (d + L->dec_blocks - 1) / L->dec_blocks <= 16) ? 8
-                          : (n - t >= 4) ? 4 : (n - t >= 2) ? 2 : 1;
+            const int64_t left = n - t;
+            const int g = (left >= 16 && wide) ? 16 : (left >= 8 && wide) ? 8 : left >= 4 ? 4 : left >= 2 ? 2 : 1;
             TD_TRY(td_decode_fused(L, static_cast<const T*>(xv) + t * d, static_cast<T*>(yv) + t * d,
                                    L->yacc + t * d, L->mask + t * L->mask_words, g, norm_out, s));
             t += g;
