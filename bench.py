@@ -29,7 +29,7 @@ TOKENS_PER_STEP = 1024
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of decode_fused_kernel from `rocprofv3 --pmc` (FETCH_SIZE and WRITE_SIZE runs,
 # scaled by a copy kernel of known size); see profiles/*hbm-traffic.md.
-MEASURED_TRAFFIC_BYTES = {8: 119086884, 4: 88680345}     # by sketch width
+MEASURED_TRAFFIC_BYTES = {8: 119074161, 4: 88663441}     # by sketch width
 
 
 def algorithmic_bytes(d: int, h: int, p: float, sketch_bits: int = 8) -> float:
