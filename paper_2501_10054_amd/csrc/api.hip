@@ -82,8 +82,9 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     TD_TRY(dev_alloc(&L->thi, (size_t)h * 4));
     TD_TRY(dev_alloc(&L->a, (size_t)h * 4));
     TD_TRY(dev_alloc(&L->c, (size_t)h * 4));
-    TD_TRY(dev_alloc(&L->yacc, nb * d * 4));
-    TD_TRY(dev_alloc(&L->mask, nb * L->mask_words * 4));
+    // (16 rows of slack: a partially filled group of tokens writes its empty slots there)
+    TD_TRY(dev_alloc(&L->yacc, (nb + kDecodeMaxTokens) * d * 4));
+    TD_TRY(dev_alloc(&L->mask, (nb + kDecodeMaxTokens) * L->mask_words * 4));
     TD_TRY(dev_alloc(&L->counts, nb * 4));
     TD_TRY(dev_alloc(&L->list, nb * h * 4));
     TD_TRY(dev_alloc(reinterpret_cast<char**>(&L->hidden), nb * h * es));

@@ -72,7 +72,9 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                     const float* __restrict__ c, const bf16_t* __restrict__ x, bf16_t* __restrict__ y,
                     float* __restrict__ yfold, float* __restrict__ yfix, int copies, uint32_t* __restrict__ mask,
                     int mask_words, int32_t* __restrict__ done, int h, int npb, int rpb, int act, int norm_out,
-                    float eps, DeferOut rec) {
+                    float eps, DeferOut rec, int n_act) {
+    // n_act <= TB tokens are real: the remaining slots of the group repeat the last real token and
+    // none of their results reaches the caller's buffers
     static_assert(D % 1024 == 0, "rows must be whole multiples of 64 lanes x 16 bytes");
     static_assert(D % BLOCK == 0 && BLOCK / TD_WAVE >= 4, "column ownership of the repair pass");
     static_assert(TB == 1 || TB == 2 || TB == 4 || ((TB == 8 || TB == 16) && DEFER), "tokens per pass");
@@ -132,7 +134,8 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
 #pragma unroll
     for (int it = 0; it < XI; ++it) {
         const int v = min(it * BLOCK + tid, TB * NVW - 1);
-        xv[it] = reinterpret_cast<const td_u32x4*>(x)[v];
+        const int tok = v / NVW;
+        xv[it] = reinterpret_cast<const td_u32x4*>(x)[min(tok, n_act - 1) * NVW + (v - tok * NVW)];
     }
     asm volatile("" ::: "memory");                   // keep the tokens' loads ahead of the row loads
     td_u32x4 q[RQ][IQ];
@@ -253,7 +256,8 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
 #pragma unroll
             for (int it = 0; it < XI; ++it) {
                 const int v = min(it * BLOCK + tid, TB * NVW - 1);
-                xv[it] = reinterpret_cast<const td_u32x4*>(x)[v];
+                const int tok = v / NVW;
+                xv[it] = reinterpret_cast<const td_u32x4*>(x)[min(tok, n_act - 1) * NVW + (v - tok * NVW)];
             }
         }
     }
@@ -396,7 +400,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
         const int nw = (jn + 31) / 32;
         for (int k = tid; k < TB * nw; k += BLOCK) {
             const int t = k / nw, w = k % nw;
-            mask[(size_t)t * mask_words + (j0 >> 5) + w] = words[t][w];
+            if (t < n_act) mask[(size_t)t * mask_words + (j0 >> 5) + w] = words[t][w];
         }
     }
     const int nf = nflag;
@@ -488,7 +492,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                 float s = bias_own;
 #pragma unroll
                 for (int w = 0; w < NW; ++w) s += wpart[w][row][t];
-                yfold[(size_t)t * D + r0 + row] = s;
+                if (t < n_act) yfold[(size_t)t * D + r0 + row] = s;
             }
         }
         return;
@@ -695,7 +699,7 @@ template <int TB, int SL>
 __global__ void __launch_bounds__(1024)
 down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int pbw, const float* __restrict__ yfold,
                     float* __restrict__ yfix, bf16_t* __restrict__ y, int32_t* __restrict__ done, int D, int nslices,
-                    int norm_out, float eps) {
+                    int norm_out, float eps, int n_act) {
     constexpr int NW = 16, U = SL == 128 ? 48 : 16;  // wavefronts; rows in flight per wavefront (4- or 8-byte loads)
     constexpr int CPL = SL / TD_WAVE;                // columns per lane: 4 (8-byte loads) or 2 (4-byte loads)
     static_assert(CPL == 4 || CPL == 2, "slice width");
@@ -809,8 +813,10 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
         for (int k = tid; k < TB * (SL / 4); k += 1024) {
             const int t = k / (SL / 4), c4 = k % (SL / 4);
             const size_t at = (size_t)t * D + slice * SL + c4 * 4;
-            const f32x4 o4 = *reinterpret_cast<const f32x4*>(yfold + at) + *reinterpret_cast<const f32x4*>(yfix + at);
+            const f32x4 fix4 = *reinterpret_cast<const f32x4*>(yfix + at);
             *reinterpret_cast<f32x4*>(yfix + at) = zero4;
+            if (t >= n_act) continue;                // a slot that repeats the last real token
+            const f32x4 o4 = *reinterpret_cast<const f32x4*>(yfold + at) + fix4;
             uint2 o;
             o.x = (uint32_t)td_f32_to_bf16(o4.x) | ((uint32_t)td_f32_to_bf16(o4.y) << 16);
             o.y = (uint32_t)td_f32_to_bf16(o4.z) | ((uint32_t)td_f32_to_bf16(o4.w) << 16);
@@ -835,7 +841,8 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
             f32x4 v[TH];
 #pragma unroll
             for (int t = 0; t < TH; ++t) {
-                const f32x4 f = live ? reinterpret_cast<const f32x4*>(yfold + (size_t)(t0 + t) * D)[k4] : zero4;
+                const f32x4 f = (live && t0 + t < n_act) ? reinterpret_cast<const f32x4*>(yfold + (size_t)(t0 + t) * D)[k4]
+                                                         : zero4;
                 const f32x4 g = live ? reinterpret_cast<const f32x4*>(yfix + (size_t)(t0 + t) * D)[k4] : zero4;
                 v[t] = f + g;
             }
@@ -866,6 +873,7 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
             if (live) {
 #pragma unroll
                 for (int t = 0; t < TH; ++t) {
+                    if (t0 + t >= n_act) continue;   // a slot that repeats the last real token
                     const f32x4 o4 = v[t] * scale[t];
                     uint2 o;
                     o.x = (uint32_t)td_f32_to_bf16(o4.x) | ((uint32_t)td_f32_to_bf16(o4.y) << 16);
@@ -924,8 +932,9 @@ mask_to_list_kernel(const uint32_t* __restrict__ mask, int words, int h, int32_t
 
 template <int D, int BLOCK, int TB, int SK, bool DEFER, int NG = 0>
 tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
-                              int norm_out, hipStream_t s) {
+                              int n_act, int norm_out, hipStream_t s) {
     constexpr int RQ = 4;
+    if (n_act < 1 || n_act > TB || (!DEFER && n_act != TB)) return TARDIS_ERR_INVALID_ARG;
     const int G = L->dec_blocks;
     const int h = (int)L->h;
     int npb = (h + G - 1) / G;
@@ -944,7 +953,7 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
                        static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), static_cast<const bf16_t*>(L->W2T),
                        L->a, L->c, static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), yfold, L->yfix,
                        L->dec_copies, mask, (int)L->mask_words, L->sync, h, npb, rpb, (int)L->act, norm_out, kRmsEps,
-                       rec);
+                       rec, n_act);
     TD_HIP(hipGetLastError());
     if (DEFER) {
         constexpr int SL = TB >= 16 ? 128 : 256;     // slice width: 16 wavefronts x TB x SL floats of LDS
@@ -954,47 +963,47 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
         const int ngroups = nslices >= 256 ? 1 : 256 / nslices;          // about one block per CU
         const int pbw = (G + 16 * ngroups - 1) / (16 * ngroups);         // predictor blocks per wavefront
         hipLaunchKernelGGL(k2, dim3(nslices * ngroups), dim3(1024), lds2, s, static_cast<const bf16_t*>(L->W2T), rec,
-                           G, pbw, yfold, L->yfix, static_cast<bf16_t*>(y), L->sync, D, nslices, norm_out, kRmsEps);
+                           G, pbw, yfold, L->yfix, static_cast<bf16_t*>(y), L->sync, D, nslices, norm_out, kRmsEps, n_act);
         TD_HIP(hipGetLastError());
     }
     return TARDIS_OK;
 }
 
+// `tokens` = group size (1, 2, 4, 8, 16), `n_act` of them real (fewer only on the two-kernel path)
 template <int D, int BLOCK, int SK>
 tardis_status_t launch_tb(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask, int tokens,
-                          int norm_out, hipStream_t s) {
+                          int n_act, int norm_out, hipStream_t s) {
+    const bf16_t* xb = static_cast<const bf16_t*>(x);
+    bf16_t* yb = static_cast<bf16_t*>(y);
     // two kernels: records, then the column-sliced pass (the block's W' rows must fit one 16-row tile)
     if (BLOCK == 1024 && L->defer_min_tokens <= tokens && (D + L->dec_blocks - 1) / L->dec_blocks <= 16) {
-        if (tokens == 4) return launch_decode<D, 1024, 4, SK, true>(L, x, y, yfold, mask, norm_out, s);
-        if (tokens == 16) {
-            const int npb = (((int)L->h + L->dec_blocks - 1) / L->dec_blocks + 31) / 32 * 32;
+        if (tokens == 4) return launch_decode<D, 1024, 4, SK, true>(L, x, y, yfold, mask, n_act, norm_out, s);
+        // eight and sixteen tokens need one-byte codes and 32 or 64 neurons per block (the matrix-core
+        // tiling); otherwise they run as two groups of half the size
+        const int npb = (((int)L->h + L->dec_blocks - 1) / L->dec_blocks + 31) / 32 * 32;
+        if (tokens == 16 || tokens == 8) {
             if constexpr (SK == 8) {
-                if (npb == 64 && D >= 1024) return launch_decode<D, 1024, 16, 8, true, 4>(L, x, y, yfold, mask, norm_out, s);
-                if (npb == 32 && D >= 1024) return launch_decode<D, 1024, 16, 8, true, 2>(L, x, y, yfold, mask, norm_out, s);
+                if (npb == 64 && tokens == 16)
+                    return launch_decode<D, 1024, 16, 8, true, 4>(L, x, y, yfold, mask, n_act, norm_out, s);
+                if (npb == 32 && tokens == 16)
+                    return launch_decode<D, 1024, 16, 8, true, 2>(L, x, y, yfold, mask, n_act, norm_out, s);
+                if (npb == 64 && tokens == 8)
+                    return launch_decode<D, 1024, 8, 8, true, 4>(L, x, y, yfold, mask, n_act, norm_out, s);
+                if (npb == 32 && tokens == 8)
+                    return launch_decode<D, 1024, 8, 8, true, 2>(L, x, y, yfold, mask, n_act, norm_out, s);
             }
-            TD_TRY((launch_tb<D, BLOCK, SK>(L, x, y, yfold, mask, 8, norm_out, s)));
-            return launch_tb<D, BLOCK, SK>(L, static_cast<const bf16_t*>(x) + 8 * (size_t)D,
-                                           static_cast<bf16_t*>(y) + 8 * (size_t)D, yfold + 8 * (size_t)D,
-                                           mask + 8 * L->mask_words, 8, norm_out, s);
-        }
-        if (tokens == 8) {
-            // eight tokens need one-byte codes and 32 or 64 neurons per block (the matrix-core tiling);
-            // otherwise two groups of four
-            const int npb = (((int)L->h + L->dec_blocks - 1) / L->dec_blocks + 31) / 32 * 32;
-            if constexpr (SK == 8) {
-                if (npb == 64 && D >= 1024) return launch_decode<D, 1024, 8, 8, true, 4>(L, x, y, yfold, mask, norm_out, s);
-                if (npb == 32 && D >= 1024) return launch_decode<D, 1024, 8, 8, true, 2>(L, x, y, yfold, mask, norm_out, s);
-            }
-            TD_TRY((launch_decode<D, 1024, 4, SK, true>(L, x, y, yfold, mask, norm_out, s)));
-            return launch_decode<D, 1024, 4, SK, true>(L, static_cast<const bf16_t*>(x) + 4 * (size_t)D,
-                                                       static_cast<bf16_t*>(y) + 4 * (size_t)D, yfold + 4 * (size_t)D,
-                                                       mask + 4 * L->mask_words, norm_out, s);
+            const int half = tokens / 2;
+            TD_TRY((launch_tb<D, BLOCK, SK>(L, x, y, yfold, mask, half, n_act < half ? n_act : half, norm_out, s)));
+            if (n_act <= half) return TARDIS_OK;
+            return launch_tb<D, BLOCK, SK>(L, xb + half * (size_t)D, yb + half * (size_t)D, yfold + half * (size_t)D,
+                                           mask + half * L->mask_words, half, n_act - half, norm_out, s);
         }
     }
+    if (n_act != tokens) return TARDIS_ERR_INVALID_ARG;      // the one-kernel form has no empty slots
     switch (tokens) {
-        case 1: return launch_decode<D, BLOCK, 1, SK, false>(L, x, y, yfold, mask, norm_out, s);
-        case 2: return launch_decode<D, BLOCK, 2, SK, false>(L, x, y, yfold, mask, norm_out, s);
-        case 4: return launch_decode<D, BLOCK, 4, SK, false>(L, x, y, yfold, mask, norm_out, s);
+        case 1: return launch_decode<D, BLOCK, 1, SK, false>(L, x, y, yfold, mask, 1, norm_out, s);
+        case 2: return launch_decode<D, BLOCK, 2, SK, false>(L, x, y, yfold, mask, 2, norm_out, s);
+        case 4: return launch_decode<D, BLOCK, 4, SK, false>(L, x, y, yfold, mask, 4, norm_out, s);
     }
     return TARDIS_ERR_INVALID_ARG;
 }
@@ -1036,28 +1045,28 @@ bool td_decode_fused_supported(const tardis_layer_s* L) {
 
 // `tokens` (1, 2, 4, or 8 on the two-kernel path) consecutive tokens
 tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
-                                int tokens, int norm_out, hipStream_t s) {
+                                int tokens, int n_act, int norm_out, hipStream_t s) {
     if (L->Q4) {   // packed 4-bit sketch (d = 2048 or 4096 only)
         if (L->dec_threads == 512) {
-            if (L->d == 2048) return launch_tb<2048, 512, 4>(L, x, y, yfold, mask, tokens, norm_out, s);
-            if (L->d == 4096) return launch_tb<4096, 512, 4>(L, x, y, yfold, mask, tokens, norm_out, s);
+            if (L->d == 2048) return launch_tb<2048, 512, 4>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
+            if (L->d == 4096) return launch_tb<4096, 512, 4>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
         } else {
-            if (L->d == 2048) return launch_tb<2048, 1024, 4>(L, x, y, yfold, mask, tokens, norm_out, s);
-            if (L->d == 4096) return launch_tb<4096, 1024, 4>(L, x, y, yfold, mask, tokens, norm_out, s);
+            if (L->d == 2048) return launch_tb<2048, 1024, 4>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
+            if (L->d == 4096) return launch_tb<4096, 1024, 4>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
         }
         return TARDIS_ERR_SHAPE;
     }
     if (L->dec_threads == 512) {
         switch (L->d) {
-            case 1024: return launch_tb<1024, 512, 8>(L, x, y, yfold, mask, tokens, norm_out, s);
-            case 2048: return launch_tb<2048, 512, 8>(L, x, y, yfold, mask, tokens, norm_out, s);
-            case 4096: return launch_tb<4096, 512, 8>(L, x, y, yfold, mask, tokens, norm_out, s);
+            case 1024: return launch_tb<1024, 512, 8>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
+            case 2048: return launch_tb<2048, 512, 8>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
+            case 4096: return launch_tb<4096, 512, 8>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
         }
     }
     switch (L->d) {
-        case 1024: return launch_tb<1024, 1024, 8>(L, x, y, yfold, mask, tokens, norm_out, s);
-        case 2048: return launch_tb<2048, 1024, 8>(L, x, y, yfold, mask, tokens, norm_out, s);
-        case 4096: return launch_tb<4096, 1024, 8>(L, x, y, yfold, mask, tokens, norm_out, s);
+        case 1024: return launch_tb<1024, 1024, 8>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
+        case 2048: return launch_tb<2048, 1024, 8>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
+        case 4096: return launch_tb<4096, 1024, 8>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
     }
     return TARDIS_ERR_SHAPE;
 }

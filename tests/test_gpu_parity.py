@@ -176,11 +176,11 @@ def test_mid_bf16_batched_high_fallback():
     assert 0.08 < r["rate"] < 0.25
 
 
-@pytest.mark.parametrize("n,coverage", [(2, 0.95), (3, 0.95), (4, 0.9), (7, 0.85), (8, 0.95), (9, 0.95), (16, 0.9), (17, 0.9),
+@pytest.mark.parametrize("n,coverage", [(2, 0.95), (3, 0.95), (4, 0.9), (7, 0.85), (5, 0.9), (6, 0.95), (8, 0.95), (9, 0.95), (11, 0.9), (15, 0.95), (16, 0.9), (17, 0.9),
                                         (20, 0.95), (48, 0.85), (64, 0.95), (70, 0.99), (150, 0.95)])
 def test_batched_passes_of_64_tokens(n, coverage):
     """Up to 16 tokens: groups of 16, 8, 4 (two kernels: records, then the column-sliced down
-    projection), 2 and 1 tokens (one kernel).  More: one weight stream per pass of up to 64 tokens, every tile
+    projection; 3, 5-7 and 9-15 tokens run as partly empty groups), 2 and 1 tokens (one kernel).  More: one weight stream per pass of up to 64 tokens, every tile
     count (1, 2, 4 token tiles), the masked-dense scatter, a ragged last pass."""
     w = synth.decode(d=1024, h=4096, n_cal=512, n_test=n, coverage=coverage, config=2)
     run_case(w.layer, w.X_cal, w.X_test, coverage, batched=True, check_calibrate=False)
@@ -456,7 +456,8 @@ def test_repeated_calls_are_stable():
 
 # ------------------------------------------------------------- stacked layers
 @pytest.mark.parametrize("d,h,dtype,n", [(1024, 4096, "bf16", 1), (1024, 4096, "bf16", 3), (64, 256, "f32", 2),
-                                         (1024, 4096, "bf16", 12), (2048, 2048, "bf16", 8), (2048, 2048, "bf16", 16)])
+                                         (1024, 4096, "bf16", 12), (2048, 2048, "bf16", 8), (2048, 2048, "bf16", 16),
+                                         (2048, 2048, "bf16", 6)])
 def test_stack_teacher_forced(d, h, dtype, n):
     """Every layer is checked on the input the GPU itself handed to it: mask bit-exact, the
     normalised hand-over and the final output within the y tolerance."""
@@ -595,7 +596,7 @@ def test_full_size_batched_matches_per_token(decode_full):
         assert rel_l2(host(y), host(Yb[t])) <= 2e-3            # bf16 output, atomic ordering
 
 
-@pytest.mark.parametrize("B", [2, 4, 7, 8, 16, 64])
+@pytest.mark.parametrize("B", [2, 3, 4, 7, 8, 13, 16, 64])
 def test_full_size_batched_decode_sampled_tokens(decode_full, B):
     """Batched decode at the full layer size, in the configuration the sweep times: the checker
     recomputes a sample of the batch's tokens one by one."""
