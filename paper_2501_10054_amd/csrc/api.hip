@@ -51,7 +51,7 @@ int env_int(const char* name, int fallback, int lo, int hi) {
 void free_layer(tardis_layer_s* L) {
     if (!L) return;
     void* owned[] = {L->W2T, L->W2, L->Wp, L->bp, L->Q, L->Q4, L->M4, L->tlo, L->thi, L->a, L->c,
-                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix, L->zeros_h, L->xnext, L->rec_count, L->rec_jb, L->rec_tb, L->rec_delta,
+                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix, L->zeros_h, L->xnext, L->rec_count, L->rec_jb, L->rec_tb, L->rec_delta, L->pf_scratch,
                      L->bt_xq, L->bt_e, L->bt_tokmask, L->bt_ulist, L->bt_ucount, L->bt_delta, L->bt_partial};
     for (void* p : owned)
         if (p) (void)hipFree(p);
@@ -118,6 +118,12 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     if (byte_codes) TD_TRY(dev_alloc(&L->Q, (size_t)h * d));
     if (packed4) TD_TRY(dev_alloc(&L->Q4, (size_t)h * d / 2));
     if (L->sketch_bits == 4) TD_TRY(dev_alloc(&L->M4, (size_t)h * ((d + 31) / 32)));
+    L->prefill_min_tokens = env_int("TARDIS_PREFILL_MIN", 256, 128, 1 << 20);
+    if (L->max_batch >= L->prefill_min_tokens && td_prefill_supported(L)) {
+        char* scratch = nullptr;
+        TD_TRY(dev_alloc(&scratch, td_prefill_scratch_bytes(L, L->max_batch)));
+        L->pf_scratch = scratch;
+    }
     if (L->use_batched) {
         TD_TRY(td_batched_init());
         TD_TRY(dev_alloc(&L->bt_xq, (size_t)64 * d));

@@ -73,6 +73,8 @@ struct tardis_layer_s {
     bf16_t* bt_delta;              // 64 x h repair factors
     float* bt_partial;             // partial products of the scatter step
     int32_t use_batched;
+    void* pf_scratch;              // prompt path: int8 tokens, exponents, int32 sums, pre-activations, delta, fp32 y
+    int32_t prefill_min_tokens;    // calls with at least this many tokens take the prompt path (if it has scratch)
     int32_t* rec_count;            // two-kernel path: flagged neurons per predictor block,
     uint32_t* rec_jb;              //   neuron index and
     uint32_t* rec_tb;              //   token bits of each record (dec_blocks x neurons per block),
@@ -181,7 +183,16 @@ tardis_status_t td_calibrate(const tardis_ffn_desc* desc, const void* X, int64_t
 // gemm.hip:  C[m][n] = sum_k A[m][k] * B[n][k]  (+ C if accumulate) (+ row_bias[m]); C fp32, ldc = N
 tardis_status_t td_gemm_nt(const void* A, const void* B, float* C, int64_t M, int64_t N, int64_t K,
                            int32_t dtype, int accumulate, const void* row_bias, hipStream_t s);
+// exact int8 x int8 -> int32 product of the same form (K a multiple of 16, operands 16-byte aligned)
+tardis_status_t td_gemm_nt_i8(const int8_t* A, const int8_t* B, int32_t* C, int64_t M, int64_t N, int64_t K,
+                              hipStream_t s);
 // decode.hip
+bool td_prefill_supported(const tardis_layer_s* L);
+size_t td_prefill_scratch_bytes(const tardis_layer_s* L, int64_t n);
+tardis_status_t td_forward_prefill(tardis_layer_s* L, const void* x, int64_t n, void* y, int norm_out, hipStream_t s);
+tardis_status_t td_gemm_init();
+tardis_status_t td_gemm_nt_split(const void* A, const void* B, float* C, int64_t M, int64_t N, int64_t K, int32_t dtype,
+                                 int accumulate, const void* row_bias, int splits, hipStream_t s);
 tardis_status_t td_decode_init();
 bool td_decode_fused_supported(const tardis_layer_s* L);
 constexpr int kDecodeMaxTokens = 16;  // tokens one weight pass of the decode kernel can be shared between

@@ -230,6 +230,7 @@ tardis_status_t forward_t(tardis_layer_s* L, const void* xv, int64_t n, void* yv
     const int pred_blocks = div_up(h, 32);
     const int fix_blocks = 256;
     // a handful of tokens is faster through the single-token kernel (one launch each)
+    if (L->pf_scratch && n >= L->prefill_min_tokens) return td_forward_prefill(L, xv, n, yv, norm_out, s);
     if (n > L->batched_min_tokens && L->use_batched) return td_forward_batched(L, xv, n, yv, norm_out, s);
     if (L->use_fused) {   // groups of 16, 8, 4, 2, 1 tokens share one pass over the weights
         const bool two4 = L->dec_threads == 1024 && L->defer_min_tokens <= 4 &&

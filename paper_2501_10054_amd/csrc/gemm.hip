@@ -5,6 +5,7 @@
 // calibration pre-activations Z^T = W1 . X_cal^T (Sec. "Non-linear Function
 // Approximation", step 2) with A = W1 (h x d) and B = X_cal (n x d).
 #include <cstdlib>
+#include <type_traits>
 
 #include "common.h"
 
@@ -76,103 +77,175 @@ gemm_nt_generic_kernel(const T* __restrict__ A, const T* __restrict__ B, float* 
 // 256x256 output tile per block of 4 wavefronts (2x2, 128x128 each = 4x4 MFMA
 // 32x32x16 tiles, 256 fp32 accumulators per lane), K in slices of 64 staged
 // through double-buffered LDS (rows padded to 144 bytes), next slice prefetched
-// global -> registers while the current one feeds the matrix cores.  Blocks are
-// numbered so that each XCD (blocks b, b+8, b+16, ...) works on a contiguous band
-// of tile rows and re-uses its slice of A from its own L2.
+// global -> registers while the current one feeds the matrix cores.
+// The int8 form (exact int32 sums, the predictor of many tokens at once) has the same byte
+// geometry - 16 bytes per lane and step are 8 bf16 or 16 int8 - so it is the same kernel with
+// v_mfma_i32_32x32x32_i8, K slices of 128 elements and an int32 result.
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+typedef int i32x16_t __attribute__((ext_vector_type(16)));
 
-constexpr int MT = 256, MK = 64;
-constexpr int MSTRIDE = MK * 2 + 16;                 // bytes per staged row
+constexpr int MT = 256;
+constexpr int MKB = 128;                             // bytes of one staged row slice
+constexpr int MSTRIDE = MKB + 16;                    // bytes per staged row (padded)
 constexpr int MSTAGE = 2 * MT * MSTRIDE;             // A tile + B tile
 constexpr int MLDS = 2 * MSTAGE;
 
-__device__ __forceinline__ td_u32x4 load_chunk(const bf16_t* base, int64_t row, int64_t rows, int64_t k,
-                                               int64_t K) {
-    if (row < rows && k + 8 <= K) return *reinterpret_cast<const td_u32x4*>(base + row * K + k);
-    td_u32x4 z = {0, 0, 0, 0};
-    if (row < rows && k < K) {                       // ragged K tail: element by element
-        bf16_t* e = reinterpret_cast<bf16_t*>(&z);
-        for (int u = 0; u < 8 && k + u < K; ++u) e[u] = base[row * K + k + u];
-    }
-    return z;
+// Byte offset of the 16-byte chunk of row `row` at element k (ES = element size; rows are `ld`
+// elements apart, K elements of them remain from the operand's start), and whether it lies inside
+// the matrix.  K is a multiple of the chunk, so a chunk is inside or outside as a whole.  Chunks
+// outside are loaded from offset 0 and zeroed when they are written to LDS: the loads stay
+// unconditional and nothing consumes them early, so the sixteen loads of a slice are in flight
+// together while the matrix cores work on the previous slice.
+template <int ES>
+__device__ __forceinline__ int64_t chunk_offset(int64_t row, int64_t rows, int64_t k, int64_t K, int64_t ld,
+                                                bool& inside) {
+    inside = row < rows && k < K;
+    return inside ? (row * ld + k) * ES : 0;
 }
 
+// Which block computes which tile.  Blocks b, b+8, b+16, ... run on one XCD and share its L2, so
+// each XCD gets a rectangle of rm x rn tiles (the 8 XCDs form a gm x gn grid over the tile grid,
+// times `splits` ranges of K), and inside the rectangle consecutive blocks walk `group` tile rows
+// column by column: the 32 blocks an XCD runs at once then cover a compact patch and re-use each
+// other's slices of A and B from L2 instead of fetching them from HBM again.
+struct TileMap {
+    int tiles_m, tiles_n;      // tile grid of C
+    int splits;                // K ranges (1, 2, 4 or 8); more than one: results are added atomically into C
+    int gn;                    // XCD grid columns (rows = 8 / splits / gn)
+    int rm, rn;                // tiles per XCD rectangle
+    int group;                 // tile rows walked together
+    int slices;                // K slices per range
+};
+
+TileMap make_tile_map(int64_t M, int64_t N, int64_t K, int es, int splits) {
+    TileMap t;
+    t.tiles_m = (int)((M + 255) / 256);
+    t.tiles_n = (int)((N + 255) / 256);
+    t.splits = splits;
+    const int nx = 8 / splits;
+    int best = 1 << 30, gm = nx;
+    for (int cand = 1; cand <= nx; cand *= 2) {            // cand = XCD grid rows
+        const int rm = (t.tiles_m + cand - 1) / cand, rn = (t.tiles_n + nx / cand - 1) / (nx / cand);
+        if (rm + rn < best) { best = rm + rn; gm = cand; }
+    }
+    t.gn = nx / gm;
+    t.rm = (t.tiles_m + gm - 1) / gm;
+    t.rn = (t.tiles_n + t.gn - 1) / t.gn;
+    t.group = t.rm < 8 ? t.rm : 8;
+    const int nk = (int)((K * es + 127) / 128);
+    t.slices = (nk + splits - 1) / splits;
+    return t;
+}
+
+template <bool I8, bool ATOMIC>
 __global__ void __launch_bounds__(256)
-gemm_nt_mfma_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, float* __restrict__ C,
-                         int64_t M, int64_t N, int64_t K, int accumulate, const bf16_t* __restrict__ row_bias,
-                         int tiles_m, int tiles_n) {
+gemm_nt_mfma_kernel(const unsigned char* __restrict__ A0, const unsigned char* __restrict__ B0, void* __restrict__ Cv,
+                    int64_t M, int64_t N, int64_t K0, int accumulate, const bf16_t* __restrict__ row_bias,
+                    TileMap tm) {
+    constexpr int ES = I8 ? 1 : 2;                   // bytes per element
+    constexpr int MK = MKB / ES;                     // elements per K slice
+    constexpr int PER = 16 / ES;                     // elements per 16-byte chunk
+    typedef typename std::conditional<I8, i32x16_t, f32x16_t>::type acc_t;
     extern __shared__ __align__(16) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
 
-    // XCD-aware tile order
-    const int T = tiles_m * tiles_n;
-    const int per_xcd = (T + 7) / 8;
-    const int tile = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
-    if (tile >= T) return;
-    const int64_t m0 = (int64_t)(tile / tiles_n) * MT, n0 = (int64_t)(tile % tiles_n) * MT;
+    const int xcd = (int)blockIdx.x & 7, local = (int)blockIdx.x >> 3;
+    const int ks = xcd % tm.splits, xg = xcd / tm.splits;
+    const int per_group = tm.group * tm.rn;
+    const int g = local / per_group, r = local % per_group;
+    const int gsz = min(tm.group, tm.rm - g * tm.group);
+    const int tile_m = (xg / tm.gn) * tm.rm + g * tm.group + r % gsz;
+    const int tile_n = (xg % tm.gn) * tm.rn + r / gsz;
+    if (tile_m >= tm.tiles_m || tile_n >= tm.tiles_n) return;
+    const int64_t m0 = (int64_t)tile_m * MT, n0 = (int64_t)tile_n * MT;
+    // this block's range of K: operands advanced to its start, K = what remains from there
+    const int64_t kskip = (int64_t)ks * tm.slices * MK;
+    if (kskip >= K0) return;
+    const unsigned char* A = A0 + kskip * ES;
+    const unsigned char* B = B0 + kskip * ES;
+    const int64_t K = K0 - kskip;
 
-    f32x16_t acc[4][4];
+    acc_t acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
     // staging map: chunk c = tid + 256*i, i = 0..7 -> row c/8, 16-byte piece c%8
     td_u32x4 ra[8], rb[8];
     const int srow = tid >> 3, spiece = tid & 7;
+    unsigned live = 0;                               // bit i: ra[i] inside A, bit 8 + i: rb[i] inside B
     auto fetch = [&](int64_t k0) {
+        live = 0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            ra[i] = load_chunk(A, m0 + srow + 32 * i, M, k0 + spiece * 8, K);
-            rb[i] = load_chunk(B, n0 + srow + 32 * i, N, k0 + spiece * 8, K);
+            bool ia, ib;
+            const int64_t oa = chunk_offset<ES>(m0 + srow + 32 * i, M, k0 + spiece * PER, K, K0, ia);
+            const int64_t ob = chunk_offset<ES>(n0 + srow + 32 * i, N, k0 + spiece * PER, K, K0, ib);
+            ra[i] = *reinterpret_cast<const td_u32x4*>(A + oa);
+            rb[i] = *reinterpret_cast<const td_u32x4*>(B + ob);
+            live |= (ia ? 1u : 0u) << i | (ib ? 1u : 0u) << (8 + i);
         }
     };
     auto stash = [&](int stage) {
         unsigned char* as = lds + stage * MSTAGE;
         unsigned char* bs = as + MT * MSTRIDE;
+        const td_u32x4 zero = {0, 0, 0, 0};
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            *reinterpret_cast<td_u32x4*>(as + (srow + 32 * i) * MSTRIDE + spiece * 16) = ra[i];
-            *reinterpret_cast<td_u32x4*>(bs + (srow + 32 * i) * MSTRIDE + spiece * 16) = rb[i];
+            *reinterpret_cast<td_u32x4*>(as + (srow + 32 * i) * MSTRIDE + spiece * 16) =
+                ((live >> i) & 1u) ? ra[i] : zero;
+            *reinterpret_cast<td_u32x4*>(bs + (srow + 32 * i) * MSTRIDE + spiece * 16) =
+                ((live >> (8 + i)) & 1u) ? rb[i] : zero;
         }
     };
 
-    const int nk = (int)((K + MK - 1) / MK);
+    const int nk = min((int)((K + MK - 1) / MK), tm.slices);
     fetch(0);
     stash(0);
     __syncthreads();
-    const int frow = lane & 31, fk = (lane >> 5) * 16;  // fragment row and byte offset of its 8 k values
+    const int frow = lane & 31, fk = (lane >> 5) * 16;  // fragment row and byte offset of its 16 bytes of k
     for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
         if (kt + 1 < nk) fetch((int64_t)(kt + 1) * MK);
-        const unsigned char* as = lds + (kt & 1) * MSTAGE + (wm * 128 + frow) * MSTRIDE + fk;
-        const unsigned char* bs = lds + (kt & 1) * MSTAGE + MT * MSTRIDE + (wn * 128 + frow) * MSTRIDE + fk;
-        // fragments of slice ks+1 are read from LDS while the 16 MFMAs of slice ks run
-        bf16x8_t fa[2][4], fb[2][4];
+        const unsigned char* as = lds + cur * MSTAGE + (wm * 128 + frow) * MSTRIDE + fk;
+        const unsigned char* bs = lds + cur * MSTAGE + MT * MSTRIDE + (wn * 128 + frow) * MSTRIDE + fk;
+        // fragments of step ks+1 are read from LDS while the 16 MFMAs of step ks run
+        td_u32x4 fa[2][4], fb[2][4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            fa[0][i] = *reinterpret_cast<const bf16x8_t*>(as + i * 32 * MSTRIDE);
-            fb[0][i] = *reinterpret_cast<const bf16x8_t*>(bs + i * 32 * MSTRIDE);
+            fa[0][i] = *reinterpret_cast<const td_u32x4*>(as + i * 32 * MSTRIDE);
+            fb[0][i] = *reinterpret_cast<const td_u32x4*>(bs + i * 32 * MSTRIDE);
         }
 #pragma unroll
-        for (int ks = 0; ks < MK / 16; ++ks) {
-            if (ks + 1 < MK / 16) {
+        for (int ks = 0; ks < MKB / 32; ++ks) {
+            if (ks + 1 < MKB / 32) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    fa[(ks + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(as + i * 32 * MSTRIDE + (ks + 1) * 32);
-                    fb[(ks + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(bs + i * 32 * MSTRIDE + (ks + 1) * 32);
+                    fa[(ks + 1) & 1][i] = *reinterpret_cast<const td_u32x4*>(as + i * 32 * MSTRIDE + (ks + 1) * 32);
+                    fb[(ks + 1) & 1][i] = *reinterpret_cast<const td_u32x4*>(bs + i * 32 * MSTRIDE + (ks + 1) * 32);
                 }
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < 4; ++j) {
+                    if constexpr (I8)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4_t, fa[ks & 1][i]),
+                                                                          __builtin_bit_cast(i32x4_t, fb[ks & 1][j]),
+                                                                          acc[i][j], 0, 0, 0);
+                    else
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8_t, fa[ks & 1][i]), __builtin_bit_cast(bf16x8_t, fb[ks & 1][j]),
+                            acc[i][j], 0, 0, 0);
+                }
         }
-        if (kt + 1 < nk) stash((kt + 1) & 1);
+        if (kt + 1 < nk) stash(cur ^ 1);
         __syncthreads();
     }
 
@@ -183,14 +256,22 @@ gemm_nt_mfma_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict_
         for (int r = 0; r < 16; ++r) {
             const int64_t m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
             if (m >= M) continue;
-            const float rbias = row_bias ? td_bf16_to_f32(row_bias[m]) : 0.0f;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int64_t n = n0 + wn * 128 + j * 32 + (lane & 31);
                 if (n >= N) continue;
-                float v = acc[i][j][r] + rbias;
-                if (accumulate) v += C[m * N + n];
-                C[m * N + n] = v;
+                if constexpr (I8) {
+                    static_cast<int32_t*>(Cv)[m * N + n] = acc[i][j][r];
+                } else {
+                    float* C = static_cast<float*>(Cv);
+                    float v = acc[i][j][r] + ((row_bias && ks == 0) ? td_bf16_to_f32(row_bias[m]) : 0.0f);
+                    if constexpr (ATOMIC) {
+                        __hip_atomic_fetch_add(C + m * N + n, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    } else {
+                        if (accumulate) v += C[m * N + n];
+                        C[m * N + n] = v;
+                    }
+                }
             }
         }
     }
@@ -211,29 +292,61 @@ bool gemm_force_generic() {
 
 }  // namespace
 
+// the matrix-core kernels use more LDS than the default limit; raised once, outside any stream capture
+tardis_status_t td_gemm_init() {
+    static bool done = false;
+    if (done) return TARDIS_OK;
+    TD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, false>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, MLDS));
+    TD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, true>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, MLDS));
+    TD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_mfma_kernel<true, false>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, MLDS));
+    done = true;
+    return TARDIS_OK;
+}
+
 tardis_status_t td_gemm_nt(const void* A, const void* B, float* C, int64_t M, int64_t N, int64_t K, int32_t dtype,
                            int accumulate, const void* row_bias, hipStream_t s) {
+    return td_gemm_nt_split(A, B, C, M, N, K, dtype, accumulate, row_bias, 1, s);
+}
+
+// the same with K cut into `splits` ranges (1, 2, 4, 8) that run as separate blocks - for products
+// whose tile grid alone would leave most of the chip idle.  With splits > 1 the ranges ADD their
+// partial sums into C atomically: C must hold the value to accumulate onto (accumulate != 0).
+tardis_status_t td_gemm_nt_split(const void* A, const void* B, float* C, int64_t M, int64_t N, int64_t K,
+                                 int32_t dtype, int accumulate, const void* row_bias, int splits, hipStream_t s) {
     if (M <= 0 || N <= 0 || K <= 0) return TARDIS_ERR_SHAPE;
     if ((M + GT - 1) / GT > 65535) return TARDIS_ERR_SHAPE;
+    if (splits != 1 && splits != 2 && splits != 4 && splits != 8) return TARDIS_ERR_INVALID_ARG;
+    if (splits > 1 && !accumulate) return TARDIS_ERR_INVALID_ARG;
     if (dtype == TARDIS_BF16 && M >= 128 && N >= 128 && K >= 64 &&
         (reinterpret_cast<uintptr_t>(A) & 15) == 0 && (reinterpret_cast<uintptr_t>(B) & 15) == 0 && K % 8 == 0 &&
         !gemm_force_generic()) {
-        const int tiles_m = (int)((M + MT - 1) / MT), tiles_n = (int)((N + MT - 1) / MT);
-        const int T = tiles_m * tiles_n;
-        const int grid = ((T + 7) / 8) * 8;
-        static bool attr_set = false;
-        if (!attr_set) {
-            TD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_mfma_bf16_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, MLDS));
-            attr_set = true;
-        }
-        hipLaunchKernelGGL(gemm_nt_mfma_bf16_kernel, dim3(grid), dim3(256), MLDS, s, static_cast<const bf16_t*>(A),
-                           static_cast<const bf16_t*>(B), C, M, N, K, accumulate,
-                           static_cast<const bf16_t*>(row_bias), tiles_m, tiles_n);
+        const TileMap tm = make_tile_map(M, N, K, 2, splits);
+        TD_TRY(td_gemm_init());
+        auto kernel = splits > 1 ? gemm_nt_mfma_kernel<false, true> : gemm_nt_mfma_kernel<false, false>;
+        hipLaunchKernelGGL(kernel, dim3(8 * tm.rm * tm.rn), dim3(256), MLDS, s,
+                           static_cast<const unsigned char*>(A), static_cast<const unsigned char*>(B),
+                           static_cast<void*>(C), M, N, K, accumulate, static_cast<const bf16_t*>(row_bias), tm);
     } else if (dtype == TARDIS_BF16)
         launch_generic<bf16_t>(A, B, C, M, N, K, accumulate, row_bias, s);
     else
         launch_generic<float>(A, B, C, M, N, K, accumulate, row_bias, s);
+    TD_HIP(hipGetLastError());
+    return TARDIS_OK;
+}
+
+// C (int32, M x N) = A (int8, M x K) . B (int8, N x K)^T, exact.  16-byte aligned operands, K % 16 == 0.
+tardis_status_t td_gemm_nt_i8(const int8_t* A, const int8_t* B, int32_t* C, int64_t M, int64_t N, int64_t K,
+                              hipStream_t s) {
+    if (M <= 0 || N <= 0 || K <= 0 || K % 16 != 0) return TARDIS_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(A) & 15) || (reinterpret_cast<uintptr_t>(B) & 15)) return TARDIS_ERR_INVALID_ARG;
+    const TileMap tm = make_tile_map(M, N, K, 1, 1);
+    TD_TRY(td_gemm_init());
+    hipLaunchKernelGGL((gemm_nt_mfma_kernel<true, false>), dim3(8 * tm.rm * tm.rn), dim3(256), MLDS, s,
+                       reinterpret_cast<const unsigned char*>(A), reinterpret_cast<const unsigned char*>(B),
+                       static_cast<void*>(C), M, N, K, 0, static_cast<const bf16_t*>(nullptr), tm);
     TD_HIP(hipGetLastError());
     return TARDIS_OK;
 }

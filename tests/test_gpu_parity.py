@@ -194,6 +194,32 @@ def test_batched_with_bias_and_relu():
     run_case(layer, X_cal, X_test, 0.9, act="relu", batched=True, check_calibrate=False)
 
 
+# ------------------------------------------------------------- prompt path (dense matrix products)
+@pytest.mark.parametrize("d,h,n,bits", [(1024, 4096, 256, 8), (1024, 4096, 333, 8), (512, 2048, 300, 4),
+                                        (1024, 4096, 700, 4)])
+def test_prompt_path_many_tokens(d, h, n, bits):
+    """256 tokens and more: integer predictor sums, pre-activations, folded product and the masked
+    delta's down projection as four matrix products (ragged token counts span a partial tile);
+    masks bit-exact, lists and counts as for every other path."""
+    w = synth.decode(d=d, h=h, n_cal=512, n_test=n, coverage=0.9, config=3)
+    run_case(w.layer, w.X_cal, w.X_test, 0.9, batched=True, check_calibrate=False, sketch_bits=bits)
+
+
+def test_prompt_path_with_bias_and_relu():
+    seed = synth.workload_seed(3, 11)
+    layer = synth.make_layer(512, 2048, "bf16", seed, w1_std=0.05, w2_std=0.05, heavy_frac=0.01, with_bias=True)
+    X_cal = synth.make_tokens(400, 512, "bf16", seed, synth.STREAM_CAL)
+    X_test = synth.make_tokens(257, 512, "bf16", seed, synth.STREAM_TEST)
+    run_case(layer, X_cal, X_test, 0.9, act="relu", batched=True, check_calibrate=False)
+
+
+def test_prompt_threshold_off_takes_token_passes(monkeypatch):
+    """With the prompt path's threshold out of reach the same 300 tokens run as passes of 64."""
+    monkeypatch.setenv("TARDIS_PREFILL_MIN", "1000000")
+    w = synth.decode(d=1024, h=4096, n_cal=512, n_test=300, coverage=0.9, config=3)
+    run_case(w.layer, w.X_cal, w.X_test, 0.9, batched=True, check_calibrate=False)
+
+
 # ------------------------------------------------------------- greedy range search
 @pytest.mark.parametrize("dtype,d,h,n_cal,t,step,act", [("f32", 64, 96, 400, 0.9, 0.05, "gelu_erf"),
                                                        ("bf16", 256, 64, 1000, 0.85, 0.1, "gelu_erf"),
@@ -617,7 +643,7 @@ def test_full_size_batched_decode_sampled_tokens(decode_full, B):
 
 
 def test_full_size_prefill_sampled_tokens(decode_full):
-    """2048 tokens x d=4096 through the layer (32 passes of 64): sampled tokens against the checker,
+    """2048 tokens x d=4096 through the layer (the prompt path): sampled tokens against the checker,
     and every token's flag count against the expected fallback rate."""
     w, ffn, _, L, oracle = decode_full
     F = oracle()
