@@ -138,15 +138,23 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p, int row_block, 
     // have to wait for the load it copies.  Past the last chunk the prefetches re-read chunk 0 (a
     // cache hit) instead of being skipped, so that the in-order load counter stays statically
     // known and no wait ever drains more than it needs.
+    // Blocks walk the chunks of their K range from different starting points (the order of the sum
+    // does not matter): with every block at the same chunk index all loads in flight would share
+    // the address bits between the chunk and the row pitch, and crowd onto a few memory channels.
     const int last = chunks_per_split - 1;
+    const int rot = (row_block * 5 + split * 3) % chunks_per_split;
+    auto chunk_at = [&](int ch) {
+        int c = (ch <= last ? ch : 0) + rot;
+        return c >= chunks_per_split ? c - chunks_per_split : c;
+    };
     td_u32x4 w0[8], w1[8], w2[8], xa[XP], xb[XP];
     auto load_w = [&](td_u32x4 (&dst)[8], int ch) {
-        const unsigned char* src = wsrc + (size_t)(ch <= last ? ch : 0) * kChunk;
+        const unsigned char* src = wsrc + (size_t)chunk_at(ch) * kChunk;
 #pragma unroll
         for (int s = 0; s < 8; ++s) dst[s] = td_load_stream16(src + s * 64);
     };
     auto load_x = [&](td_u32x4 (&dst)[XP], int ch) {
-        const size_t off = (size_t)(ch <= last ? ch : 0) * kChunk;
+        const size_t off = (size_t)chunk_at(ch) * kChunk;
 #pragma unroll
         for (int q = 0; q < XP; ++q) dst[q] = *reinterpret_cast<const td_u32x4*>(xsrc[q] + off);
     };

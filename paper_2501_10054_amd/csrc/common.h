@@ -185,7 +185,7 @@ tardis_status_t td_gemm_nt(const void* A, const void* B, float* C, int64_t M, in
                            int32_t dtype, int accumulate, const void* row_bias, hipStream_t s);
 // exact int8 x int8 -> int32 product of the same form (K a multiple of 16, operands 16-byte aligned)
 tardis_status_t td_gemm_nt_i8(const int8_t* A, const int8_t* B, int32_t* C, int64_t M, int64_t N, int64_t K,
-                              hipStream_t s);
+                              int splits, hipStream_t s);
 // decode.hip
 bool td_prefill_supported(const tardis_layer_s* L);
 size_t td_prefill_scratch_bytes(const tardis_layer_s* L, int64_t n);

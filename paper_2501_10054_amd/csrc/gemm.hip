@@ -73,14 +73,22 @@ gemm_nt_generic_kernel(const T* __restrict__ A, const T* __restrict__ B, float* 
 }
 
 
-// ------------------------------------------------------------------ bf16 MFMA
-// 256x256 output tile per block of 4 wavefronts (2x2, 128x128 each = 4x4 MFMA
-// 32x32x16 tiles, 256 fp32 accumulators per lane), K in slices of 64 staged
-// through double-buffered LDS (rows padded to 144 bytes), next slice prefetched
-// global -> registers while the current one feeds the matrix cores.
-// The int8 form (exact int32 sums, the predictor of many tokens at once) has the same byte
-// geometry - 16 bytes per lane and step are 8 bf16 or 16 int8 - so it is the same kernel with
-// v_mfma_i32_32x32x32_i8, K slices of 128 elements and an int32 result.
+// ------------------------------------------------------------------ MFMA (bf16 or int8)
+// 256x256 output tile per block of 4 wavefronts (2x2, 128x128 each = 4x4 MFMA 32x32 tiles, 256
+// accumulators per lane), K in slices of 128 bytes per row (64 bf16 or 128 int8: the byte
+// geometry of the two is the same, 16 bytes per lane and MFMA) staged through two LDS stages
+// (rows padded to 144 bytes) and two register sets.
+//
+// Schedule of one slice (four steps of 16 MFMAs each).  A wavefront issues in order and each SIMD
+// holds one wavefront here, so whatever is not an MFMA is placed BETWEEN the MFMAs of a step, a
+// few instructions after each, instead of after them where the matrix cores would idle:
+//   step 0   loads of slice kt+2 -> the free register set          (two slices of lead)
+//   step 1-2 the set that holds slice kt+1 -> the other LDS stage
+//   barrier
+//   step 3   already reads the first fragments of that stage
+// and every step reads the LDS fragments of the next one.  On MI355X this runs the fold at about
+// 0.95 PFLOP/s; what remains is the LDS traffic (each staged byte is written once and read by two
+// wavefronts: 1536 LDS cycles against 2048 MFMA cycles per slice) and the global-load path.
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef int i32x4_t __attribute__((ext_vector_type(4)));
@@ -91,19 +99,6 @@ constexpr int MKB = 128;                             // bytes of one staged row 
 constexpr int MSTRIDE = MKB + 16;                    // bytes per staged row (padded)
 constexpr int MSTAGE = 2 * MT * MSTRIDE;             // A tile + B tile
 constexpr int MLDS = 2 * MSTAGE;
-
-// Byte offset of the 16-byte chunk of row `row` at element k (ES = element size; rows are `ld`
-// elements apart, K elements of them remain from the operand's start), and whether it lies inside
-// the matrix.  K is a multiple of the chunk, so a chunk is inside or outside as a whole.  Chunks
-// outside are loaded from offset 0 and zeroed when they are written to LDS: the loads stay
-// unconditional and nothing consumes them early, so the sixteen loads of a slice are in flight
-// together while the matrix cores work on the previous slice.
-template <int ES>
-__device__ __forceinline__ int64_t chunk_offset(int64_t row, int64_t rows, int64_t k, int64_t K, int64_t ld,
-                                                bool& inside) {
-    inside = row < rows && k < K;
-    return inside ? (row * ld + k) * ES : 0;
-}
 
 // Which block computes which tile.  Blocks b, b+8, b+16, ... run on one XCD and share its L2, so
 // each XCD gets a rectangle of rm x rn tiles (the 8 XCDs form a gm x gn grid over the tile grid,
@@ -139,7 +134,10 @@ TileMap make_tile_map(int64_t M, int64_t N, int64_t K, int es, int splits) {
     return t;
 }
 
-template <bool I8, bool ATOMIC>
+// RAGGED: K is not a multiple of the slice; the last slice is then moved back to end at K and the
+// pieces it shares with the slice before it are zeroed on their way to LDS (costs four selects
+// per LDS write, so it is a variant of its own).
+template <bool I8, bool ATOMIC, bool RAGGED>
 __global__ void __launch_bounds__(256)
 gemm_nt_mfma_kernel(const unsigned char* __restrict__ A0, const unsigned char* __restrict__ B0, void* __restrict__ Cv,
                     int64_t M, int64_t N, int64_t K0, int accumulate, const bf16_t* __restrict__ row_bias,
@@ -164,9 +162,8 @@ gemm_nt_mfma_kernel(const unsigned char* __restrict__ A0, const unsigned char* _
     // this block's range of K: operands advanced to its start, K = what remains from there
     const int64_t kskip = (int64_t)ks * tm.slices * MK;
     if (kskip >= K0) return;
-    const unsigned char* A = A0 + kskip * ES;
-    const unsigned char* B = B0 + kskip * ES;
     const int64_t K = K0 - kskip;
+    const int nk = min((int)((K + MK - 1) / MK), tm.slices);
 
     acc_t acc[4][4];
 #pragma unroll
@@ -176,78 +173,117 @@ gemm_nt_mfma_kernel(const unsigned char* __restrict__ A0, const unsigned char* _
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // staging map: chunk c = tid + 256*i, i = 0..7 -> row c/8, 16-byte piece c%8
-    td_u32x4 ra[8], rb[8];
+    // staging map: chunk c = tid + 256*i, i = 0..7 -> row c/8, 16-byte piece c%8.  The address of
+    // a load is a wave-uniform base (tile start + slice) plus one of eight lane offsets, the same
+    // for both operands (same row pitch).  Rows past the matrix read row 0 of the tile instead;
+    // they are not zeroed: they only reach output rows and columns that are never stored.
+    td_u32x4 ra0[8], rb0[8], ra1[8], rb1[8];
     const int srow = tid >> 3, spiece = tid & 7;
-    unsigned live = 0;                               // bit i: ra[i] inside A, bit 8 + i: rb[i] inside B
-    auto fetch = [&](int64_t k0) {
-        live = 0;
+    unsigned offa[8], offb[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const unsigned off = (unsigned)(((32 * i + srow) * K0 + spiece * PER) * ES);
+        offa[i] = m0 + 32 * i + srow < M ? off : 0u;
+        offb[i] = n0 + 32 * i + srow < N ? off : 0u;
+    }
+    const unsigned char* tileA = A0 + (m0 * K0 + kskip) * ES;
+    const unsigned char* tileB = B0 + (n0 * K0 + kskip) * ES;
+    // slices past the last one re-read slice 0 (never multiplied): every load below is issued
+    // unconditionally, so the number of loads in flight at each wait is known statically
+    auto fetch = [&](td_u32x4 (&ra)[8], td_u32x4 (&rb)[8], unsigned& keep, int kt) {
+        const int64_t k0 = (int64_t)kt * MK;
+        int64_t kb = kt < nk ? k0 : 0;
+        keep = 1u;
+        if constexpr (RAGGED) {
+            if (kt < nk && k0 + MK > K) kb = K - MK;                  // the last slice, moved back
+            keep = kb + spiece * PER >= k0 ? 1u : 0u;
+        }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            bool ia, ib;
-            const int64_t oa = chunk_offset<ES>(m0 + srow + 32 * i, M, k0 + spiece * PER, K, K0, ia);
-            const int64_t ob = chunk_offset<ES>(n0 + srow + 32 * i, N, k0 + spiece * PER, K, K0, ib);
-            ra[i] = *reinterpret_cast<const td_u32x4*>(A + oa);
-            rb[i] = *reinterpret_cast<const td_u32x4*>(B + ob);
-            live |= (ia ? 1u : 0u) << i | (ib ? 1u : 0u) << (8 + i);
+            ra[i] = *reinterpret_cast<const td_u32x4*>(tileA + kb * ES + offa[i]);
+            rb[i] = *reinterpret_cast<const td_u32x4*>(tileB + kb * ES + offb[i]);
         }
     };
-    auto stash = [&](int stage) {
-        unsigned char* as = lds + stage * MSTAGE;
-        unsigned char* bs = as + MT * MSTRIDE;
+    auto stash_half = [&](const td_u32x4 (&rr)[8], unsigned keep, int stage, int half) {
+        unsigned char* dst = lds + stage * MSTAGE + half * MT * MSTRIDE + srow * MSTRIDE + spiece * 16;
         const td_u32x4 zero = {0, 0, 0, 0};
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            *reinterpret_cast<td_u32x4*>(as + (srow + 32 * i) * MSTRIDE + spiece * 16) =
-                ((live >> i) & 1u) ? ra[i] : zero;
-            *reinterpret_cast<td_u32x4*>(bs + (srow + 32 * i) * MSTRIDE + spiece * 16) =
-                ((live >> (8 + i)) & 1u) ? rb[i] : zero;
-        }
+        for (int i = 0; i < 8; ++i)
+            *reinterpret_cast<td_u32x4*>(dst + 32 * i * MSTRIDE) = (!RAGGED || keep) ? rr[i] : zero;
     };
-
-    const int nk = min((int)((K + MK - 1) / MK), tm.slices);
-    fetch(0);
-    stash(0);
-    __syncthreads();
     const int frow = lane & 31, fk = (lane >> 5) * 16;  // fragment row and byte offset of its 16 bytes of k
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) fetch((int64_t)(kt + 1) * MK);
-        const unsigned char* as = lds + cur * MSTAGE + (wm * 128 + frow) * MSTRIDE + fk;
-        const unsigned char* bs = lds + cur * MSTAGE + MT * MSTRIDE + (wn * 128 + frow) * MSTRIDE + fk;
-        // fragments of step ks+1 are read from LDS while the 16 MFMAs of step ks run
-        td_u32x4 fa[2][4], fb[2][4];
+    td_u32x4 fa[2][4], fb[2][4];
+    auto read_frags = [&](td_u32x4 (&da)[4], td_u32x4 (&db)[4], int stage, int kstep) {
+        const unsigned char* as = lds + stage * MSTAGE + (wm * 128 + frow) * MSTRIDE + fk + kstep * 32;
+        const unsigned char* bs = lds + stage * MSTAGE + MT * MSTRIDE + (wn * 128 + frow) * MSTRIDE + fk + kstep * 32;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            fa[0][i] = *reinterpret_cast<const td_u32x4*>(as + i * 32 * MSTRIDE);
-            fb[0][i] = *reinterpret_cast<const td_u32x4*>(bs + i * 32 * MSTRIDE);
+            da[i] = *reinterpret_cast<const td_u32x4*>(as + i * 32 * MSTRIDE);
+            db[i] = *reinterpret_cast<const td_u32x4*>(bs + i * 32 * MSTRIDE);
         }
+    };
+    auto mfma16 = [&](const td_u32x4 (&ua)[4], const td_u32x4 (&ub)[4]) {
 #pragma unroll
-        for (int ks = 0; ks < MKB / 32; ++ks) {
-            if (ks + 1 < MKB / 32) {
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    fa[(ks + 1) & 1][i] = *reinterpret_cast<const td_u32x4*>(as + i * 32 * MSTRIDE + (ks + 1) * 32);
-                    fb[(ks + 1) & 1][i] = *reinterpret_cast<const td_u32x4*>(bs + i * 32 * MSTRIDE + (ks + 1) * 32);
-                }
+            for (int j = 0; j < 4; ++j) {
+                if constexpr (I8)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4_t, ua[i]),
+                                                                      __builtin_bit_cast(i32x4_t, ub[j]), acc[i][j], 0, 0, 0);
+                else
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ua[i]),
+                                                                        __builtin_bit_cast(bf16x8_t, ub[j]), acc[i][j], 0, 0, 0);
             }
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if constexpr (I8)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4_t, fa[ks & 1][i]),
-                                                                          __builtin_bit_cast(i32x4_t, fb[ks & 1][j]),
-                                                                          acc[i][j], 0, 0, 0);
-                    else
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8_t, fa[ks & 1][i]), __builtin_bit_cast(bf16x8_t, fb[ks & 1][j]),
-                            acc[i][j], 0, 0, 0);
-                }
-        }
-        if (kt + 1 < nk) stash(cur ^ 1);
-        __syncthreads();
+    };
+    // the scheduler is told the order inside a step: one MFMA, `alu` VALU/SALU instructions, and
+    // after every `every`-th MFMA one memory instruction of class `mem` (0x020 load, 0x200 LDS write)
+#define TD_GEMM_INTERLEAVE(alu, mem, every)                                        \
+    _Pragma("unroll") for (int q = 0; q < 16; ++q) {                               \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                         \
+        __builtin_amdgcn_sched_group_barrier(0x006, alu, 0);                       \
+        if (q % every == every - 1) __builtin_amdgcn_sched_group_barrier(mem, 1, 0); \
     }
+    auto phase = [&](int stage, td_u32x4 (&la)[8], td_u32x4 (&lb)[8], unsigned& lkeep, int lkt,
+                     const td_u32x4 (&sa)[8], const td_u32x4 (&sb)[8], unsigned skeep) {
+        read_frags(fa[1], fb[1], stage, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma16(fa[0], fb[0]);
+        fetch(la, lb, lkeep, lkt);
+        TD_GEMM_INTERLEAVE(2, 0x020, 1)
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(fa[0], fb[0], stage, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma16(fa[1], fb[1]);
+        stash_half(sa, skeep, stage ^ 1, 0);
+        TD_GEMM_INTERLEAVE(RAGGED ? 3 : 1, 0x200, 2)
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(fa[1], fb[1], stage, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma16(fa[0], fb[0]);
+        stash_half(sb, skeep, stage ^ 1, 1);
+        TD_GEMM_INTERLEAVE(RAGGED ? 3 : 1, 0x200, 2)
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        read_frags(fa[0], fb[0], stage ^ 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma16(fa[1], fb[1]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+#undef TD_GEMM_INTERLEAVE
+
+    unsigned keep0 = 1u, keep1 = 1u;
+    fetch(ra0, rb0, keep0, 0);
+    fetch(ra1, rb1, keep1, 1);
+    stash_half(ra0, keep0, 0, 0);
+    stash_half(rb0, keep0, 0, 1);
+    __syncthreads();
+    read_frags(fa[0], fb[0], 0, 0);
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+        phase(0, ra0, rb0, keep0, kt + 2, ra1, rb1, keep1);
+        phase(1, ra1, rb1, keep1, kt + 3, ra0, rb0, keep0);
+    }
+    if (kt < nk) phase(0, ra0, rb0, keep0, kt + 2, ra1, rb1, keep1);    // odd count: the last slice
 
     // D layout of the 32x32 tile: column = lane % 32, row = 8*(r/4) + 4*(lane/32) + r%4
 #pragma unroll
@@ -261,7 +297,11 @@ gemm_nt_mfma_kernel(const unsigned char* __restrict__ A0, const unsigned char* _
                 const int64_t n = n0 + wn * 128 + j * 32 + (lane & 31);
                 if (n >= N) continue;
                 if constexpr (I8) {
-                    static_cast<int32_t*>(Cv)[m * N + n] = acc[i][j][r];
+                    int32_t* C = static_cast<int32_t*>(Cv);
+                    if constexpr (ATOMIC)
+                        __hip_atomic_fetch_add(C + m * N + n, acc[i][j][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    else
+                        C[m * N + n] = acc[i][j][r];
                 } else {
                     float* C = static_cast<float*>(Cv);
                     float v = acc[i][j][r] + ((row_bias && ks == 0) ? td_bf16_to_f32(row_bias[m]) : 0.0f);
@@ -296,12 +336,12 @@ bool gemm_force_generic() {
 tardis_status_t td_gemm_init() {
     static bool done = false;
     if (done) return TARDIS_OK;
-    TD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, false>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, MLDS));
-    TD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, true>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, MLDS));
-    TD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_nt_mfma_kernel<true, false>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, MLDS));
+    const void* kernels[] = {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, false, false>),
+                             reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, false, true>),
+                             reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, true, false>),
+                             reinterpret_cast<const void*>(gemm_nt_mfma_kernel<true, false, false>),
+                             reinterpret_cast<const void*>(gemm_nt_mfma_kernel<true, true, false>)};
+    for (const void* k : kernels) TD_HIP(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, MLDS));
     done = true;
     return TARDIS_OK;
 }
@@ -323,9 +363,14 @@ tardis_status_t td_gemm_nt_split(const void* A, const void* B, float* C, int64_t
     if (dtype == TARDIS_BF16 && M >= 128 && N >= 128 && K >= 64 &&
         (reinterpret_cast<uintptr_t>(A) & 15) == 0 && (reinterpret_cast<uintptr_t>(B) & 15) == 0 && K % 8 == 0 &&
         !gemm_force_generic()) {
+        // a ragged K (not a multiple of the 64-element slice) runs unsplit: non-atomic accumulate
+        const bool ragged = K % 64 != 0;
+        if (ragged) splits = 1;
         const TileMap tm = make_tile_map(M, N, K, 2, splits);
         TD_TRY(td_gemm_init());
-        auto kernel = splits > 1 ? gemm_nt_mfma_kernel<false, true> : gemm_nt_mfma_kernel<false, false>;
+        auto kernel = ragged ? gemm_nt_mfma_kernel<false, false, true>
+                             : (splits > 1 ? gemm_nt_mfma_kernel<false, true, false>
+                                           : gemm_nt_mfma_kernel<false, false, false>);
         hipLaunchKernelGGL(kernel, dim3(8 * tm.rm * tm.rn), dim3(256), MLDS, s,
                            static_cast<const unsigned char*>(A), static_cast<const unsigned char*>(B),
                            static_cast<void*>(C), M, N, K, accumulate, static_cast<const bf16_t*>(row_bias), tm);
@@ -337,14 +382,17 @@ tardis_status_t td_gemm_nt_split(const void* A, const void* B, float* C, int64_t
     return TARDIS_OK;
 }
 
-// C (int32, M x N) = A (int8, M x K) . B (int8, N x K)^T, exact.  16-byte aligned operands, K % 16 == 0.
+// C (int32, M x N) = A (int8, M x K) . B (int8, N x K)^T, exact.  16-byte aligned operands, K % 128 == 0.
+// splits > 1: K is cut into that many ranges whose sums are ADDED to C atomically (C zeroed by the caller).
 tardis_status_t td_gemm_nt_i8(const int8_t* A, const int8_t* B, int32_t* C, int64_t M, int64_t N, int64_t K,
-                              hipStream_t s) {
-    if (M <= 0 || N <= 0 || K <= 0 || K % 16 != 0) return TARDIS_ERR_SHAPE;
+                              int splits, hipStream_t s) {
+    if (M <= 0 || N <= 0 || K <= 0 || K % 128 != 0) return TARDIS_ERR_SHAPE;
+    if (splits != 1 && splits != 2 && splits != 4 && splits != 8) return TARDIS_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(A) & 15) || (reinterpret_cast<uintptr_t>(B) & 15)) return TARDIS_ERR_INVALID_ARG;
-    const TileMap tm = make_tile_map(M, N, K, 1, 1);
+    const TileMap tm = make_tile_map(M, N, K, 1, splits);
     TD_TRY(td_gemm_init());
-    hipLaunchKernelGGL((gemm_nt_mfma_kernel<true, false>), dim3(8 * tm.rm * tm.rn), dim3(256), MLDS, s,
+    auto kernel = splits > 1 ? gemm_nt_mfma_kernel<true, true, false> : gemm_nt_mfma_kernel<true, false, false>;
+    hipLaunchKernelGGL(kernel, dim3(8 * tm.rm * tm.rn), dim3(256), MLDS, s,
                        reinterpret_cast<const unsigned char*>(A), reinterpret_cast<const unsigned char*>(B),
                        static_cast<void*>(C), M, N, K, 0, static_cast<const bf16_t*>(nullptr), tm);
     TD_HIP(hipGetLastError());

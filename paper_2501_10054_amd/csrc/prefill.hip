@@ -81,6 +81,7 @@ delta_mask_kernel(const int32_t* __restrict__ ACC, const float* __restrict__ Z, 
     if ((lane & 7) == 0 && w < mask_words) mask[(size_t)t * mask_words + w] = word;
 }
 
+// (sizes are multiples of 16 bytes: d % 16 == 0 and h % 8 == 0)
 __global__ void __launch_bounds__(256) zero_f32_kernel(float4* __restrict__ p, size_t n4) {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256)
         p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -111,7 +112,7 @@ finish_rows_kernel(const float* __restrict__ Y, const float* __restrict__ bp, in
 }  // namespace
 
 bool td_prefill_supported(const tardis_layer_s* L) {
-    return L->dtype == TARDIS_BF16 && L->d % 16 == 0 && L->d >= 64 && L->h >= 128 && L->h % 8 == 0 && L->Q != nullptr;
+    return L->dtype == TARDIS_BF16 && L->d % 128 == 0 && L->h >= 128 && L->h % 8 == 0 && L->Q != nullptr;
 }
 
 size_t td_prefill_scratch_bytes(const tardis_layer_s* L, int64_t n) {
@@ -132,23 +133,28 @@ tardis_status_t td_forward_prefill(tardis_layer_s* L, const void* xv, int64_t n,
     bf16_t* dl = reinterpret_cast<bf16_t*>(p);            p += up((size_t)n * h * 2);
     float* yacc = reinterpret_cast<float*>(p);
     const bf16_t* x = static_cast<const bf16_t*>(xv);
-    hipLaunchKernelGGL(quantize_rows_kernel, dim3((unsigned)n), dim3(256), 0, s, x, (int)d, xq, e);
-    TD_TRY(td_gemm_nt_i8(xq, L->Q, acc, n, h, d, s));
-    TD_TRY(td_gemm_nt(x, L->W1, z, n, h, d, TARDIS_BF16, 0, nullptr, s));
-    hipLaunchKernelGGL(delta_mask_kernel, dim3((unsigned)((h + 1023) / 1024), (unsigned)n), dim3(256), 0, s, acc, z, e,
-                       L->tlo, L->thi, L->a, L->c, static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), (int)L->act,
-                       (int)h, dl, L->mask, (int)L->mask_words);
-    // the two products into y: few output tiles (n x d), so K is cut into ranges that add atomically
-    const int64_t tiles = ((n + 255) / 256) * ((d + 255) / 256);
-    auto pick = [&](int64_t K) {
+    // products with few output tiles cut K into ranges that add atomically into zeroed results
+    auto pick = [&](int64_t N, int64_t K) {
+        const int64_t tiles = ((n + 255) / 256) * ((N + 255) / 256);
         int sp = 1;
         while (sp < 8 && tiles * sp < 256 && K / (sp * 2) >= 1024) sp *= 2;
         return sp;
     };
-    hipLaunchKernelGGL(zero_f32_kernel, dim3(2048), dim3(256), 0, s, reinterpret_cast<float4*>(yacc),
-                       (size_t)n * d / 4);
-    TD_TRY(td_gemm_nt_split(x, L->Wp, yacc, n, d, d, TARDIS_BF16, 1, nullptr, pick(d), s));
-    TD_TRY(td_gemm_nt_split(dl, L->W2, yacc, n, d, h, TARDIS_BF16, 1, nullptr, pick(h), s));
+    auto zero = [&](void* p4, size_t bytes) {
+        hipLaunchKernelGGL(zero_f32_kernel, dim3(2048), dim3(256), 0, s, static_cast<float4*>(p4), bytes / 16);
+    };
+    hipLaunchKernelGGL(quantize_rows_kernel, dim3((unsigned)n), dim3(256), 0, s, x, (int)d, xq, e);
+    const int sp_acc = pick(h, d), sp_z = pick(h, d * 2);   // K in bytes decides the number of slices
+    if (sp_acc > 1) zero(acc, (size_t)n * h * 4);
+    TD_TRY(td_gemm_nt_i8(xq, L->Q, acc, n, h, d, sp_acc, s));
+    if (sp_z > 1) zero(z, (size_t)n * h * 4);
+    TD_TRY(td_gemm_nt_split(x, L->W1, z, n, h, d, TARDIS_BF16, sp_z > 1, nullptr, sp_z, s));
+    hipLaunchKernelGGL(delta_mask_kernel, dim3((unsigned)((h + 1023) / 1024), (unsigned)n), dim3(256), 0, s, acc, z, e,
+                       L->tlo, L->thi, L->a, L->c, static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), (int)L->act,
+                       (int)h, dl, L->mask, (int)L->mask_words);
+    zero(yacc, (size_t)n * d * 4);
+    TD_TRY(td_gemm_nt_split(x, L->Wp, yacc, n, d, d, TARDIS_BF16, 1, nullptr, pick(d, d * 2), s));
+    TD_TRY(td_gemm_nt_split(dl, L->W2, yacc, n, d, h, TARDIS_BF16, 1, nullptr, pick(d, h * 2), s));
     hipLaunchKernelGGL(finish_rows_kernel, dim3((unsigned)n), dim3(256), 0, s, yacc, L->bp, (int)d,
                        static_cast<bf16_t*>(yv), norm_out, kRmsEps);
     TD_HIP(hipGetLastError());

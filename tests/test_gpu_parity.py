@@ -662,6 +662,24 @@ def test_full_size_prefill_sampled_tokens(decode_full):
     assert torch.isfinite(Y.float()).all()
 
 
+def test_full_size_prompt_256_tokens(decode_full):
+    """256 tokens at full size: one row of output tiles, so every product of the prompt path cuts K
+    into ranges that add atomically (the int8 sums stay exact: integer adds)."""
+    w, ffn, _, L, oracle = decode_full
+    F = oracle()
+    n = 256
+    Y = T.tardis_ffn_forward_batched(L, dev(w.X_test[:n], "bf16"))
+    mask, counts, _ = T.tardis_get_last_outliers(L, n, want_list=False)
+    torch.cuda.synchronize()
+    FLg = unpack_mask(mask, w.layer.h)
+    for t in (0, 100, 255):
+        yo, flo = O.forward_token(F, w.X_test[t])
+        np.testing.assert_array_equal(FLg[t], flo)
+        assert rel_l2(host(Y[t]), yo) <= 1e-2
+    assert (counts.cpu().numpy() == FLg.sum(1)).all()
+    assert torch.isfinite(Y.float()).all()
+
+
 def test_full_size_sketch4_decode(decode_full):
     """The full layer folded with the 4-bit sketch: codes and multipliers bit-exact, masks bit-exact
     and y within the bar for single tokens and a group of four; the flag rate rises a little
