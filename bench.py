@@ -55,8 +55,9 @@ def _time_us(torch, fn, reps, warm=2):
 
 
 def prefill_run(T, synth, torch, np, to_dev):
-    """2048 tokens x d=4096 through one layer (passes of 64 tokens) against the dense FFN as two
-    vendor-BLAS GEMMs; also the offline fold/calibration GEMM rate on the matrix cores."""
+    """2048 (and 256) tokens x d=4096 through one layer - the prompt path: predictor sums,
+    pre-activations, folded product and masked-delta down projection as four matrix-core products -
+    against the dense FFN as two vendor-BLAS GEMMs; also the offline calibration and fold times."""
     n = 2048
     w = synth.decode(layer=0, n_cal=4096, n_test=n, coverage=0.95, config=3)
     ffn = T.FFN(to_dev(w.layer.W1), to_dev(w.layer.W2))
@@ -74,12 +75,16 @@ def prefill_run(T, synth, torch, np, to_dev):
     us = _time_us(torch, lambda: T.tardis_ffn_forward_batched(L, X, Y), 5, 1)
     _, counts, _ = T.tardis_get_last_outliers(L, n, want_list=False)
     p = float(counts.float().mean().item()) / H
+    X256, Y256 = X[:256].contiguous(), torch.empty_like(X[:256])
+    us256 = _time_us(torch, lambda: T.tardis_ffn_forward_batched(L, X256, Y256), 5, 1)
     W1, W2 = ffn.W1, ffn.W2
     dus = _time_us(torch, lambda: torch.nn.functional.linear(
         torch.nn.functional.gelu(torch.nn.functional.linear(X, W1)), W2), 5, 1)
     L.close()
     gemm_flop = 2.0 * D * D * H          # one of the two accumulating fold GEMMs, or the calibration GEMM
+    work = 2.0 * n * D * D + 3 * 2.0 * n * D * H      # folded + int8 predictor + pre-activations + down projection
     return {"tokens": n, "fallback_rate": p, "us": us, "tokens_per_s": n / (us * 1e-6),
+            "matrix_core_Tops": work / us / 1e6, "us_256_tokens": us256,
             "dense_torch_us": dus, "dense_torch_TFLOPs": (2.0 * 2 * n * D * H) / dus / 1e6,
             "speedup_vs_dense_torch": dus / us,
             "calibrate_us": cal_us, "fold_ms_incl_alloc": fold_ms,
@@ -188,11 +193,11 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
-                    help="skip the figures beside the headline one (batched decode at the headline coverage, 4-bit sketch)")
+                    help="skip the figures beside the headline one (batched decode at the headline coverage, 4-bit sketch, prompt shape)")
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of a replayed HIP graph")
     ap.add_argument("--sweep", action="store_true",
                     help="also run the batched decode sweep: batch {2,4,8,16,64} x coverage {0.99,0.95,0.85}")
-    ap.add_argument("--prefill", action="store_true", help="also run the 2048-token prefill shape")
+    ap.add_argument("--prefill", action="store_true", help="run the 2048-token prompt shape even with --no-extras")
     ap.add_argument("--stack", type=int, default=0, help="also run a stack of this many layers (32 = the full configuration)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a 1 GiB device copy (known HBM traffic) so that profiler counters can be scaled")
@@ -412,7 +417,8 @@ def main() -> int:
             L.close()
         covs = (0.99, 0.95, 0.85) if args.sweep else (args.coverage,)
         out["batched_sweep"] = batched_sweep(T, synth, torch, np, to_dev, pre, X, covs)
-    if args.prefill:
+    if args.prefill or not args.no_extras:
+        print("bench.py: prompt shape (2048 tokens)", file=sys.stderr, flush=True)
         out["prefill"] = prefill_run(T, synth, torch, np, to_dev)
     if args.stack > 0:
         out["stack"] = stack_run(T, synth, torch, np, to_dev, args.stack)

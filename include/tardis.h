@@ -84,7 +84,8 @@ typedef struct {
 typedef struct {
     int32_t sketch_bits;   /* predictor code width: 8, or 4 (grouped, see tardis_fold) */
     int32_t folded_dtype;  /* storage of W'; must equal desc.dtype */
-    int64_t max_batch;     /* largest n accepted by the batched online calls (>= 1) */
+    int64_t max_batch;     /* largest n accepted by the batched online calls (>= 1); from 65 on the layer
+                              also holds scratch for the prompt path, about n * (5 d + 10 h) bytes */
     int32_t deterministic; /* reserved, must be 0 */
     int32_t reserved;
 } tardis_fold_opts;
@@ -172,7 +173,11 @@ tardis_status_t tardis_fold(const tardis_ffn_desc* desc, const float* lo, const 
 tardis_status_t tardis_ffn_forward(tardis_handle_t L, const void* x, void* y, void* stream);
 
 /* n tokens (1 <= n <= max_batch), strictly per token: token t is repaired only
- * for the neurons its own predictor pass flagged.  x, y: n x d. */
+ * for the neurons its own predictor pass flagged.  x, y: n x d.
+ * How the tokens are processed depends on n (groups of up to 16 tokens per
+ * launch; passes of up to 64; from 65 tokens four dense matrix products, as the
+ * paper's remark on prompt processing suggests) and never on their values; the
+ * masks are the same bits on every path, y agrees to rounding. */
 tardis_status_t tardis_ffn_forward_batched(tardis_handle_t L, const void* x, int64_t n, void* y,
                                            void* stream);
 

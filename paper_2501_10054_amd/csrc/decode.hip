@@ -157,7 +157,8 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     td_u32x4 qm[NL];                                 // matrix-core path: row (lane % 16) of the group, 16 bytes per step
     float tl_own = 0.0f, th_own = 0.0f;              // ... and the bounds of neuron `tid` of the block
     auto load_pred_tile = [&]() {
-        const int grp = wave % NG, kq = wave / NG;
+        constexpr int NGD = NG > 0 ? NG : 1;         // (not instantiated for NG == 0; keeps the division defined)
+        const int grp = wave % NGD, kq = wave / NGD;
         const int j = min(j0 + grp * 16 + (lane & 15), h - 1);
         const td_u32x4* p = reinterpret_cast<const td_u32x4*>(Q + (size_t)j * D + kq * KS) + (lane >> 4);
 #pragma unroll

@@ -360,7 +360,8 @@ tardis_status_t td_gemm_nt_split(const void* A, const void* B, float* C, int64_t
     if ((M + GT - 1) / GT > 65535) return TARDIS_ERR_SHAPE;
     if (splits != 1 && splits != 2 && splits != 4 && splits != 8) return TARDIS_ERR_INVALID_ARG;
     if (splits > 1 && !accumulate) return TARDIS_ERR_INVALID_ARG;
-    if (dtype == TARDIS_BF16 && M >= 128 && N >= 128 && K >= 64 &&
+    // (any M, N work on the matrix cores; small products are not worth a 256 x 256 tile)
+    if (dtype == TARDIS_BF16 && M >= 32 && N >= 32 && M * N >= 128 * 128 && K >= 64 &&
         (reinterpret_cast<uintptr_t>(A) & 15) == 0 && (reinterpret_cast<uintptr_t>(B) & 15) == 0 && K % 8 == 0 &&
         !gemm_force_generic()) {
         // a ragged K (not a multiple of the 64-element slice) runs unsplit: non-atomic accumulate

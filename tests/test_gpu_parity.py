@@ -180,8 +180,9 @@ def test_mid_bf16_batched_high_fallback():
                                         (20, 0.95), (48, 0.85), (64, 0.95), (70, 0.99), (150, 0.95)])
 def test_batched_passes_of_64_tokens(n, coverage):
     """Up to 16 tokens: groups of 16, 8, 4 (two kernels: records, then the column-sliced down
-    projection; 3, 5-7 and 9-15 tokens run as partly empty groups), 2 and 1 tokens (one kernel).  More: one weight stream per pass of up to 64 tokens, every tile
-    count (1, 2, 4 token tiles), the masked-dense scatter, a ragged last pass."""
+    projection; 3, 5-7 and 9-15 tokens run as partly empty groups), 2 and 1 tokens (one kernel).
+    17 to 64: one weight stream per pass, every tile count (1, 2, 4 token tiles), the masked-dense
+    scatter.  70 and 150: the prompt path at a fraction of one tile row."""
     w = synth.decode(d=1024, h=4096, n_cal=512, n_test=n, coverage=coverage, config=2)
     run_case(w.layer, w.X_cal, w.X_test, coverage, batched=True, check_calibrate=False)
 
@@ -198,7 +199,7 @@ def test_batched_with_bias_and_relu():
 @pytest.mark.parametrize("d,h,n,bits", [(1024, 4096, 256, 8), (1024, 4096, 333, 8), (512, 2048, 300, 4),
                                         (1024, 4096, 700, 4)])
 def test_prompt_path_many_tokens(d, h, n, bits):
-    """256 tokens and more: integer predictor sums, pre-activations, folded product and the masked
+    """65 tokens and more: integer predictor sums, pre-activations, folded product and the masked
     delta's down projection as four matrix products (ragged token counts span a partial tile);
     masks bit-exact, lists and counts as for every other path."""
     w = synth.decode(d=d, h=h, n_cal=512, n_test=n, coverage=0.9, config=3)
@@ -214,7 +215,8 @@ def test_prompt_path_with_bias_and_relu():
 
 
 def test_prompt_threshold_off_takes_token_passes(monkeypatch):
-    """With the prompt path's threshold out of reach the same 300 tokens run as passes of 64."""
+    """With the prompt path's threshold out of reach the same 300 tokens run as passes of 64 (four
+    full passes and a ragged last one)."""
     monkeypatch.setenv("TARDIS_PREFILL_MIN", "1000000")
     w = synth.decode(d=1024, h=4096, n_cal=512, n_test=300, coverage=0.9, config=3)
     run_case(w.layer, w.X_cal, w.X_test, 0.9, batched=True, check_calibrate=False)
@@ -483,10 +485,11 @@ def test_repeated_calls_are_stable():
 # ------------------------------------------------------------- stacked layers
 @pytest.mark.parametrize("d,h,dtype,n", [(1024, 4096, "bf16", 1), (1024, 4096, "bf16", 3), (64, 256, "f32", 2),
                                          (1024, 4096, "bf16", 12), (2048, 2048, "bf16", 8), (2048, 2048, "bf16", 16),
-                                         (2048, 2048, "bf16", 6)])
+                                         (2048, 2048, "bf16", 6), (1024, 4096, "bf16", 40), (1024, 2048, "bf16", 90)])
 def test_stack_teacher_forced(d, h, dtype, n):
     """Every layer is checked on the input the GPU itself handed to it: mask bit-exact, the
-    normalised hand-over and the final output within the y tolerance."""
+    normalised hand-over and the final output within the y tolerance.  (40 tokens: a 64-token pass
+    per layer; 90: the prompt path, whose last kernel applies the norm.)"""
     nl = 3
     layers, oracles = [], []
     x0 = synth.make_tokens(n, d, dtype, synth.workload_seed(4, 99), synth.STREAM_TEST)
