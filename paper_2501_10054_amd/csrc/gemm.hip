@@ -82,10 +82,10 @@ gemm_nt_generic_kernel(const T* __restrict__ A, const T* __restrict__ B, float* 
 // Schedule of one slice (four steps of 16 MFMAs each).  A wavefront issues in order and each SIMD
 // holds one wavefront here, so whatever is not an MFMA is placed BETWEEN the MFMAs of a step, a
 // few instructions after each, instead of after them where the matrix cores would idle:
-//   step 0   loads of slice kt+2 -> the free register set          (two slices of lead)
-//   step 1-2 the set that holds slice kt+1 -> the other LDS stage
+//   step 1-2 the register set that holds slice kt+1 -> the other LDS stage
 //   barrier
-//   step 3   already reads the first fragments of that stage
+//   step 3   reads the first fragments of that stage; loads of slice kt+3 -> the set just freed
+//            (they are written to LDS six steps later)
 // and every step reads the LDS fragments of the next one.  On MI355X this runs the fold at about
 // 0.95 PFLOP/s; what remains is the LDS traffic (each staged byte is written once and read by two
 // wavefronts: 1536 LDS cycles against 2048 MFMA cycles per slice) and the global-load path.
@@ -243,13 +243,12 @@ gemm_nt_mfma_kernel(const unsigned char* __restrict__ A0, const unsigned char* _
         __builtin_amdgcn_sched_group_barrier(0x006, alu, 0);                       \
         if (q % every == every - 1) __builtin_amdgcn_sched_group_barrier(mem, 1, 0); \
     }
-    auto phase = [&](int stage, td_u32x4 (&la)[8], td_u32x4 (&lb)[8], unsigned& lkeep, int lkt,
-                     const td_u32x4 (&sa)[8], const td_u32x4 (&sb)[8], unsigned skeep) {
+    // `sa`/`sb` (holding slice kt+1) go to the other LDS stage in steps 1-2 and are reloaded with
+    // slice kt+3 in step 3; the other register set (slice kt+2) stays in flight through the phase
+    auto phase = [&](int stage, td_u32x4 (&sa)[8], td_u32x4 (&sb)[8], unsigned& skeep, int lkt) {
         read_frags(fa[1], fb[1], stage, 1);
         __builtin_amdgcn_sched_barrier(0);
         mfma16(fa[0], fb[0]);
-        fetch(la, lb, lkeep, lkt);
-        TD_GEMM_INTERLEAVE(2, 0x020, 1)
         __builtin_amdgcn_sched_barrier(0);
         read_frags(fa[0], fb[0], stage, 2);
         __builtin_amdgcn_sched_barrier(0);
@@ -267,6 +266,8 @@ gemm_nt_mfma_kernel(const unsigned char* __restrict__ A0, const unsigned char* _
         read_frags(fa[0], fb[0], stage ^ 1, 0);
         __builtin_amdgcn_sched_barrier(0);
         mfma16(fa[1], fb[1]);
+        fetch(sa, sb, skeep, lkt);
+        TD_GEMM_INTERLEAVE(2, 0x020, 1)
         __builtin_amdgcn_sched_barrier(0);
     };
 #undef TD_GEMM_INTERLEAVE
@@ -276,14 +277,15 @@ gemm_nt_mfma_kernel(const unsigned char* __restrict__ A0, const unsigned char* _
     fetch(ra1, rb1, keep1, 1);
     stash_half(ra0, keep0, 0, 0);
     stash_half(rb0, keep0, 0, 1);
+    fetch(ra0, rb0, keep0, 2);
     __syncthreads();
     read_frags(fa[0], fb[0], 0, 0);
     int kt = 0;
     for (; kt + 1 < nk; kt += 2) {
-        phase(0, ra0, rb0, keep0, kt + 2, ra1, rb1, keep1);
-        phase(1, ra1, rb1, keep1, kt + 3, ra0, rb0, keep0);
+        phase(0, ra1, rb1, keep1, kt + 3);           // multiplies slice kt, stages slice kt+1
+        phase(1, ra0, rb0, keep0, kt + 4);           // multiplies slice kt+1, stages slice kt+2
     }
-    if (kt < nk) phase(0, ra0, rb0, keep0, kt + 2, ra1, rb1, keep1);    // odd count: the last slice
+    if (kt < nk) phase(0, ra1, rb1, keep1, kt + 3);  // odd count: the last slice
 
     // D layout of the 32x32 tile: column = lane % 32, row = 8*(r/4) + 4*(lane/32) + r%4
 #pragma unroll
