@@ -121,7 +121,9 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     L->prefill_min_tokens = env_int("TARDIS_PREFILL_MIN", 65, 17, 1 << 20);
     if (L->max_batch >= L->prefill_min_tokens && td_prefill_supported(L)) {
         char* scratch = nullptr;
-        TD_TRY(dev_alloc(&scratch, td_prefill_scratch_bytes(L, L->max_batch)));
+        L->prefill_chunk = env_int("TARDIS_PREFILL_CHUNK", 16384, 64, 32768);
+        if (L->prefill_chunk > L->max_batch) L->prefill_chunk = (int32_t)L->max_batch;
+        TD_TRY(dev_alloc(&scratch, td_prefill_scratch_bytes(L, L->prefill_chunk)));
         L->pf_scratch = scratch;
     }
     if (L->use_batched) {

@@ -75,6 +75,7 @@ struct tardis_layer_s {
     int32_t use_batched;
     void* pf_scratch;              // prompt path: int8 tokens, exponents, int32 sums, pre-activations, delta, fp32 y
     int32_t prefill_min_tokens;    // calls with at least this many tokens take the prompt path (if it has scratch)
+    int32_t prefill_chunk;         // ... in chunks of at most this many tokens (what the scratch is sized for)
     int32_t* rec_count;            // two-kernel path: flagged neurons per predictor block,
     uint32_t* rec_jb;              //   neuron index and
     uint32_t* rec_tb;              //   token bits of each record (dec_blocks x neurons per block),

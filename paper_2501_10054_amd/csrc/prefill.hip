@@ -121,8 +121,9 @@ size_t td_prefill_scratch_bytes(const tardis_layer_s* L, int64_t n) {
     return up(nn * d) + up(nn * 4) + up(nn * h * 4) + up(nn * h * 4) + up(nn * h * 2) + up(nn * d * 4);
 }
 
-tardis_status_t td_forward_prefill(tardis_layer_s* L, const void* xv, int64_t n, void* yv, int norm_out,
-                                   hipStream_t s) {
+// one chunk of at most L->prefill_chunk tokens (the scratch is sized for that many)
+static tardis_status_t prefill_chunk(tardis_layer_s* L, const bf16_t* x, int64_t n, bf16_t* y, uint32_t* mask,
+                                     int norm_out, hipStream_t s) {
     const int64_t d = L->d, h = L->h;
     auto up = [](size_t b) { return (b + 255) / 256 * 256; };
     unsigned char* p = static_cast<unsigned char*>(L->pf_scratch);
@@ -132,7 +133,6 @@ tardis_status_t td_forward_prefill(tardis_layer_s* L, const void* xv, int64_t n,
     float* z = reinterpret_cast<float*>(p);               p += up((size_t)n * h * 4);
     bf16_t* dl = reinterpret_cast<bf16_t*>(p);            p += up((size_t)n * h * 2);
     float* yacc = reinterpret_cast<float*>(p);
-    const bf16_t* x = static_cast<const bf16_t*>(xv);
     // products with few output tiles cut K into ranges that add atomically into zeroed results
     auto pick = [&](int64_t N, int64_t K) {
         const int64_t tiles = ((n + 255) / 256) * ((N + 255) / 256);
@@ -151,13 +151,26 @@ tardis_status_t td_forward_prefill(tardis_layer_s* L, const void* xv, int64_t n,
     TD_TRY(td_gemm_nt_split(x, L->W1, z, n, h, d, TARDIS_BF16, sp_z > 1, nullptr, sp_z, s));
     hipLaunchKernelGGL(delta_mask_kernel, dim3((unsigned)((h + 1023) / 1024), (unsigned)n), dim3(256), 0, s, acc, z, e,
                        L->tlo, L->thi, L->a, L->c, static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), (int)L->act,
-                       (int)h, dl, L->mask, (int)L->mask_words);
+                       (int)h, dl, mask, (int)L->mask_words);
     zero(yacc, (size_t)n * d * 4);
     TD_TRY(td_gemm_nt_split(x, L->Wp, yacc, n, d, d, TARDIS_BF16, 1, nullptr, pick(d, d * 2), s));
     TD_TRY(td_gemm_nt_split(dl, L->W2, yacc, n, d, h, TARDIS_BF16, 1, nullptr, pick(d, h * 2), s));
-    hipLaunchKernelGGL(finish_rows_kernel, dim3((unsigned)n), dim3(256), 0, s, yacc, L->bp, (int)d,
-                       static_cast<bf16_t*>(yv), norm_out, kRmsEps);
+    hipLaunchKernelGGL(finish_rows_kernel, dim3((unsigned)n), dim3(256), 0, s, yacc, L->bp, (int)d, y, norm_out,
+                       kRmsEps);
     TD_HIP(hipGetLastError());
+    return TARDIS_OK;
+}
+
+// Long prompts run in chunks of L->prefill_chunk tokens (tokens are independent): the scratch and
+// the launch grids stay bounded whatever max_batch is.
+tardis_status_t td_forward_prefill(tardis_layer_s* L, const void* xv, int64_t n, void* yv, int norm_out,
+                                   hipStream_t s) {
+    const bf16_t* x = static_cast<const bf16_t*>(xv);
+    bf16_t* y = static_cast<bf16_t*>(yv);
+    for (int64_t t0 = 0; t0 < n; t0 += L->prefill_chunk) {
+        const int64_t nc = n - t0 < L->prefill_chunk ? n - t0 : L->prefill_chunk;
+        TD_TRY(prefill_chunk(L, x + t0 * L->d, nc, y + t0 * L->d, L->mask + t0 * L->mask_words, norm_out, s));
+    }
     L->last_n = n;
     return TARDIS_OK;
 }

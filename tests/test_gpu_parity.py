@@ -214,6 +214,14 @@ def test_prompt_path_with_bias_and_relu():
     run_case(layer, X_cal, X_test, 0.9, act="relu", batched=True, check_calibrate=False)
 
 
+def test_prompt_path_in_chunks(monkeypatch):
+    """A prompt longer than the scratch is sized for runs in chunks (here 3 of 256 tokens, the last
+    one ragged); masks and outputs land at their tokens' rows."""
+    monkeypatch.setenv("TARDIS_PREFILL_CHUNK", "256")
+    w = synth.decode(d=1024, h=4096, n_cal=512, n_test=700, coverage=0.9, config=3)
+    run_case(w.layer, w.X_cal, w.X_test, 0.9, batched=True, check_calibrate=False)
+
+
 def test_prompt_threshold_off_takes_token_passes(monkeypatch):
     """With the prompt path's threshold out of reach the same 300 tokens run as passes of 64 (four
     full passes and a ragged last one)."""
