@@ -192,6 +192,7 @@ bool td_prefill_supported(const tardis_layer_s* L);
 size_t td_prefill_scratch_bytes(const tardis_layer_s* L, int64_t n);
 tardis_status_t td_forward_prefill(tardis_layer_s* L, const void* x, int64_t n, void* y, int norm_out, hipStream_t s);
 tardis_status_t td_gemm_init();
+int td_gemm_tile_rows(int64_t M);
 tardis_status_t td_gemm_nt_split(const void* A, const void* B, float* C, int64_t M, int64_t N, int64_t K, int32_t dtype,
                                  int accumulate, const void* row_bias, int splits, hipStream_t s);
 tardis_status_t td_decode_init();

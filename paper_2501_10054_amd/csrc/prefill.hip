@@ -81,12 +81,6 @@ delta_mask_kernel(const int32_t* __restrict__ ACC, const float* __restrict__ Z, 
     if ((lane & 7) == 0 && w < mask_words) mask[(size_t)t * mask_words + w] = word;
 }
 
-// (sizes are multiples of 16 bytes: d % 16 == 0 and h % 8 == 0)
-__global__ void __launch_bounds__(256) zero_f32_kernel(float4* __restrict__ p, size_t n4) {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256)
-        p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-}
-
 // y[t] = (Y[t] + b') (optionally RMS-normalised), one block per token
 __global__ void __launch_bounds__(256)
 finish_rows_kernel(const float* __restrict__ Y, const float* __restrict__ bp, int d, bf16_t* __restrict__ y,
@@ -133,27 +127,21 @@ static tardis_status_t prefill_chunk(tardis_layer_s* L, const bf16_t* x, int64_t
     float* z = reinterpret_cast<float*>(p);               p += up((size_t)n * h * 4);
     bf16_t* dl = reinterpret_cast<bf16_t*>(p);            p += up((size_t)n * h * 2);
     float* yacc = reinterpret_cast<float*>(p);
-    // products with few output tiles cut K into ranges that add atomically into zeroed results
+    // products with few output tiles cut K into ranges (added atomically) so that >= 256 blocks run
     auto pick = [&](int64_t N, int64_t K) {
-        const int64_t tiles = ((n + 255) / 256) * ((N + 255) / 256);
+        const int64_t rows = td_gemm_tile_rows(n);
+        const int64_t tiles = ((n + rows - 1) / rows) * ((N + 255) / 256);
         int sp = 1;
         while (sp < 8 && tiles * sp < 256 && K / (sp * 2) >= 1024) sp *= 2;
         return sp;
     };
-    auto zero = [&](void* p4, size_t bytes) {
-        hipLaunchKernelGGL(zero_f32_kernel, dim3(2048), dim3(256), 0, s, static_cast<float4*>(p4), bytes / 16);
-    };
     hipLaunchKernelGGL(quantize_rows_kernel, dim3((unsigned)n), dim3(256), 0, s, x, (int)d, xq, e);
-    const int sp_acc = pick(h, d), sp_z = pick(h, d * 2);   // K in bytes decides the number of slices
-    if (sp_acc > 1) zero(acc, (size_t)n * h * 4);
-    TD_TRY(td_gemm_nt_i8(xq, L->Q, acc, n, h, d, sp_acc, s));
-    if (sp_z > 1) zero(z, (size_t)n * h * 4);
-    TD_TRY(td_gemm_nt_split(x, L->W1, z, n, h, d, TARDIS_BF16, sp_z > 1, nullptr, sp_z, s));
+    TD_TRY(td_gemm_nt_i8(xq, L->Q, acc, n, h, d, pick(h, d), s));                 // K in bytes decides the slices
+    TD_TRY(td_gemm_nt_split(x, L->W1, z, n, h, d, TARDIS_BF16, 0, nullptr, pick(h, d * 2), s));
     hipLaunchKernelGGL(delta_mask_kernel, dim3((unsigned)((h + 1023) / 1024), (unsigned)n), dim3(256), 0, s, acc, z, e,
                        L->tlo, L->thi, L->a, L->c, static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), (int)L->act,
                        (int)h, dl, mask, (int)L->mask_words);
-    zero(yacc, (size_t)n * d * 4);
-    TD_TRY(td_gemm_nt_split(x, L->Wp, yacc, n, d, d, TARDIS_BF16, 1, nullptr, pick(d, d * 2), s));
+    TD_TRY(td_gemm_nt_split(x, L->Wp, yacc, n, d, d, TARDIS_BF16, 0, nullptr, pick(d, d * 2), s));
     TD_TRY(td_gemm_nt_split(dl, L->W2, yacc, n, d, h, TARDIS_BF16, 1, nullptr, pick(d, h * 2), s));
     hipLaunchKernelGGL(finish_rows_kernel, dim3((unsigned)n), dim3(256), 0, s, yacc, L->bp, (int)d, y, norm_out,
                        kRmsEps);
