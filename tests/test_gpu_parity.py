@@ -453,6 +453,35 @@ def test_graph_capture_and_replay_of_forward():
     L.close()
 
 
+@pytest.mark.parametrize("n", [40, 100, 300])
+def test_graph_capture_of_pass_and_prompt_paths(n):
+    """40 tokens (one 64-token pass), 100 (short-tile products that add atomically into results the
+    library zeroes itself) and 300 (square tiles, K in ranges): captured once, replayed three
+    times with eager work in between; every replay reproduces the eager call, masks bit for bit."""
+    w = synth.decode(d=1024, h=4096, n_cal=256, n_test=n, coverage=0.9, config=9)
+    ffn = make_ffn(w.layer)
+    lo, hi, a, c = T.tardis_calibrate(ffn, dev(w.X_cal, "bf16"), 0.9)
+    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=n)
+    X = dev(w.X_test, "bf16")
+    y_eager = T.tardis_ffn_forward_batched(L, X).clone()
+    mask_eager = T.tardis_get_last_outliers(L, n, want_list=False)[0].clone()
+    torch.cuda.synchronize()
+    y_g = torch.zeros_like(y_eager)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        T.tardis_ffn_forward_batched(L, X, y_g)
+    for rep in range(3):
+        y_g.zero_()
+        T.tardis_ffn_forward_batched(L, torch.roll(X, 1, 0).contiguous())   # eager work on other tokens in between
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert rel_l2(host(y_g), host(y_eager)) < 2e-3, rep       # atomic ordering only
+        mask = T.tardis_get_last_outliers(L, n, want_list=False)[0]   # the replay's masks
+        assert torch.equal(mask, mask_eager), rep
+    L.close()
+
+
 def test_runtime_argument_errors():
     w = synth.tiny()
     ffn = make_ffn(w.layer)
