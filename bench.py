@@ -80,6 +80,7 @@ def prefill_run(T, synth, torch, np, to_dev):
     W1, W2 = ffn.W1, ffn.W2
     dus = _time_us(torch, lambda: torch.nn.functional.linear(
         torch.nn.functional.gelu(torch.nn.functional.linear(X, W1)), W2), 5, 1)
+    dus_own = _time_us(torch, lambda: T.tardis_dense_forward(L, X, Y), 5, 1)
     L.close()
     gemm_flop = 2.0 * D * D * H          # one of the two accumulating fold GEMMs, or the calibration GEMM
     work = 2.0 * n * D * D + 3 * 2.0 * n * D * H      # folded + int8 predictor + pre-activations + down projection
@@ -87,6 +88,7 @@ def prefill_run(T, synth, torch, np, to_dev):
             "matrix_core_Tops": work / us / 1e6, "us_256_tokens": us256,
             "dense_torch_us": dus, "dense_torch_TFLOPs": (2.0 * 2 * n * D * H) / dus / 1e6,
             "speedup_vs_dense_torch": dus / us,
+            "dense_own_us": dus_own, "dense_own_TFLOPs": (2.0 * 2 * n * D * H) / dus_own / 1e6,
             "calibrate_us": cal_us, "fold_ms_incl_alloc": fold_ms,
             "note": "fold = 2 bf16 MFMA GEMMs of %.0f GFLOP each (head + remainder of diag(a)W1); "
                     "calibrate = 1 such GEMM + per-neuron sort/fit" % (gemm_flop / 1e9)}

@@ -193,7 +193,8 @@ tardis_status_t tardis_stack_forward(const tardis_handle_t* layers, int32_t n_la
                                      int64_t n, void* y, void* stream);
 
 /* The unmodified FFN, y = W2 sigma(W1 x + b1) + b2, on the same streaming
- * kernels: the dense baseline the folded path is measured against.
+ * kernels: the dense baseline the folded path is measured against (from 65
+ * tokens on, two matrix-core products, as for the folded path's prompts).
  * 1 <= n <= max_batch.  x, y: n x d. */
 tardis_status_t tardis_dense_forward(tardis_handle_t L, const void* x, int64_t n, void* y,
                                      void* stream);

@@ -556,28 +556,28 @@ size_t td_batched_partial_floats(const tardis_layer_s* L) {
 
 // the streaming kernels use more than the default 64 KiB of dynamic LDS
 tardis_status_t td_batched_init() {
-    static bool done = false;
-    if (done) return TARDIS_OK;
-    TD_HIP((allow_big_lds(fold_predict_batched_kernel<1, 0, 0>)));
-    TD_HIP((allow_big_lds(fold_predict_batched_kernel<2, 0, 0>)));
-    TD_HIP((allow_big_lds(fold_predict_batched_kernel<4, 0, 0>)));
-    TD_HIP((allow_big_lds(fold_predict_batched_kernel<1, 16, 8>)));
-    TD_HIP((allow_big_lds(fold_predict_batched_kernel<2, 16, 8>)));
-    TD_HIP((allow_big_lds(fold_predict_batched_kernel<4, 16, 8>)));
-    TD_HIP((allow_big_lds(stream_kernel<1, EPI_DELTA, 0>)));
-    TD_HIP((allow_big_lds(stream_kernel<2, EPI_DELTA, 0>)));
-    TD_HIP((allow_big_lds(stream_kernel<4, EPI_DELTA, 0>)));
-    TD_HIP((allow_big_lds(stream_kernel<1, EPI_DELTA, 16>)));
-    TD_HIP((allow_big_lds(stream_kernel<2, EPI_DELTA, 16>)));
-    TD_HIP((allow_big_lds(stream_kernel<4, EPI_DELTA, 16>)));
-    TD_HIP((allow_big_lds(stream_kernel<1, EPI_DOWN, 0>)));
-    TD_HIP((allow_big_lds(stream_kernel<2, EPI_DOWN, 0>)));
-    TD_HIP((allow_big_lds(stream_kernel<4, EPI_DOWN, 0>)));
-    TD_HIP((allow_big_lds(stream_kernel<1, EPI_DOWN, 8>)));
-    TD_HIP((allow_big_lds(stream_kernel<2, EPI_DOWN, 8>)));
-    TD_HIP((allow_big_lds(stream_kernel<4, EPI_DOWN, 8>)));
-    done = true;
-    return TARDIS_OK;
+    static td_once once;
+    return once.run([]() -> tardis_status_t {
+        TD_HIP((allow_big_lds(fold_predict_batched_kernel<1, 0, 0>)));
+        TD_HIP((allow_big_lds(fold_predict_batched_kernel<2, 0, 0>)));
+        TD_HIP((allow_big_lds(fold_predict_batched_kernel<4, 0, 0>)));
+        TD_HIP((allow_big_lds(fold_predict_batched_kernel<1, 16, 8>)));
+        TD_HIP((allow_big_lds(fold_predict_batched_kernel<2, 16, 8>)));
+        TD_HIP((allow_big_lds(fold_predict_batched_kernel<4, 16, 8>)));
+        TD_HIP((allow_big_lds(stream_kernel<1, EPI_DELTA, 0>)));
+        TD_HIP((allow_big_lds(stream_kernel<2, EPI_DELTA, 0>)));
+        TD_HIP((allow_big_lds(stream_kernel<4, EPI_DELTA, 0>)));
+        TD_HIP((allow_big_lds(stream_kernel<1, EPI_DELTA, 16>)));
+        TD_HIP((allow_big_lds(stream_kernel<2, EPI_DELTA, 16>)));
+        TD_HIP((allow_big_lds(stream_kernel<4, EPI_DELTA, 16>)));
+        TD_HIP((allow_big_lds(stream_kernel<1, EPI_DOWN, 0>)));
+        TD_HIP((allow_big_lds(stream_kernel<2, EPI_DOWN, 0>)));
+        TD_HIP((allow_big_lds(stream_kernel<4, EPI_DOWN, 0>)));
+        TD_HIP((allow_big_lds(stream_kernel<1, EPI_DOWN, 8>)));
+        TD_HIP((allow_big_lds(stream_kernel<2, EPI_DOWN, 8>)));
+        TD_HIP((allow_big_lds(stream_kernel<4, EPI_DOWN, 8>)));
+        return TARDIS_OK;
+    });
 }
 
 tardis_status_t td_forward_batched(tardis_layer_s* L, const void* xv, int64_t n, void* yv, int norm_out,

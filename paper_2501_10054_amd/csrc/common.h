@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/tardis.h"
 
 typedef uint16_t bf16_t;  // raw bfloat16 bits
@@ -26,6 +28,20 @@ constexpr float kRmsEps = 1e-6f;
         tardis_status_t s__ = (expr);         \
         if (s__ != TARDIS_OK) return s__;     \
     } while (0)
+
+// One-time set-up that may be reached from several host threads (kernel attributes are raised
+// when the first layer is folded): `fn` runs under a lock until it has succeeded once.
+struct td_once {
+    std::mutex lock;
+    bool done = false;
+    template <typename F> tardis_status_t run(F fn) {
+        std::lock_guard<std::mutex> guard(lock);
+        if (done) return TARDIS_OK;
+        const tardis_status_t st = fn();
+        if (st == TARDIS_OK) done = true;
+        return st;
+    }
+};
 
 // Everything one folded layer owns.  Pointers are device memory.
 struct tardis_layer_s {
@@ -191,6 +207,7 @@ tardis_status_t td_gemm_nt_i8(const int8_t* A, const int8_t* B, int32_t* C, int6
 bool td_prefill_supported(const tardis_layer_s* L);
 size_t td_prefill_scratch_bytes(const tardis_layer_s* L, int64_t n);
 tardis_status_t td_forward_prefill(tardis_layer_s* L, const void* x, int64_t n, void* y, int norm_out, hipStream_t s);
+tardis_status_t td_dense_prefill(tardis_layer_s* L, const void* x, int64_t n, void* y, hipStream_t s);
 tardis_status_t td_gemm_init();
 int td_gemm_tile_rows(int64_t M);
 tardis_status_t td_gemm_nt_split(const void* A, const void* B, float* C, int64_t M, int64_t N, int64_t K, int32_t dtype,

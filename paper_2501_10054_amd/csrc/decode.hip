@@ -1019,19 +1019,19 @@ template <typename K> hipError_t allow_lds(K kernel, size_t bytes) {
 // Kernels whose dynamic LDS exceeds the default limit are enabled once, when the first layer is
 // folded (not at launch: a launch may be under stream capture).
 tardis_status_t td_decode_init() {
-    static bool done = false;
-    if (done) return TARDIS_OK;
-    TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 4>, (size_t)8 * 4096 * 3 + 256));
-    TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 2>, (size_t)8 * 4096 * 3 + 256));
-    TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 4>, (size_t)16 * (4096 + 8) * 2));
-    TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 2>, (size_t)16 * (4096 + 8) * 2));
-    TD_HIP(allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 4>, (size_t)16 * (2048 + 8) * 2));
-    TD_HIP(allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 2>, (size_t)16 * (2048 + 8) * 2));
-    TD_HIP(allow_lds((down_project_kernel<4, 256>), (size_t)16 * 4 * 256 * sizeof(float)));
-    TD_HIP(allow_lds((down_project_kernel<8, 256>), (size_t)16 * 8 * 256 * sizeof(float)));
-    TD_HIP(allow_lds((down_project_kernel<16, 128>), (size_t)16 * 16 * 128 * sizeof(float)));
-    done = true;
-    return TARDIS_OK;
+    static td_once once;
+    return once.run([]() -> tardis_status_t {
+        TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 4>, (size_t)8 * 4096 * 3 + 256));
+        TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 2>, (size_t)8 * 4096 * 3 + 256));
+        TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 4>, (size_t)16 * (4096 + 8) * 2));
+        TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 2>, (size_t)16 * (4096 + 8) * 2));
+        TD_HIP(allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 4>, (size_t)16 * (2048 + 8) * 2));
+        TD_HIP(allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 2>, (size_t)16 * (2048 + 8) * 2));
+        TD_HIP(allow_lds((down_project_kernel<4, 256>), (size_t)16 * 4 * 256 * sizeof(float)));
+        TD_HIP(allow_lds((down_project_kernel<8, 256>), (size_t)16 * 8 * 256 * sizeof(float)));
+        TD_HIP(allow_lds((down_project_kernel<16, 128>), (size_t)16 * 16 * 128 * sizeof(float)));
+        return TARDIS_OK;
+    });
 }
 
 bool td_decode_fused_supported(const tardis_layer_s* L) {

@@ -305,5 +305,6 @@ tardis_status_t td_forward(tardis_layer_s* L, const void* x, int64_t n, void* y,
 }
 
 tardis_status_t td_dense_forward(tardis_layer_s* L, const void* x, int64_t n, void* y, hipStream_t s) {
+    if (L->pf_scratch && n >= L->prefill_min_tokens) return td_dense_prefill(L, x, n, y, s);
     return L->dtype == TARDIS_BF16 ? dense_t<bf16_t>(L, x, n, y, s) : dense_t<float>(L, x, n, y, s);
 }

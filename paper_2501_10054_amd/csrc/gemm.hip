@@ -370,22 +370,22 @@ bool gemm_force_generic() {
 
 // the matrix-core kernels use more LDS than the default limit; raised once, outside any stream capture
 tardis_status_t td_gemm_init() {
-    static bool done = false;
-    if (done) return TARDIS_OK;
-    struct { const void* fn; int lds; } kernels[] = {
-        {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, false, false, 4>), mfma_lds_bytes(4)},
-        {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, false, true, 4>), mfma_lds_bytes(4)},
-        {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, true, false, 4>), mfma_lds_bytes(4)},
-        {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<true, false, false, 4>), mfma_lds_bytes(4)},
-        {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<true, true, false, 4>), mfma_lds_bytes(4)},
-        {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, true, false, 2>), mfma_lds_bytes(2)},
-        {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<true, true, false, 2>), mfma_lds_bytes(2)},
-        {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, true, false, 1>), mfma_lds_bytes(1)},
-        {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<true, true, false, 1>), mfma_lds_bytes(1)}};
-    for (const auto& k : kernels)
-        TD_HIP(hipFuncSetAttribute(k.fn, hipFuncAttributeMaxDynamicSharedMemorySize, k.lds));
-    done = true;
-    return TARDIS_OK;
+    static td_once once;
+    return once.run([]() -> tardis_status_t {
+        struct { const void* fn; int lds; } kernels[] = {
+            {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, false, false, 4>), mfma_lds_bytes(4)},
+            {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, false, true, 4>), mfma_lds_bytes(4)},
+            {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, true, false, 4>), mfma_lds_bytes(4)},
+            {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<true, false, false, 4>), mfma_lds_bytes(4)},
+            {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<true, true, false, 4>), mfma_lds_bytes(4)},
+            {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, true, false, 2>), mfma_lds_bytes(2)},
+            {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<true, true, false, 2>), mfma_lds_bytes(2)},
+            {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<false, true, false, 1>), mfma_lds_bytes(1)},
+            {reinterpret_cast<const void*>(gemm_nt_mfma_kernel<true, true, false, 1>), mfma_lds_bytes(1)}};
+        for (const auto& k : kernels)
+            TD_HIP(hipFuncSetAttribute(k.fn, hipFuncAttributeMaxDynamicSharedMemorySize, k.lds));
+        return TARDIS_OK;
+    });
 }
 
 // rows of the output tile the matrix-core kernel uses for a product with M rows

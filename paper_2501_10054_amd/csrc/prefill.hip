@@ -103,6 +103,36 @@ finish_rows_kernel(const float* __restrict__ Y, const float* __restrict__ bp, in
     for (int k = threadIdx.x; k < d; k += 256) y[(size_t)t * d + k] = td_f32_to_bf16((row[k] + bp[k]) * scale);
 }
 
+// dense FFN, hidden activations: H = act(Z + b1), rounded to bf16 (4 neurons per thread)
+__global__ void __launch_bounds__(256)
+dense_hidden_kernel(const float* __restrict__ Z, const bf16_t* __restrict__ b1, int act, int h,
+                    bf16_t* __restrict__ H) {
+    const int t = blockIdx.y;
+    const int j = ((int)blockIdx.x * 256 + (int)threadIdx.x) * 4;
+    if (j >= h) return;
+    const size_t at = (size_t)t * h + j;
+    const float4 z4 = *reinterpret_cast<const float4*>(Z + at);
+    const uint2 braw = *reinterpret_cast<const uint2*>(b1 + j);
+    const float zv[4] = {z4.x, z4.y, z4.z, z4.w};
+    const float bv[4] = {__uint_as_float(braw.x << 16), __uint_as_float(braw.x & 0xffff0000u),
+                         __uint_as_float(braw.y << 16), __uint_as_float(braw.y & 0xffff0000u)};
+    bf16_t out[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) out[u] = td_f32_to_bf16(td_act(zv[u] + bv[u], act));
+    uint2 packed;
+    packed.x = (uint32_t)out[0] | ((uint32_t)out[1] << 16);
+    packed.y = (uint32_t)out[2] | ((uint32_t)out[3] << 16);
+    *reinterpret_cast<uint2*>(H + at) = packed;
+}
+
+// dense FFN, output: y[t] = Y[t] + b2 (b2 may be null), one block per token
+__global__ void __launch_bounds__(256)
+dense_output_kernel(const float* __restrict__ Y, const bf16_t* __restrict__ b2, int d, bf16_t* __restrict__ y) {
+    const int t = blockIdx.x;
+    for (int k = threadIdx.x; k < d; k += 256)
+        y[(size_t)t * d + k] = td_f32_to_bf16(Y[(size_t)t * d + k] + (b2 ? td_bf16_to_f32(b2[k]) : 0.0f));
+}
+
 }  // namespace
 
 bool td_prefill_supported(const tardis_layer_s* L) {
@@ -160,5 +190,36 @@ tardis_status_t td_forward_prefill(tardis_layer_s* L, const void* xv, int64_t n,
         TD_TRY(prefill_chunk(L, x + t0 * L->d, nc, y + t0 * L->d, L->mask + t0 * L->mask_words, norm_out, s));
     }
     L->last_n = n;
+    return TARDIS_OK;
+}
+
+// The unmodified FFN on many tokens: two matrix-core products with the activation between them
+// (the hidden activations are rounded to bf16, as the per-token dense kernels round them).
+tardis_status_t td_dense_prefill(tardis_layer_s* L, const void* xv, int64_t n, void* yv, hipStream_t s) {
+    const int64_t d = L->d, h = L->h;
+    auto up = [](size_t b) { return (b + 255) / 256 * 256; };
+    for (int64_t t0 = 0; t0 < n; t0 += L->prefill_chunk) {
+        const int64_t nc = n - t0 < L->prefill_chunk ? n - t0 : L->prefill_chunk;
+        unsigned char* p = static_cast<unsigned char*>(L->pf_scratch) + up((size_t)nc * d) + up((size_t)nc * 4) +
+                           up((size_t)nc * h * 4);                        // (the layout of prefill_chunk)
+        float* z = reinterpret_cast<float*>(p);               p += up((size_t)nc * h * 4);
+        bf16_t* hid = reinterpret_cast<bf16_t*>(p);           p += up((size_t)nc * h * 2);
+        float* yacc = reinterpret_cast<float*>(p);
+        const bf16_t* x = static_cast<const bf16_t*>(xv) + t0 * d;
+        auto pick = [&](int64_t N, int64_t K) {
+            const int64_t rows = td_gemm_tile_rows(nc);
+            const int64_t tiles = ((nc + rows - 1) / rows) * ((N + 255) / 256);
+            int sp = 1;
+            while (sp < 8 && tiles * sp < 256 && K / (sp * 2) >= 1024) sp *= 2;
+            return sp;
+        };
+        TD_TRY(td_gemm_nt_split(x, L->W1, z, nc, h, d, TARDIS_BF16, 0, nullptr, pick(h, d * 2), s));
+        hipLaunchKernelGGL(dense_hidden_kernel, dim3((unsigned)((h + 1023) / 1024), (unsigned)nc), dim3(256), 0, s, z,
+                           static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), (int)L->act, (int)h, hid);
+        TD_TRY(td_gemm_nt_split(hid, L->W2, yacc, nc, d, h, TARDIS_BF16, 0, nullptr, pick(d, h * 2), s));
+        hipLaunchKernelGGL(dense_output_kernel, dim3((unsigned)nc), dim3(256), 0, s, yacc,
+                           static_cast<const bf16_t*>(L->b2), (int)d, static_cast<bf16_t*>(yv) + t0 * d);
+    }
+    TD_HIP(hipGetLastError());
     return TARDIS_OK;
 }
