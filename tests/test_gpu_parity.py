@@ -197,11 +197,14 @@ def test_batched_with_bias_and_relu():
 
 # ------------------------------------------------------------- prompt path (dense matrix products)
 @pytest.mark.parametrize("d,h,n,bits", [(1024, 4096, 256, 8), (1024, 4096, 333, 8), (512, 2048, 300, 4),
-                                        (1024, 4096, 700, 4)])
+                                        (1024, 4096, 700, 4), (384, 1152, 200, 8), (384, 1160, 66, 8),
+                                        (640, 1992, 129, 8)])
 def test_prompt_path_many_tokens(d, h, n, bits):
     """65 tokens and more: integer predictor sums, pre-activations, folded product and the masked
     delta's down projection as four matrix products (ragged token counts span a partial tile);
-    masks bit-exact, lists and counts as for every other path."""
+    masks bit-exact, lists and counts as for every other path.  d = 384 and 640: odd numbers of K
+    slices (3 and 5 of int8, 9 per range of the down projection); h = 1160, 1992: a ragged last
+    tile column and a K of the down projection that is no multiple of the slice."""
     w = synth.decode(d=d, h=h, n_cal=512, n_test=n, coverage=0.9, config=3)
     run_case(w.layer, w.X_cal, w.X_test, 0.9, batched=True, check_calibrate=False, sketch_bits=bits)
 
