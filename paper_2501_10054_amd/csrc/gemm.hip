@@ -1,9 +1,13 @@
-// C[m][n] = sum_k A[m][k] * B[n][k]  -- both operands K-contiguous ("NT"), C fp32.
+// C[m][n] = sum_k A[m][k] * B[n][k]  -- both operands K-contiguous ("NT"); C fp32 (bf16 or fp32
+// operands) or exact int32 (int8 operands).
 //
 // Used offline: the fold  W' = W2 . (diag(a) W1)  (Sec. "Constant Folded Matrix
 // Generation") with A = W2 (d x h) and B = (diag(a) W1)^T (d x h), and the
 // calibration pre-activations Z^T = W1 . X_cal^T (Sec. "Non-linear Function
-// Approximation", step 2) with A = W1 (h x d) and B = X_cal (n x d).
+// Approximation", step 2) with A = W1 (h x d) and B = X_cal (n x d).  Used online for calls with
+// many tokens (prompts), where every step of the method is a product of the token matrix with a
+// weight matrix: predictor sums Xq . Q^T (int8), pre-activations X . W1^T, folded product X . W'^T
+// and the down projection of the masked delta.
 #include <cstdlib>
 #include <type_traits>
 
@@ -87,7 +91,7 @@ gemm_nt_generic_kernel(const T* __restrict__ A, const T* __restrict__ B, float* 
 //   step 3   reads the first fragments of that stage; loads of slice kt+3 -> the set just freed
 //            (they are written to LDS six steps later)
 // and every step reads the LDS fragments of the next one.  On MI355X this runs the fold at about
-// 0.95 PFLOP/s; what remains is the LDS traffic (each staged byte is written once and read by two
+// 1 PFLOP/s; what remains is the LDS traffic (each staged byte is written once and read by two
 // wavefronts: 1536 LDS cycles against 2048 MFMA cycles per slice) and the global-load path.
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
