@@ -118,7 +118,7 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     if (byte_codes) TD_TRY(dev_alloc(&L->Q, (size_t)h * d));
     if (packed4) TD_TRY(dev_alloc(&L->Q4, (size_t)h * d / 2));
     if (L->sketch_bits == 4) TD_TRY(dev_alloc(&L->M4, (size_t)h * ((d + 31) / 32)));
-    L->prefill_min_tokens = env_int("TARDIS_PREFILL_MIN", 65, 17, 1 << 20);
+    L->prefill_min_tokens = env_int("TARDIS_PREFILL_MIN", 65, 33, 1 << 20);
     if (L->max_batch >= L->prefill_min_tokens && td_prefill_supported(L)) {
         char* scratch = nullptr;
         L->prefill_chunk = env_int("TARDIS_PREFILL_CHUNK", 16384, 64, 32768);
