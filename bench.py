@@ -29,7 +29,9 @@ TOKENS_PER_STEP = 1024
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of decode_fused_kernel from `rocprofv3 --pmc` (FETCH_SIZE and WRITE_SIZE runs,
 # scaled by a copy kernel of known size); see profiles/*hbm-traffic.md.
-MEASURED_TRAFFIC_BYTES = {8: 119074161, 4: 88663441}     # by sketch width
+MEASURED_TRAFFIC_BYTES = {8: 133046911, 4: 102575216}     # by sketch width, with the next-layer hint (the
+# requested rows cross the fabric twice: once ahead of time, once - from the last-level cache - when used)
+MEASURED_TRAFFIC_BYTES_NO_HINT = {8: 119111012, 4: 88642936}
 
 
 def algorithmic_bytes(d: int, h: int, p: float, sketch_bits: int = 8) -> float:
@@ -196,6 +198,8 @@ def main() -> int:
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the figures beside the headline one (batched decode at the headline coverage, 4-bit sketch, prompt shape)")
+    ap.add_argument("--no-chain", action="store_true",
+                    help="do not tell each layer copy which copy runs next (no cache-warming hint)")
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of a replayed HIP graph")
     ap.add_argument("--sweep", action="store_true",
                     help="also run the batched decode sweep: batch {2,4,8,16,64} x coverage {0.99,0.95,0.85}")
@@ -313,6 +317,14 @@ def main() -> int:
     p = float(np.mean(rates))
 
     use_graph = not args.no_graph
+    # The timed loop walks the layer copies in a fixed order, as a model walks its layers: each
+    # copy names the one that follows (tardis_set_next_layer), so a launch spends its idle tail
+    # requesting the next copy's first predictor rows.  The figure without the hint is kept beside it.
+    plain_ms = None
+    if not args.no_chain and len(layers) > 1:
+        plain_ms, _ = timed(handles, max(2, args.steps // 2), 1, graph=use_graph)
+        for i, L in enumerate(layers):
+            T.tardis_set_next_layer(L, layers[(i + 1) % len(layers)])
     cold_ms, cold_wall = timed(handles, args.steps, args.warmup, graph=use_graph)
     hot_ms, _ = timed(handles[:1], max(2, args.steps // 2), 1, graph=use_graph)
     stream_ms = None
@@ -378,17 +390,22 @@ def main() -> int:
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": "decode single layer d=4096 ffn=16384 bf16, batch 1, 1024 tokens/step, "
-                               f"cold over {args.layers} seeded layer copies", "coverage_t": args.coverage,
+                               f"cold over {args.layers} seeded layer copies"
+                               + (", each copy naming the next (cache-warming hint)" if plain_ms else ""),
+                   "coverage_t": args.coverage,
                    "measured_fallback_rate": p, "tokens_per_step": TOKENS_PER_STEP,
                    "sketch_bits": args.sketch_bits},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES[args.sketch_bits],
+                     "traffic": (MEASURED_TRAFFIC_BYTES if plain_ms else MEASURED_TRAFFIC_BYTES_NO_HINT)[args.sketch_bits],
                      "kernel": "decode_fused_kernel", "algorithmic_bytes_per_launch": bytes_tok,
                      "avg_launch_us": launch_s * 1e6},
         "cpu_baseline": cpu,
         "hot": {"tokens_per_s": TOKENS_PER_STEP / (hot_ms * 1e-3),
                 "GBs": bytes_tok / (hot_ms * 1e-3 / TOKENS_PER_STEP) / 1e9},
+        "without_next_layer_hint": ({"tokens_per_s": TOKENS_PER_STEP / (plain_ms * 1e-3),
+                                     "us_per_token": plain_ms * 1e3 / TOKENS_PER_STEP,
+                                     "GBs": bytes_tok / (plain_ms * 1e-3 / TOKENS_PER_STEP) / 1e9} if plain_ms else None),
         "launch_mode": "hip graph replay (one graph = one 1024-token step)" if use_graph else "stream",
         "stream_launch_tokens_per_s": (TOKENS_PER_STEP / (stream_ms * 1e-3)) if stream_ms else None,
         "host_wall_ms_per_step": cold_wall,
@@ -402,6 +419,9 @@ def main() -> int:
         # the same decode loop with the 4-bit sketch (same layers, same ranges and lines)
         l4 = [T.tardis_fold(L.ffn, *cal, max_batch=1, sketch_bits=4) for L, cal in zip(layers, cals)]
         h4 = [L.handle for L in l4]
+        if plain_ms:
+            for i, L in enumerate(l4):
+                T.tardis_set_next_layer(L, l4[(i + 1) % len(l4)])
         step(h4[:1])
         torch.cuda.synchronize()
         r4 = []

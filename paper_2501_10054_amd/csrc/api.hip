@@ -2,7 +2,9 @@
 // dispatch.  No kernel lives here.
 #include <cmath>
 #include <cstdlib>
+#include <mutex>
 #include <new>
+#include <unordered_set>
 
 #include "common.h"
 
@@ -14,6 +16,11 @@ constexpr int64_t kMaxCal = 32768;        // one neuron's samples are sorted in 
 constexpr int64_t kMaxSearchCal = 8192;   // range search also keeps sigma of every sample there, in fp64
 constexpr int64_t kMaxBatch = 4096;
 constexpr size_t kTokenLdsCap = 60 * 1024;
+
+// Live handles: a layer may name the layer that runs after it (a hint for cache warming); before
+// that pointer is used it is looked up here, so that a hint to a destroyed layer is ignored.
+std::mutex g_live_lock;
+std::unordered_set<const tardis_layer_s*> g_live;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -96,6 +103,7 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     L->dec_threads = env_int("TARDIS_DECODE_THREADS", 1024, 512, 1024) == 512 ? 512 : 1024;
     L->dec_blocks = env_int("TARDIS_DECODE_BLOCKS", L->dec_threads == 512 ? 512 : 256, 1, 4096);
     L->dec_copies = env_int("TARDIS_DECODE_COPIES", 2, 1, 4);
+    L->prefetch_bytes = env_int("TARDIS_PREFETCH_KB", 96, 0, 256) * 1024;
     TD_TRY(dev_alloc(&L->yfix, (size_t)L->dec_copies * kDecodeMaxTokens * d * 4));
     TD_HIP(hipMemsetAsync(L->yfix, 0, (size_t)L->dec_copies * kDecodeMaxTokens * d * 4, s));
     L->use_fused = env_int("TARDIS_DECODE_FUSED", 1, 0, 1) && td_decode_fused_supported(L);
@@ -154,6 +162,11 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
 
 }  // namespace
 
+bool td_layer_is_live(const tardis_layer_s* L) {
+    std::lock_guard<std::mutex> guard(g_live_lock);
+    return g_live.count(L) != 0;
+}
+
 extern "C" {
 
 tardis_status_t tardis_calibrate(const tardis_ffn_desc* desc, const void* X_cal, int64_t n_cal, float coverage,
@@ -201,7 +214,19 @@ tardis_status_t tardis_fold(const tardis_ffn_desc* desc, const float* lo, const 
         free_layer(L);
         return st;
     }
+    {
+        std::lock_guard<std::mutex> guard(g_live_lock);
+        g_live.insert(L);
+    }
     *out = L;
+    return TARDIS_OK;
+}
+
+tardis_status_t tardis_set_next_layer(tardis_handle_t L, tardis_handle_t next) {
+    if (!L || !td_layer_is_live(L)) return TARDIS_ERR_STATE;
+    if (L == next) return TARDIS_ERR_INVALID_ARG;
+    if (next && !td_layer_is_live(next)) return TARDIS_ERR_STATE;
+    L->next_layer = next;
     return TARDIS_OK;
 }
 
@@ -232,7 +257,11 @@ tardis_status_t tardis_stack_forward(const tardis_handle_t* layers, int32_t n_la
     for (int32_t l = 0; l < n_layers; ++l) {
         const bool last = l == n_layers - 1;
         void* out = last ? y : layers[l]->xnext;
-        TD_TRY(td_forward(layers[l], cur, n, out, last ? 0 : 1, s));
+        const tardis_layer_s* keep = layers[l]->next_layer;
+        if (!last) layers[l]->next_layer = layers[l + 1];        // the stack knows what runs next
+        const tardis_status_t st = td_forward(layers[l], cur, n, out, last ? 0 : 1, s);
+        layers[l]->next_layer = keep;
+        TD_TRY(st);
         cur = out;
     }
     return TARDIS_OK;
@@ -296,6 +325,10 @@ tardis_status_t tardis_get_handover(tardis_handle_t L, int64_t n, void* out, voi
 }
 
 tardis_status_t tardis_destroy(tardis_handle_t L) {
+    if (L) {
+        std::lock_guard<std::mutex> guard(g_live_lock);
+        g_live.erase(L);
+    }
     free_layer(L);
     return TARDIS_OK;
 }

@@ -76,6 +76,8 @@ struct tardis_layer_s {
     void* zeros_h;     // h zero elements of the layer dtype (stands in for a missing b1)
     void* xnext;       // max_batch x d, layer dtype: normalised output handed to the next stacked layer
     float* yfix;       // dec_copies x kDecodeMaxTokens x d fp32 repair accumulators of the fused decode kernel (zero between calls)
+    const tardis_layer_s* next_layer;   // the layer that runs after this one (hint, may be null; not owned)
+    int32_t prefetch_bytes;             // bytes of that layer's predictor rows each finished block requests
     int32_t dec_blocks;   // grid of the fused decode kernel
     int32_t dec_threads;  // block size of the fused decode kernel (512 or 1024)
     int32_t dec_copies;   // number of repair accumulator copies
@@ -208,6 +210,7 @@ bool td_prefill_supported(const tardis_layer_s* L);
 size_t td_prefill_scratch_bytes(const tardis_layer_s* L, int64_t n);
 tardis_status_t td_forward_prefill(tardis_layer_s* L, const void* x, int64_t n, void* y, int norm_out, hipStream_t s);
 tardis_status_t td_dense_prefill(tardis_layer_s* L, const void* x, int64_t n, void* y, hipStream_t s);
+bool td_layer_is_live(const tardis_layer_s* L);
 tardis_status_t td_gemm_init();
 int td_gemm_tile_rows(int64_t M);
 tardis_status_t td_gemm_nt_split(const void* A, const void* B, float* C, int64_t M, int64_t N, int64_t K, int32_t dtype,

@@ -14,6 +14,8 @@
 // into one of K accumulator copies.  The last block to finish (a device
 // counter) adds the copies to the speculative result, converts to bf16, and
 // re-arms the accumulators and the counter for the next call.
+#include <cstdlib>
+
 #include "common.h"
 #include "rowdot.h"
 
@@ -57,6 +59,21 @@ struct DeferOut {
     int cap;           // record slots per block (= neurons per block)
 };
 
+// A block that has finished while the rest of the launch drains (atomics, the last block's
+// assembly) requests `bytes` (whole 16-byte vectors, >= 16) of rows it will read first in the
+// launch that follows - the predictor rows of its block index in the next layer.  The values are
+// discarded; the point is that they sit in cache when that launch asks for them.
+template <int BLOCK>
+__device__ __forceinline__ void warm_rows(const unsigned char* __restrict__ p, int bytes, int tid) {
+    constexpr int PFU = 256 * 1024 / (BLOCK * 16);   // up to 256 KB per block
+    td_u32x4 v[PFU];
+#pragma unroll
+    for (int u = 0; u < PFU; ++u)                    // past the limit: re-read the last vector
+        v[u] = *reinterpret_cast<const td_u32x4*>(p + min((u * BLOCK + tid) * 16, bytes - 16));
+#pragma unroll
+    for (int u = 0; u < PFU; ++u) asm volatile("" ::"v"(v[u]));
+}
+
 //
 // NG > 0 (8 tokens): the predictor rows go through the int8 matrix cores instead of packed dot
 // products: the block's rows form NG groups of 16, each group is shared by NW/NG wavefronts that
@@ -72,7 +89,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                     const float* __restrict__ c, const bf16_t* __restrict__ x, bf16_t* __restrict__ y,
                     float* __restrict__ yfold, float* __restrict__ yfix, int copies, uint32_t* __restrict__ mask,
                     int mask_words, int32_t* __restrict__ done, int h, int npb, int rpb, int act, int norm_out,
-                    float eps, DeferOut rec, int n_act) {
+                    float eps, DeferOut rec, int n_act, const unsigned char* __restrict__ pf_rows, int pf_bytes) {
     // n_act <= TB tokens are real: the remaining slots of the group repeat the last real token and
     // none of their results reaches the caller's buffers
     static_assert(D % 1024 == 0, "rows must be whole multiples of 64 lanes x 16 bytes");
@@ -613,7 +630,13 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     if (tid == 0)
         is_last = (__hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1);
     __syncthreads();
-    if (!is_last) return;
+    if (!is_last) {
+        // ---- this block is done, the memory system idles while the atomics drain and the last
+        //      block assembles y: warm the caches with the predictor rows this block index reads
+        //      first in the layer that runs next (pf_rows = that layer's codes, null if unknown)
+        if (pf_rows != nullptr && jn > 0) warm_rows<BLOCK>(pf_rows + (size_t)j0 * QROW, min(pf_bytes, jn * QROW), tid);
+        return;
+    }
 
     // ---- the last block to finish assembles y and re-arms the scratch
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
@@ -700,7 +723,8 @@ template <int TB, int SL>
 __global__ void __launch_bounds__(1024)
 down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int pbw, const float* __restrict__ yfold,
                     float* __restrict__ yfix, bf16_t* __restrict__ y, int32_t* __restrict__ done, int D, int nslices,
-                    int norm_out, float eps, int n_act) {
+                    int norm_out, float eps, int n_act, const unsigned char* __restrict__ pf_rows, int pf_bytes,
+                    int pf_row_bytes, int npb, int h) {
     constexpr int NW = 16, U = SL == 128 ? 48 : 16;  // wavefronts; rows in flight per wavefront (4- or 8-byte loads)
     constexpr int CPL = SL / TD_WAVE;                // columns per lane: 4 (8-byte loads) or 2 (4-byte loads)
     static_assert(CPL == 4 || CPL == 2, "slice width");
@@ -717,6 +741,13 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
 #pragma unroll
         for (int q = 0; q < CPL; ++q) acc[t * SL + q] = 0.0f;
     }
+    // a block that is not the last to finish warms the caches for the next layer's first kernel:
+    // the predictor rows of block index blockIdx.x there (same grid size as that kernel)
+    auto warm_next = [&]() {
+        const int j0n = (int)blockIdx.x * npb, jnn = min(npb, h - j0n);
+        if (pf_rows != nullptr && (int)blockIdx.x < nblk && jnn > 0)
+            warm_rows<1024>(pf_rows + (size_t)j0n * pf_row_bytes, min(pf_bytes, jnn * pf_row_bytes), tid);
+    };
     const bf16_t* base = W2T + (size_t)slice * SL + lane * CPL;
     // a wavefront takes `pbw` predictor blocks in turn
     for (int pi = 0; pi < pbw; ++pi) {
@@ -809,7 +840,10 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
             is_last = (__hip_atomic_fetch_add(done + 1 + slice, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
                        ngroups - 1);
         __syncthreads();
-        if (!is_last) return;
+        if (!is_last) {
+            warm_next();
+            return;
+        }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         for (int k = tid; k < TB * (SL / 4); k += 1024) {
             const int t = k / (SL / 4), c4 = k % (SL / 4);
@@ -829,7 +863,10 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
     if (tid == 0)
         is_last = (__hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1);
     __syncthreads();
-    if (!is_last) return;
+    if (!is_last) {
+        warm_next();
+        return;
+    }
 
     // ---- the last block assembles the tokens (with their row-wide norm) and re-arms the scratch
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
@@ -948,13 +985,20 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
                                      : (size_t)TB * (DEFER ? D + 8 : D) * 2 + (size_t)TB * (NG > 0 ? D + 16 : D);
     auto kernel = decode_fused_kernel<D, BLOCK, RQ, TB, SK, DEFER, NG>;
     const DeferOut rec{L->rec_count, L->rec_jb, L->rec_tb, L->rec_delta, npb};
+    // the layer that runs next, if the caller said so and it has this layer's geometry
+    const unsigned char* pf_rows = nullptr;
+    const tardis_layer_s* nx = L->next_layer;
+    if (nx && L->prefetch_bytes > 0 && td_layer_is_live(nx) && nx->d == L->d && nx->h == L->h && nx->dec_blocks == G &&
+        nx->dtype == L->dtype)
+        pf_rows = reinterpret_cast<const unsigned char*>(SK == 8 ? static_cast<const void*>(nx->Q)
+                                                                 : static_cast<const void*>(nx->Q4));
     hipLaunchKernelGGL(kernel, dim3(G), dim3(BLOCK), lds, s,
                        static_cast<const bf16_t*>(L->Wp), L->bp, codes, L->M4, L->tlo, L->thi,
                        static_cast<const bf16_t*>(L->W1),
                        static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), static_cast<const bf16_t*>(L->W2T),
                        L->a, L->c, static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), yfold, L->yfix,
                        L->dec_copies, mask, (int)L->mask_words, L->sync, h, npb, rpb, (int)L->act, norm_out, kRmsEps,
-                       rec, n_act);
+                       rec, n_act, DEFER ? nullptr : pf_rows, (int)L->prefetch_bytes);
     TD_HIP(hipGetLastError());
     if (DEFER) {
         constexpr int SL = TB >= 16 ? 128 : 256;     // slice width: 16 wavefronts x TB x SL floats of LDS
@@ -964,7 +1008,8 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
         const int ngroups = nslices >= 256 ? 1 : 256 / nslices;          // about one block per CU
         const int pbw = (G + 16 * ngroups - 1) / (16 * ngroups);         // predictor blocks per wavefront
         hipLaunchKernelGGL(k2, dim3(nslices * ngroups), dim3(1024), lds2, s, static_cast<const bf16_t*>(L->W2T), rec,
-                           G, pbw, yfold, L->yfix, static_cast<bf16_t*>(y), L->sync, D, nslices, norm_out, kRmsEps, n_act);
+                           G, pbw, yfold, L->yfix, static_cast<bf16_t*>(y), L->sync, D, nslices, norm_out, kRmsEps, n_act,
+                           pf_rows, (int)L->prefetch_bytes, SK == 8 ? D : D / 2, npb, h);
         TD_HIP(hipGetLastError());
     }
     return TARDIS_OK;

@@ -24,7 +24,8 @@ _DTYPE_CODE = {torch.float32: F32, torch.bfloat16: BF16}
 EXPORTS = (
     "tardis_calibrate", "tardis_calibrate_search", "tardis_fold", "tardis_ffn_forward", "tardis_ffn_forward_batched",
     "tardis_stack_forward", "tardis_dense_forward", "tardis_get_folded", "tardis_get_predictor_state",
-    "tardis_get_sketch_groups", "tardis_get_last_outliers", "tardis_get_handover", "tardis_destroy", "tardis_status_string", "tardis_version",
+    "tardis_get_sketch_groups", "tardis_get_last_outliers", "tardis_get_handover", "tardis_set_next_layer",
+    "tardis_destroy", "tardis_status_string", "tardis_version",
 )
 
 
@@ -63,6 +64,7 @@ def lib() -> C.CDLL:
         L.tardis_ffn_forward_batched.argtypes = [vp, vp, i64, vp, vp]
         L.tardis_dense_forward.argtypes = [vp, vp, i64, vp, vp]
         L.tardis_stack_forward.argtypes = [C.POINTER(vp), C.c_int32, vp, i64, vp, vp]
+        L.tardis_set_next_layer.argtypes = [vp, vp]
         L.tardis_get_folded.argtypes = [vp, vp, vp, vp]
         L.tardis_get_predictor_state.argtypes = [vp, vp, vp, vp, vp]
         L.tardis_get_sketch_groups.argtypes = [vp, vp, vp]
@@ -193,6 +195,11 @@ def tardis_stack_forward(layers, x, y=None, stream=None):
     n = 1 if x.dim() == 1 else x.shape[0]
     _check(lib().tardis_stack_forward(arr, len(layers), _ptr(x), n, _ptr(y), _stream(stream)), "tardis_stack_forward")
     return y
+
+
+def tardis_set_next_layer(L: Layer, nxt):
+    """Hint: `nxt` (a Layer or None) is the layer whose call follows L's."""
+    _check(lib().tardis_set_next_layer(L.handle, nxt.handle if nxt is not None else None), "tardis_set_next_layer")
 
 
 def tardis_dense_forward(L: Layer, x, y=None, stream=None):

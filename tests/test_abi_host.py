@@ -113,6 +113,8 @@ def test_online_calls_reject_null_handle():
     assert lib.tardis_stack_forward(arr, 2, p, 1, C.c_void_p(0x8000), None) == T.ERR_STATE
     assert lib.tardis_stack_forward(None, 2, p, 1, C.c_void_p(0x8000), None) == T.ERR_INVALID_ARG
     assert lib.tardis_stack_forward(arr, 0, p, 1, C.c_void_p(0x8000), None) == T.ERR_INVALID_ARG
+    assert lib.tardis_set_next_layer(None, None) == T.ERR_STATE
+    assert lib.tardis_set_next_layer(p, None) == T.ERR_STATE     # not a handle this library made
     assert lib.tardis_destroy(None) == T.OK
 
 

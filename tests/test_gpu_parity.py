@@ -485,6 +485,54 @@ def test_graph_capture_of_pass_and_prompt_paths(n):
     L.close()
 
 
+def test_next_layer_hint_changes_nothing_but_time():
+    """Two layers that name each other as next: one- and two-token calls request the other layer's
+    first predictor rows at the end of their kernel; masks and outputs are those of the unhinted
+    calls.  A hint to a destroyed layer is ignored, a hint to a layer of another shape too."""
+    ws = [synth.decode(d=1024, h=4096, n_cal=256, n_test=4, coverage=0.9, config=9, layer=li) for li in range(2)]
+    Ls = []
+    for w in ws:
+        ffn = make_ffn(w.layer)
+        lo, hi, a, c = T.tardis_calibrate(ffn, dev(w.X_cal, "bf16"), 0.9)
+        Ls.append(T.tardis_fold(ffn, lo, hi, a, c, max_batch=4))
+    X = dev(ws[0].X_test, "bf16")
+
+    def run_all():
+        out = []
+        for L in Ls:
+            for n in (1, 2):
+                y = T.tardis_ffn_forward_batched(L, X[:n].contiguous()).clone()
+                m = T.tardis_get_last_outliers(L, n, want_list=False)[0].clone()
+                out.append((y, m))
+        torch.cuda.synchronize()
+        return out
+
+    ref = run_all()
+    T.tardis_set_next_layer(Ls[0], Ls[1])
+    T.tardis_set_next_layer(Ls[1], Ls[0])
+    for (y, m), (yr, mr) in zip(run_all(), ref):
+        assert torch.equal(m, mr)
+        assert rel_l2(host(y), host(yr)) < 2e-3                  # atomic ordering only
+    with pytest.raises(T.TardisError):
+        T.tardis_set_next_layer(Ls[0], Ls[0])                   # a layer cannot follow itself
+    # another shape: accepted, ignored at launch
+    w3 = synth.decode(d=1024, h=2048, n_cal=256, n_test=2, coverage=0.9, config=9, layer=5)
+    ffn3 = make_ffn(w3.layer)
+    L3 = T.tardis_fold(ffn3, *T.tardis_calibrate(ffn3, dev(w3.X_cal, "bf16"), 0.9), max_batch=2)
+    T.tardis_set_next_layer(Ls[0], L3)
+    y = T.tardis_ffn_forward(Ls[0], X[0])
+    assert rel_l2(host(y), host(ref[0][0][0])) < 2e-3
+    # destroyed: the stale hint is ignored
+    T.tardis_set_next_layer(Ls[0], Ls[1])
+    Ls[1].close()
+    y = T.tardis_ffn_forward(Ls[0], X[0])
+    torch.cuda.synchronize()
+    assert rel_l2(host(y), host(ref[0][0][0])) < 2e-3
+    T.tardis_set_next_layer(Ls[0], None)
+    Ls[0].close()
+    L3.close()
+
+
 def test_runtime_argument_errors():
     w = synth.tiny()
     ffn = make_ffn(w.layer)
