@@ -131,7 +131,7 @@ def stack_run(T, synth, torch, np, to_dev, n_layers):
     return out
 
 
-def batched_sweep(T, synth, torch, np, to_dev, pre, X, coverages):
+def batched_sweep(T, synth, torch, np, to_dev, pre, X, coverages, chain=True):
     """Batched decode: tokens/s, algorithmic GB/s and union size per (batch, coverage), cold over
     the given layer copies (`pre`: FFN and device calibration tokens of each), against the
     vendor-BLAS dense FFN at the same batch."""
@@ -144,6 +144,9 @@ def batched_sweep(T, synth, torch, np, to_dev, pre, X, coverages):
         for ffn, xc in zip(ffns, Xc):
             lo, hi, a, c = T.tardis_calibrate(ffn, xc, cov)
             layers.append(T.tardis_fold(ffn, lo, hi, a, c, max_batch=64))
+        if chain:
+            for i, L in enumerate(layers):      # the timed loop walks the copies in this order
+                T.tardis_set_next_layer(L, layers[(i + 1) % len(layers)])
         for B in (2, 4, 8, 16, 64):
             xb = X[:B].contiguous()
             yb = torch.empty_like(xb)
@@ -438,7 +441,7 @@ def main() -> int:
         for L in l4:
             L.close()
         covs = (0.99, 0.95, 0.85) if args.sweep else (args.coverage,)
-        out["batched_sweep"] = batched_sweep(T, synth, torch, np, to_dev, pre, X, covs)
+        out["batched_sweep"] = batched_sweep(T, synth, torch, np, to_dev, pre, X, covs, chain=not args.no_chain)
     if args.prefill or not args.no_extras:
         print("bench.py: prompt shape (2048 tokens)", file=sys.stderr, flush=True)
         out["prefill"] = prefill_run(T, synth, torch, np, to_dev)
