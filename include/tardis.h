@@ -200,7 +200,9 @@ tardis_status_t tardis_stack_forward(const tardis_handle_t* layers, int32_t n_la
  * call finds in cache (about 8 % per layer at d = 4096, ffn = 16384).  Results
  * are unchanged.  next = NULL clears the hint; a hint to a layer that has been
  * destroyed since, or of another shape, is ignored.  tardis_stack_forward sets
- * it by itself for the duration of the call. */
+ * it by itself for the duration of the call.  A HIP graph captured from a
+ * hinted call keeps the address it was captured with: like a graph of a
+ * destroyed layer's own call, it must not be replayed once `next` is destroyed. */
 tardis_status_t tardis_set_next_layer(tardis_handle_t L, tardis_handle_t next);
 
 /* The unmodified FFN, y = W2 sigma(W1 x + b1) + b2, on the same streaming
