@@ -485,6 +485,31 @@ def test_graph_capture_of_pass_and_prompt_paths(n):
     L.close()
 
 
+def test_result_does_not_depend_on_how_many_tokens_share_a_call():
+    """The same tokens through every dispatch path - single launches, groups of 2-16, a 64-token
+    pass, short and square tiles of the prompt path: the masks of a token are the same bits whatever
+    call it is part of, its output agrees to rounding (strictly per-token semantics)."""
+    w = synth.decode(d=1024, h=4096, n_cal=512, n_test=300, coverage=0.9, config=3)
+    ffn = make_ffn(w.layer)
+    lo, hi, a, c = T.tardis_calibrate(ffn, dev(w.X_cal, "bf16"), 0.9)
+    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=300)
+    X = dev(w.X_test, "bf16")
+    ref_y, ref_m = [], []
+    for t in range(300):
+        ref_y.append(T.tardis_ffn_forward(L, X[t]).clone())
+        ref_m.append(T.tardis_get_last_outliers(L, 1, want_list=False)[0][0].clone())
+    ref_y, ref_m = torch.stack(ref_y), torch.stack(ref_m)
+    torch.cuda.synchronize()
+    for n in (2, 3, 5, 8, 13, 16, 17, 31, 64, 65, 100, 128, 129, 200, 256, 257, 300):
+        y = T.tardis_ffn_forward_batched(L, X[:n].contiguous())
+        m = T.tardis_get_last_outliers(L, n, want_list=False)[0]
+        torch.cuda.synchronize()
+        assert torch.equal(m, ref_m[:n]), n
+        err = np.linalg.norm(host(y) - host(ref_y[:n]), axis=1) / np.linalg.norm(host(ref_y[:n]), axis=1)
+        assert err.max() < 8e-3, (n, err.max())                  # two bf16 roundings of y apart at most
+    L.close()
+
+
 def test_next_layer_hint_changes_nothing_but_time():
     """Two layers that name each other as next: one- and two-token calls request the other layer's
     first predictor rows at the end of their kernel; masks and outputs are those of the unhinted
