@@ -1,7 +1,8 @@
-// Single-launch decode path (one token, bf16 storage): the whole online step of
-// Sec. "Inference Runtime" -- speculative product, predictor, mask, result
-// fixing -- in ONE kernel, so that a token costs one launch and every weight
-// byte is requested exactly once.
+// Decode path (1 to 16 tokens per launch, bf16 storage): the whole online step of
+// Sec. "Inference Runtime" -- speculative product, predictor, mask, result fixing --
+// in ONE kernel for one or two tokens, so that a token costs one launch and every
+// weight byte is requested exactly once; groups of 4, 8 and 16 tokens take a second
+// kernel for the down projection (see DEFER below).
 //
 // Work split.  The grid has G blocks; block b owns
 //   * neurons   [b*npb, (b+1)*npb)   : predictor rows of Q, and the repair of
@@ -9,11 +10,12 @@
 //   * outputs   [b*rpb, (b+1)*rpb)   : rows of W' for the speculative product
 // so no block ever waits for another: a neuron's flag is known inside the block
 // that will repair it.  The repair needs y += delta_j * W2[:, j] over ALL
-// outputs; each block sums its flagged neurons into a block-private fp32
-// vector in LDS and adds that vector once, with fully coalesced fp32 atomics,
+// outputs; each thread keeps its columns of the block's sum over its flagged
+// neurons in registers and adds them once, with fully coalesced fp32 atomics,
 // into one of K accumulator copies.  The last block to finish (a device
 // counter) adds the copies to the speculative result, converts to bf16, and
-// re-arms the accumulators and the counter for the next call.
+// re-arms the accumulators and the counter for the next call; the others spend
+// that time warming the caches for the layer that runs next, if it is known.
 #include <cstdlib>
 
 #include "common.h"
@@ -38,7 +40,7 @@ __device__ __forceinline__ void load_row(td_u32x4 (&dst)[N], const void* row, in
     for (int it = 0; it < N; ++it) dst[it] = td_load_stream16(p + it * TD_WAVE);
 }
 
-// TB tokens (1, 2 or 4) share one pass over the weights: x, y, yfold are TB x D, mask has TB rows of
+// TB tokens (1, 2, 4, 8 or 16) share one pass over the weights: x, y, yfold are TB x D, mask has TB rows of
 // mask_words words, yfix is copies x TB x D.
 //
 // SK = 8: Q holds one int8 code per weight.  SK = 4: Q holds the packed 4-bit sketch, one 16-byte
