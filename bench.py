@@ -201,6 +201,8 @@ def main() -> int:
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the figures beside the headline one (batched decode at the headline coverage, 4-bit sketch, prompt shape)")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="time only the headline loop (for profiler runs whose kernel average should be that loop's)")
     ap.add_argument("--no-chain", action="store_true",
                     help="do not tell each layer copy which copy runs next (no cache-warming hint)")
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of a replayed HIP graph")
@@ -324,14 +326,21 @@ def main() -> int:
     # copy names the one that follows (tardis_set_next_layer), so a launch spends its idle tail
     # requesting the next copy's first predictor rows.  The figure without the hint is kept beside it.
     plain_ms = None
+    chained = False
+    if args.headline_only:
+        args.no_dense = args.no_extras = args.no_cpu_baseline = True
     if not args.no_chain and len(layers) > 1:
-        plain_ms, _ = timed(handles, max(2, args.steps // 2), 1, graph=use_graph)
+        if not args.headline_only:
+            plain_ms, _ = timed(handles, max(2, args.steps // 2), 1, graph=use_graph)
+        chained = True
         for i, L in enumerate(layers):
             T.tardis_set_next_layer(L, layers[(i + 1) % len(layers)])
     cold_ms, cold_wall = timed(handles, args.steps, args.warmup, graph=use_graph)
-    hot_ms, _ = timed(handles[:1], max(2, args.steps // 2), 1, graph=use_graph)
+    hot_ms = None
+    if not args.headline_only:
+        hot_ms, _ = timed(handles[:1], max(2, args.steps // 2), 1, graph=use_graph)
     stream_ms = None
-    if use_graph:
+    if use_graph and not args.headline_only:
         stream_ms, _ = timed(handles, max(2, args.steps // 4), 1)
     res_dense = {}
     if not args.no_dense:
@@ -394,18 +403,18 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "decode single layer d=4096 ffn=16384 bf16, batch 1, 1024 tokens/step, "
                                f"cold over {args.layers} seeded layer copies"
-                               + (", each copy naming the next (cache-warming hint)" if plain_ms else ""),
+                               + (", each copy naming the next (cache-warming hint)" if chained else ""),
                    "coverage_t": args.coverage,
                    "measured_fallback_rate": p, "tokens_per_step": TOKENS_PER_STEP,
                    "sketch_bits": args.sketch_bits},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": (MEASURED_TRAFFIC_BYTES if plain_ms else MEASURED_TRAFFIC_BYTES_NO_HINT)[args.sketch_bits],
+                     "traffic": (MEASURED_TRAFFIC_BYTES if chained else MEASURED_TRAFFIC_BYTES_NO_HINT)[args.sketch_bits],
                      "kernel": "decode_fused_kernel", "algorithmic_bytes_per_launch": bytes_tok,
                      "avg_launch_us": launch_s * 1e6},
         "cpu_baseline": cpu,
-        "hot": {"tokens_per_s": TOKENS_PER_STEP / (hot_ms * 1e-3),
-                "GBs": bytes_tok / (hot_ms * 1e-3 / TOKENS_PER_STEP) / 1e9},
+        "hot": ({"tokens_per_s": TOKENS_PER_STEP / (hot_ms * 1e-3),
+                 "GBs": bytes_tok / (hot_ms * 1e-3 / TOKENS_PER_STEP) / 1e9} if hot_ms else None),
         "without_next_layer_hint": ({"tokens_per_s": TOKENS_PER_STEP / (plain_ms * 1e-3),
                                      "us_per_token": plain_ms * 1e3 / TOKENS_PER_STEP,
                                      "GBs": bytes_tok / (plain_ms * 1e-3 / TOKENS_PER_STEP) / 1e9} if plain_ms else None),
@@ -422,7 +431,7 @@ def main() -> int:
         # the same decode loop with the 4-bit sketch (same layers, same ranges and lines)
         l4 = [T.tardis_fold(L.ffn, *cal, max_batch=1, sketch_bits=4) for L, cal in zip(layers, cals)]
         h4 = [L.handle for L in l4]
-        if plain_ms:
+        if chained:
             for i, L in enumerate(l4):
                 T.tardis_set_next_layer(L, l4[(i + 1) % len(l4)])
         step(h4[:1])
