@@ -338,7 +338,11 @@ def main() -> int:
     cold_ms, cold_wall = timed(handles, args.steps, args.warmup, graph=use_graph)
     hot_ms = None
     if not args.headline_only:
+        if chained:
+            T.tardis_set_next_layer(layers[0], layers[0])        # one layer over and over: it follows itself
         hot_ms, _ = timed(handles[:1], max(2, args.steps // 2), 1, graph=use_graph)
+        if chained:
+            T.tardis_set_next_layer(layers[0], layers[1 % len(layers)])
     stream_ms = None
     if use_graph and not args.headline_only:
         stream_ms, _ = timed(handles, max(2, args.steps // 4), 1)

@@ -198,7 +198,8 @@ tardis_status_t tardis_stack_forward(const tardis_handle_t* layers, int32_t n_la
  * the end of their kernel - when most of the chip has finished and the memory
  * system idles - requesting the first predictor rows of `next`, which the next
  * call finds in cache (about 8 % per layer at d = 4096, ffn = 16384).  Results
- * are unchanged.  next = NULL clears the hint; a hint to a layer that has been
+ * are unchanged.  next may be L itself (the same layer is called again);
+ * next = NULL clears the hint; a hint to a layer that has been
  * destroyed since, or of another shape, is ignored.  tardis_stack_forward sets
  * it by itself for the duration of the call.  A HIP graph captured from a
  * hinted call keeps the address it was captured with: like a graph of a

@@ -224,7 +224,6 @@ tardis_status_t tardis_fold(const tardis_ffn_desc* desc, const float* lo, const 
 
 tardis_status_t tardis_set_next_layer(tardis_handle_t L, tardis_handle_t next) {
     if (!L || !td_layer_is_live(L)) return TARDIS_ERR_STATE;
-    if (L == next) return TARDIS_ERR_INVALID_ARG;
     if (next && !td_layer_is_live(next)) return TARDIS_ERR_STATE;
     L->next_layer = next;
     return TARDIS_OK;
