@@ -180,13 +180,24 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p, int row_block, 
         load_w(pre, ch + 2);
         asm volatile("" ::: "memory");
         const unsigned char* xf0 = lds + (ch & 1) * (kTB * kXPitch) + l16 * kXPitch + g * 16;
+        // the token fragments of sub-step s+1 are read from LDS while the MFMAs of sub-step s run
+        // (the scheduler, left alone, reads each fragment right before its use and the matrix
+        // cores wait out the LDS latency thirty-two times per chunk)
+        td_u32x4 xf[2][NT];
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt) xf[0][tt] = *reinterpret_cast<const td_u32x4*>(xf0 + tt * 16 * kXPitch);
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
+            if (s + 1 < 8) {
 #pragma unroll
-            for (int tt = 0; tt < NT; ++tt) {
-                const td_u32x4 xf = *reinterpret_cast<const td_u32x4*>(xf0 + tt * 16 * kXPitch + s * 64);
-                acc[tt] = TOKEN_ROWS ? mma16<I8>(xf, cur[s], acc[tt]) : mma16<I8>(cur[s], xf, acc[tt]);
+                for (int tt = 0; tt < NT; ++tt)
+                    xf[(s + 1) & 1][tt] = *reinterpret_cast<const td_u32x4*>(xf0 + tt * 16 * kXPitch + (s + 1) * 64);
             }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int tt = 0; tt < NT; ++tt)
+                acc[tt] = TOKEN_ROWS ? mma16<I8>(xf[s & 1][tt], cur[s], acc[tt]) : mma16<I8>(cur[s], xf[s & 1][tt], acc[tt]);
+            __builtin_amdgcn_sched_barrier(0);
         }
         stash_x(xs, (ch + 1) & 1);
         __syncthreads();
