@@ -343,11 +343,17 @@ __global__ void __launch_bounds__(256) stream_kernel(StreamArgs p, int chunks_pe
     stream_body<false, NT, EPI, NCH>(p, blockIdx.x, blockIdx.y, chunks_per_split, lds);
 }
 
-// per token: max|x|, exponent, int8 code (one block per token)
+// per token: max|x|, exponent, int8 code (one block per token).  The first kernel of a pass also
+// re-arms what the later ones accumulate into: the union counter and, for the masked dense
+// scatter, the token-major delta buffer (zero_words 32-bit words; 0 = leave it alone).
 __global__ void __launch_bounds__(256)
-quantize_tokens_kernel(const bf16_t* __restrict__ X, int d, int8_t* __restrict__ XQ, int32_t* __restrict__ E) {
+quantize_tokens_kernel(const bf16_t* __restrict__ X, int d, int8_t* __restrict__ XQ, int32_t* __restrict__ E,
+                       int32_t* __restrict__ ucount, uint4* __restrict__ zero_buf, size_t zero_vecs) {
     __shared__ float red[4];
     const int t = blockIdx.x;
+    if (t == 0 && threadIdx.x == 0) *ucount = 0;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < zero_vecs; i += (size_t)gridDim.x * 256)
+        zero_buf[i] = make_uint4(0u, 0u, 0u, 0u);
     const bf16_t* x = X + (size_t)t * d;
     float m = 0.0f;
     for (int k = threadIdx.x; k < d; k += 256) m = fmaxf(m, fabsf(td_bf16_to_f32(x[k])));
@@ -466,10 +472,12 @@ template <int NT>
 tardis_status_t pass_t(tardis_layer_s* L, const bf16_t* x, int nt, bf16_t* y, uint32_t* mask, float* yfold,
                        int norm_out, hipStream_t s) {
     const int d = (int)L->d, h = (int)L->h;
-    hipLaunchKernelGGL(quantize_tokens_kernel, dim3(nt), dim3(256), 0, s, x, d, L->bt_xq, L->bt_e);
-    hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(256), 0, s, reinterpret_cast<uint32_t*>(L->bt_ucount), (size_t)1, 0u);
     const bool gather_scatter = nt <= L->gather_max_tokens;
-    if (!gather_scatter) {
+    // (the delta buffer is kTB x h bf16 from a 256-byte aligned allocation: whole 16-byte vectors when h % 8 == 0)
+    const size_t zero_vecs = gather_scatter ? 0 : (size_t)kTB * h * 2 / 16;
+    hipLaunchKernelGGL(quantize_tokens_kernel, dim3(nt), dim3(256), 0, s, x, d, L->bt_xq, L->bt_e, L->bt_ucount,
+                       reinterpret_cast<uint4*>(L->bt_delta), zero_vecs);
+    if (!gather_scatter && ((size_t)kTB * h * 2) % 16 != 0) {          // odd h: the tail by the word
         const size_t words = (size_t)kTB * h / 2;
         hipLaunchKernelGGL(fill_u32_kernel, dim3(div_up(words, 256)), dim3(256), 0, s,
                            reinterpret_cast<uint32_t*>(L->bt_delta), words, 0u);
