@@ -53,7 +53,25 @@ def build(verbose: bool = True) -> str:
     os.replace(tmp, LIB)
     if verbose:
         print(f"built {LIB}")
+    build_c_demo(verbose)
     return LIB
+
+
+def build_c_demo(verbose: bool = True) -> str | None:
+    """examples/c_abi_demo: plain C99 (gcc, no C++) against include/tardis.h and the HIP runtime's C API."""
+    root = os.path.dirname(HERE)
+    src = os.path.join(root, "examples", "c_abi_demo.c")
+    gcc = shutil.which("gcc")
+    if not os.path.exists(src) or gcc is None:
+        return None
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    out = os.path.join(root, "examples", "c_abi_demo")
+    _run([gcc, "-std=c99", "-O2", "-Wall", "-D__HIP_PLATFORM_AMD__", f"-I{rocm}/include",
+          "-I" + os.path.join(root, "include"), src, "-o", out, LIB, f"-L{rocm}/lib", "-lamdhip64", "-lm",
+          "-Wl,-rpath,$ORIGIN/../paper_2501_10054_amd", f"-Wl,-rpath,{rocm}/lib"])
+    if verbose:
+        print(f"built {out}")
+    return out
 
 
 if __name__ == "__main__":
