@@ -92,11 +92,13 @@ __device__ __forceinline__ i32x4_t mma16<true>(const td_u32x4& ra, const td_u32x
 // One block: 64 weight rows (16 per wavefront) against NT*16 tokens over this block's K range.
 // TOKEN_ROWS: the tile is produced as D[token][weight row] (stores contiguous along the weight
 // rows) instead of D[weight row][token].
-template <bool I8, int NT, int EPI, int NCH>
+template <bool I8, int NT, int EPI, int NCH, int WV = 4>
 __device__ __forceinline__ void stream_body(const StreamArgs& p, int row_block, int split, int chunks_rt,
                                             unsigned char* lds) {
     // NCH > 0: the chunk count is a compile-time constant and the pipeline below is fully unrolled
     // (straight-line code lets the compiler count outstanding loads exactly); NCH == 0: run time.
+    constexpr int kRows = 16 * WV;                   // weight rows of this block (kRowsPerBlock with 4 wavefronts)
+    constexpr int kThreads = 64 * WV;
     const int chunks_per_split = NCH > 0 ? NCH : chunks_rt;
     constexpr bool TOKEN_ROWS = (EPI == EPI_FOLD || EPI == EPI_DOWN);
     typedef typename Acc<I8>::type acc_t;
@@ -106,9 +108,9 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p, int row_block, 
     int count = p.M;
     if (p.gather) {
         count = min(*p.gather_count, p.M);
-        if (row_block * kRowsPerBlock >= count) return;          // uniform: nothing gathered for this block
+        if (row_block * kRows >= count) return;                  // uniform: nothing gathered for this block
     }
-    const int rw = row_block * kRowsPerBlock + wave * 16;        // first row (or list slot) of this wavefront
+    const int rw = row_block * kRows + wave * 16;                // first row (or list slot) of this wavefront
     int my_row = min(rw + l16, count - 1);
     if (p.gather) my_row = p.gather[my_row];
     const unsigned char* wsrc = p.W + (size_t)my_row * p.row_bytes + (size_t)split * chunks_per_split * kChunk + g * 16;
@@ -117,12 +119,12 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p, int row_block, 
     // Token slots past n_tok re-read the last token: every load is unconditional (the in-order
     // load counter stays statically known to the compiler) and the columns they produce are never
     // stored (each token is an independent column of the product).
-    constexpr int XP = NT * 2;
+    constexpr int XP = NT * 512 / kThreads;          // 16-byte pieces of the token chunk per thread
     const unsigned char* xsrc[XP];
     int xdst[XP];
 #pragma unroll
     for (int q = 0; q < XP; ++q) {
-        const int idx = tid + 256 * q;
+        const int idx = tid + kThreads * q;
         const int t = idx >> 5, piece = idx & 31;
         xsrc[q] = p.X + (size_t)min(t, p.n_tok - 1) * p.row_bytes + (size_t)split * chunks_per_split * kChunk + piece * 16;
         xdst[q] = t * kXPitch + piece * 16;
@@ -337,10 +339,13 @@ fold_predict_batched_kernel(StreamArgs fold, StreamArgs pred, int fold_blocks, i
         stream_body<true, NT, EPI_PRED, PCH>(pred, (int)blockIdx.x - fold_blocks, 0, pred_chunks, lds);
 }
 
-template <int NT, int EPI, int NCH>
-__global__ void __launch_bounds__(256) stream_kernel(StreamArgs p, int chunks_per_split) {
+// WV wavefronts of 16 rows each per block.  Every block stages the pass's token chunks through LDS
+// itself, so token bytes cross L2 once per block: the masked dense scatter, whose K is split
+// anyway, runs 8 wavefronts (128 rows) per block and halves that traffic.
+template <int NT, int EPI, int NCH, int WV = 4>
+__global__ void __launch_bounds__(64 * WV) stream_kernel(StreamArgs p, int chunks_per_split) {
     extern __shared__ __align__(16) unsigned char lds[];
-    stream_body<false, NT, EPI, NCH>(p, blockIdx.x, blockIdx.y, chunks_per_split, lds);
+    stream_body<false, NT, EPI, NCH, WV>(p, blockIdx.x, blockIdx.y, chunks_per_split, lds);
 }
 
 // per token: max|x|, exponent, int8 code (one block per token).  The first kernel of a pass also
@@ -549,7 +554,10 @@ tardis_status_t pass_t(tardis_layer_s* L, const bf16_t* x, int nt, bf16_t* y, ui
         down.M = d;
         down.X = reinterpret_cast<const unsigned char*>(L->bt_delta);
         down.partial = L->bt_partial;
-        if (h == 16384)
+        if (h == 16384 && NT == 4)
+            hipLaunchKernelGGL((stream_kernel<NT, EPI_DOWN, 8, 8>), dim3(div_up(d, 128), kDownSplits), dim3(512),
+                               kStreamLds, s, down, 8);
+        else if (h == 16384)
             hipLaunchKernelGGL((stream_kernel<NT, EPI_DOWN, 8>), dim3(fold_blocks, kDownSplits), dim3(256), kStreamLds,
                                s, down, 8);
         else
@@ -595,6 +603,7 @@ tardis_status_t td_batched_init() {
         TD_HIP((allow_big_lds(stream_kernel<1, EPI_DOWN, 8>)));
         TD_HIP((allow_big_lds(stream_kernel<2, EPI_DOWN, 8>)));
         TD_HIP((allow_big_lds(stream_kernel<4, EPI_DOWN, 8>)));
+        TD_HIP((allow_big_lds(stream_kernel<4, EPI_DOWN, 8, 8>)));
         return TARDIS_OK;
     });
 }
