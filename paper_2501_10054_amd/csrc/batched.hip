@@ -48,6 +48,7 @@ struct StreamArgs {
     // fold
     const float* bp;
     float* yfold;                  // [token][d]
+    float* yfold2;                 // [token][d]: sums of the second half of K when the fold rows are split (no bias)
     int d;
     // predict
     const float* tlo;
@@ -242,7 +243,10 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p, int row_block, 
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int t = tt * 16 + 4 * g + i;
-                    if (t < p.n_tok) p.yfold[(size_t)t * p.d + r] = acc[tt][i] + b;
+                    if (t < p.n_tok) {
+                        if (split == 0) p.yfold[(size_t)t * p.d + r] = acc[tt][i] + b;
+                        else p.yfold2[(size_t)t * p.d + r] = acc[tt][i];
+                    }
                 }
         }
     } else if constexpr (EPI == EPI_DOWN) {
@@ -331,12 +335,17 @@ constexpr int kStreamLds = 2 * kTB * kXPitch + 1024;
 // FCH, PCH: compile-time chunk counts of the fold / predictor rows (0 = run time)
 template <int NT, int FCH, int PCH>
 __global__ void __launch_bounds__(256)
-fold_predict_batched_kernel(StreamArgs fold, StreamArgs pred, int fold_blocks, int fold_chunks, int pred_chunks) {
+fold_predict_batched_kernel(StreamArgs fold, StreamArgs pred, int fold_blocks, int fold_splits, int fold_chunks,
+                            int pred_chunks) {
+    // fold rows are twice as long as predictor rows (bf16 against int8): with K of the fold cut in
+    // two (fold_chunks per half, the halves summed by the finishing kernel) every block of the
+    // launch streams the same number of chunks and the chip stays full to the end
     extern __shared__ __align__(16) unsigned char lds[];
-    if ((int)blockIdx.x < fold_blocks)
-        stream_body<false, NT, EPI_FOLD, FCH>(fold, blockIdx.x, 0, fold_chunks, lds);
+    const int b = (int)blockIdx.x;
+    if (b < fold_blocks * fold_splits)
+        stream_body<false, NT, EPI_FOLD, FCH>(fold, b % fold_blocks, b / fold_blocks, fold_chunks, lds);
     else
-        stream_body<true, NT, EPI_PRED, PCH>(pred, (int)blockIdx.x - fold_blocks, 0, pred_chunks, lds);
+        stream_body<true, NT, EPI_PRED, PCH>(pred, b - fold_blocks * fold_splits, 0, pred_chunks, lds);
 }
 
 // WV wavefronts of 16 rows each per block.  Every block stages the pass's token chunks through LDS
@@ -514,12 +523,19 @@ tardis_status_t pass_t(tardis_layer_s* L, const bf16_t* x, int nt, bf16_t* y, ui
     pred.ulist = L->bt_ulist;
     pred.ucount = L->bt_ucount;
     const int fold_blocks = div_up(d, kRowsPerBlock), pred_blocks = div_up(h, kRowsPerBlock);
-    if (d == 4096)
-        hipLaunchKernelGGL((fold_predict_batched_kernel<NT, 16, 8>), dim3(fold_blocks + pred_blocks), dim3(256),
-                           kStreamLds, s, fold, pred, fold_blocks, 16, 8);
+    // (the gather scatter already uses every partial slot the finishing kernel can sum)
+    const int fsplit = (!gather_scatter && (d * 2 / kChunk) % 2 == 0) ? 2 : 1;
+    fold.yfold2 = L->bt_partial + (size_t)kDownSplits * kTB * d;
+    const dim3 fp_grid(fold_blocks * fsplit + pred_blocks);
+    if (d == 4096 && fsplit == 2)
+        hipLaunchKernelGGL((fold_predict_batched_kernel<NT, 8, 8>), fp_grid, dim3(256), kStreamLds, s, fold, pred,
+                           fold_blocks, 2, 8, 8);
+    else if (d == 4096)
+        hipLaunchKernelGGL((fold_predict_batched_kernel<NT, 16, 8>), fp_grid, dim3(256), kStreamLds, s, fold, pred,
+                           fold_blocks, 1, 16, 8);
     else
-        hipLaunchKernelGGL((fold_predict_batched_kernel<NT, 0, 0>), dim3(fold_blocks + pred_blocks), dim3(256),
-                           kStreamLds, s, fold, pred, fold_blocks, d * 2 / kChunk, d / kChunk);
+        hipLaunchKernelGGL((fold_predict_batched_kernel<NT, 0, 0>), fp_grid, dim3(256), kStreamLds, s, fold, pred,
+                           fold_blocks, fsplit, d * 2 / kChunk / fsplit, d / kChunk);
 
     StreamArgs del = base;
     del.W = static_cast<const unsigned char*>(L->W1);
@@ -547,7 +563,7 @@ tardis_status_t pass_t(tardis_layer_s* L, const bf16_t* x, int nt, bf16_t* y, ui
                            static_cast<const bf16_t*>(L->W2T), L->bt_delta, L->bt_ulist, L->bt_ucount, h, d, nt,
                            L->bt_partial);
     } else {
-        nparts = kDownSplits;
+        nparts = kDownSplits + (fsplit - 1);         // the fold's second half sits in the slot after the scatter's
         StreamArgs down = base;
         down.W = static_cast<const unsigned char*>(L->W2);
         down.row_bytes = (int64_t)h * 2;
@@ -588,6 +604,9 @@ tardis_status_t td_batched_init() {
         TD_HIP((allow_big_lds(fold_predict_batched_kernel<1, 0, 0>)));
         TD_HIP((allow_big_lds(fold_predict_batched_kernel<2, 0, 0>)));
         TD_HIP((allow_big_lds(fold_predict_batched_kernel<4, 0, 0>)));
+        TD_HIP((allow_big_lds(fold_predict_batched_kernel<1, 8, 8>)));
+        TD_HIP((allow_big_lds(fold_predict_batched_kernel<2, 8, 8>)));
+        TD_HIP((allow_big_lds(fold_predict_batched_kernel<4, 8, 8>)));
         TD_HIP((allow_big_lds(fold_predict_batched_kernel<1, 16, 8>)));
         TD_HIP((allow_big_lds(fold_predict_batched_kernel<2, 16, 8>)));
         TD_HIP((allow_big_lds(fold_predict_batched_kernel<4, 16, 8>)));
