@@ -118,7 +118,7 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     }
     L->use_batched = env_int("TARDIS_BATCHED", 1, 0, 1) && td_batched_supported(L);
     L->gather_max_tokens = env_int("TARDIS_GATHER_MAX", 16, 0, 16);
-    L->batched_min_tokens = env_int("TARDIS_BATCHED_MIN", L->use_fused ? 16 : 1, 1, 64);
+    L->batched_min_tokens = env_int("TARDIS_BATCHED_MIN", L->use_fused ? 17 : 1, 1, 64);
     // 4-bit sketch: the decode kernel reads the packed form (d = 2048, 4096); every other path
     // reads one-byte effective codes, kept only where such a path can run
     const bool packed4 = L->sketch_bits == 4 && L->use_fused && (d == 2048 || d == 4096);
