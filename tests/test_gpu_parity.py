@@ -559,6 +559,33 @@ def test_next_layer_hint_changes_nothing_but_time():
     L3.close()
 
 
+def test_destroy_returns_the_layer_s_memory():
+    """Folding and destroying a layer many times (with every scratch area: records, 64-token
+    passes, prompt path) leaves the device's free memory where it was."""
+    w = synth.decode(d=1024, h=4096, n_cal=256, n_test=128, coverage=0.9, config=9)
+    ffn = make_ffn(w.layer)
+    cal = T.tardis_calibrate(ffn, dev(w.X_cal, "bf16"), 0.9)
+    X = dev(w.X_test, "bf16")
+    Y = torch.empty_like(X)
+
+    def cycle():
+        L = T.tardis_fold(ffn, *cal, max_batch=128)
+        T.tardis_ffn_forward_batched(L, X, Y)
+        T.tardis_ffn_forward_batched(L, X[:40].contiguous(), Y[:40])
+        T.tardis_ffn_forward(L, X[0], Y[0])
+        torch.cuda.synchronize()
+        L.close()
+
+    cycle()
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    for _ in range(20):
+        cycle()
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert abs(free1 - free0) <= 8 << 20, (free0, free1)      # nothing of a layer's ~100 MB stays behind
+
+
 def test_runtime_argument_errors():
     w = synth.tiny()
     ffn = make_ffn(w.layer)
