@@ -84,7 +84,8 @@ typedef struct {
 typedef struct {
     int32_t sketch_bits;   /* predictor code width: 8, or 4 (grouped, see tardis_fold) */
     int32_t folded_dtype;  /* storage of W'; must equal desc.dtype */
-    int64_t max_batch;     /* largest n accepted by the batched online calls (>= 1); from 65 on the layer
+    int64_t max_batch;     /* largest n accepted by the batched online calls (1 .. 4096; longer prompts are
+                              the caller's to cut); from 65 on the layer
                               also holds scratch for the prompt path, about n * (5 d + 10 h) bytes */
     int32_t deterministic; /* reserved, must be 0 */
     int32_t reserved;
