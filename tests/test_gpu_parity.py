@@ -340,6 +340,26 @@ def test_degenerate_tokens_and_neurons():
     run_case(layer, X_cal, X_test, 0.9)
 
 
+@pytest.mark.parametrize("n", [8, 40, 130])
+def test_degenerate_tokens_on_the_bf16_paths(n):
+    """Zero, tiny, huge and one-hot tokens and all-zero neurons through the fused decode kernels
+    (8 tokens), a 64-token pass (40) and the prompt path (130)."""
+    d, h = 1024, 2048
+    seed = synth.workload_seed(9, 17)
+    layer = synth.make_layer(d, h, "bf16", seed, w1_std=0.04, w2_std=0.03, heavy_frac=0.01, with_bias=True)
+    layer.W1[5] = 0.0                       # all-zero neurons: z = b1 for every token
+    layer.W1[700] = 0.0
+    layer.b1[700] = 100.0
+    X_cal = synth.make_tokens(300, d, "bf16", seed, synth.STREAM_CAL)
+    X_test = synth.make_tokens(n, d, "bf16", seed, synth.STREAM_TEST)
+    X_test[0] = 0.0                         # zero token
+    X_test[1] = (X_test[1].astype(np.float64) * 2.0 ** -100).astype(X_test.dtype)    # tiny token
+    X_test[2] = (X_test[2].astype(np.float64) * 2.0 ** 40).astype(X_test.dtype)      # huge token: everything out of range
+    X_test[3, 1:] = 0.0                     # one-hot-like
+    X_test[n - 1] = 0.0
+    run_case(layer, X_cal, X_test, 0.9, batched=True, check_calibrate=False)
+
+
 def test_all_flagged_equals_dense_and_none_flagged_equals_folded():
     w = synth.tiny(hard=True)
     layer = w.layer
