@@ -147,7 +147,9 @@ tardis_status_t tardis_calibrate_search(const tardis_ffn_desc* desc, const void*
  * all in fp64, and the predictor uses the integer code Q_jk = m_jG q_jk (|Q| <= 105)
  * exactly as it uses the 8-bit code; tlo, thi as above with this s_j.  Storage is
  * 4 bits per weight plus one multiplier per group where the decode kernel reads the
- * packed form (bf16, d = 2048 or 4096), one byte per weight elsewhere.
+ * packed form (bf16, d = 2048 or 4096), one byte per weight elsewhere; a layer
+ * folded for more than 17 tokens per call keeps both, and its calls with 4 to 17
+ * tokens read the one-byte form (same integers, faster there).
  *
  * W1, b1, b2 are BORROWED: they must stay valid and unchanged until
  * tardis_destroy (the repair step reads W1 in place).  W2 is copied into a

@@ -1094,7 +1094,11 @@ bool td_decode_fused_supported(const tardis_layer_s* L) {
 // `tokens` (1, 2, 4, or 8 on the two-kernel path) consecutive tokens
 tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
                                 int tokens, int n_act, int norm_out, hipStream_t s) {
-    if (L->Q4) {   // packed 4-bit sketch (d = 2048 or 4096 only)
+    // packed 4-bit sketch (d = 2048 or 4096 only).  Groups of 8 and 16 tokens need one-byte codes
+    // (the matrix-core predictor), and with 4 tokens the unpacking already costs more vector ALU
+    // time than the halved stream saves (49 against 41 us at d = 4096, h = 16384): where the layer
+    // keeps one-byte codes as well - the same integers by definition - groups of 4 and more read those
+    if (L->Q4 && !(tokens >= 4 && L->Q && L->dec_threads == 1024)) {
         if (L->dec_threads == 512) {
             if (L->d == 2048) return launch_tb<2048, 512, 4>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
             if (L->d == 4096) return launch_tb<4096, 512, 4>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);

@@ -51,7 +51,8 @@ def custom_layer(d, h, dtype, seed, w1_std, bias):
     return synth.make_layer(d, h, dtype, seed, w1_std=w1_std, w2_std=0.05, heavy_frac=0.02, with_bias=bias)
 
 
-def run_case(layer, X_cal, X_test, coverage, act="gelu_erf", batched=False, check_calibrate=True, sketch_bits=8):
+def run_case(layer, X_cal, X_test, coverage, act="gelu_erf", batched=False, check_calibrate=True, sketch_bits=8,
+             max_batch=None):
     """Full pipeline on the GPU and in the checker; returns a dict of diagnostics."""
     dt = layer.dtype
     ffn = make_ffn(layer, act)
@@ -71,7 +72,7 @@ def run_case(layer, X_cal, X_test, coverage, act="gelu_erf", batched=False, chec
         assert np.abs(c_h - oc).max() <= (5.0 / n_cal + 1e-4) * max(1.0, scale)
 
     # from here on both sides use the SAME (lo, hi, a, c): the library's
-    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=max(1, X_test.shape[0]), sketch_bits=sketch_bits)
+    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=max_batch or max(1, X_test.shape[0]), sketch_bits=sketch_bits)
     F = O.build(layer.W1, layer.b1, layer.W2, layer.b2, lo_h, hi_h, a_h, c_h, act, sketch_bits=sketch_bits)
 
     Wp, bp = T.tardis_get_folded(L)
@@ -321,6 +322,19 @@ def test_sketch4_bf16_paths(d, h, n, batched):
     X_cal = synth.make_tokens(256, d, "bf16", seed, synth.STREAM_CAL)
     X_test = synth.make_tokens(n, d, "bf16", seed, synth.STREAM_TEST)
     run_case(layer, X_cal, X_test, 0.9, check_calibrate=False, batched=batched, sketch_bits=4)
+
+
+@pytest.mark.parametrize("n", [3, 4, 8, 13, 16])
+def test_sketch4_groups_on_one_byte_codes(n):
+    """A 4-bit layer that also keeps one-byte effective codes (folded for more tokens than one
+    decode call takes): groups of 4, 8 and 16 tokens read those (8 and 16 through the matrix-core
+    predictor instead of running as two groups of half the size); same integers, same masks."""
+    seed = synth.workload_seed(9, 21)
+    d, h = 2048, 8192
+    layer = synth.make_layer(d, h, "bf16", seed, w1_std=0.03, w2_std=0.03, heavy_frac=0.01, with_bias=True)
+    X_cal = synth.make_tokens(256, d, "bf16", seed, synth.STREAM_CAL)
+    X_test = synth.make_tokens(n, d, "bf16", seed, synth.STREAM_TEST)
+    run_case(layer, X_cal, X_test, 0.9, check_calibrate=False, batched=True, sketch_bits=4, max_batch=32)
 
 
 # ----------------------------------------------------------------- edge cases
