@@ -883,6 +883,9 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
     }
 
     // ---- the last block assembles the tokens (with their row-wide norm) and re-arms the scratch
+    //      (a single block at the very end: one cache invalidation and 16-byte loads are cheaper
+    //      here than many four-byte device-coherent loads per thread)
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     float* redt = accL;                              // NW x TB floats, free by now
     constexpr int TH = TB < 4 ? TB : 4;              // tokens assembled together
     for (int t0 = 0; t0 < TB; t0 += TH) {
@@ -894,7 +897,7 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
             for (int t = 0; t < TH; ++t) {
                 const f32x4 f = (live && t0 + t < n_act) ? reinterpret_cast<const f32x4*>(yfold + (size_t)(t0 + t) * D)[k4]
                                                          : zero4;
-                const f32x4 g = live ? load_coherent4(yfix + (size_t)(t0 + t) * D + 4 * k4) : zero4;
+                const f32x4 g = live ? reinterpret_cast<const f32x4*>(yfix + (size_t)(t0 + t) * D)[k4] : zero4;
                 v[t] = f + g;
             }
             if (live) {
@@ -1022,7 +1025,8 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
         const int pbw = (G + 16 * ngroups - 1) / (16 * ngroups);         // predictor blocks per wavefront
         hipLaunchKernelGGL(k2, dim3(nslices * ngroups), dim3(1024), lds2, s, static_cast<const bf16_t*>(L->W2T), rec,
                            G, pbw, yfold, L->yfix, static_cast<bf16_t*>(y), L->sync, D, nslices, norm_out, kRmsEps, n_act,
-                           pf_rows, (int)L->prefetch_bytes, SK == 8 ? D : D / 2, npb, h);
+                           TB >= 16 ? nullptr : pf_rows,   // (sixteen tokens: its blocks end too close together for the warming to pay)
+                           (int)L->prefetch_bytes, SK == 8 ? D : D / 2, npb, h);
         TD_HIP(hipGetLastError());
     }
     return TARDIS_OK;
