@@ -218,10 +218,9 @@ tardis_status_t td_gemm_nt_split(const void* A, const void* B, float* C, int64_t
 tardis_status_t td_decode_init();
 bool td_decode_fused_supported(const tardis_layer_s* L);
 constexpr int kDecodeMaxTokens = 16;  // tokens one weight pass of the decode kernel can be shared between
-// a group of `tokens` (1, 2, 4, 8, 16) slots of which the first n_act hold real tokens (n_act < tokens only
-// for groups that take the two-kernel path)
-tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
-                                int tokens, int n_act, int norm_out, hipStream_t s);
+// n consecutive tokens (bf16 layers the fused kernels support) as groups of 16, 8, 4, 2, 1 with the
+// layer's own working memory
+tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, int64_t n, void* y, int norm_out, hipStream_t s);
 tardis_status_t td_mask_to_list(const tardis_layer_s* L, int64_t n, int32_t* counts, int32_t* list, hipStream_t s);
 // batched.hip
 bool td_batched_supported(const tardis_layer_s* L);

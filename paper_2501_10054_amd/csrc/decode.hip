@@ -28,6 +28,10 @@ namespace {
 constexpr int kMaxNeuronsPerBlock = 512;
 constexpr int kMaxCopies = 4;                  // repair accumulator copies (blocks spread over them)
 
+// Wait until every vector-memory operation this wavefront has issued (loads, stores, atomics
+// without return) has been acknowledged.  No cache write-back or invalidation is involved.
+__device__ __forceinline__ void td_wait_memory_acks() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 __device__ __forceinline__ float load_coherent(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -71,6 +75,17 @@ struct DeferOut {
     uint32_t* tb;      // blocks x cap: bit t set iff token t flagged the neuron
     float* delta;      // blocks x cap x TB
     int cap;           // record slots per block (= neurons per block)
+};
+
+// Device working memory of one decode call beyond its inputs and outputs: the layer's own
+// buffers, or the library's static scratch (tardis_ffn_forward_static).
+struct DecodeScratch {
+    float* yfix;        // copies x kDecodeMaxTokens x d repair accumulators (zero between calls)
+    int32_t* sync;      // completion counters (zero between calls)
+    int32_t* rec_count; // records of the two-kernel path
+    uint32_t* rec_jb;
+    uint32_t* rec_tb;
+    float* rec_delta;
 };
 
 // A block that has finished while the rest of the launch drains (atomics, the last block's
@@ -637,8 +652,12 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                                    __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    // ---- signal completion; every store and atomic of this block has been acknowledged
-    //      (vmcnt drained by the workgroup-scope release) before the counter moves
+    // ---- signal completion.  Every wavefront first waits until its own stores and atomics have
+    //      been acknowledged by memory (they are written through / executed memory-side, so
+    //      acknowledged means visible to every XCD); only then does the block meet at the barrier
+    //      and move the counter.  The fence alone does not do it: at workgroup scope it waits for
+    //      LDS traffic only.
+    td_wait_memory_acks();
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (tid == 0)
@@ -845,6 +864,7 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
             __hip_atomic_fetch_add(yfix + (size_t)t * D + slice * SL + col, sum, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
     }
+    td_wait_memory_acks();   // this wavefront's atomics have been performed before the block's counter moves
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (!norm_out) {
@@ -985,8 +1005,8 @@ mask_to_list_kernel(const uint32_t* __restrict__ mask, int words, int h, int32_t
 }
 
 template <int D, int BLOCK, int TB, int SK, bool DEFER, int NG = 0>
-tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
-                              int n_act, int norm_out, hipStream_t s) {
+tardis_status_t launch_decode(tardis_layer_s* L, const DecodeScratch& ws, const void* x, void* y, float* yfold,
+                              uint32_t* mask, int n_act, int norm_out, hipStream_t s) {
     constexpr int RQ = 4;
     if (n_act < 1 || n_act > TB || (!DEFER && n_act != TB)) return TARDIS_ERR_INVALID_ARG;
     const int G = L->dec_blocks;
@@ -1000,7 +1020,7 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
                        : TB == 16    ? (size_t)TB * (D + 8) * 2      // the int8 codes share the tokens' place
                                      : (size_t)TB * (DEFER ? D + 8 : D) * 2 + (size_t)TB * (NG > 0 ? D + 16 : D);
     auto kernel = decode_fused_kernel<D, BLOCK, RQ, TB, SK, DEFER, NG>;
-    const DeferOut rec{L->rec_count, L->rec_jb, L->rec_tb, L->rec_delta, npb};
+    const DeferOut rec{ws.rec_count, ws.rec_jb, ws.rec_tb, ws.rec_delta, npb};
     // the layer that runs next, if the caller said so and it has this layer's geometry
     const unsigned char* pf_rows = nullptr;
     const tardis_layer_s* nx = L->next_layer;
@@ -1012,8 +1032,8 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
                        static_cast<const bf16_t*>(L->Wp), L->bp, codes, L->M4, L->tlo, L->thi,
                        static_cast<const bf16_t*>(L->W1),
                        static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), static_cast<const bf16_t*>(L->W2T),
-                       L->a, L->c, static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), yfold, L->yfix,
-                       L->dec_copies, mask, (int)L->mask_words, L->sync, h, npb, rpb, (int)L->act, norm_out, kRmsEps,
+                       L->a, L->c, static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), yfold, ws.yfix,
+                       L->dec_copies, mask, (int)L->mask_words, ws.sync, h, npb, rpb, (int)L->act, norm_out, kRmsEps,
                        rec, n_act, DEFER ? nullptr : pf_rows, (int)L->prefetch_bytes);
     TD_HIP(hipGetLastError());
     if (DEFER) {
@@ -1024,7 +1044,7 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
         const int ngroups = nslices >= 256 ? 1 : 256 / nslices;          // about one block per CU
         const int pbw = (G + 16 * ngroups - 1) / (16 * ngroups);         // predictor blocks per wavefront
         hipLaunchKernelGGL(k2, dim3(nslices * ngroups), dim3(1024), lds2, s, static_cast<const bf16_t*>(L->W2T), rec,
-                           G, pbw, yfold, L->yfix, static_cast<bf16_t*>(y), L->sync, D, nslices, norm_out, kRmsEps, n_act,
+                           G, pbw, yfold, ws.yfix, static_cast<bf16_t*>(y), ws.sync, D, nslices, norm_out, kRmsEps, n_act,
                            TB >= 16 ? nullptr : pf_rows,   // (sixteen tokens: its blocks end too close together for the warming to pay)
                            (int)L->prefetch_bytes, SK == 8 ? D : D / 2, npb, h);
         TD_HIP(hipGetLastError());
@@ -1034,39 +1054,39 @@ tardis_status_t launch_decode(tardis_layer_s* L, const void* x, void* y, float* 
 
 // `tokens` = group size (1, 2, 4, 8, 16), `n_act` of them real (fewer only on the two-kernel path)
 template <int D, int BLOCK, int SK>
-tardis_status_t launch_tb(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask, int tokens,
-                          int n_act, int norm_out, hipStream_t s) {
+tardis_status_t launch_tb(tardis_layer_s* L, const DecodeScratch& ws, const void* x, void* y, float* yfold,
+                          uint32_t* mask, int tokens, int n_act, int norm_out, hipStream_t s) {
     const bf16_t* xb = static_cast<const bf16_t*>(x);
     bf16_t* yb = static_cast<bf16_t*>(y);
     // two kernels: records, then the column-sliced pass (the block's W' rows must fit one 16-row tile)
     if (BLOCK == 1024 && L->defer_min_tokens <= tokens && (D + L->dec_blocks - 1) / L->dec_blocks <= 16) {
-        if (tokens == 4) return launch_decode<D, 1024, 4, SK, true>(L, x, y, yfold, mask, n_act, norm_out, s);
+        if (tokens == 4) return launch_decode<D, 1024, 4, SK, true>(L, ws, x, y, yfold, mask, n_act, norm_out, s);
         // eight and sixteen tokens need one-byte codes and 32 or 64 neurons per block (the matrix-core
         // tiling); otherwise they run as two groups of half the size
         const int npb = (((int)L->h + L->dec_blocks - 1) / L->dec_blocks + 31) / 32 * 32;
         if (tokens == 16 || tokens == 8) {
             if constexpr (SK == 8) {
                 if (npb == 64 && tokens == 16)
-                    return launch_decode<D, 1024, 16, 8, true, 4>(L, x, y, yfold, mask, n_act, norm_out, s);
+                    return launch_decode<D, 1024, 16, 8, true, 4>(L, ws, x, y, yfold, mask, n_act, norm_out, s);
                 if (npb == 32 && tokens == 16)
-                    return launch_decode<D, 1024, 16, 8, true, 2>(L, x, y, yfold, mask, n_act, norm_out, s);
+                    return launch_decode<D, 1024, 16, 8, true, 2>(L, ws, x, y, yfold, mask, n_act, norm_out, s);
                 if (npb == 64 && tokens == 8)
-                    return launch_decode<D, 1024, 8, 8, true, 4>(L, x, y, yfold, mask, n_act, norm_out, s);
+                    return launch_decode<D, 1024, 8, 8, true, 4>(L, ws, x, y, yfold, mask, n_act, norm_out, s);
                 if (npb == 32 && tokens == 8)
-                    return launch_decode<D, 1024, 8, 8, true, 2>(L, x, y, yfold, mask, n_act, norm_out, s);
+                    return launch_decode<D, 1024, 8, 8, true, 2>(L, ws, x, y, yfold, mask, n_act, norm_out, s);
             }
             const int half = tokens / 2;
-            TD_TRY((launch_tb<D, BLOCK, SK>(L, x, y, yfold, mask, half, n_act < half ? n_act : half, norm_out, s)));
+            TD_TRY((launch_tb<D, BLOCK, SK>(L, ws, x, y, yfold, mask, half, n_act < half ? n_act : half, norm_out, s)));
             if (n_act <= half) return TARDIS_OK;
-            return launch_tb<D, BLOCK, SK>(L, xb + half * (size_t)D, yb + half * (size_t)D, yfold + half * (size_t)D,
+            return launch_tb<D, BLOCK, SK>(L, ws, xb + half * (size_t)D, yb + half * (size_t)D, yfold + half * (size_t)D,
                                            mask + half * L->mask_words, half, n_act - half, norm_out, s);
         }
     }
     if (n_act != tokens) return TARDIS_ERR_INVALID_ARG;      // the one-kernel form has no empty slots
     switch (tokens) {
-        case 1: return launch_decode<D, BLOCK, 1, SK, false>(L, x, y, yfold, mask, 1, norm_out, s);
-        case 2: return launch_decode<D, BLOCK, 2, SK, false>(L, x, y, yfold, mask, 2, norm_out, s);
-        case 4: return launch_decode<D, BLOCK, 4, SK, false>(L, x, y, yfold, mask, 4, norm_out, s);
+        case 1: return launch_decode<D, BLOCK, 1, SK, false>(L, ws, x, y, yfold, mask, 1, norm_out, s);
+        case 2: return launch_decode<D, BLOCK, 2, SK, false>(L, ws, x, y, yfold, mask, 2, norm_out, s);
+        case 4: return launch_decode<D, BLOCK, 4, SK, false>(L, ws, x, y, yfold, mask, 4, norm_out, s);
     }
     return TARDIS_ERR_INVALID_ARG;
 }
@@ -1106,36 +1126,70 @@ bool td_decode_fused_supported(const tardis_layer_s* L) {
     return npb <= kMaxNeuronsPerBlock;
 }
 
-// `tokens` (1, 2, 4, or 8 on the two-kernel path) consecutive tokens
-tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, void* y, float* yfold, uint32_t* mask,
-                                int tokens, int n_act, int norm_out, hipStream_t s) {
+namespace {
+
+// one group of `tokens` (1, 2, 4, 8, 16) slots, n_act of them real, with working memory `ws`
+tardis_status_t decode_group(tardis_layer_s* L, const DecodeScratch& ws, const void* x, void* y, float* yfold,
+                             uint32_t* mask, int tokens, int n_act, int norm_out, hipStream_t s) {
     // packed 4-bit sketch (d = 2048 or 4096 only).  Groups of 8 and 16 tokens need one-byte codes
     // (the matrix-core predictor), and with 4 tokens the unpacking already costs more vector ALU
     // time than the halved stream saves (49 against 41 us at d = 4096, h = 16384): where the layer
     // keeps one-byte codes as well - the same integers by definition - groups of 4 and more read those
     if (L->Q4 && !(tokens >= 4 && L->Q && L->dec_threads == 1024)) {
         if (L->dec_threads == 512) {
-            if (L->d == 2048) return launch_tb<2048, 512, 4>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
-            if (L->d == 4096) return launch_tb<4096, 512, 4>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
+            if (L->d == 2048) return launch_tb<2048, 512, 4>(L, ws, x, y, yfold, mask, tokens, n_act, norm_out, s);
+            if (L->d == 4096) return launch_tb<4096, 512, 4>(L, ws, x, y, yfold, mask, tokens, n_act, norm_out, s);
         } else {
-            if (L->d == 2048) return launch_tb<2048, 1024, 4>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
-            if (L->d == 4096) return launch_tb<4096, 1024, 4>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
+            if (L->d == 2048) return launch_tb<2048, 1024, 4>(L, ws, x, y, yfold, mask, tokens, n_act, norm_out, s);
+            if (L->d == 4096) return launch_tb<4096, 1024, 4>(L, ws, x, y, yfold, mask, tokens, n_act, norm_out, s);
         }
         return TARDIS_ERR_SHAPE;
     }
     if (L->dec_threads == 512) {
         switch (L->d) {
-            case 1024: return launch_tb<1024, 512, 8>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
-            case 2048: return launch_tb<2048, 512, 8>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
-            case 4096: return launch_tb<4096, 512, 8>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
+            case 1024: return launch_tb<1024, 512, 8>(L, ws, x, y, yfold, mask, tokens, n_act, norm_out, s);
+            case 2048: return launch_tb<2048, 512, 8>(L, ws, x, y, yfold, mask, tokens, n_act, norm_out, s);
+            case 4096: return launch_tb<4096, 512, 8>(L, ws, x, y, yfold, mask, tokens, n_act, norm_out, s);
         }
     }
     switch (L->d) {
-        case 1024: return launch_tb<1024, 1024, 8>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
-        case 2048: return launch_tb<2048, 1024, 8>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
-        case 4096: return launch_tb<4096, 1024, 8>(L, x, y, yfold, mask, tokens, n_act, norm_out, s);
+        case 1024: return launch_tb<1024, 1024, 8>(L, ws, x, y, yfold, mask, tokens, n_act, norm_out, s);
+        case 2048: return launch_tb<2048, 1024, 8>(L, ws, x, y, yfold, mask, tokens, n_act, norm_out, s);
+        case 4096: return launch_tb<4096, 1024, 8>(L, ws, x, y, yfold, mask, tokens, n_act, norm_out, s);
     }
     return TARDIS_ERR_SHAPE;
+}
+
+// n tokens as groups of 16, 8, 4, 2, 1 that share one pass over the weights each; yfold: n + 16
+// rows of d floats, mask: n + 16 rows of mask words (a partly filled group may touch the slack)
+tardis_status_t decode_tokens(tardis_layer_s* L, const DecodeScratch& ws, const bf16_t* x, int64_t n, bf16_t* y,
+                              float* yfold, uint32_t* mask, int norm_out, hipStream_t s) {
+    const int d = (int)L->d;
+    const bool two4 = L->dec_threads == 1024 && L->defer_min_tokens <= 4 &&
+                      (d + L->dec_blocks - 1) / L->dec_blocks <= 16;   // two-kernel groups of 4 exist
+    const bool wide = two4 || (L->dec_threads == 1024 && L->defer_min_tokens <= 8 &&
+                               (d + L->dec_blocks - 1) / L->dec_blocks <= 16);   // ... of 8 and 16
+    for (int64_t t = 0; t < n;) {
+        const int64_t left = n - t;
+        // a two-kernel group may be partly empty: 3 tokens cost less as a group of 4 than as 2 + 1,
+        // 5-7 less as a group of 8, 9-15 less as a group of 16
+        // (only where every two-kernel group size exists, so that a split group stays on that path)
+        int g, act;
+        if (wide && (left >= 16 || (two4 && left >= 9))) { g = 16; act = left >= 16 ? 16 : (int)left; }
+        else if (wide && (left >= 8 || (two4 && left >= 5))) { g = 8; act = left >= 8 ? 8 : (int)left; }
+        else if (left >= 4 || (two4 && left == 3)) { g = 4; act = left >= 4 ? 4 : 3; }
+        else { g = left >= 2 ? 2 : 1; act = g; }
+        TD_TRY(decode_group(L, ws, x + t * d, y + t * d, yfold + t * d, mask + t * L->mask_words, g, act, norm_out, s));
+        t += act;
+    }
+    return TARDIS_OK;
+}
+
+}  // namespace
+
+tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, int64_t n, void* y, int norm_out, hipStream_t s) {
+    const DecodeScratch ws{L->yfix, L->sync, L->rec_count, L->rec_jb, L->rec_tb, L->rec_delta};
+    return decode_tokens(L, ws, static_cast<const bf16_t*>(x), n, static_cast<bf16_t*>(y), L->yacc, L->mask, norm_out, s);
 }
 
 tardis_status_t td_mask_to_list(const tardis_layer_s* L, int64_t n, int32_t* counts, int32_t* list, hipStream_t s) {

@@ -233,24 +233,7 @@ tardis_status_t forward_t(tardis_layer_s* L, const void* xv, int64_t n, void* yv
     if (L->pf_scratch && n >= L->prefill_min_tokens) return td_forward_prefill(L, xv, n, yv, norm_out, s);
     if (n > L->batched_min_tokens && L->use_batched) return td_forward_batched(L, xv, n, yv, norm_out, s);
     if (L->use_fused) {   // groups of 16, 8, 4, 2, 1 tokens share one pass over the weights
-        const bool two4 = L->dec_threads == 1024 && L->defer_min_tokens <= 4 &&
-                          (d + L->dec_blocks - 1) / L->dec_blocks <= 16;   // two-kernel groups of 4 exist
-        const bool wide = two4 || (L->dec_threads == 1024 && L->defer_min_tokens <= 8 &&
-                                   (d + L->dec_blocks - 1) / L->dec_blocks <= 16);   // ... of 8 and 16
-        for (int64_t t = 0; t < n;) {
-            const int64_t left = n - t;
-            // a two-kernel group may be partly empty: 3 tokens cost less as a group of 4 than as 2 + 1,
-            // 5-7 less as a group of 8, 9-15 less as a group of 16
-            // (only where every two-kernel group size exists, so that a split group stays on that path)
-            int g, act;
-            if (wide && (left >= 16 || (two4 && left >= 9))) { g = 16; act = left >= 16 ? 16 : (int)left; }
-            else if (wide && (left >= 8 || (two4 && left >= 5))) { g = 8; act = left >= 8 ? 8 : (int)left; }
-            else if (left >= 4 || (two4 && left == 3)) { g = 4; act = left >= 4 ? 4 : 3; }
-            else { g = left >= 2 ? 2 : 1; act = g; }
-            TD_TRY(td_decode_fused(L, static_cast<const T*>(xv) + t * d, static_cast<T*>(yv) + t * d,
-                                   L->yacc + t * d, L->mask + t * L->mask_words, g, act, norm_out, s));
-            t += act;
-        }
+        TD_TRY(td_decode_fused(L, xv, n, yv, norm_out, s));
         L->last_n = n;
         return TARDIS_OK;
     }
