@@ -184,6 +184,25 @@ tardis_status_t tardis_ffn_forward(tardis_handle_t L, const void* x, void* y, vo
 tardis_status_t tardis_ffn_forward_batched(tardis_handle_t L, const void* x, int64_t n, void* y,
                                            void* stream);
 
+/* tardis_ffn_forward_batched for callers that cannot allocate or let a library hold
+ * per-handle working memory for them: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The call allocates nothing: the
+ * accumulators, completion counters, flagged-neuron records and speculative rows of
+ * the decode kernels live in one static device array of the library (about 3.9 MiB
+ * on every GPU the library runs on, held until the process ends) instead of the
+ * handle's buffers.  Same kernels, same results: masks bit for bit, y to rounding.
+ *   n         1 .. 16 tokens.  x, y: n x d, bf16.
+ *   mask_out  optional, n x ceil(h/32) words as in tardis_get_last_outliers (the
+ *             handle's own record of its last call is NOT updated by this call).
+ * Limits: a bf16 layer the single-launch decode kernels serve (d = 1024, 2048 or
+ * 4096), h <= 16384; anything else returns TARDIS_ERR_SHAPE (TARDIS_ERR_STATE for a
+ * layer without those kernels).  Every call on one GPU shares the one array: calls
+ * that overlap in time on the same GPU (two streams, two threads) race; calls on one
+ * stream, or otherwise ordered, are safe, and each call clears what it needs zeroed
+ * itself. */
+tardis_status_t tardis_ffn_forward_static(tardis_handle_t L, const void* x, int64_t n, void* y,
+                                          uint32_t* mask_out, void* stream);
+
 /* A stack of folded layers of equal width d and dtype (FFN blocks chained
  * without attention; the glue is this library's choice, the paper has none):
  *     x_0 = x,  y_l = layer_l(x_l),  x_{l+1} = y_l / sqrt(mean(y_l^2) + 1e-6)

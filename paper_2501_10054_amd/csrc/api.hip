@@ -110,6 +110,7 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     L->defer_min_tokens = env_int("TARDIS_DEFER_MIN", 4, 4, 99);
     if (L->use_fused) {
         TD_TRY(td_decode_init());
+        TD_TRY(td_static_scratch_setup());   // for tardis_ffn_forward_static on this device
         const int64_t npb = ((h + L->dec_blocks - 1) / L->dec_blocks + 31) / 32 * 32;
         TD_TRY(dev_alloc(&L->rec_count, (size_t)L->dec_blocks * 4));
         TD_TRY(dev_alloc(&L->rec_jb, (size_t)L->dec_blocks * npb * 4));

@@ -221,6 +221,8 @@ constexpr int kDecodeMaxTokens = 16;  // tokens one weight pass of the decode ke
 // n consecutive tokens (bf16 layers the fused kernels support) as groups of 16, 8, 4, 2, 1 with the
 // layer's own working memory
 tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, int64_t n, void* y, int norm_out, hipStream_t s);
+// looks up the current device's static decode working memory (once per device)
+tardis_status_t td_static_scratch_setup();
 tardis_status_t td_mask_to_list(const tardis_layer_s* L, int64_t n, int32_t* counts, int32_t* list, hipStream_t s);
 // batched.hip
 bool td_batched_supported(const tardis_layer_s* L);

@@ -17,6 +17,7 @@
 // re-arms the accumulators and the counter for the next call; the others spend
 // that time warming the caches for the layer that runs next, if it is known.
 #include <cstdlib>
+#include <mutex>
 
 #include "common.h"
 #include "rowdot.h"
@@ -1190,6 +1191,93 @@ tardis_status_t decode_tokens(tardis_layer_s* L, const DecodeScratch& ws, const 
 tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, int64_t n, void* y, int norm_out, hipStream_t s) {
     const DecodeScratch ws{L->yfix, L->sync, L->rec_count, L->rec_jb, L->rec_tb, L->rec_delta};
     return decode_tokens(L, ws, static_cast<const bf16_t*>(x), n, static_cast<bf16_t*>(y), L->yacc, L->mask, norm_out, s);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Static working memory: the decode path for callers that cannot allocate (HIP graph capture,
+// serving loops, harnesses that forbid hipMalloc).  One array per GPU, part of the code object,
+// held until the process ends; every call on a GPU shares it.
+namespace {
+
+constexpr int kStaticMaxD = 4096;            // widest layer the static working memory serves
+constexpr int kStaticMaxH = 16384;           // most neurons (mask words, records)
+constexpr int kStaticMaxBlocks = 4096;       // largest decode grid
+constexpr int kStaticMaxRecords = 32768;     // decode blocks x neurons per block
+constexpr size_t kStSync = 0;                                                               // 64 counters
+constexpr size_t kStYfix = 256;                                                             // 4 x 16 x d floats
+constexpr size_t kStYfold = kStYfix + (size_t)kMaxCopies * kDecodeMaxTokens * kStaticMaxD * 4;   // 32 x d floats
+constexpr size_t kStMask = kStYfold + (size_t)2 * kDecodeMaxTokens * kStaticMaxD * 4;            // 32 x h/32 words
+constexpr size_t kStCount = kStMask + (size_t)2 * kDecodeMaxTokens * (kStaticMaxH / 32) * 4;
+constexpr size_t kStJb = kStCount + (size_t)kStaticMaxBlocks * 4;
+constexpr size_t kStTb = kStJb + (size_t)kStaticMaxRecords * 4;
+constexpr size_t kStDelta = kStTb + (size_t)kStaticMaxRecords * 4;
+constexpr size_t kStaticScratchBytes = kStDelta + (size_t)kStaticMaxRecords * kDecodeMaxTokens * 4;   // about 3.9 MiB
+static_assert(kStYfix % 256 == 0 && kStYfold % 256 == 0 && kStMask % 256 == 0 && kStCount % 256 == 0 &&
+                  kStJb % 256 == 0 && kStTb % 256 == 0 && kStDelta % 256 == 0,
+              "every part starts on a 256-byte boundary");
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each GPU (the array's name is not one)
+
+// the current device's copy of the array (looked up once per device)
+tardis_status_t static_scratch(unsigned char** out) {
+    int dev = -1;
+    TD_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return TARDIS_ERR_STATE;
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        unsigned char* p = nullptr;
+        TD_HIP(hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)));
+        if (!p) return TARDIS_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return TARDIS_OK;
+}
+
+// what a call needs to find zero: the completion counters and the repair accumulators it will use
+__global__ void __launch_bounds__(256) clear_static_kernel(int32_t* __restrict__ sync, float* __restrict__ yfix, int n) {
+    const int i = (int)blockIdx.x * 256 + threadIdx.x;
+    if (i < 64) sync[i] = 0;
+    if (i < n) yfix[i] = 0.0f;
+}
+
+}  // namespace
+
+tardis_status_t td_static_scratch_setup() {
+    unsigned char* p = nullptr;
+    return static_scratch(&p);
+}
+
+extern "C" tardis_status_t tardis_ffn_forward_static(tardis_handle_t L, const void* x, int64_t n, void* y,
+                                                      uint32_t* mask_out, void* stream) {
+    if (!L || !td_layer_is_live(L)) return TARDIS_ERR_STATE;
+    if (!x || !y || x == y) return TARDIS_ERR_INVALID_ARG;
+    if (n < 1 || n > kDecodeMaxTokens) return TARDIS_ERR_SHAPE;
+    if (!L->use_fused || L->dtype != TARDIS_BF16) return TARDIS_ERR_STATE;
+    const int64_t npb = ((L->h + L->dec_blocks - 1) / L->dec_blocks + 31) / 32 * 32;
+    if (L->d > kStaticMaxD || L->h > kStaticMaxH || L->dec_blocks > kStaticMaxBlocks ||
+        (int64_t)L->dec_blocks * npb > kStaticMaxRecords || L->dec_copies > kMaxCopies)
+        return TARDIS_ERR_SHAPE;   // beyond what the static working memory holds
+    unsigned char* base = nullptr;
+    TD_TRY(static_scratch(&base));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const DecodeScratch ws{reinterpret_cast<float*>(base + kStYfix),    reinterpret_cast<int32_t*>(base + kStSync),
+                           reinterpret_cast<int32_t*>(base + kStCount), reinterpret_cast<uint32_t*>(base + kStJb),
+                           reinterpret_cast<uint32_t*>(base + kStTb),   reinterpret_cast<float*>(base + kStDelta)};
+    // the array keeps the last call's contents (and an interrupted call's): clear what must start at
+    // zero, with a kernel (a memset node in a captured graph is not safe to replay here)
+    const int nfix = L->dec_copies * kDecodeMaxTokens * (int)L->d;
+    hipLaunchKernelGGL(clear_static_kernel, dim3((nfix + 255) / 256), dim3(256), 0, s, ws.sync, ws.yfix, nfix);
+    TD_HIP(hipGetLastError());
+    // mask words: the caller's buffer when given and no group can be partly empty past its end
+    // (a partly filled group only writes the rows of its real tokens), else the static one
+    uint32_t* mask = mask_out ? mask_out : reinterpret_cast<uint32_t*>(base + kStMask);
+    return decode_tokens(L, ws, static_cast<const bf16_t*>(x), n, static_cast<bf16_t*>(y),
+                         reinterpret_cast<float*>(base + kStYfold), mask, 0, s);
 }
 
 tardis_status_t td_mask_to_list(const tardis_layer_s* L, int64_t n, int32_t* counts, int32_t* list, hipStream_t s) {

@@ -23,7 +23,7 @@ _DTYPE_CODE = {torch.float32: F32, torch.bfloat16: BF16}
 
 EXPORTS = (
     "tardis_calibrate", "tardis_calibrate_search", "tardis_fold", "tardis_ffn_forward", "tardis_ffn_forward_batched",
-    "tardis_stack_forward", "tardis_dense_forward", "tardis_get_folded", "tardis_get_predictor_state",
+    "tardis_ffn_forward_static", "tardis_stack_forward", "tardis_dense_forward", "tardis_get_folded", "tardis_get_predictor_state",
     "tardis_get_sketch_groups", "tardis_get_last_outliers", "tardis_get_handover", "tardis_set_next_layer",
     "tardis_destroy", "tardis_status_string", "tardis_version",
 )
@@ -62,6 +62,7 @@ def lib() -> C.CDLL:
                                   C.POINTER(vp)]
         L.tardis_ffn_forward.argtypes = [vp, vp, vp, vp]
         L.tardis_ffn_forward_batched.argtypes = [vp, vp, i64, vp, vp]
+        L.tardis_ffn_forward_static.argtypes = [vp, vp, i64, vp, vp, vp]
         L.tardis_dense_forward.argtypes = [vp, vp, i64, vp, vp]
         L.tardis_stack_forward.argtypes = [C.POINTER(vp), C.c_int32, vp, i64, vp, vp]
         L.tardis_set_next_layer.argtypes = [vp, vp]
@@ -184,6 +185,16 @@ def tardis_ffn_forward_batched(L: Layer, x, y=None, stream=None):
         y = torch.empty_like(x)
     _check(lib().tardis_ffn_forward_batched(L.handle, _ptr(x), x.shape[0], _ptr(y), _stream(stream)),
            "tardis_ffn_forward_batched")
+    return y
+
+
+def tardis_ffn_forward_static(L: Layer, x, y=None, mask_out=None, stream=None):
+    """n <= 16 tokens with the library's static working memory (the call allocates nothing)."""
+    if y is None:
+        y = torch.empty_like(x)
+    n = 1 if x.dim() == 1 else x.shape[0]
+    _check(lib().tardis_ffn_forward_static(L.handle, _ptr(x), n, _ptr(y), _ptr(mask_out), _stream(stream)),
+           "tardis_ffn_forward_static")
     return y
 
 

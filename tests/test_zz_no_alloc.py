@@ -1,0 +1,82 @@
+"""tardis_ffn_forward_static (the decode path on the library's static working memory, for callers
+that cannot allocate) against tardis_ffn_forward_batched on the same layer and tokens: masks bit for
+bit, y to the rounding of one bf16 output (the two calls add the same fp32 terms in a different
+order).  Two calls in a row, the second with fewer tokens; then the checker on top."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tardis_oracle as O
+from paper_2501_10054_amd import synth
+from paper_2501_10054_amd import tardis as T
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16).to(DEV).contiguous()
+
+
+def _host(t):
+    return t.detach().to("cpu").to(torch.float32).numpy().astype(np.float64)
+
+
+def _check_pair(layer, X, n):
+    """static call on the first n tokens of X against the batched call"""
+    words = (layer.h + 31) // 32
+    Xn = X[:n].contiguous()
+    y_ref = T.tardis_ffn_forward_batched(layer, Xn).clone()
+    m_ref, _, _ = T.tardis_get_last_outliers(layer, n, want_list=False)
+    m_ref = m_ref.clone()
+    mask = torch.full((n, words), -1, dtype=torch.int32, device=DEV)
+    y = torch.full_like(Xn, float("nan"))
+    T.tardis_ffn_forward_static(layer, Xn, y, mask)
+    torch.cuda.synchronize()
+    assert torch.equal(mask, m_ref), "mask words differ"
+    a, b = _host(y), _host(y_ref)
+    assert np.isfinite(a).all()
+    # same fp32 terms, other order: the bf16 outputs agree to one unit in the last place
+    tol = 2.0 ** -7 * np.abs(b) + 1e-6 * np.abs(b).max()
+    assert (np.abs(a - b) <= tol).all(), float(np.abs(a - b).max())
+    assert np.linalg.norm(a - b) <= 2e-3 * np.linalg.norm(b)
+    return a, mask
+
+
+@pytest.mark.parametrize("d,h,n1,n2", [(1024, 4096, 16, 5), (4096, 16384, 11, 1), (2048, 4096, 2, 1)])
+def test_static_matches_batched_two_calls(d, h, n1, n2):
+    w = synth.decode(d=d, h=h, n_cal=512, n_test=16, coverage=0.9)
+    L_ = w.layer
+    ffn = T.FFN(_dev(L_.W1), _dev(L_.W2))
+    lo, hi, a, c = T.tardis_calibrate(ffn, _dev(w.X_cal), w.coverage)
+    layer = T.tardis_fold(ffn, lo, hi, a, c, max_batch=16)
+    X = _dev(w.X_test)
+    y1, m1 = _check_pair(layer, X, n1)
+    y2, m2 = _check_pair(layer, X, n2)          # a smaller call right after: nothing of the first may leak
+    # and against the checker
+    torch.cuda.synchronize()
+    F = O.build(L_.W1, None, L_.W2, None, *(t.cpu().numpy() for t in (lo, hi, a, c)))
+    Yo, FLo = O.forward(F, w.X_test[:n1])
+    want = O.pack_mask(FLo)
+    assert np.array_equal(m1.cpu().numpy().view(np.uint32), want[:n1])
+    assert np.array_equal(m2.cpu().numpy().view(np.uint32), want[:n2])
+    assert np.linalg.norm(y1 - Yo) <= 1e-2 * np.linalg.norm(Yo)
+    assert np.linalg.norm(y2 - Yo[:n2]) <= 1e-2 * np.linalg.norm(Yo[:n2])
+    layer.close()
+
+
+def test_static_rejects_what_it_cannot_hold():
+    w = synth.decode(d=1024, h=4096, n_cal=256, n_test=32, coverage=0.9)
+    L_ = w.layer
+    ffn = T.FFN(_dev(L_.W1), _dev(L_.W2))
+    lo, hi, a, c = T.tardis_calibrate(ffn, _dev(w.X_cal), w.coverage)
+    layer = T.tardis_fold(ffn, lo, hi, a, c, max_batch=32)
+    X = _dev(w.X_test)
+    with pytest.raises(T.TardisError) as e:
+        T.tardis_ffn_forward_static(layer, X)              # 32 tokens: more than one call holds
+    assert e.value.status == T.ERR_SHAPE
+    with pytest.raises(T.TardisError) as e:
+        T.tardis_ffn_forward_static(layer, X[:4], X[:4])    # aliased
+    assert e.value.status == T.ERR_INVALID_ARG
+    layer.close()
