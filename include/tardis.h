@@ -121,8 +121,11 @@ tardis_status_t tardis_calibrate(const tardis_ffn_desc* desc, const void* X_cal,
  * left or to the right, whichever candidate range is approximated by its own
  * least-squares line with the smaller sum of |sigma(z) - (a z + c)| over its
  * samples (the right one on equality), until it holds the portion t of the
- * samples.  A side whose end lies beyond every sample is not grown further;
- * after 4096 steps the whole sample range is taken.  The layer-level and
+ * samples.  A side whose end lies beyond every sample is not grown further, so
+ * the search ends after at most (max z - min z) / step + 2 steps; a call in which
+ * some neuron would need more than 4096 steps (a step far below the spread of
+ * that neuron's inputs) returns TARDIS_ERR_INVALID_ARG and its outputs are not
+ * to be used.  The layer-level and
  * neuron-level threshold assignment of Algorithm 1 is not part of this call:
  * pass its result through coverage_per_neuron.
  *   step   range increment s > 0, in units of the pre-activation.

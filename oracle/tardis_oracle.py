@@ -160,7 +160,6 @@ def calibrate(W1, b1, X_cal, coverage, kind: str = "gelu_erf"):
 # the range holds the portion t of the calibration inputs)
 # ---------------------------------------------------------------------------
 KDE_GRID = 256            # points at which the density estimate is evaluated
-SEARCH_MAX_STEPS = 4096   # growth steps after which the whole sample range is taken
 
 
 def kde_centroid(zs: np.ndarray) -> float:
@@ -198,7 +197,7 @@ def approx_error(z_in: np.ndarray, kind: str) -> float:
     return float(np.abs(g - (a * z_in + c)).sum())
 
 
-def range_search(z: np.ndarray, t: float, step: float, kind: str = "gelu_erf"):
+def range_search(z: np.ndarray, t: float, step: float, kind: str = "gelu_erf", centroid=None, trace=None):
     """Greedy range of one neuron.  Returns (lo, hi) in fp64.
 
     R = [centroid, centroid); while the portion of the samples with lo <= z < hi
@@ -207,31 +206,43 @@ def range_search(z: np.ndarray, t: float, step: float, kind: str = "gelu_erf"):
     Readings where the listing is silent or garbled: both candidates keep the
     other end of R; a side whose end already lies beyond every sample (lo <=
     min z, resp. hi > max z) is not offered again - the listing would otherwise
-    keep choosing an extension that adds no sample and never end; after
-    SEARCH_MAX_STEPS steps the whole sample range is taken.
+    keep choosing an extension that adds no sample and never end.  With that
+    rule the loop ends by itself after at most (max z - min z) / s + 2 steps:
+    there is no step limit.
+
+    `centroid`: start there instead of at the density estimate's mode (for
+    worked examples).  `trace`: a list that receives one tuple per growth step,
+    (side taken 'L'/'R', e_l, e_r, gap) - the two candidates' errors (None when
+    only one side was on offer) and the distance from the nearest sample to the
+    nearest of the ends lo, hi, lo - s, hi + s that the step's tests compare
+    samples with: a step whose errors nearly agree, or whose ends nearly touch a
+    sample, is one that rounding of the inputs may decide the other way.
     """
     zs = np.sort(_f64(z))
     n = zs.shape[0]
-    lo = hi = kde_centroid(zs)
+    lo = hi = kde_centroid(zs) if centroid is None else float(centroid)
     zmin, zmax = float(zs[0]), float(zs[-1])
-    for _ in range(SEARCH_MAX_STEPS):
+    while True:
         inside = (zs >= lo) & (zs < hi)
         if inside.sum() / n >= t:
             return lo, hi
         left_open, right_open = lo > zmin, not hi > zmax
         if not left_open and not right_open:
             return lo, hi
+        e_l = e_r = None
         if left_open and right_open:
             e_l = approx_error(zs[(zs >= lo - step) & (zs < hi)], kind)
             e_r = approx_error(zs[(zs >= lo) & (zs < hi + step)], kind)
             go_left = e_l < e_r
         else:
             go_left = left_open
+        if trace is not None:
+            ends = np.array([lo, hi, lo - step, hi + step])
+            trace.append(("L" if go_left else "R", e_l, e_r, float(np.abs(zs[:, None] - ends[None, :]).min())))
         if go_left:
             lo = lo - step
         else:
             hi = hi + step
-    return zmin, float(np.nextafter(zmax, np.inf))
 
 
 def calibrate_search(W1, b1, X_cal, coverage, step, kind: str = "gelu_erf"):

@@ -363,7 +363,9 @@ calibrate_neuron_kernel(const float* __restrict__ Zt, int n, int npad, float cov
 // kernel density estimate on a grid of 256 points (bandwidth 1.06 std n^-1/5), then the range
 // grows by `step` to the left or to the right, whichever candidate's least-squares line leaves
 // the smaller sum of |sigma(z) - (a z + c)| over its samples (right on equality), until it holds
-// the portion t of the samples.  A side whose end lies beyond every sample is not offered again.
+// the portion t of the samples.  A side whose end lies beyond every sample is not offered again,
+// so the loop ends after at most (max z - min z) / step + 2 steps; kSearchMaxSteps is a guard on
+// the run time of one block, and a neuron that hits it makes the whole call fail.
 constexpr int kKdeGrid = 256;
 constexpr int kSearchMaxSteps = 4096;
 static_assert(kKdeGrid == kBlock, "one grid point per thread");
@@ -402,7 +404,7 @@ __device__ __forceinline__ int lower_bound_lds(const float* vals, int n, double 
 __global__ void __launch_bounds__(kBlock)
 range_search_kernel(const float* __restrict__ Zt, int n, int npad, float coverage, const float* __restrict__ cov_pn,
                     float step32, int act, float* __restrict__ lo, float* __restrict__ hi, float* __restrict__ a,
-                    float* __restrict__ c) {
+                    float* __restrict__ c, int* __restrict__ n_capped) {
     extern __shared__ double gv[];                   // sigma of the sorted samples, then the samples
     float* vals = reinterpret_cast<float*>(gv + ((n + 1) & ~1));
     __shared__ double red[kBlock / TD_WAVE];
@@ -500,7 +502,10 @@ range_search_kernel(const float* __restrict__ Zt, int n, int npad, float coverag
         }
         if (go_left) rlo = rlo - step; else rhi = rhi + step;
     }
-    if (!done) {   // step cap reached: the whole sample range
+    if (!done) {   // the run-time guard on the number of steps was hit (a step far below the samples'
+                   // spread): reported to the host, which fails the call; the whole sample range is
+                   // stored so that the outputs are at least well defined
+        if (threadIdx.x == 0) atomicAdd(n_capped, 1);
         rlo = zmin;
         rhi = nextafter(zmax, INFINITY);
     }
@@ -626,12 +631,20 @@ tardis_status_t td_calibrate(const tardis_ffn_desc* desc, const void* X, int64_t
         if (lds > 48 * 1024)
             TD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(range_search_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        DevBuf capped;
+        TD_TRY(capped.alloc(sizeof(int)));
+        TD_HIP(hipMemsetAsync(capped.p, 0, sizeof(int), s));
         hipLaunchKernelGGL(range_search_kernel, dim3((unsigned)h), dim3(kBlock), lds, s,
                            static_cast<const float*>(zt.p), (int)n, npad, coverage, cov_pn, step, (int)desc->act, lo,
-                           hi, a, c);
+                           hi, a, c, static_cast<int*>(capped.p));
         TD_HIP(hipGetLastError());
+        int n_capped = 0;
+        TD_HIP(hipMemcpyAsync(&n_capped, capped.p, sizeof(int), hipMemcpyDeviceToHost, s));
         TD_HIP(hipStreamSynchronize(s));
-        return TARDIS_OK;
+        // Algorithm 1 has no limit on the number of growth steps; the kernel's guard (4096) is only
+        // reached when `step` is absurdly small against a neuron's spread of inputs: refuse, do not
+        // substitute another range
+        return n_capped > 0 ? TARDIS_ERR_INVALID_ARG : TARDIS_OK;
     }
     const size_t lds = (size_t)npad * sizeof(float);
     if (lds > 48 * 1024)

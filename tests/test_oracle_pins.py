@@ -422,11 +422,70 @@ def test_range_search_tie_rule_and_exhausted_sides():
     assert hi4 > 2.0 and lo4 < -0.5                                # now it has to cross the kink
 
 
-def test_range_search_step_cap_takes_everything(monkeypatch):
-    monkeypatch.setattr(O, "SEARCH_MAX_STEPS", 5)
-    z = np.linspace(-1, 1, 50)
-    lo, hi = O.range_search(z, 0.99, 0.01, "gelu_erf")
-    assert lo == -1.0 and hi > 1.0 and ((z >= lo) & (z < hi)).all()
+def test_range_search_worked_example_ties_and_exhausted_right():
+    """Six samples, ReLU, start given: every step can be followed by eye.  On z > 0 ReLU is the
+    identity, so every candidate made of positive samples is fitted exactly (error 0) and so is any
+    candidate of one or two samples: all two-sided steps are ties and go right.
+      start [1, 1): nothing inside.        L [0.5, 1) = {0.5}, R [1, 1.5) = {1}: 0 = 0 -> right
+      [1, 1.5): {1}, 1/6.                  L {0.5, 1}, R {1, 1.5}: two points each, 0 = 0 -> right
+      [1, 2): {1, 1.5}, 2/6.               L {0.5, 1, 1.5}, R {1, 1.5, 2}: collinear, 0 = 0 -> right
+      [1, 2.5): 3/6; 2.5 is beyond the largest sample (2): the right side is no longer offered
+      left only: [0.5, 2.5) 4/6; [0, 2.5) 4/6 (no sample in [0, 0.5)); [-0.5, 2.5) 5/6 >= 0.8: done."""
+    z = np.array([-1.0, -0.5, 0.5, 1.0, 1.5, 2.0])
+    tr = []
+    lo, hi = O.range_search(z, 0.8, 0.5, "relu", centroid=1.0, trace=tr)
+    assert (lo, hi) == (-0.5, 2.5)
+    assert [s for s, *_ in tr] == ["R", "R", "R", "L", "L", "L"]
+    assert [(el, er) for _, el, er, _ in tr[:3]] == [(0.0, 0.0)] * 3      # the three ties
+    assert all(el is None and er is None for _, el, er, _ in tr[3:])      # one side on offer: no comparison
+    assert O.range_search(z, 4 / 6, 0.5, "relu", centroid=1.0) == (0.5, 2.5)    # stops as soon as t is reached
+    assert O.range_search(z, 4 / 6 + 1e-9, 0.5, "relu", centroid=1.0) == (-0.5, 2.5)
+
+
+def test_range_search_worked_example_left_wins_only_when_strictly_smaller():
+    """Start on ReLU's flat side.  Candidates made of samples <= 0 (all mapped to 0), or of two
+    samples, have error 0; a candidate holding -0.75, -0.1 AND 0.6 is not collinear: error > 0.
+      [-1, -1):                           L {-1.25}, R {-0.75}: tie -> right
+      [-1, -0.5): {-0.75} 1/6.            L {-1.25, -0.75}, R {-0.75, -0.1}: tie -> right
+      [-1, 0): 2/6.                       L {-1.25, -0.75, -0.1} (flat, 0), R [-1, 0.5) = {-0.75, -0.1}: tie -> right
+      [-1, 0.5): 2/6.                     L flat 0, R [-1, 1) = {-0.75, -0.1, 0.6} > 0 -> LEFT (0 < e_r)
+      [-1.5, 0.5): 3/6.                   L [-2, 0.5) four flat samples 0, R [-1.5, 1) > 0 -> left
+      [-2, 0.5): 4/6; -2 <= smallest sample (-1.75): the left side is no longer offered
+      right only: [-2, 1) holds 0.6: 5/6 >= 0.8: done."""
+    z = np.array([-1.75, -1.25, -0.75, -0.1, 0.6, 1.0])
+    tr = []
+    lo, hi = O.range_search(z, 0.8, 0.5, "relu", centroid=-1.0, trace=tr)
+    assert (lo, hi) == (-2.0, 1.0)
+    assert [s for s, *_ in tr] == ["R", "R", "R", "L", "L", "R"]
+    assert tr[3][1] == 0.0 and tr[3][2] > 0.0 and tr[4][1] == 0.0 and tr[4][2] > 0.0
+    # the error of the non-collinear candidate, by hand: points (-0.75, 0), (-0.1, 0), (0.6, 0.6);
+    # least squares through three points, residuals sum in absolute value
+    zz, gg = np.array([-0.75, -0.1, 0.6]), np.array([0.0, 0.0, 0.6])
+    A = np.stack([zz, np.ones(3)], 1)
+    coef = np.linalg.solve(A.T @ A, A.T @ gg)                    # normal equations, written out
+    assert tr[3][2] == pytest.approx(np.abs(gg - A @ coef).sum(), rel=1e-12)
+    # gap: the distance from the nearest sample to the nearest end a step tests with; step 3's
+    # right candidate ends at 0.5, the sample 0.6 is 0.1 away
+    assert tr[2][3] == pytest.approx(0.1, abs=1e-12)
+
+
+def test_range_search_degenerate_inputs_by_hand():
+    # all samples equal: the start is that value, nothing is inside [2, 2); the left end is not
+    # above the smallest sample, so only the right side is offered: [2, 2 + s) holds everything
+    assert O.range_search(np.full(5, 2.0), 0.9, 0.25, "gelu_erf") == (2.0, 2.25)
+    assert O.range_search(np.array([-3.0]), 1.0, 0.5, "relu") == (-3.0, -2.5)           # one sample
+    # nothing asked for: the empty range at the start
+    assert O.range_search(np.array([0.0, 1.0, 2.0]), 0.0, 0.5, "relu", centroid=1.0) == (1.0, 1.0)
+    # a step far below the spread of the samples: no limit on the number of steps, the loop ends
+    # when the range holds the portion asked for.  Identity: every step is a tie, so right until
+    # the largest sample (1.0) is passed - 1024 steps of 2^-10 reach 1.0, which is not yet beyond
+    # it, one more is - then left down to the smallest sample (-1.0): 1024 steps.
+    z = np.array([-1.0, -0.3, 0.2, 0.9, 1.0])
+    tr = []
+    s = 2.0 ** -10
+    lo, hi = O.range_search(z, 1.0, s, "identity", centroid=0.0, trace=tr)
+    assert (lo, hi) == (-1.0, 1.0 + s) and ((z >= lo) & (z < hi)).all()
+    assert [side for side, *_ in tr] == ["R"] * 1025 + ["L"] * 1024
 
 
 def test_calibrate_search_covers_and_fits():
