@@ -27,11 +27,22 @@ if ROOT not in sys.path:
 D, H = 4096, 16384
 TOKENS_PER_STEP = 1024
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of decode_fused_kernel from `rocprofv3 --pmc` (FETCH_SIZE and WRITE_SIZE runs,
-# scaled by a copy kernel of known size); see profiles/*hbm-traffic.md.
-MEASURED_TRAFFIC_BYTES = {8: 133046911, 4: 102575216}     # by sketch width, with the next-layer hint (the
-# requested rows cross the fabric twice: once ahead of time, once - from the last-level cache - when used)
-MEASURED_TRAFFIC_BYTES_NO_HINT = {8: 119111012, 4: 88642936}
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
+
+
+def measured_traffic(kernel: str, sketch_bits: int, hint: bool):
+    """HBM bytes per launch of `kernel` from the rocprofv3 counter runs recorded in
+    profiles/traffic.json (FETCH_SIZE and WRITE_SIZE, scaled by a copy of known size), or None if
+    no record matches - never a number typed into this file."""
+    try:
+        with open(TRAFFIC_JSON) as f:
+            rec = json.load(f)
+    except (OSError, ValueError):
+        return None
+    for r in rec.get("records", []):
+        if r.get("kernel") == kernel and r.get("sketch_bits") == sketch_bits and bool(r.get("next_layer_hint")) == hint:
+            return r.get("hbm_bytes_per_launch")
+    return None
 
 
 def algorithmic_bytes(d: int, h: int, p: float, sketch_bits: int = 8) -> float:
@@ -96,8 +107,11 @@ def prefill_run(T, synth, torch, np, to_dev):
                     "calibrate = 1 such GEMM + per-neuron sort/fit" % (gemm_flop / 1e9)}
 
 
-def stack_run(T, synth, torch, np, to_dev, n_layers):
-    """n_layers independent layers chained with RMS-norm glue, batch 1 and 32."""
+def stack_run(T, synth, torch, np, to_dev, n_layers, batches=(1, 32)):
+    """n_layers independent layers chained with RMS-norm glue (config 4): per batch size the time
+    of one pass through the whole stack, the per-layer measured fallback rates and the algorithmic
+    bytes one pass must move (every layer's folded matrix and sketch once, the W1/W2 rows of the
+    union of each layer's flagged neurons, the tokens) against the HBM peak."""
     layers = []
     for li in range(n_layers):
         w = synth.decode(layer=li, n_cal=2048, n_test=32, coverage=0.95, config=4)
@@ -106,16 +120,19 @@ def stack_run(T, synth, torch, np, to_dev, n_layers):
         layers.append(T.tardis_fold(ffn, lo, hi, a, c, max_batch=32))
         if li == 0:
             X = to_dev(w.X_test)
-        print(f"bench.py: stack layer {li + 1}/{n_layers} folded", file=sys.stderr, flush=True)
+        if (li + 1) % 8 == 0:
+            print(f"bench.py: stack layer {li + 1}/{n_layers} folded", file=sys.stderr, flush=True)
     out = {"layers": n_layers}
-    for B in (1, 4, 8, 32):
+    for B in batches:
         xb = X[:B].contiguous()
         yb = torch.empty_like(xb)
         us = _time_us(torch, lambda: T.tardis_stack_forward(layers, xb, yb), 10, 2)
-        rates = []
+        rates, unions = [], []
         for L in layers:
             _, cnt, _ = T.tardis_get_last_outliers(L, B, want_list=False)
+            ucnt, _ = T.tardis_get_last_union(L, B)
             rates.append(float(cnt.float().mean().item()) / H)
+            unions.append(int(ucnt.item()))
         def dense_stack():
             h_ = xb
             for L in layers:
@@ -123,9 +140,14 @@ def stack_run(T, synth, torch, np, to_dev, n_layers):
                 h_ = torch.nn.functional.rms_norm(h_, (D,), eps=1e-6)
             return h_
         dus = _time_us(torch, dense_stack, 10, 2)
-        out[f"batch{B}"] = {"us_per_step": us, "tokens_per_s": B / (us * 1e-6), "dense_torch_us_per_step": dus,
-                            "speedup_vs_dense_torch": dus / us,
-                            "per_layer_fallback_rate": [round(r, 4) for r in rates]}
+        alg = sum(2.0 * D * D + 1.0 * D * H + u * 4.0 * D + B * 6.0 * D for u in unions)
+        out[f"batch{B}"] = {"us_per_step": us, "us_per_layer": us / n_layers, "tokens_per_s": B / (us * 1e-6),
+                            "dense_torch_us_per_step": dus, "speedup_vs_dense_torch": dus / us,
+                            "per_layer_fallback_rate": [round(r, 4) for r in rates],
+                            "per_layer_union_neurons": unions,
+                            "roofline_stack": {"bound": "hbm", "algorithmic_bytes_per_step": alg,
+                                               "achieved": alg / us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                               "frac": alg / us / 1e3 / HBM_PEAK_GBS}}
     for L in layers:
         L.close()
     return out
@@ -151,9 +173,9 @@ def batched_sweep(T, synth, torch, np, to_dev, pre, X, coverages, chain=True):
             xb = X[:B].contiguous()
             yb = torch.empty_like(xb)
             T.tardis_ffn_forward_batched(layers[0], xb, yb)
-            mask, counts, _ = T.tardis_get_last_outliers(layers[0], B, want_list=False)
-            union = int((mask.cpu().numpy().view(np.uint32)[:, None, :] >> np.arange(32, dtype=np.uint32)[None, :, None] & 1)
-                        .any(axis=0).sum())
+            _, counts, _ = T.tardis_get_last_outliers(layers[0], B, want_list=False)
+            ucnt, _ = T.tardis_get_last_union(layers[0], B)
+            union = int(ucnt.item())                  # computed on the device from the call's mask words
             p = float(counts.float().mean().item()) / H
             reps = 60
             for L in layers:
@@ -180,6 +202,7 @@ def batched_sweep(T, synth, torch, np, to_dev, pre, X, coverages, chain=True):
             alg = 2.0 * D * D + D * H + union * 4.0 * D + B * 6.0 * D
             rows.append({"batch": B, "coverage_t": cov, "fallback_rate": p, "union_neurons": union,
                          "us_per_batch": us, "tokens_per_s": B / (us * 1e-6), "algorithmic_GBs": alg / us / 1e3,
+                         "frac": alg / us / 1e3 / HBM_PEAK_GBS,
                          "dense_torch_us_per_batch": dus, "speedup_vs_dense_torch": dus / us})
         for L in layers:
             L.close()
@@ -206,10 +229,11 @@ def main() -> int:
     ap.add_argument("--no-chain", action="store_true",
                     help="do not tell each layer copy which copy runs next (no cache-warming hint)")
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of a replayed HIP graph")
-    ap.add_argument("--sweep", action="store_true",
-                    help="also run the batched decode sweep: batch {2,4,8,16,64} x coverage {0.99,0.95,0.85}")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="batched decode at the headline coverage only (default: batch {2,4,8,16,64} x coverage {0.99,0.95,0.85})")
     ap.add_argument("--prefill", action="store_true", help="run the 2048-token prompt shape even with --no-extras")
-    ap.add_argument("--stack", type=int, default=0, help="also run a stack of this many layers (32 = the full configuration)")
+    ap.add_argument("--stack", type=int, default=None,
+                    help="layers of the FFN stack run at batch 1 and 32 (32 = the full configuration; 0 = skip)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a 1 GiB device copy (known HBM traffic) so that profiler counters can be scaled")
     args = ap.parse_args()
@@ -329,6 +353,8 @@ def main() -> int:
     chained = False
     if args.headline_only:
         args.no_dense = args.no_extras = args.no_cpu_baseline = True
+    if args.stack is None:
+        args.stack = 0 if args.no_extras else 32
     if not args.no_chain and len(layers) > 1:
         if not args.headline_only:
             plain_ms, _ = timed(handles, max(2, args.steps // 2), 1, graph=use_graph)
@@ -413,7 +439,7 @@ def main() -> int:
                    "sketch_bits": args.sketch_bits},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": (MEASURED_TRAFFIC_BYTES if chained else MEASURED_TRAFFIC_BYTES_NO_HINT)[args.sketch_bits],
+                     "traffic": measured_traffic("decode_fused_kernel", args.sketch_bits, chained),
                      "kernel": "decode_fused_kernel", "algorithmic_bytes_per_launch": bytes_tok,
                      "avg_launch_us": launch_s * 1e6},
         "cpu_baseline": cpu,
@@ -453,12 +479,15 @@ def main() -> int:
                           "algorithmic_GBs": b4 / (ms4 * 1e-3 / TOKENS_PER_STEP) / 1e9}
         for L in l4:
             L.close()
-        covs = (0.99, 0.95, 0.85) if args.sweep else (args.coverage,)
+        covs = (args.coverage,) if args.no_sweep else (0.99, 0.95, 0.85)
         out["batched_sweep"] = batched_sweep(T, synth, torch, np, to_dev, pre, X, covs, chain=not args.no_chain)
     if args.prefill or not args.no_extras:
         print("bench.py: prompt shape (2048 tokens)", file=sys.stderr, flush=True)
         out["prefill"] = prefill_run(T, synth, torch, np, to_dev)
     if args.stack > 0:
+        for L in layers:                    # the headline copies are no longer needed: make room
+            L.close()
+        layers = []
         out["stack"] = stack_run(T, synth, torch, np, to_dev, args.stack)
     if args.copy_probe:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()

@@ -29,6 +29,12 @@
  *     anything is launched; an asynchronous GPU fault surfaces at the caller's
  *     next synchronisation.  One stream at a time may use a handle.
  *   - Ranges are half open: a neuron is "in range" iff lo_j <= z_j < hi_j.
+ *   - Handles are checked against the library's table of live layers: NULL, a
+ *     pointer this library did not hand out, or a destroyed handle gives
+ *     TARDIS_ERR_STATE (never a dereference).  If an online call returns
+ *     TARDIS_ERR_HIP (a launch failed half way) the handle's working memory is in
+ *     an unknown state: every later online call on it returns TARDIS_ERR_STATE;
+ *     destroy it and fold again.
  */
 #ifndef TARDIS_H
 #define TARDIS_H
@@ -263,13 +269,24 @@ tardis_status_t tardis_get_sketch_groups(tardis_handle_t L, uint8_t* M, void* st
 tardis_status_t tardis_get_last_outliers(tardis_handle_t L, int64_t n, uint32_t* mask,
                                          int32_t* counts, int32_t* list, void* stream);
 
+/* The union over the n tokens of the most recent online call: the neurons flagged
+ * by at least one of them - what a batch has to fetch of the original weights
+ * (Sec. "Inference Runtime", memory footprint; the batched-decode figures report
+ * it).  Computed on the device, stream-ordered; either output may be NULL.
+ *   union_mask   ceil(h/32) words, bit layout as in tardis_get_last_outliers
+ *   union_count  one int (device memory): the number of set bits
+ * n must equal the token count of that call. */
+tardis_status_t tardis_get_last_union(tardis_handle_t L, int64_t n, uint32_t* union_mask,
+                                      int32_t* union_count, void* stream);
+
 /* The normalised activation this layer handed to the next one in the most
  * recent tardis_stack_forward (n x d, layer dtype; stream-ordered copy).  Only
  * meaningful for a layer that was not last in that stack. */
 tardis_status_t tardis_get_handover(tardis_handle_t L, int64_t n, void* out, void* stream);
 
 /* Frees everything the handle owns.  The caller must have synchronised every
- * stream that used it.  NULL is accepted. */
+ * stream that used it.  NULL is accepted; a pointer that is not a live handle
+ * (destroyed before, or never made here) returns TARDIS_ERR_STATE. */
 tardis_status_t tardis_destroy(tardis_handle_t L);
 
 /* Static, NUL-terminated description of a status code (host). */

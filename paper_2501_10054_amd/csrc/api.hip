@@ -168,6 +168,24 @@ bool td_layer_is_live(const tardis_layer_s* L) {
     return g_live.count(L) != 0;
 }
 
+namespace {
+
+// a handle this library made and has not destroyed, and whose working memory is in a known state
+tardis_status_t check_handle(const tardis_layer_s* L) {
+    if (!L || !td_layer_is_live(L)) return TARDIS_ERR_STATE;
+    return L->poisoned ? TARDIS_ERR_STATE : TARDIS_OK;
+}
+
+// An online call that fails after its first launch may leave completion counters and accumulators
+// armed; every later call on the handle would then assemble garbage without saying so.  Such a
+// handle is marked and refuses further online calls (destroy and fold again).
+tardis_status_t online_result(tardis_layer_s* L, tardis_status_t st) {
+    if (st == TARDIS_ERR_HIP) L->poisoned = 1;
+    return st;
+}
+
+}  // namespace
+
 extern "C" {
 
 tardis_status_t tardis_calibrate(const tardis_ffn_desc* desc, const void* X_cal, int64_t n_cal, float coverage,
@@ -235,10 +253,10 @@ tardis_status_t tardis_ffn_forward(tardis_handle_t L, const void* x, void* y, vo
 }
 
 tardis_status_t tardis_ffn_forward_batched(tardis_handle_t L, const void* x, int64_t n, void* y, void* stream) {
-    if (!L) return TARDIS_ERR_STATE;
+    TD_TRY(check_handle(L));
     if (!x || !y || x == y) return TARDIS_ERR_INVALID_ARG;
     if (n < 1 || n > L->max_batch) return TARDIS_ERR_SHAPE;
-    return td_forward(L, x, n, y, 0, static_cast<hipStream_t>(stream));
+    return online_result(L, td_forward(L, x, n, y, 0, static_cast<hipStream_t>(stream)));
 }
 
 tardis_status_t tardis_stack_forward(const tardis_handle_t* layers, int32_t n_layers, const void* x, int64_t n,
@@ -246,7 +264,7 @@ tardis_status_t tardis_stack_forward(const tardis_handle_t* layers, int32_t n_la
     if (!layers || n_layers < 1 || n_layers > 4096) return TARDIS_ERR_INVALID_ARG;
     if (!x || !y || x == y) return TARDIS_ERR_INVALID_ARG;
     for (int32_t l = 0; l < n_layers; ++l) {
-        if (!layers[l]) return TARDIS_ERR_STATE;
+        TD_TRY(check_handle(layers[l]));
         if (layers[l]->d != layers[0]->d || layers[l]->dtype != layers[0]->dtype) return TARDIS_ERR_SHAPE;
         if (n < 1 || n > layers[l]->max_batch) return TARDIS_ERR_SHAPE;
         for (int32_t m = 0; m < l; ++m)
@@ -259,7 +277,7 @@ tardis_status_t tardis_stack_forward(const tardis_handle_t* layers, int32_t n_la
         void* out = last ? y : layers[l]->xnext;
         const tardis_layer_s* keep = layers[l]->next_layer;
         if (!last) layers[l]->next_layer = layers[l + 1];        // the stack knows what runs next
-        const tardis_status_t st = td_forward(layers[l], cur, n, out, last ? 0 : 1, s);
+        const tardis_status_t st = online_result(layers[l], td_forward(layers[l], cur, n, out, last ? 0 : 1, s));
         layers[l]->next_layer = keep;
         TD_TRY(st);
         cur = out;
@@ -268,14 +286,14 @@ tardis_status_t tardis_stack_forward(const tardis_handle_t* layers, int32_t n_la
 }
 
 tardis_status_t tardis_dense_forward(tardis_handle_t L, const void* x, int64_t n, void* y, void* stream) {
-    if (!L) return TARDIS_ERR_STATE;
+    TD_TRY(check_handle(L));
     if (!x || !y || x == y) return TARDIS_ERR_INVALID_ARG;
     if (n < 1 || n > L->max_batch) return TARDIS_ERR_SHAPE;
     return td_dense_forward(L, x, n, y, static_cast<hipStream_t>(stream));
 }
 
 tardis_status_t tardis_get_folded(tardis_handle_t L, void* Wp, float* bp, void* stream) {
-    if (!L) return TARDIS_ERR_STATE;
+    if (!L || !td_layer_is_live(L)) return TARDIS_ERR_STATE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (Wp) TD_HIP(hipMemcpyAsync(Wp, L->Wp, (size_t)L->d * L->d * td_elem_size(L->dtype), hipMemcpyDeviceToDevice, s));
     if (bp) TD_HIP(hipMemcpyAsync(bp, L->bp, (size_t)L->d * 4, hipMemcpyDeviceToDevice, s));
@@ -283,7 +301,7 @@ tardis_status_t tardis_get_folded(tardis_handle_t L, void* Wp, float* bp, void* 
 }
 
 tardis_status_t tardis_get_predictor_state(tardis_handle_t L, int8_t* Q, float* tlo, float* thi, void* stream) {
-    if (!L) return TARDIS_ERR_STATE;
+    if (!L || !td_layer_is_live(L)) return TARDIS_ERR_STATE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (Q) {
         if (L->Q)
@@ -297,7 +315,7 @@ tardis_status_t tardis_get_predictor_state(tardis_handle_t L, int8_t* Q, float* 
 }
 
 tardis_status_t tardis_get_sketch_groups(tardis_handle_t L, uint8_t* M, void* stream) {
-    if (!L || L->sketch_bits != 4) return TARDIS_ERR_STATE;
+    if (!L || !td_layer_is_live(L) || L->sketch_bits != 4) return TARDIS_ERR_STATE;
     if (!M) return TARDIS_ERR_INVALID_ARG;
     TD_HIP(hipMemcpyAsync(M, L->M4, (size_t)L->h * ((L->d + 31) / 32), hipMemcpyDeviceToDevice,
                           static_cast<hipStream_t>(stream)));
@@ -306,7 +324,7 @@ tardis_status_t tardis_get_sketch_groups(tardis_handle_t L, uint8_t* M, void* st
 
 tardis_status_t tardis_get_last_outliers(tardis_handle_t L, int64_t n, uint32_t* mask, int32_t* counts,
                                          int32_t* list, void* stream) {
-    if (!L) return TARDIS_ERR_STATE;
+    if (!L || !td_layer_is_live(L)) return TARDIS_ERR_STATE;
     if (n < 1 || n != L->last_n) return TARDIS_ERR_STATE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const size_t nn = (size_t)n;
@@ -315,8 +333,16 @@ tardis_status_t tardis_get_last_outliers(tardis_handle_t L, int64_t n, uint32_t*
     return TARDIS_OK;
 }
 
+tardis_status_t tardis_get_last_union(tardis_handle_t L, int64_t n, uint32_t* union_mask, int32_t* union_count,
+                                      void* stream) {
+    if (!L || !td_layer_is_live(L)) return TARDIS_ERR_STATE;
+    if (n < 1 || n != L->last_n) return TARDIS_ERR_STATE;
+    if (!union_mask && !union_count) return TARDIS_OK;
+    return td_mask_union(L, n, union_mask, union_count, static_cast<hipStream_t>(stream));
+}
+
 tardis_status_t tardis_get_handover(tardis_handle_t L, int64_t n, void* out, void* stream) {
-    if (!L) return TARDIS_ERR_STATE;
+    if (!L || !td_layer_is_live(L)) return TARDIS_ERR_STATE;
     if (!out) return TARDIS_ERR_INVALID_ARG;
     if (n < 1 || n > L->max_batch) return TARDIS_ERR_SHAPE;
     TD_HIP(hipMemcpyAsync(out, L->xnext, (size_t)n * L->d * td_elem_size(L->dtype), hipMemcpyDeviceToDevice,
@@ -325,9 +351,10 @@ tardis_status_t tardis_get_handover(tardis_handle_t L, int64_t n, void* out, voi
 }
 
 tardis_status_t tardis_destroy(tardis_handle_t L) {
-    if (L) {
+    if (!L) return TARDIS_OK;
+    {
         std::lock_guard<std::mutex> guard(g_live_lock);
-        g_live.erase(L);
+        if (g_live.erase(L) == 0) return TARDIS_ERR_STATE;   // not a handle of this library, or destroyed already
     }
     free_layer(L);
     return TARDIS_OK;

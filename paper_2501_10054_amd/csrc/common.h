@@ -102,6 +102,7 @@ struct tardis_layer_s {
     int32_t gather_max_tokens;     // passes of up to this many tokens scatter through the union rows of W2^T
     int32_t batched_min_tokens;    // token counts up to this go through the single-token path
     int64_t last_n;    // token count of the most recent online call
+    int32_t poisoned;  // a launch of an online call failed half way: counters and accumulators may be left armed
 };
 
 static inline size_t td_elem_size(int32_t dtype) { return dtype == TARDIS_BF16 ? 2 : 4; }
@@ -223,6 +224,8 @@ constexpr int kDecodeMaxTokens = 16;  // tokens one weight pass of the decode ke
 tardis_status_t td_decode_fused(tardis_layer_s* L, const void* x, int64_t n, void* y, int norm_out, hipStream_t s);
 // looks up the current device's static decode working memory (once per device)
 tardis_status_t td_static_scratch_setup();
+tardis_status_t td_mask_union(const tardis_layer_s* L, int64_t n, uint32_t* union_mask, int32_t* union_count,
+                              hipStream_t s);
 tardis_status_t td_mask_to_list(const tardis_layer_s* L, int64_t n, int32_t* counts, int32_t* list, hipStream_t s);
 // batched.hip
 bool td_batched_supported(const tardis_layer_s* L);

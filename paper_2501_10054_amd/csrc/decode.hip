@@ -1005,6 +1005,25 @@ mask_to_list_kernel(const uint32_t* __restrict__ mask, int words, int h, int32_t
     if (threadIdx.x == 0 && counts) counts[t] = carry;
 }
 
+// union over the n tokens of a call: the neurons flagged by at least one of them (mask words and
+// their number); one block, no atomics
+__global__ void __launch_bounds__(256)
+mask_union_kernel(const uint32_t* __restrict__ mask, int words, int n, uint32_t* __restrict__ union_mask,
+                  int32_t* __restrict__ union_count) {
+    __shared__ int wave_tot[4];
+    int mine = 0;
+    for (int w = threadIdx.x; w < words; w += 256) {
+        uint32_t bits = 0u;
+        for (int t = 0; t < n; ++t) bits |= mask[(size_t)t * words + w];
+        if (union_mask) union_mask[w] = bits;
+        mine += __popc(bits);
+    }
+    mine = td_wave_sum_i(mine);
+    if ((threadIdx.x & 63) == 0) wave_tot[threadIdx.x >> 6] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0 && union_count) *union_count = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+}
+
 template <int D, int BLOCK, int TB, int SK, bool DEFER, int NG = 0>
 tardis_status_t launch_decode(tardis_layer_s* L, const DecodeScratch& ws, const void* x, void* y, float* yfold,
                               uint32_t* mask, int n_act, int norm_out, hipStream_t s) {
@@ -1254,7 +1273,7 @@ tardis_status_t td_static_scratch_setup() {
 
 extern "C" tardis_status_t tardis_ffn_forward_static(tardis_handle_t L, const void* x, int64_t n, void* y,
                                                       uint32_t* mask_out, void* stream) {
-    if (!L || !td_layer_is_live(L)) return TARDIS_ERR_STATE;
+    if (!L || !td_layer_is_live(L) || L->poisoned) return TARDIS_ERR_STATE;
     if (!x || !y || x == y) return TARDIS_ERR_INVALID_ARG;
     if (n < 1 || n > kDecodeMaxTokens) return TARDIS_ERR_SHAPE;
     if (!L->use_fused || L->dtype != TARDIS_BF16) return TARDIS_ERR_STATE;
@@ -1278,6 +1297,14 @@ extern "C" tardis_status_t tardis_ffn_forward_static(tardis_handle_t L, const vo
     uint32_t* mask = mask_out ? mask_out : reinterpret_cast<uint32_t*>(base + kStMask);
     return decode_tokens(L, ws, static_cast<const bf16_t*>(x), n, static_cast<bf16_t*>(y),
                          reinterpret_cast<float*>(base + kStYfold), mask, 0, s);
+}
+
+tardis_status_t td_mask_union(const tardis_layer_s* L, int64_t n, uint32_t* union_mask, int32_t* union_count,
+                              hipStream_t s) {
+    hipLaunchKernelGGL(mask_union_kernel, dim3(1), dim3(256), 0, s, L->mask, (int)L->mask_words, (int)n, union_mask,
+                       union_count);
+    TD_HIP(hipGetLastError());
+    return TARDIS_OK;
 }
 
 tardis_status_t td_mask_to_list(const tardis_layer_s* L, int64_t n, int32_t* counts, int32_t* list, hipStream_t s) {

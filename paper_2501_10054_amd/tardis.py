@@ -24,7 +24,7 @@ _DTYPE_CODE = {torch.float32: F32, torch.bfloat16: BF16}
 EXPORTS = (
     "tardis_calibrate", "tardis_calibrate_search", "tardis_fold", "tardis_ffn_forward", "tardis_ffn_forward_batched",
     "tardis_ffn_forward_static", "tardis_stack_forward", "tardis_dense_forward", "tardis_get_folded", "tardis_get_predictor_state",
-    "tardis_get_sketch_groups", "tardis_get_last_outliers", "tardis_get_handover", "tardis_set_next_layer",
+    "tardis_get_sketch_groups", "tardis_get_last_outliers", "tardis_get_last_union", "tardis_get_handover", "tardis_set_next_layer",
     "tardis_destroy", "tardis_status_string", "tardis_version",
 )
 
@@ -70,6 +70,7 @@ def lib() -> C.CDLL:
         L.tardis_get_predictor_state.argtypes = [vp, vp, vp, vp, vp]
         L.tardis_get_sketch_groups.argtypes = [vp, vp, vp]
         L.tardis_get_last_outliers.argtypes = [vp, i64, vp, vp, vp, vp]
+        L.tardis_get_last_union.argtypes = [vp, i64, vp, vp, vp]
         L.tardis_get_handover.argtypes = [vp, i64, vp, vp]
         L.tardis_destroy.argtypes = [vp]
         L.tardis_status_string.argtypes = [C.c_int]
@@ -258,3 +259,11 @@ def tardis_get_last_outliers(L: Layer, n: int, want_list: bool = True, stream=No
     _check(lib().tardis_get_last_outliers(L.handle, n, _ptr(mask), _ptr(counts), _ptr(lst), _stream(stream)),
            "tardis_get_last_outliers")
     return mask, counts, lst
+
+
+def tardis_get_last_union(L: Layer, n: int, want_mask: bool = False, stream=None):
+    """-> (union_count int32[1] on the device, union mask int32[ceil(h/32)] or None)."""
+    cnt = torch.empty(1, dtype=torch.int32, device=L.device)
+    um = torch.empty((L.h + 31) // 32, dtype=torch.int32, device=L.device) if want_mask else None
+    _check(lib().tardis_get_last_union(L.handle, n, _ptr(um), _ptr(cnt), _stream(stream)), "tardis_get_last_union")
+    return cnt, um

@@ -113,9 +113,32 @@ def test_online_calls_reject_null_handle():
     assert lib.tardis_stack_forward(arr, 2, p, 1, C.c_void_p(0x8000), None) == T.ERR_STATE
     assert lib.tardis_stack_forward(None, 2, p, 1, C.c_void_p(0x8000), None) == T.ERR_INVALID_ARG
     assert lib.tardis_stack_forward(arr, 0, p, 1, C.c_void_p(0x8000), None) == T.ERR_INVALID_ARG
+    assert lib.tardis_get_last_union(None, 1, p, p, None) == T.ERR_STATE
+    assert lib.tardis_ffn_forward_static(None, p, 1, C.c_void_p(0x8000), None, None) == T.ERR_STATE
     assert lib.tardis_set_next_layer(None, None) == T.ERR_STATE
     assert lib.tardis_set_next_layer(p, None) == T.ERR_STATE     # not a handle this library made
     assert lib.tardis_destroy(None) == T.OK
+
+
+def test_calls_reject_a_pointer_that_is_not_a_live_handle():
+    """Every entry point looks the handle up in the table of live layers before touching it: a
+    stale or foreign pointer is an error, never a dereference (0x4000 is not mapped)."""
+    lib = T.lib()
+    bogus = C.c_void_p(0x4000)
+    p, q = C.c_void_p(0x10000), C.c_void_p(0x20000)
+    assert lib.tardis_ffn_forward(bogus, p, q, None) == T.ERR_STATE
+    assert lib.tardis_ffn_forward_batched(bogus, p, 1, q, None) == T.ERR_STATE
+    assert lib.tardis_ffn_forward_static(bogus, p, 1, q, None, None) == T.ERR_STATE
+    assert lib.tardis_dense_forward(bogus, p, 1, q, None) == T.ERR_STATE
+    assert lib.tardis_get_folded(bogus, p, p, None) == T.ERR_STATE
+    assert lib.tardis_get_predictor_state(bogus, p, p, p, None) == T.ERR_STATE
+    assert lib.tardis_get_sketch_groups(bogus, p, None) == T.ERR_STATE
+    assert lib.tardis_get_last_outliers(bogus, 1, p, p, p, None) == T.ERR_STATE
+    assert lib.tardis_get_last_union(bogus, 1, p, p, None) == T.ERR_STATE
+    assert lib.tardis_get_handover(bogus, 1, p, None) == T.ERR_STATE
+    arr = (C.c_void_p * 1)(bogus)
+    assert lib.tardis_stack_forward(arr, 1, p, 1, q, None) == T.ERR_STATE
+    assert lib.tardis_destroy(bogus) == T.ERR_STATE
 
 
 def test_error_type_carries_status():

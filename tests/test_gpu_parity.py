@@ -123,7 +123,11 @@ def run_case(layer, X_cal, X_test, coverage, act="gelu_erf", batched=False, chec
     if batched:
         Y = T.tardis_ffn_forward_batched(L, Xd)
         mask, counts, lst = T.tardis_get_last_outliers(L, n)
+        ucnt, umask = T.tardis_get_last_union(L, n, want_mask=True)
         torch.cuda.synchronize()
+        # the union of the call's flag sets, computed on the device: what the batch must fetch
+        assert int(ucnt.item()) == int(FLo.any(axis=0).sum())
+        np.testing.assert_array_equal(umask.cpu().numpy().view(np.uint32), O.pack_mask(FLo.any(axis=0)[None])[0])
         Yg = host(Y)
         FLg = unpack_mask(mask, layer.h)
         counts = counts.cpu().numpy()
@@ -262,32 +266,63 @@ def test_prompt_threshold_off_takes_token_passes(monkeypatch):
 
 
 # ------------------------------------------------------------- greedy range search
-@pytest.mark.parametrize("dtype,d,h,n_cal,t,step,act", [("f32", 64, 96, 400, 0.9, 0.05, "gelu_erf"),
-                                                       ("bf16", 256, 64, 1000, 0.85, 0.1, "gelu_erf"),
-                                                       ("f32", 64, 48, 300, 0.8, 0.08, "relu"),
-                                                       ("f32", 48, 40, 257, 1.0, 0.25, "gelu_tanh")])
-def test_calibrate_search_against_checker(dtype, d, h, n_cal, t, step, act):
+TIE_REL = 1e-3      # two candidates' errors closer than this (relative) ...
+TIE_GAP = 2e-5      # ... or a sample this close (x the largest range end) to an end a step compares with
+
+
+def assert_search_differences_are_near_ties(Z, tj, step, act, differing, scale):
+    """Every neuron whose searched range differs from the checker's had a growth step that the
+    rounding of the pre-activations (fp32 dot products here, fp64 there) can decide either way:
+    two candidate errors within TIE_REL of each other, or a sample within TIE_GAP x scale of one
+    of the range ends that step compares samples with."""
+    for j in differing:
+        tr = []
+        O.range_search(Z[:, j], float(tj[j]), step, act, trace=tr)
+        rel = [abs(el - er) / max(el, er, 1e-300) for _, el, er, _ in tr if el is not None]
+        gap = [g for *_, g in tr]
+        assert min(rel, default=1.0) <= TIE_REL or min(gap, default=1.0) <= TIE_GAP * scale, \
+            (j, min(rel, default=None), min(gap, default=None))
+
+
+@pytest.mark.parametrize("dtype,d,h,n_cal,t,step,act,per_neuron",
+                         [("f32", 64, 96, 400, 0.9, 0.05, "gelu_erf", False),
+                          ("bf16", 256, 64, 1000, 0.85, 0.1, "gelu_erf", False),
+                          ("f32", 64, 48, 300, 0.8, 0.08, "relu", True),
+                          ("bf16", 128, 72, 600, 0.8, 0.06, "gelu_erf", True),
+                          ("f32", 48, 40, 257, 1.0, 0.25, "gelu_tanh", False)])
+def test_calibrate_search_against_checker(dtype, d, h, n_cal, t, step, act, per_neuron):
     """The two sides see pre-activations that differ in the last bits (fp32 against fp64 dot
-    products), and every growth step is a comparison of two error sums: a step decided by less than
-    that noise may go the other way, so a few neurons may end a whole number of steps apart.  Nearly
-    all neurons must agree to rounding, every neuron must satisfy what defines the search."""
-    t, step = float(np.float32(t)), float(np.float32(step))     # the interface carries both as fp32
+    products), and every growth step is a comparison of two error sums and of samples with range
+    ends: a step decided by less than that noise may go the other way.  So: almost all neurons
+    equal to rounding; every neuron that is not is SHOWN to have had such a step (the checker
+    reports each step's margins), lies a whole number of steps away, and satisfies the search's
+    invariants.  With per_neuron, every neuron has its own target portion (coverage_per_neuron)."""
+    t, step = float(np.float32(t)), float(np.float32(step))
     seed = synth.workload_seed(9, 21)
     layer = synth.make_layer(d, h, dtype, seed, w1_std=0.2 if d < 128 else 0.1, w2_std=0.05, heavy_frac=0.02,
                              with_bias=True)
     X_cal = synth.make_tokens(n_cal, d, dtype, seed, synth.STREAM_CAL)
     ffn = make_ffn(layer, act)
-    lo, hi, a, c = (v.cpu().numpy() for v in T.tardis_calibrate_search(ffn, dev(X_cal, dtype), t, step))
-    olo, ohi, oa, oc = O.calibrate_search(layer.W1, layer.b1, X_cal, t, step, act)
+    if per_neuron:      # 0.7, 0.8, 0.9 of t's neighbourhood in turn (all exactly representable steps apart in fp32)
+        tj32 = (np.float32(t) + np.float32(0.1) * (np.arange(h) % 3 - 1).astype(np.float32)).astype(np.float32)
+        tj = tj32.astype(np.float64)
+        got = T.tardis_calibrate_search(ffn, dev(X_cal, dtype), t, step,
+                                        coverage_per_neuron=torch.from_numpy(tj32).to(DEV))
+    else:
+        tj = np.full(h, t)
+        got = T.tardis_calibrate_search(ffn, dev(X_cal, dtype), t, step)
+    lo, hi, a, c = (v.cpu().numpy() for v in got)
+    olo, ohi, oa, oc = O.calibrate_search(layer.W1, layer.b1, X_cal, tj, step, act)
     scale = float(np.abs(np.concatenate([olo, ohi])).max())
     same = (np.abs(lo - olo) <= 1e-4 * scale) & (np.abs(hi - ohi) <= 1e-4 * scale)
     assert same.mean() >= 0.95, same.mean()
     assert np.abs(a - oa)[same].max() <= 5.0 / n_cal + 1e-4
     assert np.abs(c - oc)[same].max() <= (5.0 / n_cal + 1e-4) * max(1.0, scale)
     Z = O.preact(layer.W1, layer.b1, X_cal)
+    assert_search_differences_are_near_ties(Z, tj, step, act, np.flatnonzero(~same), scale)
     for j in range(h):
         inside = (Z[:, j] >= np.float64(lo[j])) & (Z[:, j] < np.float64(hi[j]))
-        assert inside.mean() >= t - 2.0 / n_cal                   # reached the target (up to samples on the edge)
+        assert inside.mean() >= tj[j] - 2.0 / n_cal               # reached the target (up to samples on the edge)
         # the range is the centroid grown by whole steps on either side
         cen = O.kde_centroid(np.sort(Z[:, j]))
         kl, kr = (cen - lo[j]) / step, (hi[j] - cen) / step
@@ -298,6 +333,21 @@ def test_calibrate_search_against_checker(dtype, d, h, n_cal, t, step, act):
         # and its line is the least-squares line of its own samples
         aj, cj = O.fit_line(Z[inside, j], O.act(Z[inside, j], act), float(lo[j]), act)
         assert abs(a[j] - aj) <= 5.0 / n_cal + 1e-4 and abs(c[j] - cj) <= (5.0 / n_cal + 1e-4) * max(1.0, scale)
+    if per_neuron:      # the three groups of neurons really got three different portions
+        cov = np.array([((Z[:, j] >= np.float64(lo[j])) & (Z[:, j] < np.float64(hi[j]))).mean() for j in range(h)])
+        assert cov[0::3].mean() < cov[1::3].mean() < cov[2::3].mean()
+
+
+def test_calibrate_search_refuses_a_step_that_needs_too_many_steps():
+    """Algorithm 1 has no limit on the number of growth steps; the kernel guards one block's run time
+    with 4096 and fails the whole call rather than substitute a range."""
+    w = synth.tiny(hard=True)
+    ffn = make_ffn(w.layer)
+    with pytest.raises(T.TardisError) as e:
+        T.tardis_calibrate_search(ffn, dev(w.X_cal, "f32"), 0.99, 1e-5)
+    assert e.value.status == T.ERR_INVALID_ARG
+    lo, hi, a, c = T.tardis_calibrate_search(ffn, dev(w.X_cal, "f32"), 0.9, 0.05)       # and works afterwards
+    assert torch.isfinite(lo).all() and (hi > lo).all()
 
 
 def test_calibrate_search_feeds_the_online_path():
@@ -772,6 +822,8 @@ def test_full_size_calibrate_search_on_sampled_neurons(decode_full):
     scale = float(np.abs(np.concatenate([olo, ohi])).max())
     same = (np.abs(lo[sub] - olo) <= 1e-4 * scale) & (np.abs(hi[sub] - ohi) <= 1e-4 * scale)
     assert same.mean() >= 0.9, same.mean()
+    Zs = O.preact(w.layer.W1[sub], None, w.X_cal)
+    assert_search_differences_are_near_ties(Zs, np.full(len(sub), t), step, "gelu_erf", np.flatnonzero(~same), scale)
     assert np.abs(a[sub] - oa)[same].max() <= 2e-3 and np.abs(c[sub] - oc)[same].max() <= 2e-3 * max(1.0, scale)
     Z = O.preact(w.layer.W1[sub], None, w.X_cal)
     frac = ((Z >= lo[sub][None, :].astype(np.float64)) & (Z < hi[sub][None, :].astype(np.float64))).mean(0)
@@ -843,8 +895,8 @@ def test_full_size_batched_decode_sampled_tokens(decode_full, B):
         np.testing.assert_array_equal(FLg[t], flo)
         assert int(counts[t].item()) == flo.sum()
         assert_y_close(host(Y[t]), yo, F.Wp, X[t])
-    union = FLg.any(axis=0).sum()
-    assert union >= FLg[0].sum()
+    ucnt, _ = T.tardis_get_last_union(L, B)
+    assert int(ucnt.item()) == FLg.any(axis=0).sum() >= FLg[0].sum()
 
 
 @pytest.fixture(scope="module", params=[0.99, 0.85])
