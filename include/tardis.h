@@ -93,7 +93,14 @@ typedef struct {
     int64_t max_batch;     /* largest n accepted by the batched online calls (1 .. 4096; longer prompts are
                               the caller's to cut); from 65 on the layer
                               also holds scratch for the prompt path, about n * (5 d + 10 h) bytes */
-    int32_t deterministic; /* reserved, must be 0 */
+    int32_t deterministic; /* 0, or 1: results that are bit-identical from run to run.  Every online call on
+                              the layer then runs as groups of up to 16 tokens whose repair is accumulated
+                              in counted fixed-point words (integer adds commute; a word's unit comes from
+                              a bound, computed at fold time, on what an output can receive), flagged lists
+                              are processed in ascending order, and nothing is summed in an order that
+                              depends on timing.  Needs a bf16 layer with d = 1024, 2048 or 4096
+                              (TARDIS_ERR_SHAPE otherwise); calls with more than 16 tokens are slower
+                              than on a layer folded without it. */
     int32_t reserved;
 } tardis_fold_opts;
 

@@ -58,7 +58,7 @@ int env_int(const char* name, int fallback, int lo, int hi) {
 void free_layer(tardis_layer_s* L) {
     if (!L) return;
     void* owned[] = {L->W2T, L->W2, L->Wp, L->bp, L->Q, L->Q4, L->M4, L->tlo, L->thi, L->a, L->c,
-                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix, L->zeros_h, L->xnext, L->rec_count, L->rec_jb, L->rec_tb, L->rec_delta, L->pf_scratch,
+                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix, L->fx_bound, L->zeros_h, L->xnext, L->rec_count, L->rec_jb, L->rec_tb, L->rec_delta, L->pf_scratch,
                      L->bt_xq, L->bt_e, L->bt_tokmask, L->bt_ulist, L->bt_ucount, L->bt_delta, L->bt_partial};
     for (void* p : owned)
         if (p) (void)hipFree(p);
@@ -104,8 +104,10 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     L->dec_blocks = env_int("TARDIS_DECODE_BLOCKS", L->dec_threads == 512 ? 512 : 256, 1, 4096);
     L->dec_copies = env_int("TARDIS_DECODE_COPIES", 2, 1, 4);
     L->prefetch_bytes = env_int("TARDIS_PREFETCH_KB", 96, 0, 256) * 1024;
-    TD_TRY(dev_alloc(&L->yfix, (size_t)L->dec_copies * kDecodeMaxTokens * d * 4));
-    TD_HIP(hipMemsetAsync(L->yfix, 0, (size_t)L->dec_copies * kDecodeMaxTokens * d * 4, s));
+    // (at least two copies' worth: the fixed-point accumulators are 8 bytes per token and column)
+    const size_t yfix_bytes = (size_t)(L->dec_copies < 2 ? 2 : L->dec_copies) * kDecodeMaxTokens * d * 4;
+    TD_TRY(dev_alloc(&L->yfix, yfix_bytes));
+    TD_HIP(hipMemsetAsync(L->yfix, 0, yfix_bytes, s));
     L->use_fused = env_int("TARDIS_DECODE_FUSED", 1, 0, 1) && td_decode_fused_supported(L);
     L->defer_min_tokens = env_int("TARDIS_DEFER_MIN", 4, 4, 99);
     if (L->use_fused) {
@@ -117,6 +119,11 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
         TD_TRY(dev_alloc(&L->rec_tb, (size_t)L->dec_blocks * npb * 4));
         TD_TRY(dev_alloc(&L->rec_delta, (size_t)L->dec_blocks * npb * kDecodeMaxTokens * 4));
     }
+    // counted fixed-point repair accumulators: asked for by opts->deterministic, or by the knob
+    L->deterministic = opts ? opts->deterministic : 0;
+    L->fx = (L->deterministic || env_int("TARDIS_FIXED_POINT", 0, 0, 1)) && L->use_fused && L->dec_threads == 1024 &&
+            (d + L->dec_blocks - 1) / L->dec_blocks <= 64 && L->dec_blocks <= 65535;
+    if (L->deterministic && !L->fx) return TARDIS_ERR_SHAPE;   // only the fused decode kernels have the ordered path
     L->use_batched = env_int("TARDIS_BATCHED", 1, 0, 1) && td_batched_supported(L);
     L->gather_max_tokens = env_int("TARDIS_GATHER_MAX", 16, 0, 16);
     L->batched_min_tokens = env_int("TARDIS_BATCHED_MIN", L->use_fused ? 17 : 1, 1, 64);
@@ -157,6 +164,10 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     TD_TRY(td_build_sketch(desc->W1, desc->b1, lo, hi, h, d, desc->dtype, L->sketch_bits, L->Q, L->Q4, L->M4, L->tlo,
                            L->thi, s));
     TD_TRY(td_fold(desc, L->a, L->c, L->Wp, L->bp, s));
+    if (L->fx) {
+        TD_TRY(dev_alloc(&L->fx_bound, 8));
+        TD_TRY(td_fx_bounds(L, L->fx_bound, s));
+    }
     TD_HIP(hipStreamSynchronize(s));
     return TARDIS_OK;
 }
@@ -223,7 +234,7 @@ tardis_status_t tardis_fold(const tardis_ffn_desc* desc, const float* lo, const 
         if (opts->sketch_bits != 8 && opts->sketch_bits != 4) return TARDIS_ERR_INVALID_ARG;
         if (opts->folded_dtype != desc->dtype) return TARDIS_ERR_DTYPE;
         if (opts->max_batch < 1 || opts->max_batch > kMaxBatch) return TARDIS_ERR_SHAPE;
-        if (opts->deterministic != 0) return TARDIS_ERR_INVALID_ARG;
+        if (opts->deterministic != 0 && opts->deterministic != 1) return TARDIS_ERR_INVALID_ARG;
     }
     tardis_layer_s* L = new (std::nothrow) tardis_layer_s();
     if (!L) return TARDIS_ERR_OOM;

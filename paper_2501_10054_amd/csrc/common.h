@@ -102,6 +102,9 @@ struct tardis_layer_s {
     int32_t gather_max_tokens;     // passes of up to this many tokens scatter through the union rows of W2^T
     int32_t batched_min_tokens;    // token counts up to this go through the single-token path
     int64_t last_n;    // token count of the most recent online call
+    int32_t fx;        // decode kernels accumulate the repair in counted fixed-point words (deterministic results)
+    int32_t deterministic;   // every online call runs as decode groups on those accumulators
+    float* fx_bound;   // K1, K2 of the accumulators' magnitude bound (device, 2 floats)
     int32_t poisoned;  // a launch of an online call failed half way: counters and accumulators may be left armed
 };
 
@@ -200,6 +203,7 @@ tardis_status_t td_fold(const tardis_ffn_desc* desc, const float* a, const float
 tardis_status_t td_calibrate(const tardis_ffn_desc* desc, const void* X, int64_t n, float coverage,
                              const float* cov_pn, float step, float* lo, float* hi, float* a, float* c,
                              hipStream_t s);
+tardis_status_t td_fx_bounds(const tardis_layer_s* L, float* out2, hipStream_t s);
 // gemm.hip:  C[m][n] = sum_k A[m][k] * B[n][k]  (+ C if accumulate) (+ row_bias[m]); C fp32, ldc = N
 tardis_status_t td_gemm_nt(const void* A, const void* B, float* C, int64_t M, int64_t N, int64_t K,
                            int32_t dtype, int accumulate, const void* row_bias, hipStream_t s);

@@ -57,6 +57,38 @@ __device__ __forceinline__ void load_row(td_u32x4 (&dst)[N], const void* row, in
     for (int it = 0; it < N; ++it) dst[it] = td_load_stream16(p + it * TD_WAVE);
 }
 
+// Counted fixed-point accumulator.  Bits 0..15 count the contributions received, bits 16..63 hold
+// their sum as a signed integer number of units.  The unit of a token is a power of two chosen from
+// a bound on the magnitude of ANY partial sum of contributions to one output of that token,
+//     |.| <= K1 * max|x| + K2        (K1, K2 per layer, computed when the layer is folded),
+// so that the sum never leaves the 48-bit field: unit = 2^(e - 46) with 2^e > the bound.  Adding the
+// 64-bit words with integer atomics adds both fields at once and exactly; the add that returns
+// count == expected - 1 is the last one and its thread holds the finished sum.
+struct FxAcc {
+    static constexpr int kCountBits = 16;
+    static constexpr int kValueBits = 46;            // bound / unit
+    // exponent e with 2^e > bound (clamped so that every scale below is a normal float)
+    static __device__ __forceinline__ int exponent(float k1, float k2, float xmax) {
+        const float bound = fmaf(k1, xmax, k2);
+        int e = 0;
+        if (bound > 0.0f && bound < INFINITY) (void)frexpf(bound, &e);
+        return min(max(e, -60), 120);
+    }
+    static __device__ __forceinline__ unsigned long long encode(float v, int e) {
+        const long long q = __float2ll_rn(ldexpf(v, kValueBits - e));
+        return (static_cast<unsigned long long>(q) << kCountBits) + 1ull;
+    }
+    static __device__ __forceinline__ bool completes(unsigned long long before, int expected) {
+        return (int)(before & ((1u << kCountBits) - 1u)) == expected - 1;
+    }
+    static __device__ __forceinline__ float decode(unsigned long long total, int e) {
+        return ldexpf((float)(static_cast<long long>(total) >> kCountBits), e - kValueBits);
+    }
+    static __device__ __forceinline__ unsigned long long add(unsigned long long* p, unsigned long long enc) {
+        return __hip_atomic_fetch_add(p, enc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+};
+
 // TB tokens (1, 2, 4, 8 or 16) share one pass over the weights: x, y, yfold are TB x D, mask has TB rows of
 // mask_words words, yfix is copies x TB x D.
 //
@@ -111,7 +143,13 @@ __device__ __forceinline__ void warm_rows(const unsigned char* __restrict__ p, i
 // v_mfma_i32_16x16x64_i8 (tokens 8..15 of the tile repeat tokens 0..7 and are ignored), and the
 // partial sums meet in LDS.  Eight tokens of packed dot products would keep the vector ALUs busy
 // for longer than the rows take to arrive.
-template <int D, int BLOCK, int RQ, int TB, int SK, bool DEFER, int NG>
+//
+// FX = true: the repair accumulators are 64-bit fixed-point words that also count their
+// contributions (see FxAcc): every block adds to every column exactly once, integer adds commute,
+// so the result does not depend on the order in which blocks finish (bit-identical from run to
+// run), and the thread whose add completes a column's count holds that column's finished sum and
+// writes y itself - no completion counter and no assembling block on the way out.
+template <int D, int BLOCK, int RQ, int TB, int SK, bool DEFER, int NG, bool FX>
 __global__ void __launch_bounds__(BLOCK)
 decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp, const int8_t* __restrict__ Q,
                     const uint8_t* __restrict__ M4, const float* __restrict__ tlo, const float* __restrict__ thi, const bf16_t* __restrict__ W1,
@@ -119,7 +157,8 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                     const float* __restrict__ c, const bf16_t* __restrict__ x, bf16_t* __restrict__ y,
                     float* __restrict__ yfold, float* __restrict__ yfix, int copies, uint32_t* __restrict__ mask,
                     int mask_words, int32_t* __restrict__ done, int h, int npb, int rpb, int act, int norm_out,
-                    float eps, DeferOut rec, int n_act, const unsigned char* __restrict__ pf_rows, int pf_bytes) {
+                    float eps, DeferOut rec, int n_act, const unsigned char* __restrict__ pf_rows, int pf_bytes,
+                    const float* __restrict__ fx_bound, int32_t* __restrict__ fx_exp) {
     // n_act <= TB tokens are real: the remaining slots of the group repeat the last real token and
     // none of their results reaches the caller's buffers
     static_assert(D % 1024 == 0, "rows must be whole multiples of 64 lanes x 16 bytes");
@@ -385,9 +424,11 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
 #pragma unroll
                 for (int t = 0; t < TB; ++t)
                     if ((bits[i] >> t) & 1u) atomicOr(&words[t][jl >> 5], 1u << (jl & 31));
-                const int pos = atomicAdd(&nflag, 1);
-                flist[pos] = j0 + jl;
-                fbits[pos] = (unsigned short)bits[i];
+                if constexpr (!FX) {   // (FX: the list is built in ascending order from the words below)
+                    const int pos = atomicAdd(&nflag, 1);
+                    flist[pos] = j0 + jl;
+                    fbits[pos] = (unsigned short)bits[i];
+                }
             }
         }
     }
@@ -430,9 +471,11 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
 #pragma unroll
                 for (int t = 0; t < TB; ++t)
                     if ((bits >> t) & 1u) atomicOr(&words[t][tid >> 5], 1u << (tid & 31));
-                const int pos = atomicAdd(&nflag, 1);
-                flist[pos] = j0 + tid;
-                fbits[pos] = (unsigned short)bits;
+                if constexpr (!FX) {
+                    const int pos = atomicAdd(&nflag, 1);
+                    flist[pos] = j0 + tid;
+                    fbits[pos] = (unsigned short)bits;
+                }
             }
         }
         if constexpr (kAlias) {   // every wavefront is past its last read of the int8 codes: the tokens take their place
@@ -444,6 +487,42 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
         }
     }
     __syncthreads();
+    if constexpr (FX) {
+        // the block's flagged neurons in ascending order, from the mask words: positions by
+        // population count, so the order - and with it every floating-point sum over the list -
+        // is the same in every run
+        if (tid < kMaxNeuronsPerBlock && tid < jn) {
+            const int w = tid >> 5, b = tid & 31;
+            uint32_t tb = 0u, uw = 0u;
+#pragma unroll
+            for (int t = 0; t < TB; ++t) {
+                tb |= ((words[t][w] >> b) & 1u) << t;
+                uw |= words[t][w];
+            }
+            if (tb) {
+                int pos = __popc(uw & ((1u << b) - 1u));
+                for (int ww = 0; ww < w; ++ww) {
+                    uint32_t u = 0u;
+#pragma unroll
+                    for (int t = 0; t < TB; ++t) u |= words[t][ww];
+                    pos += __popc(u);
+                }
+                flist[pos] = j0 + tid;
+                fbits[pos] = (unsigned short)tb;
+            }
+        }
+        if (tid == 0) {
+            int tot = 0;
+            for (int ww = 0; ww < MW; ++ww) {
+                uint32_t u = 0u;
+#pragma unroll
+                for (int t = 0; t < TB; ++t) u |= words[t][ww];
+                tot += __popc(u);
+            }
+            nflag = tot;
+        }
+        __syncthreads();
+    }
     if (jn > 0) {
         const int nw = (jn + 31) / 32;
         for (int k = tid; k < TB * nw; k += BLOCK) {
@@ -469,6 +548,10 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     if constexpr (DEFER) {
         // ---- one wavefront per flagged neuron: exact z and delta for the tokens that flagged it
         if (tid == 0) rec.count[blk] = nf;
+        if constexpr (FX) {   // the second kernel needs every token's fixed-point exponent
+            if (blk == 0 && tid < TB)
+                fx_exp[tid] = FxAcc::exponent(fx_bound[0], fx_bound[1], __int_as_float(tmax[tid]));
+        }
         if (nf == 0) {
 #pragma unroll
             for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * WSTEP);
@@ -620,6 +703,113 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
         for (int f0 = FCH; f0 < nf; f0 += FCH) repair_pass(std::false_type{}, f0);
     }
 
+    if constexpr (FX) {
+        // ---- counted fixed-point accumulators.  Every block adds its repair vector to every column
+        //      once (zeros included: the count is how a column knows it is finished); the block that
+        //      owns rows [r0, r0 + rn) of W' adds the speculative value of those columns in the same
+        //      word.  Columns of other blocks' rows go out now, while this block's W' rows are still
+        //      arriving; its own columns follow the dot products.
+        constexpr int kOwnMax = 64;                  // W' rows per block this path serves (launcher checks)
+        __shared__ float ysp[TB][kOwnMax];
+        unsigned long long* acc64 = reinterpret_cast<unsigned long long*>(yfix);
+        const int G = (int)gridDim.x;
+        int fxe[TB];
+#pragma unroll
+        for (int t = 0; t < TB; ++t) fxe[t] = FxAcc::exponent(fx_bound[0], fx_bound[1], __int_as_float(tmax[t]));
+        unsigned long long before[TB][CPT];
+        bool own[CPT];
+#pragma unroll
+        for (int u = 0; u < CPT; ++u) {
+            const int col = ctid + u * BLOCK;
+            own[u] = col >= r0 && col < r0 + rn;
+        }
+#pragma unroll
+        for (int t = 0; t < TB; ++t)
+#pragma unroll
+            for (int u = 0; u < CPT; ++u)
+                if (!own[u])
+                    before[t][u] = FxAcc::add(acc64 + (size_t)t * D + ctid + u * BLOCK, FxAcc::encode(yacc[t][u], fxe[t]));
+        for (int ri = wave; ri < rn; ri += NW) {
+            asm volatile("" ::: "memory");
+            if (ri != wave) load_row<IW>(wp, Wp + (size_t)(r0 + ri) * D, lane);
+            const float bias = ri == wave ? bias_out : bp[r0 + ri];
+#pragma unroll
+            for (int t = 0; t < TB; ++t) {
+                if (TB > 1) asm volatile("" ::: "memory");
+                float sp = 0.0f;
+#pragma unroll
+                for (int it = 0; it < IW; ++it) sp = RowVec<bf16_t>::dot(wp[it], xsv(t, it), sp);
+                sp = td_wave_sum(sp);
+                if (lane == 0) ysp[t][ri] = sp + bias;
+            }
+        }
+        if (tid == 0) is_last = 0;
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < TB; ++t)
+#pragma unroll
+            for (int u = 0; u < CPT; ++u)
+                if (own[u]) {
+                    yacc[t][u] += ysp[t][ctid + u * BLOCK - r0];
+                    before[t][u] = FxAcc::add(acc64 + (size_t)t * D + ctid + u * BLOCK, FxAcc::encode(yacc[t][u], fxe[t]));
+                }
+        // ---- the add that completed a column's count holds its finished sum: write it, re-arm the word
+        int finished = 0;
+#pragma unroll
+        for (int t = 0; t < TB; ++t)
+#pragma unroll
+            for (int u = 0; u < CPT; ++u) {
+                if (FxAcc::completes(before[t][u], G)) {
+                    const int col = ctid + u * BLOCK;
+                    const float v = FxAcc::decode(before[t][u] + FxAcc::encode(yacc[t][u], fxe[t]), fxe[t]);
+                    acc64[(size_t)t * D + col] = 0ull;
+                    if (norm_out)   // whole rows are needed: parked (written through) for the assembling block
+                        __hip_atomic_store(yfold + (size_t)t * D + col, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    else
+                        y[(size_t)t * D + col] = td_f32_to_bf16(v);
+                    ++finished;
+                }
+            }
+        // a wavefront that completed nothing is not among the last to finish: it warms the caches for
+        // the layer that runs next while the rest of the launch drains
+        if (pf_rows != nullptr && jn > 0 && !__any(finished > 0))
+            warm_rows<BLOCK>(pf_rows + (size_t)j0 * QROW, min(pf_bytes, jn * QROW), tid);
+        if (!norm_out) return;
+        // ---- stacked layers: the block that parks the last column normalises the rows
+        finished = td_wave_sum_i(finished);
+        if (finished > 0 && lane == 0) {
+            td_wait_memory_acks();
+            if (__hip_atomic_fetch_add(done, finished, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + finished == TB * D)
+                is_last = 1;
+        }
+        __syncthreads();
+        if (!is_last) return;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        float* redt = &dl[0][0];
+#pragma unroll
+        for (int t = 0; t < TB; ++t) {
+            float v[CPT];
+            float ss = 0.0f;
+#pragma unroll
+            for (int u = 0; u < CPT; ++u) {
+                v[u] = yfold[(size_t)t * D + tid + u * BLOCK];
+                ss += v[u] * v[u];
+            }
+            ss = td_wave_sum(ss);
+            __syncthreads();
+            if (lane == 0) redt[wave] = ss;
+            __syncthreads();
+            float tot = 0.0f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) tot += redt[w];
+            const float scale = 1.0f / sqrtf(tot / (float)D + eps);
+#pragma unroll
+            for (int u = 0; u < CPT; ++u) y[(size_t)t * D + tid + u * BLOCK] = td_f32_to_bf16(v[u] * scale);
+        }
+        if (tid == 0) __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+
     // ---- one coalesced atomic pass per block and token into an accumulator copy (fire and forget)
     auto atomic_pass = [&]() {
         if (nf > 0) {
@@ -754,12 +944,14 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
 // block reduces over its wavefronts and adds TB x 256 floats to the accumulators in memory - 16
 // times fewer atomics than one d-vector per predictor block and token.  The last block to finish
 // assembles the tokens.
-template <int TB, int SL>
+// FX = true: counted fixed-point accumulators (see FxAcc) instead of fp32 atomics and per-slice
+// completion counters; the add that completes a column writes it.
+template <int TB, int SL, bool FX>
 __global__ void __launch_bounds__(1024)
-down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int pbw, const float* __restrict__ yfold,
+down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int pbw, float* __restrict__ yfold,
                     float* __restrict__ yfix, bf16_t* __restrict__ y, int32_t* __restrict__ done, int D, int nslices,
                     int norm_out, float eps, int n_act, const unsigned char* __restrict__ pf_rows, int pf_bytes,
-                    int pf_row_bytes, int npb, int h) {
+                    int pf_row_bytes, int npb, int h, const int32_t* __restrict__ fx_exp) {
     constexpr int NW = 16, U = SL == 128 ? 48 : 16;  // wavefronts; rows in flight per wavefront (4- or 8-byte loads)
     constexpr int CPL = SL / TD_WAVE;                // columns per lane: 4 (8-byte loads) or 2 (4-byte loads)
     static_assert(CPL == 4 || CPL == 2, "slice width");
@@ -855,8 +1047,53 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
         }
     }
     __syncthreads();
+    if constexpr (FX) {
+        // ---- reduce over the wavefronts (fixed order); one counted fixed-point add per (token, column)
+        //      of the slice, zeros included; the add that completes a column's count finishes it
+        unsigned long long* acc64 = reinterpret_cast<unsigned long long*>(yfix);
+        const int ngroups = (int)gridDim.x / nslices;
+        int finished = 0;
+        if (tid == 0) is_last = 0;
+        for (int k = tid; k < TB * SL; k += 1024) {
+            const int t = k / SL, col = k % SL;
+            float sum = 0.0f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) sum += accL[((size_t)w * TB + t) * SL + col];
+            const int e = fx_exp[t];
+            const size_t at = (size_t)t * D + slice * SL + col;
+            const unsigned long long enc = FxAcc::encode(sum, e);
+            const unsigned long long before = FxAcc::add(acc64 + at, enc);
+            if (FxAcc::completes(before, ngroups)) {
+                acc64[at] = 0ull;
+                if (t < n_act) {                     // (else: a slot that repeats the last real token)
+                    const float v = yfold[at] + FxAcc::decode(before + enc, e);
+                    if (norm_out)
+                        __hip_atomic_store(yfold + at, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    else
+                        y[at] = td_f32_to_bf16(v);
+                }
+                ++finished;
+            }
+        }
+        if (!norm_out) {
+            if (!__any(finished > 0)) warm_next();
+            return;
+        }
+        finished = td_wave_sum_i(finished);
+        __syncthreads();                             // is_last = 0 is in place
+        if (finished > 0 && lane == 0) {
+            td_wait_memory_acks();
+            if (__hip_atomic_fetch_add(done, finished, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + finished == TB * D)
+                is_last = 1;
+        }
+        __syncthreads();
+        if (!is_last) {
+            warm_next();
+            return;
+        }
+    }
     // ---- reduce over the wavefronts; one atomic per (token, column) of the slice
-    for (int k = tid; k < TB * SL; k += 1024) {
+    for (int k = tid; FX == false && k < TB * SL; k += 1024) {
         const int t = k / SL, col = k % SL;
         float sum = 0.0f;
 #pragma unroll
@@ -865,10 +1102,12 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
             __hip_atomic_fetch_add(yfix + (size_t)t * D + slice * SL + col, sum, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
     }
+    if constexpr (!FX) {
     td_wait_memory_acks();   // this wavefront's atomics have been performed before the block's counter moves
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
-    if (!norm_out) {
+    }
+    if (!FX && !norm_out) {
         // ---- no row-wide quantity is needed: the last of the blocks that share this slice of
         //      columns assembles the slice (counter 1 + slice), all slices in parallel
         const int ngroups = (int)gridDim.x / nslices;
@@ -895,12 +1134,14 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
         if (tid == 0) __hip_atomic_store(done + 1 + slice, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
-    if (tid == 0)
-        is_last = (__hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1);
-    __syncthreads();
-    if (!is_last) {
-        warm_next();
-        return;
+    if constexpr (!FX) {
+        if (tid == 0)
+            is_last = (__hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1);
+        __syncthreads();
+        if (!is_last) {
+            warm_next();
+            return;
+        }
     }
 
     // ---- the last block assembles the tokens (with their row-wide norm) and re-arms the scratch
@@ -918,10 +1159,11 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
             for (int t = 0; t < TH; ++t) {
                 const f32x4 f = (live && t0 + t < n_act) ? reinterpret_cast<const f32x4*>(yfold + (size_t)(t0 + t) * D)[k4]
                                                          : zero4;
-                const f32x4 g = live ? reinterpret_cast<const f32x4*>(yfix + (size_t)(t0 + t) * D)[k4] : zero4;
+                // (FX: the parked rows are complete and the accumulators re-armed already)
+                const f32x4 g = (live && !FX) ? reinterpret_cast<const f32x4*>(yfix + (size_t)(t0 + t) * D)[k4] : zero4;
                 v[t] = f + g;
             }
-            if (live) {
+            if (live && !FX) {
 #pragma unroll
                 for (int t = 0; t < TH; ++t) reinterpret_cast<f32x4*>(yfix + (size_t)(t0 + t) * D)[k4] = zero4;
             }
@@ -1024,9 +1266,11 @@ mask_union_kernel(const uint32_t* __restrict__ mask, int words, int n, uint32_t*
     if (threadIdx.x == 0 && union_count) *union_count = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
 }
 
-template <int D, int BLOCK, int TB, int SK, bool DEFER, int NG = 0>
-tardis_status_t launch_decode(tardis_layer_s* L, const DecodeScratch& ws, const void* x, void* y, float* yfold,
-                              uint32_t* mask, int n_act, int norm_out, hipStream_t s) {
+constexpr int kFxExpAt = 40;   // where, among the 64 counters of a call's working memory, the tokens' fixed-point exponents sit
+
+template <int D, int BLOCK, int TB, int SK, bool DEFER, int NG, bool FX>
+tardis_status_t launch_decode_impl(tardis_layer_s* L, const DecodeScratch& ws, const void* x, void* y, float* yfold,
+                                   uint32_t* mask, int n_act, int norm_out, hipStream_t s) {
     constexpr int RQ = 4;
     if (n_act < 1 || n_act > TB || (!DEFER && n_act != TB)) return TARDIS_ERR_INVALID_ARG;
     const int G = L->dec_blocks;
@@ -1039,7 +1283,8 @@ tardis_status_t launch_decode(tardis_layer_s* L, const DecodeScratch& ws, const 
     const size_t lds = static_tokens ? 0
                        : TB == 16    ? (size_t)TB * (D + 8) * 2      // the int8 codes share the tokens' place
                                      : (size_t)TB * (DEFER ? D + 8 : D) * 2 + (size_t)TB * (NG > 0 ? D + 16 : D);
-    auto kernel = decode_fused_kernel<D, BLOCK, RQ, TB, SK, DEFER, NG>;
+    auto kernel = decode_fused_kernel<D, BLOCK, RQ, TB, SK, DEFER, NG, FX>;
+    if (FX && (rpb > 64 || G > 65535)) return TARDIS_ERR_SHAPE;   // own-column staging, 16-bit contribution count
     const DeferOut rec{ws.rec_count, ws.rec_jb, ws.rec_tb, ws.rec_delta, npb};
     // the layer that runs next, if the caller said so and it has this layer's geometry
     const unsigned char* pf_rows = nullptr;
@@ -1054,22 +1299,31 @@ tardis_status_t launch_decode(tardis_layer_s* L, const DecodeScratch& ws, const 
                        static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), static_cast<const bf16_t*>(L->W2T),
                        L->a, L->c, static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), yfold, ws.yfix,
                        L->dec_copies, mask, (int)L->mask_words, ws.sync, h, npb, rpb, (int)L->act, norm_out, kRmsEps,
-                       rec, n_act, DEFER ? nullptr : pf_rows, (int)L->prefetch_bytes);
+                       rec, n_act, DEFER ? nullptr : pf_rows, (int)L->prefetch_bytes, L->fx_bound, ws.sync + kFxExpAt);
     TD_HIP(hipGetLastError());
     if (DEFER) {
         constexpr int SL = TB >= 16 ? 128 : 256;     // slice width: 16 wavefronts x TB x SL floats of LDS
         constexpr size_t lds2 = (size_t)16 * TB * SL * sizeof(float);
-        auto k2 = down_project_kernel<TB, SL>;
+        auto k2 = down_project_kernel<TB, SL, FX>;
         const int nslices = D / SL;
         const int ngroups = nslices >= 256 ? 1 : 256 / nslices;          // about one block per CU
         const int pbw = (G + 16 * ngroups - 1) / (16 * ngroups);         // predictor blocks per wavefront
         hipLaunchKernelGGL(k2, dim3(nslices * ngroups), dim3(1024), lds2, s, static_cast<const bf16_t*>(L->W2T), rec,
                            G, pbw, yfold, ws.yfix, static_cast<bf16_t*>(y), ws.sync, D, nslices, norm_out, kRmsEps, n_act,
                            TB >= 16 ? nullptr : pf_rows,   // (sixteen tokens: its blocks end too close together for the warming to pay)
-                           (int)L->prefetch_bytes, SK == 8 ? D : D / 2, npb, h);
+                           (int)L->prefetch_bytes, SK == 8 ? D : D / 2, npb, h, ws.sync + kFxExpAt);
         TD_HIP(hipGetLastError());
     }
     return TARDIS_OK;
+}
+
+template <int D, int BLOCK, int TB, int SK, bool DEFER, int NG = 0>
+tardis_status_t launch_decode(tardis_layer_s* L, const DecodeScratch& ws, const void* x, void* y, float* yfold,
+                              uint32_t* mask, int n_act, int norm_out, hipStream_t s) {
+    if constexpr (BLOCK == 1024) {   // (the 512-thread variant keeps fp32 accumulators)
+        if (L->fx) return launch_decode_impl<D, BLOCK, TB, SK, DEFER, NG, true>(L, ws, x, y, yfold, mask, n_act, norm_out, s);
+    }
+    return launch_decode_impl<D, BLOCK, TB, SK, DEFER, NG, false>(L, ws, x, y, yfold, mask, n_act, norm_out, s);
 }
 
 // `tokens` = group size (1, 2, 4, 8, 16), `n_act` of them real (fewer only on the two-kernel path)
@@ -1123,15 +1377,24 @@ template <typename K> hipError_t allow_lds(K kernel, size_t bytes) {
 tardis_status_t td_decode_init() {
     static td_once once;
     return once.run([]() -> tardis_status_t {
-        TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 4>, (size_t)8 * 4096 * 3 + 256));
-        TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 2>, (size_t)8 * 4096 * 3 + 256));
-        TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 4>, (size_t)16 * (4096 + 8) * 2));
-        TD_HIP(allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 2>, (size_t)16 * (4096 + 8) * 2));
-        TD_HIP(allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 4>, (size_t)16 * (2048 + 8) * 2));
-        TD_HIP(allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 2>, (size_t)16 * (2048 + 8) * 2));
-        TD_HIP(allow_lds((down_project_kernel<4, 256>), (size_t)16 * 4 * 256 * sizeof(float)));
-        TD_HIP(allow_lds((down_project_kernel<8, 256>), (size_t)16 * 8 * 256 * sizeof(float)));
-        TD_HIP(allow_lds((down_project_kernel<16, 128>), (size_t)16 * 16 * 128 * sizeof(float)));
+        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 4, false>, (size_t)8 * 4096 * 3 + 256)));
+        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 2, false>, (size_t)8 * 4096 * 3 + 256)));
+        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 4, false>, (size_t)16 * (4096 + 8) * 2)));
+        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 2, false>, (size_t)16 * (4096 + 8) * 2)));
+        TD_HIP((allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 4, false>, (size_t)16 * (2048 + 8) * 2)));
+        TD_HIP((allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 2, false>, (size_t)16 * (2048 + 8) * 2)));
+        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 4, true>, (size_t)8 * 4096 * 3 + 256)));
+        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 2, true>, (size_t)8 * 4096 * 3 + 256)));
+        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 4, true>, (size_t)16 * (4096 + 8) * 2)));
+        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 2, true>, (size_t)16 * (4096 + 8) * 2)));
+        TD_HIP((allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 4, true>, (size_t)16 * (2048 + 8) * 2)));
+        TD_HIP((allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 2, true>, (size_t)16 * (2048 + 8) * 2)));
+        TD_HIP((allow_lds((down_project_kernel<4, 256, false>), (size_t)16 * 4 * 256 * sizeof(float))));
+        TD_HIP((allow_lds((down_project_kernel<8, 256, false>), (size_t)16 * 8 * 256 * sizeof(float))));
+        TD_HIP((allow_lds((down_project_kernel<16, 128, false>), (size_t)16 * 16 * 128 * sizeof(float))));
+        TD_HIP((allow_lds((down_project_kernel<4, 256, true>), (size_t)16 * 4 * 256 * sizeof(float))));
+        TD_HIP((allow_lds((down_project_kernel<8, 256, true>), (size_t)16 * 8 * 256 * sizeof(float))));
+        TD_HIP((allow_lds((down_project_kernel<16, 128, true>), (size_t)16 * 16 * 128 * sizeof(float))));
         return TARDIS_OK;
     });
 }
@@ -1289,7 +1552,7 @@ extern "C" tardis_status_t tardis_ffn_forward_static(tardis_handle_t L, const vo
                            reinterpret_cast<uint32_t*>(base + kStTb),   reinterpret_cast<float*>(base + kStDelta)};
     // the array keeps the last call's contents (and an interrupted call's): clear what must start at
     // zero, with a kernel (a memset node in a captured graph is not safe to replay here)
-    const int nfix = L->dec_copies * kDecodeMaxTokens * (int)L->d;
+    const int nfix = (L->dec_copies < 2 ? 2 : L->dec_copies) * kDecodeMaxTokens * (int)L->d;   // (8-byte fixed-point words fit too)
     hipLaunchKernelGGL(clear_static_kernel, dim3((nfix + 255) / 256), dim3(256), 0, s, ws.sync, ws.yfix, nfix);
     TD_HIP(hipGetLastError());
     // mask words: the caller's buffer when given and no group can be partly empty past its end

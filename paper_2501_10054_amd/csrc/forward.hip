@@ -230,8 +230,12 @@ tardis_status_t forward_t(tardis_layer_s* L, const void* xv, int64_t n, void* yv
     const int pred_blocks = div_up(h, 32);
     const int fix_blocks = 256;
     // a handful of tokens is faster through the single-token kernel (one launch each)
-    if (L->pf_scratch && n >= L->prefill_min_tokens) return td_forward_prefill(L, xv, n, yv, norm_out, s);
-    if (n > L->batched_min_tokens && L->use_batched) return td_forward_batched(L, xv, n, yv, norm_out, s);
+    // (a deterministic layer runs every call as decode groups on the counted fixed-point accumulators:
+    //  the pass and prompt kernels add fp32 partial sums in an order that varies from run to run)
+    if (!L->deterministic) {
+        if (L->pf_scratch && n >= L->prefill_min_tokens) return td_forward_prefill(L, xv, n, yv, norm_out, s);
+        if (n > L->batched_min_tokens && L->use_batched) return td_forward_batched(L, xv, n, yv, norm_out, s);
+    }
     if (L->use_fused) {   // groups of 16, 8, 4, 2, 1 tokens share one pass over the weights
         TD_TRY(td_decode_fused(L, xv, n, yv, norm_out, s));
         L->last_n = n;

@@ -513,6 +513,78 @@ range_search_kernel(const float* __restrict__ Zt, int n, int npad, float coverag
     fit_and_store(vals, n, (float)rlo, (float)rhi, act, red, j, lo, hi, a, c);
 }
 
+// ------------------------------------------------- bound for the fixed-point repair accumulators
+// For a token x and any set F of neurons, every partial sum of the terms that make up output i,
+//     W'[i,:] x + b'_i      and      delta_j W2[i,j]  (j in F),
+// is bounded in magnitude by  K1 max|x| + K2  with
+//     K1 = max_i ( sum_k |W'_ik| + sum_j |W2_ij| (1 + |a_j|) ||W1_j||_1 )
+//     K2 = max_i ( |b'_i|        + sum_j |W2_ij| ((1 + |a_j|) |b1_j| + |c_j|) )
+// because |delta_j| = |sigma(z_j) - (a_j z_j + c_j)| <= (1 + |a_j|) |z_j| + |c_j| for every supported
+// activation (|sigma(z)| <= |z|) and |z_j| <= ||W1_j||_1 max|x| + |b1_j|.
+template <typename T>
+__global__ void __launch_bounds__(kBlock)
+fx_row_terms_kernel(const T* __restrict__ W1, const T* __restrict__ b1, const float* __restrict__ a,
+                    const float* __restrict__ c, int64_t d, float* __restrict__ g, float* __restrict__ kk) {
+    __shared__ float red[kBlock / TD_WAVE];
+    const int64_t j = blockIdx.x;
+    float sabs = 0.0f;
+    for (int64_t k = threadIdx.x; k < d; k += kBlock) sabs += fabsf(td_load<T>(W1 + j * d + k));
+    sabs = td_wave_sum(sabs);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sabs;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float tot = 0.0f;
+        for (int w = 0; w < kBlock / TD_WAVE; ++w) tot += red[w];
+        const float aj = 1.0f + fabsf(a[j]);
+        g[j] = aj * tot;
+        kk[j] = aj * (b1 ? fabsf(td_load<T>(b1 + j)) : 0.0f) + fabsf(c[j]);
+    }
+}
+
+// P[(chunk * 2 + q) * d + i] = sum over the chunk's neurons j of |W2T[j][i]| * (q == 0 ? g_j : kk_j)
+template <typename T>
+__global__ void __launch_bounds__(kBlock)
+fx_col_terms_kernel(const T* __restrict__ W2T, int64_t h, int64_t d, const float* __restrict__ g,
+                    const float* __restrict__ kk, int64_t rows_per_chunk, float* __restrict__ P) {
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t ch = blockIdx.y;
+    if (i >= d) return;
+    const int64_t j0 = ch * rows_per_chunk, j1 = j0 + rows_per_chunk < h ? j0 + rows_per_chunk : h;
+    float s1 = 0.0f, s2 = 0.0f;
+    for (int64_t j = j0; j < j1; ++j) {
+        const float w = fabsf(td_load<T>(W2T + j * d + i));
+        s1 = fmaf(w, g[j], s1);
+        s2 = fmaf(w, kk[j], s2);
+    }
+    P[(ch * 2 + 0) * d + i] = s1;
+    P[(ch * 2 + 1) * d + i] = s2;
+}
+
+// out[0] = K1, out[1] = K2 (maxima over the outputs; non-negative floats order like their bit patterns)
+template <typename T>
+__global__ void __launch_bounds__(kBlock)
+fx_bound_kernel(const T* __restrict__ Wp, const float* __restrict__ bp, int64_t d, const float* __restrict__ P,
+                int chunks, float* __restrict__ out) {
+    __shared__ float red[kBlock / TD_WAVE];
+    const int64_t i = blockIdx.x;
+    float sabs = 0.0f;
+    for (int64_t k = threadIdx.x; k < d; k += kBlock) sabs += fabsf(td_load<T>(Wp + i * d + k));
+    sabs = td_wave_sum(sabs);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sabs;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float k1 = 0.0f, k2 = fabsf(bp[i]);
+        for (int w = 0; w < kBlock / TD_WAVE; ++w) k1 += red[w];
+        for (int ch = 0; ch < chunks; ++ch) {
+            k1 += P[((int64_t)ch * 2 + 0) * d + i];
+            k2 += P[((int64_t)ch * 2 + 1) * d + i];
+        }
+        // a little above the fp32 value of the sums, so that their own rounding cannot undercut the bound
+        atomicMax(reinterpret_cast<int*>(out), __float_as_int(k1 * 1.01f));
+        atomicMax(reinterpret_cast<int*>(out) + 1, __float_as_int(k2 * 1.01f));
+    }
+}
+
 struct DevBuf {  // frees on scope exit
     void* p = nullptr;
     ~DevBuf() {
@@ -532,6 +604,33 @@ struct DevBuf {  // frees on scope exit
 dim3 tile_grid(int64_t cols, int64_t rows) { return dim3((unsigned)((cols + 31) / 32), (unsigned)((rows + 31) / 32)); }
 
 }  // namespace
+
+template <typename T>
+static tardis_status_t fx_bounds_t(const tardis_layer_s* L, float* out2, hipStream_t s) {
+    const int64_t d = L->d, h = L->h;
+    const int chunks = 32;
+    const int64_t rpc = (h + chunks - 1) / chunks;
+    DevBuf g, kk, P;
+    TD_TRY(g.alloc((size_t)h * 4));
+    TD_TRY(kk.alloc((size_t)h * 4));
+    TD_TRY(P.alloc((size_t)chunks * 2 * d * 4));
+    TD_HIP(hipMemsetAsync(out2, 0, 8, s));
+    hipLaunchKernelGGL(fx_row_terms_kernel<T>, dim3((unsigned)h), dim3(kBlock), 0, s, static_cast<const T*>(L->W1),
+                       static_cast<const T*>(L->b1), L->a, L->c, d, static_cast<float*>(g.p), static_cast<float*>(kk.p));
+    hipLaunchKernelGGL(fx_col_terms_kernel<T>, dim3((unsigned)((d + kBlock - 1) / kBlock), chunks), dim3(kBlock), 0, s,
+                       static_cast<const T*>(L->W2T), h, d, static_cast<const float*>(g.p),
+                       static_cast<const float*>(kk.p), rpc, static_cast<float*>(P.p));
+    hipLaunchKernelGGL(fx_bound_kernel<T>, dim3((unsigned)d), dim3(kBlock), 0, s, static_cast<const T*>(L->Wp), L->bp, d,
+                       static_cast<const float*>(P.p), chunks, out2);
+    TD_HIP(hipGetLastError());
+    TD_HIP(hipStreamSynchronize(s));   // the temporaries go out of scope
+    return TARDIS_OK;
+}
+
+// K1, K2 of the fixed-point accumulators' magnitude bound into out2[0..1] (device); needs W2T, W', b', a, c
+tardis_status_t td_fx_bounds(const tardis_layer_s* L, float* out2, hipStream_t s) {
+    return L->dtype == TARDIS_BF16 ? fx_bounds_t<bf16_t>(L, out2, s) : fx_bounds_t<float>(L, out2, s);
+}
 
 tardis_status_t td_transpose(const void* src, void* dst, int64_t rows, int64_t cols, int32_t dtype, hipStream_t s) {
     if ((rows + 31) / 32 > 65535) return TARDIS_ERR_SHAPE;

@@ -163,10 +163,11 @@ class Layer:
             pass
 
 
-def tardis_fold(ffn: FFN, lo, hi, a, c, max_batch: int = 1, sketch_bits: int = 8, stream=None) -> Layer:
+def tardis_fold(ffn: FFN, lo, hi, a, c, max_batch: int = 1, sketch_bits: int = 8, deterministic: bool = False,
+                stream=None) -> Layer:
     for t in (lo, hi, a, c):
         assert t.is_cuda and t.is_contiguous() and t.dtype == torch.float32 and t.numel() == ffn.h
-    opts = tardis_fold_opts(sketch_bits, ffn.dtype, max_batch, 0, 0)
+    opts = tardis_fold_opts(sketch_bits, ffn.dtype, max_batch, 1 if deterministic else 0, 0)
     handle = C.c_void_p()
     st = lib().tardis_fold(C.byref(ffn.desc), _ptr(lo), _ptr(hi), _ptr(a), _ptr(c), C.byref(opts),
                            _stream(stream), C.byref(handle))

@@ -36,29 +36,39 @@ def rel_l2(got, want):
     return float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30))
 
 
-def assert_y_close(got, want, Wp, X, dtype="bf16"):
+def assert_y_close(got, want, F, X, flags, dtype="bf16"):
     """y against the checker: relative L2 over all tokens, per token, and ELEMENT BY ELEMENT.
 
-    Element bound for bf16 storage (fp32 accumulation): the library's W' is the checker's rounded
-    once to bf16, |eps_ik| <= 2^-9 |W'_ik| and, as a rounding error, uniform within that: the folded
-    product of token x is off by a sum of independent terms of standard deviation at most
-    2^-9/sqrt(3) * r_i, r_i = sqrt(sum_k (W'_ik x_k)^2) - six of those are allowed; the bf16 output
-    adds half a unit in the last place, <= 2^-9 |y_i| (2^-8 allowed); everything else (fp32 sums,
-    erf) is orders below.  One wrong element - off by its own size - fails this, where a norm over
-    the token would let it pass.  fp32 storage: 1e-4 of |y_i| + r_i (sums of d and h fp32 terms)."""
+    Element bound for bf16 storage (fp32 accumulation); bf16 keeps 8 significant bits, so rounding
+    to it moves a value by at most 2^-8 of itself (half a unit in the last place at the bottom of a
+    binade).  (1) The library's W' is the checker's rounded once to bf16, |eps_ik| <= 2^-8 |W'_ik|
+    and, as a rounding error, uniform within its half unit: the folded product of token x is off by
+    a sum of independent terms of standard deviation at most 2^-8/sqrt(3) * r_i,
+    r_i = sqrt(sum_k (W'_ik x_k)^2).  (2) The paths that carry the repair factors delta_j as bf16
+    (passes of 17-64 tokens, prompts) add the same kind of sum over the token's flagged neurons,
+    q_i = sqrt(sum_j (delta_j W2_ij)^2).  Six standard deviations of (1) + (2) are allowed.
+    (3) The bf16 output adds at most 2^-8 |y_i| (1.5 x 2^-8 of the checker's value allowed).
+    Everything else (fp32 sums, erf) is orders below.  One wrong element - off by its own size -
+    fails this, where a norm over the token would let it pass.
+    fp32 storage: 1e-4 of |y_i| + r_i + q_i (sums of d and h fp32 terms)."""
     got = np.atleast_2d(np.asarray(got, np.float64))
     want = np.atleast_2d(np.asarray(want, np.float64))
     X = np.atleast_2d(np.asarray(X, np.float64))
-    assert got.shape == want.shape and X.shape[0] == want.shape[0]
+    flags = np.atleast_2d(np.asarray(flags, bool))
+    assert got.shape == want.shape and X.shape[0] == want.shape[0] == flags.shape[0]
     assert np.isfinite(got).all()
     err = rel_l2(got, want)
     assert err <= Y_TOL[dtype], err
     per_tok = np.linalg.norm(got - want, axis=1) / np.maximum(np.linalg.norm(want, axis=1), 1e-30)
     assert per_tok.max() <= 3 * Y_TOL[dtype], per_tok.max()
-    r = np.sqrt((X * X) @ (np.asarray(Wp, np.float64) ** 2).T)
+    r2 = (X * X) @ (F.Wp ** 2).T
+    for t in range(X.shape[0]):
+        idx, delta = O.fix_terms(F, X[t], flags[t])
+        r2[t] += (F.W2[:, idx] ** 2) @ (delta ** 2)
+    r = np.sqrt(r2)
     floor = 1e-6 * np.abs(want).max()
     if dtype == "bf16":
-        tol = 2.0 ** -8 * np.abs(want) + 6.0 * (2.0 ** -9 / np.sqrt(3.0)) * r + floor
+        tol = 1.5 * 2.0 ** -8 * np.abs(want) + 6.0 * (2.0 ** -8 / np.sqrt(3.0)) * r + floor
     else:
         tol = 1e-4 * (np.abs(want) + r) + floor
     bad = np.abs(got - want) > tol
@@ -151,7 +161,7 @@ def run_case(layer, X_cal, X_test, coverage, act="gelu_erf", batched=False, chec
     for t in range(n):
         assert counts[t] == FLo[t].sum()
         np.testing.assert_array_equal(np.sort(lists[t]), np.flatnonzero(FLo[t]))   # list: same set
-    err = assert_y_close(Yg, Yo, F.Wp, X_test, dt)               # norms and element by element
+    err = assert_y_close(Yg, Yo, F, X_test, FLo, dt)               # norms and element by element
 
     # dense baseline against the checker's dense FFN
     Yd = host(T.tardis_dense_forward(L, Xd))
@@ -361,7 +371,7 @@ def test_calibrate_search_feeds_the_online_path():
     Y = T.tardis_ffn_forward_batched(L, dev(w.X_test, "bf16"))
     mask, _, _ = T.tardis_get_last_outliers(L, 4, want_list=False)
     np.testing.assert_array_equal(unpack_mask(mask, 512), FLo)
-    assert_y_close(host(Y), Yo, F.Wp, w.X_test)
+    assert_y_close(host(Y), Yo, F, w.X_test, FLo)
     assert 0.05 < FLo.mean() < 0.2
     L.close()
 
@@ -735,6 +745,95 @@ def test_repeated_calls_are_stable():
 
 
 # ------------------------------------------------------------- stacked layers
+@pytest.mark.parametrize("d,h", [(1024, 4096), (4096, 2048), (2048, 1000)])
+def test_deterministic_layer_is_bit_identical_from_run_to_run(d, h):
+    """opts.deterministic = 1: the repair is accumulated in counted fixed-point words (integer adds
+    commute) and flagged lists are walked in ascending order, so twenty repeats of a call give the
+    same bits; against the checker the results are held to the same bars as any layer."""
+    w = synth.decode(d=d, h=h, n_cal=512, n_test=40, coverage=0.9)
+    lay = w.layer
+    ffn = make_ffn(lay)
+    lo, hi, a, c = T.tardis_calibrate(ffn, dev(w.X_cal, "bf16"), 0.9)
+    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=40, deterministic=True)
+    Lf = T.tardis_fold(ffn, lo, hi, a, c, max_batch=40)
+    F = O.build(lay.W1, None, lay.W2, None, *(t.cpu().numpy() for t in (lo, hi, a, c)))
+    X = dev(w.X_test, "bf16")
+    for n in (1, 2, 3, 4, 7, 8, 13, 16, 40):
+        xb = X[:n].contiguous()
+        first = T.tardis_ffn_forward_batched(L, xb).clone()
+        mask, counts, lst = T.tardis_get_last_outliers(L, n)
+        mask, counts, lst = mask.clone(), counts.clone(), lst.clone()
+        for rep in range(20):
+            y = T.tardis_ffn_forward_batched(L, xb)
+            assert torch.equal(y, first), (n, rep)
+        Yo, FLo = O.forward(F, w.X_test[:n])
+        np.testing.assert_array_equal(unpack_mask(mask, h), FLo)
+        assert_y_close(host(first), Yo, F, w.X_test[:n], FLo)
+        cn, ls = counts.cpu().numpy(), lst.cpu().numpy()
+        for t in range(n):
+            np.testing.assert_array_equal(ls[t, :cn[t]], np.flatnonzero(FLo[t]))       # ascending
+        # and the same numbers, to rounding, as the layer folded without the option
+        yf = T.tardis_ffn_forward_batched(Lf, xb)
+        assert rel_l2(host(first), host(yf)) < 2e-3
+    L.close()
+    Lf.close()
+
+
+def test_deterministic_stack_and_refusals():
+    d, h, nl = 1024, 2048, 3
+    layers, oracles = [], []
+    for li in range(nl):
+        seed = synth.workload_seed(4, 50 + li)
+        lay = synth.make_layer(d, h, "bf16", seed, w1_std=0.03, w2_std=0.03, heavy_frac=0.01)
+        ffn = make_ffn(lay)
+        X_cal = synth.make_tokens(512, d, "bf16", seed, synth.STREAM_CAL)
+        lo, hi, a, c = T.tardis_calibrate(ffn, dev(X_cal, "bf16"), 0.9)
+        layers.append(T.tardis_fold(ffn, lo, hi, a, c, max_batch=8, deterministic=True))
+        oracles.append(O.build(lay.W1, None, lay.W2, None, *(t.cpu().numpy() for t in (lo, hi, a, c))))
+    x0 = synth.make_tokens(8, d, "bf16", synth.workload_seed(4, 60), synth.STREAM_TEST)
+    for n in (1, 2, 5, 8):
+        xb = dev(x0[:n], "bf16")
+        first = T.tardis_stack_forward(layers, xb).clone()
+        hand = [T.tardis_get_handover(layers[li], n).clone() for li in range(nl - 1)]
+        for rep in range(10):
+            assert torch.equal(T.tardis_stack_forward(layers, xb), first), (n, rep)
+        x_in = x0[:n].astype(np.float64)
+        for li in range(nl):      # teacher-forced against the checker, as for any stack
+            Yo, FLo = O.forward(oracles[li], x_in)
+            mask, _, _ = T.tardis_get_last_outliers(layers[li], n, want_list=False)
+            np.testing.assert_array_equal(unpack_mask(mask, h), FLo)
+            if li < nl - 1:
+                assert rel_l2(host(hand[li]), O.to_bf16(O.rmsnorm(Yo))) <= 1e-2
+                x_in = host(hand[li])
+            else:
+                assert_y_close(host(first), Yo, oracles[li], x_in, FLo)
+    for L in layers:
+        L.close()
+    # an fp32 layer has no ordered path: refused when folded, not silently run unordered
+    wt = synth.tiny()
+    ffn = make_ffn(wt.layer)
+    lo, hi, a, c = T.tardis_calibrate(ffn, dev(wt.X_cal, "f32"), 0.9)
+    with pytest.raises(T.TardisError) as e:
+        T.tardis_fold(ffn, lo, hi, a, c, deterministic=True)
+    assert e.value.status == T.ERR_SHAPE
+
+
+def test_fixed_point_accumulators_by_knob(monkeypatch):
+    """TARDIS_FIXED_POINT=1 puts the counted fixed-point accumulators under the ordinary dispatch
+    (token passes and prompts unchanged): the decode groups against the checker, single token,
+    groups, a partly filled group, graph replay."""
+    monkeypatch.setenv("TARDIS_FIXED_POINT", "1")
+    w = synth.decode(d=2048, h=4096, n_cal=512, n_test=16, coverage=0.9)
+    r = run_case(w.layer, w.X_cal, w.X_test[:11], 0.9, batched=True, check_calibrate=False, max_batch=16)
+    assert r["y_err"] < 1e-2
+    r = run_case(w.layer, w.X_cal, w.X_test[:3], 0.9, batched=False, check_calibrate=False)
+    assert r["y_err"] < 1e-2
+    lay = custom_layer(1024, 777, "bf16", synth.workload_seed(5, 3), 0.05, True)     # ragged h, biases
+    Xc = synth.make_tokens(400, 1024, "bf16", 77, synth.STREAM_CAL)
+    Xt = synth.make_tokens(9, 1024, "bf16", 77, synth.STREAM_TEST)
+    run_case(lay, Xc, Xt, 0.8, act="gelu_tanh", batched=True, max_batch=9)
+
+
 @pytest.mark.parametrize("d,h,dtype,n", [(1024, 4096, "bf16", 1), (1024, 4096, "bf16", 3), (64, 256, "f32", 2),
                                          (1024, 4096, "bf16", 12), (2048, 2048, "bf16", 8), (2048, 2048, "bf16", 16),
                                          (2048, 2048, "bf16", 6), (1024, 4096, "bf16", 40), (1024, 2048, "bf16", 90)])
@@ -770,7 +869,7 @@ def test_stack_teacher_forced(d, h, dtype, n):
             assert rel_l2(xn, want) <= Y_TOL[dtype]
             x_in = xn                                   # teacher forcing: the GPU's own hand-over
         else:
-            assert_y_close(host(y), Yo, oracles[li].Wp, x_in, dtype)
+            assert_y_close(host(y), Yo, oracles[li], x_in, FLo, dtype)
     # one call per layer with host-side glue gives the same final result
     for L in layers:
         L.close()
@@ -857,7 +956,7 @@ def test_full_size_decode_batch1(decode_full):
         assert k == FLo[t].sum()
         np.testing.assert_array_equal(np.sort(lst.cpu().numpy()[0, :k]), np.flatnonzero(FLo[t]))
         rates.append(k / layer.h)
-    assert_y_close(Yg, Yo, F.Wp, w.X_test[:n])
+    assert_y_close(Yg, Yo, F, w.X_test[:n], FLo)
     assert abs(np.mean(rates) - 0.05) < 0.01                      # test-time fallback rate ~ 1 - t
     # the fix matters: without it the folded product alone is far from the checker's result
     Y0, _ = O.forward(F, w.X_test[:n], np.zeros_like(FLo))
@@ -894,7 +993,7 @@ def test_full_size_batched_decode_sampled_tokens(decode_full, B):
         yo, flo = O.forward_token(F, X[t])
         np.testing.assert_array_equal(FLg[t], flo)
         assert int(counts[t].item()) == flo.sum()
-        assert_y_close(host(Y[t]), yo, F.Wp, X[t])
+        assert_y_close(host(Y[t]), yo, F, X[t], flo)
     ucnt, _ = T.tardis_get_last_union(L, B)
     assert int(ucnt.item()) == FLg.any(axis=0).sum() >= FLg[0].sum()
 
@@ -927,7 +1026,7 @@ def test_full_size_batched_decode_other_fallback_rates(decode_full_other_rates, 
         yo, flo = O.forward_token(F, X[t])
         np.testing.assert_array_equal(FLg[t], flo)
         assert int(counts[t].item()) == flo.sum()
-        assert_y_close(host(Y[t]), yo, F.Wp, X[t])
+        assert_y_close(host(Y[t]), yo, F, X[t], flo)
     # every token's mask against the checker's predictor alone (cheap: no repair)
     for t in range(B):
         np.testing.assert_array_equal(FLg[t], O.predict(F.sk, X[t]))
@@ -948,7 +1047,7 @@ def test_full_size_prefill_sampled_tokens(decode_full):
     for t in (0, 63, 64, 1000, 2047):
         yo, flo = O.forward_token(F, w.X_test[t])
         np.testing.assert_array_equal(FLg[t], flo)
-        assert_y_close(host(Y[t]), yo, F.Wp, w.X_test[t])
+        assert_y_close(host(Y[t]), yo, F, w.X_test[t], flo)
     cnt = counts.cpu().numpy()
     assert (cnt == FLg.sum(1)).all()
     assert abs(cnt.mean() / w.layer.h - 0.05) < 0.005
@@ -968,7 +1067,7 @@ def test_full_size_prompt_256_tokens(decode_full):
     for t in (0, 100, 255):
         yo, flo = O.forward_token(F, w.X_test[t])
         np.testing.assert_array_equal(FLg[t], flo)
-        assert_y_close(host(Y[t]), yo, F.Wp, w.X_test[t])
+        assert_y_close(host(Y[t]), yo, F, w.X_test[t], flo)
     assert (counts.cpu().numpy() == FLg.sum(1)).all()
     assert torch.isfinite(Y.float()).all()
 
@@ -993,11 +1092,11 @@ def test_full_size_sketch4_decode(decode_full):
         y = T.tardis_ffn_forward(L4, Xd[t])
         mask, cnt, _ = T.tardis_get_last_outliers(L4, 1, want_list=False)
         np.testing.assert_array_equal(unpack_mask(mask, w.layer.h)[0], FLo[t])
-        assert_y_close(host(y), Yo[t], F.Wp, X[t])
+        assert_y_close(host(y), Yo[t], F, X[t], FLo[t])
     Y = T.tardis_ffn_forward_batched(L4, Xd)                     # 4 + 2 tokens per launch
     mask, counts, _ = T.tardis_get_last_outliers(L4, 6, want_list=False)
     np.testing.assert_array_equal(unpack_mask(mask, w.layer.h), FLo)
-    assert_y_close(host(Y), Yo, F.Wp, X)
+    assert_y_close(host(Y), Yo, F, X, FLo)
     assert 0.04 < FLo.mean() < 0.09
     L4.close()
 
@@ -1032,7 +1131,7 @@ def test_full_size_stack_of_three_layers():
                 if li < nl - 1:
                     assert rel_l2(xn[t], O.to_bf16(O.rmsnorm(yo[None])[0])) <= 1e-2
                 else:
-                    assert_y_close(host(y)[t], yo, F.Wp, x_in[t])
+                    assert_y_close(host(y)[t], yo, F, x_in[t], flo)
             del F
             x_in = xn
     for L in layers:
