@@ -268,6 +268,56 @@ def calibrate_search(W1, b1, X_cal, coverage, step, kind: str = "gelu_erf"):
 
 
 # ---------------------------------------------------------------------------
+# adaptive thresholding  (Sec. "Non-linear Function Approximation", "Adaptive
+# Thresholding"; the two error_aware_threshold calls and the two estimate_error
+# calls of Algorithm 1)
+# ---------------------------------------------------------------------------
+def neuron_errors(W1, b1, W2, X_cal, lo, hi, a, c, kind: str = "gelu_erf"):
+    """Empirical error of every neuron over the calibration inputs,
+        E_n = sum_x err_n(x),
+        err_n(x) = || sigma(z_n) W2[:, n] - phi_n(z_n) W2[:, n] ||_2
+                 = |sigma(z_n) - (a_n z_n + c_n)| * ||W2[:, n]||_2   if lo_n <= z_n < hi_n, else 0
+    (the per-neuron error metric of the section; phi_n equals sigma outside the
+    range).  Returns fp64[h].  The layer's error is the sum over its neurons
+    (err(x) = sum_n err_n(x))."""
+    Z = preact(W1, b1, X_cal)
+    lo = _f64(lo); hi = _f64(hi); a = _f64(a); c = _f64(c)
+    inside = (Z >= lo[None, :]) & (Z < hi[None, :])
+    resid = np.abs(act(Z, kind) - (Z * a[None, :] + c[None, :]))
+    colnorm = np.sqrt((_f64(W2) ** 2).sum(axis=0))
+    return (resid * inside).sum(axis=0) * colnorm
+
+
+def error_aware_threshold(E, t: float, t_min: float, t_max: float):
+    """Thresholds t_i for items (layers, or the neurons of a layer) with errors E_i:
+        minimise sum_i E_i t_i   subject to   sum_i t_i = t * n,   t_min <= t_i <= t_max.
+    The section prints the objective and the equality only; a linear objective
+    under one equality has no minimum without bounds, so the caller supplies them
+    (reading; 0 <= t_min <= t <= t_max <= 1).  The solution of this linear
+    programme is the greedy one: the items with the largest errors sit at t_min,
+    the others at t_max, and at most one item in between takes what is left of the
+    budget.  Items of equal error are ordered by index (lower index first).
+    Returns fp32[n]."""
+    E = _f64(E)
+    n = E.shape[0]
+    t, t_min, t_max = float(t), float(t_min), float(t_max)
+    if not (t_min <= t <= t_max):
+        raise ValueError("need t_min <= t <= t_max")
+    out = np.full(n, t_max, np.float64)
+    if t_max > t_min:
+        width = t_max - t_min
+        excess = n * t_max - t * n                 # what has to be taken away from "everybody at t_max"
+        k = int(math.floor(excess / width))
+        k = min(k, n)
+        order = sorted(range(n), key=lambda i: (-E[i], i))
+        for r in range(k):
+            out[order[r]] = t_min
+        if k < n:
+            out[order[k]] = t_max - (excess - k * width)
+    return out.astype(np.float32)
+
+
+# ---------------------------------------------------------------------------
 # constant folding  (Sec. "Constant Folded Matrix Generation")
 # ---------------------------------------------------------------------------
 def fold(W1, b1, W2, b2, a, c):

@@ -504,6 +504,64 @@ def test_calibrate_search_covers_and_fits():
     assert (((hi > qhi) & (lo > qlo)) | ((hi < qhi) & (lo < qlo))).mean() > 0.8
 
 
+# --------------------------------------------------------- adaptive thresholding
+def test_neuron_errors_against_the_error_metric_written_out():
+    """err_n(x) as the section defines it - the L2 distance between the neuron's exact and
+    approximated contributions to the output - evaluated literally, vector by vector."""
+    rng = np.random.default_rng(41)
+    d, h, n = 6, 5, 40
+    W1, b1, W2 = rng.normal(size=(h, d)), rng.normal(size=h) * 0.1, rng.normal(size=(d, h))
+    X = rng.normal(size=(n, d))
+    lo, hi = -np.abs(rng.normal(size=h)) - 0.2, np.abs(rng.normal(size=h)) + 0.2
+    a, c = rng.normal(size=h) * 0.5, rng.normal(size=h) * 0.1
+    E = O.neuron_errors(W1, b1, W2, X, lo, hi, a, c)
+    want = np.zeros(h)
+    for i in range(n):
+        for j in range(h):
+            z = float(W1[j] @ X[i] + b1[j])
+            exact = O.act(np.array([z]))[0] * W2[:, j]
+            phi = (a[j] * z + c[j]) if lo[j] <= z < hi[j] else O.act(np.array([z]))[0]
+            want[j] += math.sqrt(((exact - phi * W2[:, j]) ** 2).sum())
+    np.testing.assert_allclose(E, want, rtol=1e-12, atol=1e-14)
+    # an exact line (identity) or an empty range leaves no error
+    assert np.all(O.neuron_errors(W1, b1, W2, X, lo, hi, np.ones(h), np.zeros(h), "identity") < 1e-12)
+    assert np.all(O.neuron_errors(W1, b1, W2, X, lo, lo, a, c) == 0.0)
+
+
+def test_error_aware_threshold_by_hand_and_against_a_linear_programme_solver():
+    # by hand: 5 items, t = 0.8, bounds [0.6, 0.9]: everybody at 0.9 is 0.5 over the budget of 4.0;
+    # each item moved down to 0.6 takes 0.3 away: one whole item (the largest error) and 0.2 of the next
+    E = np.array([3.0, 10.0, 1.0, 7.0, 2.0])
+    t = O.error_aware_threshold(E, 0.8, 0.6, 0.9)
+    np.testing.assert_allclose(t, [0.9, 0.6, 0.9, 0.7, 0.9], atol=1e-7)
+    assert t.sum() == pytest.approx(4.0, abs=1e-6)
+    # equal errors: the lower index counts as the larger
+    t = O.error_aware_threshold(np.array([5.0, 5.0, 5.0, 5.0]), 0.75, 0.5, 1.0)
+    np.testing.assert_allclose(t, [0.5, 0.5, 1.0, 1.0], atol=1e-7)
+    # degenerate bounds: nothing to distribute
+    np.testing.assert_allclose(O.error_aware_threshold(E, 0.8, 0.8, 0.8), np.full(5, 0.8), atol=1e-7)
+    np.testing.assert_allclose(O.error_aware_threshold(E, 0.9, 0.6, 0.9), np.full(5, 0.9), atol=1e-7)
+    np.testing.assert_allclose(O.error_aware_threshold(E, 0.6, 0.6, 0.9), np.full(5, 0.6), atol=1e-7)
+    with pytest.raises(ValueError):
+        O.error_aware_threshold(E, 0.95, 0.6, 0.9)
+    # against a library solver of the printed programme (objective + equality) with the bounds added
+    from scipy.optimize import linprog
+    rng = np.random.default_rng(42)
+    for n, tt, lo_b, hi_b in [(7, 0.85, 0.7, 0.95), (12, 0.9, 0.5, 1.0), (30, 0.6, 0.0, 1.0), (9, 0.77, 0.75, 0.8)]:
+        E = rng.uniform(0.1, 5.0, n)
+        mine = O.error_aware_threshold(E, tt, lo_b, hi_b).astype(np.float64)
+        res = linprog(E, A_eq=np.ones((1, n)), b_eq=[tt * n], bounds=[(lo_b, hi_b)] * n, method="highs")
+        assert res.status == 0
+        assert float(E @ mine) == pytest.approx(res.fun, rel=1e-6)
+        np.testing.assert_allclose(mine, res.x, atol=1e-6)               # distinct errors: the minimiser is unique
+        assert mine.sum() == pytest.approx(tt * n, abs=1e-5) and mine.min() >= lo_b - 1e-7 and mine.max() <= hi_b + 1e-7
+    # larger errors never get a larger threshold
+    E = rng.uniform(0.0, 1.0, 200)
+    t = O.error_aware_threshold(E, 0.9, 0.8, 1.0)
+    o = np.argsort(-E, kind="stable")
+    assert (np.diff(t[o]) >= -1e-7).all()
+
+
 # ------------------------------------------------------------------- predictor
 def test_sketch_codes_brute_force():
     rng = np.random.default_rng(12)
