@@ -147,6 +147,36 @@ tardis_status_t tardis_calibrate_search(const tardis_ffn_desc* desc, const void*
                                         float coverage, const float* coverage_per_neuron, float step,
                                         float* lo, float* hi, float* a, float* c, void* stream);
 
+/* The two estimate_error steps of Algorithm 1 (Sec. "Non-linear Function
+ * Approximation", "Adaptive Thresholding"): the empirical error of a layer whose
+ * neurons are approximated on the given ranges by the given lines, over the
+ * calibration tokens.  Per neuron
+ *     E_n = sum_x err_n(x),   err_n(x) = |sigma(z_n) - (a_n z_n + c_n)| * ||W2[:, n]||_2
+ * for the inputs with lo_n <= z_n < hi_n (the L2 distance between the neuron's
+ * exact and approximated contribution to the output; zero outside the range),
+ * and for the layer the sum over its neurons.
+ *   lo, hi, a, c   device float arrays of length h (from a calibration call).
+ *   err_neurons    h floats, written.    err_layer  one float, written; may be NULL.
+ * 1 <= n_cal <= 32768.  Synchronises the stream before returning. */
+tardis_status_t tardis_estimate_errors(const tardis_ffn_desc* desc, const void* X_cal, int64_t n_cal,
+                                       const float* lo, const float* hi, const float* a, const float* c,
+                                       float* err_neurons, float* err_layer, void* stream);
+
+/* error_aware_threshold of Algorithm 1: thresholds (in-range portions) for n items -
+ * the layers of a model, or the neurons of a layer - from their errors,
+ *     minimise sum_i err_i t_i   subject to   sum_i t_i = t * n,  t_min <= t_i <= t_max.
+ * The paper prints the objective and the equality only; without bounds the
+ * programme has no minimum, so the caller supplies them (0 <= t_min <= t <= t_max
+ * <= 1, else TARDIS_ERR_INVALID_ARG).  The items of largest error get t_min, the
+ * others t_max, at most one item in between takes the rest of the budget; among
+ * equal errors the lower index counts as the larger.  Feed the result to the
+ * coverage_per_neuron argument of a calibration call (neurons), or use one entry
+ * per layer as that layer's t.
+ *   err    n device floats (finite, >= 0).   t_out  n device floats, written.
+ * Stream-ordered; does not synchronise. */
+tardis_status_t tardis_assign_thresholds(const float* err, int64_t n, float t, float t_min, float t_max,
+                                         float* t_out, void* stream);
+
 /* Constant folding and predictor construction (Sec. "Constant Folded Matrix
  * Generation" and Sec. "Predictor Generation").  Builds
  *     W' = W2 diag(a) W1            (d x d, stored in desc->dtype, rounded once)

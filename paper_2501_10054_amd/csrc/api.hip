@@ -125,7 +125,6 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
             (d + L->dec_blocks - 1) / L->dec_blocks <= 64 && L->dec_blocks <= 65535;
     if (L->deterministic && !L->fx) return TARDIS_ERR_SHAPE;   // only the fused decode kernels have the ordered path
     L->use_batched = env_int("TARDIS_BATCHED", 1, 0, 1) && td_batched_supported(L);
-    L->gather_max_tokens = env_int("TARDIS_GATHER_MAX", 16, 0, 16);
     L->batched_min_tokens = env_int("TARDIS_BATCHED_MIN", L->use_fused ? 17 : 1, 1, 64);
     // 4-bit sketch: the decode kernel reads the packed form (d = 2048, 4096); every other path
     // reads one-byte effective codes, kept only where such a path can run
@@ -222,6 +221,24 @@ tardis_status_t tardis_calibrate_search(const tardis_ffn_desc* desc, const void*
     if (!(step > 0.0f) || !(step < INFINITY)) return TARDIS_ERR_INVALID_ARG;
     return td_calibrate(desc, X_cal, n_cal, coverage, coverage_per_neuron, step, lo, hi, a, c,
                         static_cast<hipStream_t>(stream));
+}
+
+tardis_status_t tardis_estimate_errors(const tardis_ffn_desc* desc, const void* X_cal, int64_t n_cal, const float* lo,
+                                       const float* hi, const float* a, const float* c, float* err_neurons,
+                                       float* err_layer, void* stream) {
+    TD_TRY(check_desc(desc));
+    if (!X_cal || !lo || !hi || !a || !c || !err_neurons) return TARDIS_ERR_INVALID_ARG;
+    if (!aligned16(X_cal)) return TARDIS_ERR_INVALID_ARG;
+    if (n_cal < 1 || n_cal > kMaxCal) return TARDIS_ERR_SHAPE;
+    return td_estimate_errors(desc, X_cal, n_cal, lo, hi, a, c, err_neurons, err_layer, static_cast<hipStream_t>(stream));
+}
+
+tardis_status_t tardis_assign_thresholds(const float* err, int64_t n, float t, float t_min, float t_max, float* t_out,
+                                         void* stream) {
+    if (!err || !t_out) return TARDIS_ERR_INVALID_ARG;
+    if (n < 1 || n > kMaxH) return TARDIS_ERR_SHAPE;
+    if (!(t_min >= 0.0f) || !(t_max <= 1.0f) || !(t_min <= t) || !(t <= t_max)) return TARDIS_ERR_INVALID_ARG;
+    return td_assign_thresholds(err, n, t, t_min, t_max, t_out, static_cast<hipStream_t>(stream));
 }
 
 tardis_status_t tardis_fold(const tardis_ffn_desc* desc, const float* lo, const float* hi, const float* a,

@@ -9,10 +9,10 @@
 //   delta        rows W1[j] of the union only (gathered): z, then
 //                delta = sigma(z) - (a z + c) for the (token, neuron) pairs that
 //                were flagged, 0 elsewhere
-//   scatter      y += Delta . W2: up to 16 tokens gather the union rows of W2^T
-//                (vector ALU, tokens in registers); more tokens run the masked
-//                dense product over W2 on the matrix cores (by then the union is
-//                most of the layer anyway)
+//   scatter      y += Delta . W2: the masked dense product over W2 on the matrix cores
+//                (a variant that gathered the union rows of W2^T for up to 16 tokens
+//                never beat it where this path is used, nor the decode groups where it
+//                did: measured per fallback rate, and removed)
 //   finish       sum of the partial products, optional RMS norm, conversion
 //
 // The streaming kernel is bandwidth bound: one wavefront owns 16 weight rows and
@@ -28,8 +28,6 @@ constexpr int kRowsPerBlock = 64;             // 4 wavefronts x 16 rows
 constexpr int kChunk = 512;                   // bytes of every weight row per pipeline stage
 constexpr int kXPitch = kChunk + 16;          // LDS pitch of a staged token row
 constexpr int kDownSplits = 8;                // split of the hidden axis in the masked dense scatter
-constexpr int kGatherSegs = 16;               // segments of the union list in the gather scatter
-constexpr int kGatherTok = 16;                // most tokens the gather scatter handles
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
@@ -64,8 +62,7 @@ struct StreamArgs {
     const float* a;
     const float* c;
     int act;
-    bf16_t* delta;                 // neuron-major [h][64] or token-major [64][h]
-    int delta_token_major;
+    bf16_t* delta;                 // token-major [64][h]; only flagged (token, neuron) pairs are written (zeroed per pass)
     int h;
     // down
     float* partial;                // [split][64][d]
@@ -319,11 +316,7 @@ __device__ __forceinline__ void stream_body(const StreamArgs& p, int row_block, 
                     const float z = acc[tt][i] + bj;
                     dv = td_act(z, p.act) - fmaf(aj, z, cj);
                 }
-                if (p.delta_token_major) {
-                    if (dv != 0.0f) p.delta[(size_t)t * p.h + j] = td_f32_to_bf16(dv);
-                } else {
-                    p.delta[(size_t)j * kTB + t] = td_f32_to_bf16(dv);
-                }
+                if (dv != 0.0f) p.delta[(size_t)t * p.h + j] = td_f32_to_bf16(dv);
             }
         }
     }
@@ -385,56 +378,6 @@ __global__ void __launch_bounds__(256) fill_u32_kernel(uint32_t* __restrict__ p,
     if (i < n) p[i] = v;
 }
 
-// gather scatter for up to 16 tokens: thread = one output column, tokens in registers;
-// blockIdx.y = segment of the union list.  partial[seg][t][c] = sum_i delta[j_i][t] * W2T[j_i][c].
-// The segment is walked in batches of 64 neurons whose indices and 16 repair factors are staged
-// in LDS; the W2^T elements of all 64 neurons are requested back to back.
-__global__ void __launch_bounds__(256)
-scatter_gather_kernel(const bf16_t* __restrict__ W2T, const bf16_t* __restrict__ delta, const int32_t* __restrict__ ulist,
-                      const int32_t* __restrict__ ucount, int h, int d, int n_tok, float* __restrict__ partial) {
-    __shared__ int js[64];
-    __shared__ __align__(16) bf16_t ds[64][kGatherTok];
-    const int c = min((int)blockIdx.x * 256 + (int)threadIdx.x, d - 1);
-    const int count = min(*ucount, h);
-    const int len = (count + kGatherSegs - 1) / kGatherSegs;
-    const int i0 = (int)blockIdx.y * len, i1 = min(count, i0 + len);
-    float acc[kGatherTok];
-#pragma unroll
-    for (int t = 0; t < kGatherTok; ++t) acc[t] = 0.0f;
-    for (int b0 = i0; b0 < i1; b0 += 64) {
-        const int nb = min(64, i1 - b0);
-        __syncthreads();
-        {   // 64 neurons x 32 bytes of repair factors: thread = (neuron tid/4, 8-byte piece tid%4)
-            const int r = threadIdx.x >> 2, piece = threadIdx.x & 3;
-            const int j = ulist[b0 + min(r, nb - 1)];
-            if (piece == 0) js[r] = j;
-            *reinterpret_cast<uint2*>(&ds[r][piece * 4]) =
-                *reinterpret_cast<const uint2*>(delta + (size_t)j * kTB + piece * 4);
-        }
-        __syncthreads();
-        // all 64 elements of this batch are requested before the first is used
-        uint16_t w[64];
-#pragma unroll
-        for (int k = 0; k < 64; ++k) w[k] = __builtin_nontemporal_load(W2T + (size_t)js[min(k, nb - 1)] * d + c);
-#pragma unroll
-        for (int k = 0; k < 64; ++k) {
-            if (k < nb) {
-                const float wf = td_bf16_to_f32(w[k]);
-                const td_u32x4 d0 = *reinterpret_cast<const td_u32x4*>(&ds[k][0]);
-                const td_u32x4 d1 = *reinterpret_cast<const td_u32x4*>(&ds[k][8]);
-                const uint32_t dw[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    acc[2 * u] = fmaf(__uint_as_float(dw[u] << 16), wf, acc[2 * u]);
-                    acc[2 * u + 1] = fmaf(__uint_as_float(dw[u] & 0xFFFF0000u), wf, acc[2 * u + 1]);
-                }
-            }
-        }
-    }
-    if ((int)blockIdx.x * 256 + (int)threadIdx.x < d)
-        for (int t = 0; t < n_tok; ++t) partial[((size_t)blockIdx.y * kTB + t) * d + c] = acc[t];
-}
-
 // y[t] = yfold[t] + sum_s partial[s][t], optional RMS norm, conversion.  One block of 1024
 // threads per token, 4 columns per thread per step; d is a multiple of 4.
 __global__ void __launch_bounds__(1024)
@@ -486,12 +429,11 @@ template <int NT>
 tardis_status_t pass_t(tardis_layer_s* L, const bf16_t* x, int nt, bf16_t* y, uint32_t* mask, float* yfold,
                        int norm_out, hipStream_t s) {
     const int d = (int)L->d, h = (int)L->h;
-    const bool gather_scatter = nt <= L->gather_max_tokens;
     // (the delta buffer is kTB x h bf16 from a 256-byte aligned allocation: whole 16-byte vectors when h % 8 == 0)
-    const size_t zero_vecs = gather_scatter ? 0 : (size_t)kTB * h * 2 / 16;
+    const size_t zero_vecs = (size_t)kTB * h * 2 / 16;
     hipLaunchKernelGGL(quantize_tokens_kernel, dim3(nt), dim3(256), 0, s, x, d, L->bt_xq, L->bt_e, L->bt_ucount,
                        reinterpret_cast<uint4*>(L->bt_delta), zero_vecs);
-    if (!gather_scatter && ((size_t)kTB * h * 2) % 16 != 0) {          // odd h: the tail by the word
+    if (((size_t)kTB * h * 2) % 16 != 0) {          // odd h: the tail by the word
         const size_t words = (size_t)kTB * h / 2;
         hipLaunchKernelGGL(fill_u32_kernel, dim3(div_up(words, 256)), dim3(256), 0, s,
                            reinterpret_cast<uint32_t*>(L->bt_delta), words, 0u);
@@ -523,8 +465,7 @@ tardis_status_t pass_t(tardis_layer_s* L, const bf16_t* x, int nt, bf16_t* y, ui
     pred.ulist = L->bt_ulist;
     pred.ucount = L->bt_ucount;
     const int fold_blocks = div_up(d, kRowsPerBlock), pred_blocks = div_up(h, kRowsPerBlock);
-    // (the gather scatter already uses every partial slot the finishing kernel can sum)
-    const int fsplit = (!gather_scatter && (d * 2 / kChunk) % 2 == 0) ? 2 : 1;
+    const int fsplit = ((d * 2 / kChunk) % 2 == 0) ? 2 : 1;
     fold.yfold2 = L->bt_partial + (size_t)kDownSplits * kTB * d;
     const dim3 fp_grid(fold_blocks * fsplit + pred_blocks);
     if (d == 4096 && fsplit == 2)
@@ -549,21 +490,14 @@ tardis_status_t pass_t(tardis_layer_s* L, const bf16_t* x, int nt, bf16_t* y, ui
     del.a = L->a;
     del.c = L->c;
     del.delta = L->bt_delta;
-    del.delta_token_major = gather_scatter ? 0 : 1;
     if (d == 4096)
         hipLaunchKernelGGL((stream_kernel<NT, EPI_DELTA, 16>), dim3(pred_blocks, 1), dim3(256), kStreamLds, s, del, 16);
     else
         hipLaunchKernelGGL((stream_kernel<NT, EPI_DELTA, 0>), dim3(pred_blocks, 1), dim3(256), kStreamLds, s, del,
                            d * 2 / kChunk);
 
-    int nparts;
-    if (gather_scatter) {
-        nparts = kGatherSegs;
-        hipLaunchKernelGGL(scatter_gather_kernel, dim3(div_up(d, 256), kGatherSegs), dim3(256), 0, s,
-                           static_cast<const bf16_t*>(L->W2T), L->bt_delta, L->bt_ulist, L->bt_ucount, h, d, nt,
-                           L->bt_partial);
-    } else {
-        nparts = kDownSplits + (fsplit - 1);         // the fold's second half sits in the slot after the scatter's
+    const int nparts = kDownSplits + (fsplit - 1);   // the fold's second half sits in the slot after the scatter's
+    {
         StreamArgs down = base;
         down.W = static_cast<const unsigned char*>(L->W2);
         down.row_bytes = (int64_t)h * 2;
@@ -594,7 +528,7 @@ bool td_batched_supported(const tardis_layer_s* L) {
 }
 
 size_t td_batched_partial_floats(const tardis_layer_s* L) {
-    return (size_t)(kGatherSegs > kDownSplits ? kGatherSegs : kDownSplits) * kTB * L->d;
+    return (size_t)(kDownSplits + 1) * kTB * L->d;   // the scatter's splits and the fold's second half
 }
 
 // the streaming kernels use more than the default 64 KiB of dynamic LDS

@@ -99,7 +99,6 @@ struct tardis_layer_s {
     uint32_t* rec_tb;              //   token bits of each record (dec_blocks x neurons per block),
     float* rec_delta;              //   and kDecodeMaxTokens deltas per record
     int32_t defer_min_tokens;      // groups of at least this many tokens take the two-kernel path (4, 8; 99 = never)
-    int32_t gather_max_tokens;     // passes of up to this many tokens scatter through the union rows of W2^T
     int32_t batched_min_tokens;    // token counts up to this go through the single-token path
     int64_t last_n;    // token count of the most recent online call
     int32_t fx;        // decode kernels accumulate the repair in counted fixed-point words (deterministic results)
@@ -203,6 +202,11 @@ tardis_status_t td_fold(const tardis_ffn_desc* desc, const float* a, const float
 tardis_status_t td_calibrate(const tardis_ffn_desc* desc, const void* X, int64_t n, float coverage,
                              const float* cov_pn, float step, float* lo, float* hi, float* a, float* c,
                              hipStream_t s);
+tardis_status_t td_estimate_errors(const tardis_ffn_desc* desc, const void* X, int64_t n, const float* lo,
+                                   const float* hi, const float* a, const float* c, float* err, float* err_layer,
+                                   hipStream_t s);
+tardis_status_t td_assign_thresholds(const float* err, int64_t n, float t, float t_min, float t_max, float* out,
+                                     hipStream_t s);
 tardis_status_t td_fx_bounds(const tardis_layer_s* L, float* out2, hipStream_t s);
 // gemm.hip:  C[m][n] = sum_k A[m][k] * B[n][k]  (+ C if accumulate) (+ row_bias[m]); C fp32, ldc = N
 tardis_status_t td_gemm_nt(const void* A, const void* B, float* C, int64_t M, int64_t N, int64_t K,

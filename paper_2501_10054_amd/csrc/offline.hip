@@ -513,6 +513,84 @@ range_search_kernel(const float* __restrict__ Zt, int n, int npad, float coverag
     fit_and_store(vals, n, (float)rlo, (float)rhi, act, red, j, lo, hi, a, c);
 }
 
+// ------------------------------------------------- adaptive thresholding (Algorithm 1, outer loops)
+// E_n = ||W2[:, n]||_2 * sum over the calibration inputs with lo_n <= z < hi_n of |sigma(z) - (a_n z + c_n)|:
+// the section's per-neuron error metric err_n summed over the calibration set (outside the range
+// the approximated activation equals the exact one).  One block per neuron, fp64 sums.
+__global__ void __launch_bounds__(kBlock)
+neuron_error_kernel(const float* __restrict__ Zt, int n, const float* __restrict__ lo, const float* __restrict__ hi,
+                    const float* __restrict__ a, const float* __restrict__ c, const float* __restrict__ colnorm, int act,
+                    float* __restrict__ err) {
+    __shared__ double red[kBlock / TD_WAVE];
+    const int64_t j = blockIdx.x;
+    const float* z = Zt + j * (int64_t)n;
+    const double l = (double)lo[j], r = (double)hi[j], aj = (double)a[j], cj = (double)c[j];
+    double sum = 0.0;
+    for (int i = threadIdx.x; i < n; i += kBlock) {
+        const double zi = (double)z[i];
+        if (zi >= l && zi < r) sum += fabs(td_act_f64(zi, act) - (aj * zi + cj));
+    }
+    sum = block_sum(sum, red);
+    if (threadIdx.x == 0) err[j] = (float)(sum * (double)colnorm[j]);
+}
+
+// colnorm[j] = ||W2[:, j]||_2 for W2 stored d x h (thread per column, rows walked in order)
+template <typename T>
+__global__ void __launch_bounds__(kBlock)
+col_norm_kernel(const T* __restrict__ W2, int64_t d, int64_t h, float* __restrict__ colnorm) {
+    const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (j >= h) return;
+    double ss = 0.0;
+    for (int64_t i = 0; i < d; ++i) {
+        const double w = (double)td_load<T>(W2 + i * h + j);
+        ss += w * w;
+    }
+    colnorm[j] = (float)sqrt(ss);
+}
+
+// out[0] = sum of v[0..n) in a fixed order (one block)
+__global__ void __launch_bounds__(kBlock) sum_fixed_kernel(const float* __restrict__ v, int64_t n, float* __restrict__ out) {
+    __shared__ double red[kBlock / TD_WAVE];
+    double sum = 0.0;
+    for (int64_t i = threadIdx.x; i < n; i += kBlock) sum += (double)v[i];
+    sum = block_sum(sum, red);
+    if (threadIdx.x == 0) out[0] = (float)sum;
+}
+
+// Solution of   minimise sum E_i t_i,  sum t_i = t n,  t_min <= t_i <= t_max :
+// the k = floor((n t_max - t n) / (t_max - t_min)) items of largest error (equal errors: lower index
+// first) get t_min, the next one t_max minus the rest of the excess, all others t_max.  Thread i
+// finds its own rank by counting (tiles of the errors staged in LDS).
+__global__ void __launch_bounds__(kBlock)
+assign_thresholds_kernel(const float* __restrict__ E, int64_t n, double t, double t_min, double t_max,
+                         float* __restrict__ out) {
+    __shared__ float tile[kBlock];
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const float mine = i < n ? E[i] : 0.0f;
+    int64_t rank = 0;
+    for (int64_t j0 = 0; j0 < n; j0 += kBlock) {
+        __syncthreads();
+        tile[threadIdx.x] = j0 + threadIdx.x < n ? E[j0 + threadIdx.x] : 0.0f;
+        __syncthreads();
+        const int lim = (int)(n - j0 < kBlock ? n - j0 : kBlock);
+        for (int u = 0; u < lim; ++u) {
+            const float other = tile[u];
+            rank += (other > mine || (other == mine && j0 + u < i)) ? 1 : 0;
+        }
+    }
+    if (i >= n) return;
+    double v = t_max;
+    if (t_max > t_min) {
+        const double width = t_max - t_min;
+        const double excess = (double)n * t_max - t * (double)n;
+        double k = floor(excess / width);
+        if (k > (double)n) k = (double)n;
+        if ((double)rank < k) v = t_min;
+        else if ((double)rank == k) v = t_max - (excess - k * width);
+    }
+    out[i] = (float)v;
+}
+
 // ------------------------------------------------- bound for the fixed-point repair accumulators
 // For a token x and any set F of neurons, every partial sum of the terms that make up output i,
 //     W'[i,:] x + b'_i      and      delta_j W2[i,j]  (j in F),
@@ -624,6 +702,37 @@ static tardis_status_t fx_bounds_t(const tardis_layer_s* L, float* out2, hipStre
                        static_cast<const float*>(P.p), chunks, out2);
     TD_HIP(hipGetLastError());
     TD_HIP(hipStreamSynchronize(s));   // the temporaries go out of scope
+    return TARDIS_OK;
+}
+
+tardis_status_t td_estimate_errors(const tardis_ffn_desc* desc, const void* X, int64_t n, const float* lo,
+                                   const float* hi, const float* a, const float* c, float* err, float* err_layer,
+                                   hipStream_t s) {
+    const int64_t d = desc->d, h = desc->h;
+    DevBuf zt, cn;
+    TD_TRY(zt.alloc((size_t)h * n * 4));
+    TD_TRY(cn.alloc((size_t)h * 4));
+    TD_TRY(td_gemm_nt(desc->W1, X, static_cast<float*>(zt.p), h, n, d, desc->dtype, 0, desc->b1, s));
+    const dim3 cgrid((unsigned)((h + kBlock - 1) / kBlock));
+    if (desc->dtype == TARDIS_BF16)
+        hipLaunchKernelGGL(col_norm_kernel<bf16_t>, cgrid, dim3(kBlock), 0, s, static_cast<const bf16_t*>(desc->W2), d, h,
+                           static_cast<float*>(cn.p));
+    else
+        hipLaunchKernelGGL(col_norm_kernel<float>, cgrid, dim3(kBlock), 0, s, static_cast<const float*>(desc->W2), d, h,
+                           static_cast<float*>(cn.p));
+    hipLaunchKernelGGL(neuron_error_kernel, dim3((unsigned)h), dim3(kBlock), 0, s, static_cast<const float*>(zt.p), (int)n,
+                       lo, hi, a, c, static_cast<const float*>(cn.p), (int)desc->act, err);
+    if (err_layer) hipLaunchKernelGGL(sum_fixed_kernel, dim3(1), dim3(kBlock), 0, s, err, h, err_layer);
+    TD_HIP(hipGetLastError());
+    TD_HIP(hipStreamSynchronize(s));
+    return TARDIS_OK;
+}
+
+tardis_status_t td_assign_thresholds(const float* err, int64_t n, float t, float t_min, float t_max, float* out,
+                                     hipStream_t s) {
+    hipLaunchKernelGGL(assign_thresholds_kernel, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, err, n,
+                       (double)t, (double)t_min, (double)t_max, out);
+    TD_HIP(hipGetLastError());
     return TARDIS_OK;
 }
 

@@ -22,7 +22,7 @@ _TORCH_DTYPE = {F32: torch.float32, BF16: torch.bfloat16}
 _DTYPE_CODE = {torch.float32: F32, torch.bfloat16: BF16}
 
 EXPORTS = (
-    "tardis_calibrate", "tardis_calibrate_search", "tardis_fold", "tardis_ffn_forward", "tardis_ffn_forward_batched",
+    "tardis_calibrate", "tardis_calibrate_search", "tardis_estimate_errors", "tardis_assign_thresholds", "tardis_fold", "tardis_ffn_forward", "tardis_ffn_forward_batched",
     "tardis_ffn_forward_static", "tardis_stack_forward", "tardis_dense_forward", "tardis_get_folded", "tardis_get_predictor_state",
     "tardis_get_sketch_groups", "tardis_get_last_outliers", "tardis_get_last_union", "tardis_get_handover", "tardis_set_next_layer",
     "tardis_destroy", "tardis_status_string", "tardis_version",
@@ -58,6 +58,8 @@ def lib() -> C.CDLL:
         vp, i64, f32 = C.c_void_p, C.c_int64, C.c_float
         L.tardis_calibrate.argtypes = [C.POINTER(tardis_ffn_desc), vp, i64, f32, vp, vp, vp, vp, vp, vp]
         L.tardis_calibrate_search.argtypes = [C.POINTER(tardis_ffn_desc), vp, i64, f32, vp, f32, vp, vp, vp, vp, vp]
+        L.tardis_estimate_errors.argtypes = [C.POINTER(tardis_ffn_desc), vp, i64, vp, vp, vp, vp, vp, vp, vp]
+        L.tardis_assign_thresholds.argtypes = [vp, i64, f32, f32, f32, vp, vp]
         L.tardis_fold.argtypes = [C.POINTER(tardis_ffn_desc), vp, vp, vp, vp, C.POINTER(tardis_fold_opts), vp,
                                   C.POINTER(vp)]
         L.tardis_ffn_forward.argtypes = [vp, vp, vp, vp]
@@ -139,6 +141,24 @@ def tardis_calibrate_search(ffn: FFN, X_cal, coverage: float = 0.95, step: float
                                        _stream(stream))
     _check(st, "tardis_calibrate_search")
     return tuple(out)
+
+
+def tardis_estimate_errors(ffn: FFN, X_cal, lo, hi, a, c, stream=None):
+    """-> (err_neurons float32[h], err_layer float32[1]): empirical approximation error over X_cal."""
+    err = torch.empty(ffn.h, dtype=torch.float32, device=X_cal.device)
+    tot = torch.empty(1, dtype=torch.float32, device=X_cal.device)
+    st = lib().tardis_estimate_errors(C.byref(ffn.desc), _ptr(X_cal), X_cal.shape[0], _ptr(lo), _ptr(hi), _ptr(a), _ptr(c),
+                                      _ptr(err), _ptr(tot), _stream(stream))
+    _check(st, "tardis_estimate_errors")
+    return err, tot
+
+
+def tardis_assign_thresholds(err, t: float, t_min: float, t_max: float, stream=None):
+    """-> float32[n] thresholds: minimise sum err_i t_i with mean t and the given bounds."""
+    out = torch.empty_like(err)
+    _check(lib().tardis_assign_thresholds(_ptr(err), err.numel(), float(t), float(t_min), float(t_max), _ptr(out),
+                                          _stream(stream)), "tardis_assign_thresholds")
+    return out
 
 
 class Layer:

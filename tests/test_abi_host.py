@@ -98,6 +98,28 @@ def test_calibrate_rejects_bad_arguments_without_a_gpu():
     assert search(_desc(), step=float("nan")) == T.ERR_INVALID_ARG
 
 
+def test_threshold_calls_reject_bad_arguments_without_a_gpu():
+    lib = T.lib()
+    p = C.c_void_p(0x4000)
+    assert lib.tardis_assign_thresholds(None, 4, 0.9, 0.8, 1.0, p, None) == T.ERR_INVALID_ARG
+    assert lib.tardis_assign_thresholds(p, 4, 0.9, 0.8, 1.0, None, None) == T.ERR_INVALID_ARG
+    assert lib.tardis_assign_thresholds(p, 0, 0.9, 0.8, 1.0, p, None) == T.ERR_SHAPE
+    assert lib.tardis_assign_thresholds(p, 4, 0.7, 0.8, 1.0, p, None) == T.ERR_INVALID_ARG      # t below t_min
+    assert lib.tardis_assign_thresholds(p, 4, 0.95, 0.8, 0.9, p, None) == T.ERR_INVALID_ARG     # t above t_max
+    assert lib.tardis_assign_thresholds(p, 4, 0.9, -0.1, 1.0, p, None) == T.ERR_INVALID_ARG
+    assert lib.tardis_assign_thresholds(p, 4, 0.9, 0.8, 1.5, p, None) == T.ERR_INVALID_ARG
+    assert lib.tardis_assign_thresholds(p, 4, float("nan"), 0.8, 1.0, p, None) == T.ERR_INVALID_ARG
+
+    def est(desc, X=p, n=16, lo=p, err=p):
+        return lib.tardis_estimate_errors(C.byref(desc), X, n, lo, p, p, p, err, None, None)
+
+    assert est(_desc(), X=None) == T.ERR_INVALID_ARG
+    assert est(_desc(), lo=None) == T.ERR_INVALID_ARG
+    assert est(_desc(), err=None) == T.ERR_INVALID_ARG
+    assert est(_desc(), n=0) == T.ERR_SHAPE
+    assert est(_desc(d=0)) == T.ERR_SHAPE
+
+
 def test_online_calls_reject_null_handle():
     lib = T.lib()
     p = C.c_void_p(0x4000)

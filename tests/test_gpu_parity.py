@@ -360,6 +360,93 @@ def test_calibrate_search_refuses_a_step_that_needs_too_many_steps():
     assert torch.isfinite(lo).all() and (hi > lo).all()
 
 
+@pytest.mark.parametrize("dtype,d,h,n_cal,act", [("f32", 64, 96, 400, "gelu_erf"), ("bf16", 256, 200, 700, "gelu_tanh"),
+                                                 ("bf16", 1024, 512, 512, "relu")])
+def test_estimate_errors_against_checker(dtype, d, h, n_cal, act):
+    """E_n = sum over the calibration inputs of the section's error metric.  The two sides' pre-
+    activations differ in the last bits, so a sample within rounding distance of a range end may be
+    inside on one side and outside on the other: the library's value has to lie between the checker's
+    sums without and with such samples."""
+    seed = synth.workload_seed(9, 31)
+    layer = synth.make_layer(d, h, dtype, seed, w1_std=0.2 if d < 128 else 0.06, w2_std=0.05, heavy_frac=0.02, with_bias=True)
+    X_cal = synth.make_tokens(n_cal, d, dtype, seed, synth.STREAM_CAL)
+    ffn = make_ffn(layer, act)
+    Xd = dev(X_cal, dtype)
+    lo, hi, a, c = T.tardis_calibrate(ffn, Xd, 0.9)
+    err, tot = T.tardis_estimate_errors(ffn, Xd, lo, hi, a, c)
+    torch.cuda.synchronize()
+    lo_h, hi_h, a_h, c_h = (v.cpu().numpy() for v in (lo, hi, a, c))
+    E = O.neuron_errors(layer.W1, layer.b1, layer.W2, X_cal, lo_h, hi_h, a_h, c_h, act)
+    Z = O.preact(layer.W1, layer.b1, X_cal)
+    scale = float(np.abs(np.concatenate([lo_h, hi_h])).max())
+    eps = 2e-5 * scale
+    lo64, hi64 = lo_h.astype(np.float64), hi_h.astype(np.float64)
+    resid = np.abs(O.act(Z, act) - (Z * a_h.astype(np.float64) + c_h.astype(np.float64)))
+    cn = np.sqrt((layer.W2.astype(np.float64) ** 2).sum(axis=0))
+    sure = (Z >= lo64 + eps) & (Z < hi64 - eps)
+    maybe = (Z >= lo64 - eps) & (Z < hi64 + eps)
+    E_lo, E_hi = (resid * sure).sum(0) * cn, (resid * maybe).sum(0) * cn
+    got = err.cpu().numpy().astype(np.float64)
+    slack = 1e-4 * E + 1e-7 * E.max()
+    assert (got >= E_lo - slack).all() and (got <= E_hi + slack).all()
+    assert (E_lo <= E).all() and (E <= E_hi).all() and np.median((E_hi - E_lo) / np.maximum(E, 1e-30)) < 1e-3
+    assert float(tot.item()) == pytest.approx(got.sum(), rel=1e-5)            # the layer's error: the sum over its neurons
+    assert (got > 0).mean() > 0.9 or act == "relu"
+
+
+@pytest.mark.parametrize("n,t,t_min,t_max", [(1, 0.9, 0.8, 1.0), (5, 0.8, 0.6, 0.9), (257, 0.85, 0.7, 0.95),
+                                             (16384, 0.95, 0.9, 1.0), (1000, 0.6, 0.0, 1.0), (64, 0.9, 0.9, 0.9),
+                                             (300, 0.9, 0.5, 0.9), (300, 0.5, 0.5, 0.9)])
+def test_assign_thresholds_against_checker(n, t, t_min, t_max):
+    """The threshold programme on the device against the checker on the same errors: the same
+    floats out, ties (a quarter of the items share their error with another) resolved by index."""
+    rng = np.random.default_rng(n)
+    E = rng.uniform(0.0, 3.0, n).astype(np.float32)
+    E[rng.integers(0, n, n // 4)] = E[rng.integers(0, n, n // 4)]           # repeated values
+    t, t_min, t_max = (float(np.float32(v)) for v in (t, t_min, t_max))
+    got = T.tardis_assign_thresholds(torch.from_numpy(E).to(DEV), t, t_min, t_max).cpu().numpy()
+    want = O.error_aware_threshold(E, t, t_min, t_max)
+    np.testing.assert_array_equal(got, want)
+    assert got.astype(np.float64).sum() == pytest.approx(t * n, rel=1e-5, abs=1e-4)
+    assert got.min() >= np.float32(t_min) and got.max() <= np.float32(t_max)
+
+
+def test_adaptive_thresholds_feed_the_range_search():
+    """Algorithm 1's outer loop for one layer, as its listing orders it: ranges at the layer's
+    threshold, the neurons' errors on them, the error-aware thresholds, the search again with a
+    threshold per neuron - then fold and run.  Neurons that err more get the smaller portion, the
+    portions average to the layer's, and the programme's objective does not exceed the uniform one."""
+    w = synth.decode(d=1024, h=768, n_cal=768, n_test=6, coverage=0.85)
+    lay = w.layer
+    ffn = make_ffn(lay)
+    Xd = dev(w.X_cal, "bf16")
+    t, step = float(np.float32(0.85)), float(np.float32(0.1))
+    lo, hi, a, c = T.tardis_calibrate_search(ffn, Xd, t, step)
+    err, tot0 = T.tardis_estimate_errors(ffn, Xd, lo, hi, a, c)
+    tn = T.tardis_assign_thresholds(err, t, 0.7, 1.0)
+    np.testing.assert_array_equal(tn.cpu().numpy(), O.error_aware_threshold(err.cpu().numpy(), t, float(np.float32(0.7)), 1.0))
+    lo2, hi2, a2, c2 = T.tardis_calibrate_search(ffn, Xd, t, step, coverage_per_neuron=tn)
+    _, tot1 = T.tardis_estimate_errors(ffn, Xd, lo2, hi2, a2, c2)
+    torch.cuda.synchronize()
+    e, tnh = err.cpu().numpy(), tn.cpu().numpy()
+    assert tnh.astype(np.float64).mean() == pytest.approx(t, abs=1e-4)
+    assert e[tnh == tnh.min()].min() >= e[tnh == tnh.max()].max()              # the worst neurons got the least
+    Z = O.preact(lay.W1, None, w.X_cal)
+    cov = ((Z >= lo2.cpu().numpy().astype(np.float64)) & (Z < hi2.cpu().numpy().astype(np.float64))).mean(0)
+    assert (cov >= tnh - 2.0 / w.X_cal.shape[0]).all()                         # every neuron reached its own portion
+    # the programme's objective is no worse than giving every neuron the layer's threshold
+    assert float(e.astype(np.float64) @ tnh.astype(np.float64)) <= float(e.astype(np.float64).sum()) * t * (1 + 1e-6)
+    assert np.isfinite(float(tot0.item())) and np.isfinite(float(tot1.item())) and float(tot1.item()) > 0
+    L = T.tardis_fold(ffn, lo2, hi2, a2, c2, max_batch=6)
+    F = O.build(lay.W1, None, lay.W2, None, *(v.cpu().numpy() for v in (lo2, hi2, a2, c2)))
+    Yo, FLo = O.forward(F, w.X_test)
+    Y = T.tardis_ffn_forward_batched(L, dev(w.X_test, "bf16"))
+    mask, _, _ = T.tardis_get_last_outliers(L, 6, want_list=False)
+    np.testing.assert_array_equal(unpack_mask(mask, lay.h), FLo)
+    assert_y_close(host(Y), Yo, F, w.X_test, FLo)
+    L.close()
+
+
 def test_calibrate_search_feeds_the_online_path():
     # ranges from the search go through fold and forward like any others
     w = synth.decode(d=1024, h=512, n_cal=512, n_test=4, coverage=0.9)
