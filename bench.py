@@ -107,6 +107,34 @@ def prefill_run(T, synth, torch, np, to_dev):
                     "calibrate = 1 such GEMM + per-neuron sort/fit" % (gemm_flop / 1e9)}
 
 
+def sketch_study(T, torch, ffn, cal, X64):
+    """Predictor width study on the decode layer (the paper's Sec. "Predictor Size" sweep, here for
+    round-to-nearest codes): per code width and margin the flags of 64 tokens against the exact
+    pre-activations (harness-side torch product, fp32) - flag rate, precision, recall - and the bytes
+    a token would stream with codes packed at that width (3- and 2-bit codes sit in 4-bit slots in
+    this build, so their measured bytes are the 4-bit sketch's)."""
+    lo, hi, a, c = cal
+    z = X64.float() @ ffn.W1.float().t()
+    truth = ~((z >= lo[None, :]) & (z < hi[None, :]))
+    rows = []
+    for bits in (8, 4, 3, 2):
+        for margin in (0.0, 0.1):
+            L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=64, sketch_bits=bits, margin=margin)
+            T.tardis_ffn_forward_batched(L, X64)
+            mask, _, _ = T.tardis_get_last_outliers(L, 64, want_list=False)
+            sh = torch.arange(32, device=mask.device, dtype=torch.int32)
+            flags = ((mask[:, :, None] >> sh[None, None, :]) & 1).bool().reshape(64, -1)[:, :H]
+            tp = float((flags & truth).sum().item())
+            p = float(flags.float().mean().item())
+            sketch_bytes = D * H * bits / 8.0 + (D * H / 32.0 if bits < 8 else 0.0)
+            rows.append({"sketch_bits": bits, "margin": margin, "flag_rate": p,
+                         "precision": tp / max(1.0, float(flags.sum().item())),
+                         "recall": tp / max(1.0, float(truth.sum().item())),
+                         "bytes_per_token_if_packed": 2.0 * D * D + sketch_bytes + 4.0 * p * D * H})
+            L.close()
+    return {"true_out_of_range_rate": float(truth.float().mean().item()), "rows": rows}
+
+
 def stack_run(T, synth, torch, np, to_dev, n_layers, batches=(1, 32)):
     """n_layers independent layers chained with RMS-norm glue (config 4): per batch size the time
     of one pass through the whole stack, the per-layer measured fallback rates and the algorithmic
@@ -479,6 +507,7 @@ def main() -> int:
                           "algorithmic_GBs": b4 / (ms4 * 1e-3 / TOKENS_PER_STEP) / 1e9}
         for L in l4:
             L.close()
+        out["sketch_study"] = sketch_study(T, torch, layers[0].ffn, cals[0], X[:64].contiguous())
         covs = (args.coverage,) if args.no_sweep else (0.99, 0.95, 0.85)
         out["batched_sweep"] = batched_sweep(T, synth, torch, np, to_dev, pre, X, covs, chain=not args.no_chain)
     if args.prefill or not args.no_extras:

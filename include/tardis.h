@@ -88,7 +88,7 @@ typedef struct {
 } tardis_ffn_desc;
 
 typedef struct {
-    int32_t sketch_bits;   /* predictor code width: 8, or 4 (grouped, see tardis_fold) */
+    int32_t sketch_bits;   /* predictor code width: 8, or 4, 3, 2 (grouped, see tardis_fold) */
     int32_t folded_dtype;  /* storage of W'; must equal desc.dtype */
     int64_t max_batch;     /* largest n accepted by the batched online calls (1 .. 4096; longer prompts are
                               the caller's to cut); from 65 on the layer
@@ -101,7 +101,10 @@ typedef struct {
                               depends on timing.  Needs a bf16 layer with d = 1024, 2048 or 4096
                               (TARDIS_ERR_SHAPE otherwise); calls with more than 16 tokens are slower
                               than on a layer folded without it. */
-    int32_t reserved;
+    float margin;          /* 0 <= margin < 0.5: the predictor tests against each neuron's range narrowed by
+                              this fraction of its width at either end, lo + margin (hi - lo) <= z' < hi -
+                              margin (hi - lo); more neurons are flagged (and repaired exactly), fewer
+                              out-of-range ones are missed by a coarse sketch.  0: the range itself. */
 } tardis_fold_opts;
 
 /* ---------------------------------------------------------------- offline */
@@ -190,7 +193,10 @@ tardis_status_t tardis_assign_thresholds(const float* err, int64_t n, float t, f
  *     g_jG = max_{k in G}|W1[j,k]|,  s_j = max_G g_jG / (7*15),
  *     m_jG = ceil(g_jG / (7 s_j)) clamped to [1,15],
  *     q_jk = rint(W1[j,k] / (m_jG s_j)) clamped to [-7,7],
- * all in fp64, and the predictor uses the integer code Q_jk = m_jG q_jk (|Q| <= 105)
+ * all in fp64 (sketch_bits = 3 and 2: the same with 3 and 1 in place of 7, i.e.
+ * codes in [-3, 3] and [-1, 1]; this build keeps them in 4-bit slots, so they cost
+ * the bytes of the 4-bit sketch - they are there to measure what narrower codes do
+ * to the flags, Sec. "Predictor Size"), and the predictor uses the integer code Q_jk = m_jG q_jk (|Q| <= 105)
  * exactly as it uses the 8-bit code; tlo, thi as above with this s_j.  Storage is
  * 4 bits per weight plus one multiplier per group where the decode kernel reads the
  * packed form (bf16, d = 2048 or 4096), one byte per weight elsewhere; a layer
@@ -293,7 +299,7 @@ tardis_status_t tardis_get_predictor_state(tardis_handle_t L, int8_t* Q, float* 
                                            void* stream);
 
 /* Group multipliers of a 4-bit sketch: M is h x ceil(d/32) bytes, M[j][G] = m_jG.
- * TARDIS_ERR_STATE for a layer folded with an 8-bit sketch. */
+ * TARDIS_ERR_STATE for a layer folded with an 8-bit sketch (4-, 3- and 2-bit sketches have them). */
 tardis_status_t tardis_get_sketch_groups(tardis_handle_t L, uint8_t* M, void* stream);
 
 /* Predictor output of the most recent online call on this handle, for its n

@@ -377,7 +377,7 @@ def _thresholds(lo, hi, b, s):
     return tlo, thi
 
 
-def sketch(W1, b1, lo, hi, bits: int = 8) -> Sketch:
+def sketch(W1, b1, lo, hi, bits: int = 8, margin: float = 0.0) -> Sketch:
     """Integer sketch of W1 (the "quantised copy of W1" of Sec. "Predictor
     Generation", round-to-nearest) and the range bounds in sketch units.
 
@@ -394,9 +394,14 @@ def sketch(W1, b1, lo, hi, bits: int = 8) -> Sketch:
     the dot product stays one exact integer sum.  Storage: 4 bits per weight plus
     4 bits per group of 32.
 
-    bits = 3, 2 (checker only, for the predictor-width study of Sec. "Predictor
-    Size"; the library builds 8 and 4): the same grouped form with the largest
-    code 2^(bits-1) - 1 in place of 7.
+    bits = 3, 2 (the predictor-width study of Sec. "Predictor Size"): the same
+    grouped form with the largest code 2^(bits-1) - 1 in place of 7.
+
+    margin (0 <= margin < 0.5; not in the paper, which only names a quantised
+    W1): the predictor tests against the range narrowed by that fraction of its
+    width at either end, [lo + margin (hi - lo), hi - margin (hi - lo)): more
+    neurons are flagged - and then repaired exactly - so fewer out-of-range
+    neurons slip through a coarse sketch.
 
     Either way the test lo <= s_j*(Q_j . x) + b1_j < hi becomes
     tlo_j <= Q_j . x < thi_j with tlo = (lo-b1)/s, thi = (hi-b1)/s.
@@ -404,6 +409,12 @@ def sketch(W1, b1, lo, hi, bits: int = 8) -> Sketch:
     W1 = _f64(W1)
     h, d = W1.shape
     lo = _f64(lo); hi = _f64(hi)
+    if margin > 0.0:
+        w = hi - lo
+        ok = (w > 0.0) & np.isfinite(w)
+        mu = float(np.float32(margin))             # the interface carries fp32
+        w_ok = np.where(ok, w, 0.0)                # (an empty or unbounded range is left as it is)
+        lo, hi = np.where(ok, lo + mu * w_ok, lo), np.where(ok, hi - mu * w_ok, hi)
     b = np.zeros(h) if b1 is None else _f64(b1)
     if bits == 8:
         Q = np.zeros((h, d), np.int8)
@@ -485,7 +496,8 @@ class Folded:
     sk: Sketch
 
 
-def build(W1, b1, W2, b2, lo, hi, a, c, kind: str = "gelu_erf", wp_round=None, sketch_bits: int = 8) -> Folded:
+def build(W1, b1, W2, b2, lo, hi, a, c, kind: str = "gelu_erf", wp_round=None, sketch_bits: int = 8,
+          margin: float = 0.0) -> Folded:
     """Everything the online path needs.  `wp_round`, if given, is applied to W'
     once (e.g. rounding to the storage dtype) for the storage-matched variant."""
     Wp, bp = fold(W1, b1, W2, b2, a, c)
@@ -493,7 +505,7 @@ def build(W1, b1, W2, b2, lo, hi, a, c, kind: str = "gelu_erf", wp_round=None, s
         Wp = np.asarray(wp_round(Wp), dtype=np.float64)
     h, d = np.shape(W1)
     return Folded(d=d, h=h, kind=kind, W1=_f64(W1), b1=_f64(b1), W2=_f64(W2),
-                  a=_f64(a), c=_f64(c), Wp=Wp, bp=bp, sk=sketch(W1, b1, lo, hi, sketch_bits))
+                  a=_f64(a), c=_f64(c), Wp=Wp, bp=bp, sk=sketch(W1, b1, lo, hi, sketch_bits, margin))
 
 
 def fix_terms(F: Folded, x, flags):

@@ -75,6 +75,7 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     L->act = desc->act;
     L->max_batch = opts ? opts->max_batch : 1;
     L->sketch_bits = opts ? opts->sketch_bits : 8;
+    L->margin = opts ? opts->margin : 0.0f;
     L->mask_words = (h + 31) / 32;
     L->W1 = desc->W1;
     L->b1 = desc->b1;
@@ -104,6 +105,7 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     L->dec_blocks = env_int("TARDIS_DECODE_BLOCKS", L->dec_threads == 512 ? 512 : 256, 1, 4096);
     L->dec_copies = env_int("TARDIS_DECODE_COPIES", 2, 1, 4);
     L->prefetch_bytes = env_int("TARDIS_PREFETCH_KB", 96, 0, 256) * 1024;
+    L->strict_release = env_int("TARDIS_STRICT_RELEASE", 0, 0, 1);
     // (at least two copies' worth: the fixed-point accumulators are 8 bytes per token and column)
     const size_t yfix_bytes = (size_t)(L->dec_copies < 2 ? 2 : L->dec_copies) * kDecodeMaxTokens * d * 4;
     TD_TRY(dev_alloc(&L->yfix, yfix_bytes));
@@ -128,11 +130,11 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     L->batched_min_tokens = env_int("TARDIS_BATCHED_MIN", L->use_fused ? 17 : 1, 1, 64);
     // 4-bit sketch: the decode kernel reads the packed form (d = 2048, 4096); every other path
     // reads one-byte effective codes, kept only where such a path can run
-    const bool packed4 = L->sketch_bits == 4 && L->use_fused && (d == 2048 || d == 4096);
+    const bool packed4 = L->sketch_bits < 8 && L->use_fused && (d == 2048 || d == 4096);
     const bool byte_codes = !packed4 || (L->use_batched && L->max_batch > L->batched_min_tokens);
     if (byte_codes) TD_TRY(dev_alloc(&L->Q, (size_t)h * d));
     if (packed4) TD_TRY(dev_alloc(&L->Q4, (size_t)h * d / 2));
-    if (L->sketch_bits == 4) TD_TRY(dev_alloc(&L->M4, (size_t)h * ((d + 31) / 32)));
+    if (L->sketch_bits < 8) TD_TRY(dev_alloc(&L->M4, (size_t)h * ((d + 31) / 32)));
     L->prefill_min_tokens = env_int("TARDIS_PREFILL_MIN", 65, 33, 1 << 20);
     if (L->max_batch >= L->prefill_min_tokens && td_prefill_supported(L)) {
         char* scratch = nullptr;
@@ -160,7 +162,7 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     TD_HIP(hipMemcpyAsync(L->c, c, (size_t)h * 4, hipMemcpyDeviceToDevice, s));
     TD_HIP(hipMemcpyAsync(L->W2, desc->W2, (size_t)h * d * es, hipMemcpyDeviceToDevice, s));
     TD_TRY(td_transpose(desc->W2, L->W2T, d, h, desc->dtype, s));
-    TD_TRY(td_build_sketch(desc->W1, desc->b1, lo, hi, h, d, desc->dtype, L->sketch_bits, L->Q, L->Q4, L->M4, L->tlo,
+    TD_TRY(td_build_sketch(desc->W1, desc->b1, lo, hi, h, d, desc->dtype, L->sketch_bits, L->margin, L->Q, L->Q4, L->M4, L->tlo,
                            L->thi, s));
     TD_TRY(td_fold(desc, L->a, L->c, L->Wp, L->bp, s));
     if (L->fx) {
@@ -248,7 +250,9 @@ tardis_status_t tardis_fold(const tardis_ffn_desc* desc, const float* lo, const 
     TD_TRY(check_desc(desc));
     if (!lo || !hi || !a || !c) return TARDIS_ERR_INVALID_ARG;
     if (opts) {
-        if (opts->sketch_bits != 8 && opts->sketch_bits != 4) return TARDIS_ERR_INVALID_ARG;
+        if (opts->sketch_bits != 8 && opts->sketch_bits != 4 && opts->sketch_bits != 3 && opts->sketch_bits != 2)
+            return TARDIS_ERR_INVALID_ARG;
+        if (!(opts->margin >= 0.0f) || !(opts->margin < 0.5f)) return TARDIS_ERR_INVALID_ARG;
         if (opts->folded_dtype != desc->dtype) return TARDIS_ERR_DTYPE;
         if (opts->max_batch < 1 || opts->max_batch > kMaxBatch) return TARDIS_ERR_SHAPE;
         if (opts->deterministic != 0 && opts->deterministic != 1) return TARDIS_ERR_INVALID_ARG;
@@ -343,7 +347,7 @@ tardis_status_t tardis_get_predictor_state(tardis_handle_t L, int8_t* Q, float* 
 }
 
 tardis_status_t tardis_get_sketch_groups(tardis_handle_t L, uint8_t* M, void* stream) {
-    if (!L || !td_layer_is_live(L) || L->sketch_bits != 4) return TARDIS_ERR_STATE;
+    if (!L || !td_layer_is_live(L) || L->sketch_bits >= 8) return TARDIS_ERR_STATE;
     if (!M) return TARDIS_ERR_INVALID_ARG;
     TD_HIP(hipMemcpyAsync(M, L->M4, (size_t)L->h * ((L->d + 31) / 32), hipMemcpyDeviceToDevice,
                           static_cast<hipStream_t>(stream)));

@@ -61,7 +61,8 @@ struct tardis_layer_s {
     int8_t* Q;     // h x d predictor codes, one byte each (absent when only the packed 4-bit form is kept)
     uint8_t* Q4;   // packed 4-bit sketch, h x d/2 bytes: one 16-byte vector per group of 32 columns (or null)
     uint8_t* M4;   // 4-bit sketch: h x ceil(d/32) group multipliers, one byte each (or null)
-    int32_t sketch_bits;
+    int32_t sketch_bits;   // 8, or 4 / 3 / 2: grouped codes in 4-bit slots
+    float margin;          // fraction of a range's width the predictor's test is narrowed by at either end
     float* tlo;    // h
     float* thi;    // h
     float* a;      // h
@@ -78,6 +79,7 @@ struct tardis_layer_s {
     float* yfix;       // dec_copies x kDecodeMaxTokens x d fp32 repair accumulators of the fused decode kernel (zero between calls)
     const tardis_layer_s* next_layer;   // the layer that runs after this one (hint, may be null; not owned)
     int32_t prefetch_bytes;             // bytes of that layer's predictor rows each finished block requests
+    int32_t strict_release;             // the signalling thread of a decode block also executes an agent-scope release fence
     int32_t dec_blocks;   // grid of the fused decode kernel
     int32_t dec_threads;  // block size of the fused decode kernel (512 or 1024)
     int32_t dec_copies;   // number of repair accumulator copies
@@ -188,11 +190,12 @@ __device__ __forceinline__ double td_act_f64(double z, int act) {
 
 // offline.hip
 tardis_status_t td_transpose(const void* src, void* dst, int64_t rows, int64_t cols, int32_t dtype, hipStream_t s);
-// bits = 8: Q (required).  bits = 4: M4 (required), Q (effective one-byte codes, optional) and Q4
-// (packed, optional, needs d % 32 == 0).
+// bits = 8: Q (required).  bits = 4, 3, 2 (codes up to 7, 3, 1 in 4-bit slots): M4 (required), Q
+// (effective one-byte codes, optional) and Q4 (packed, optional, needs d % 32 == 0).  margin: fraction
+// of every range's width taken off at either end for the predictor's test.
 tardis_status_t td_build_sketch(const void* W1, const void* b1, const float* lo, const float* hi, int64_t h,
-                                int64_t d, int32_t dtype, int32_t bits, int8_t* Q, uint8_t* Q4, uint8_t* M4,
-                                float* tlo, float* thi, hipStream_t s);
+                                int64_t d, int32_t dtype, int32_t bits, float margin, int8_t* Q, uint8_t* Q4,
+                                uint8_t* M4, float* tlo, float* thi, hipStream_t s);
 // one-byte effective codes (multiplier * 4-bit code) from the packed 4-bit sketch
 tardis_status_t td_unpack_sketch4(const uint8_t* Q4, const uint8_t* M4, int64_t h, int64_t d, int8_t* Q,
                                   hipStream_t s);

@@ -113,11 +113,24 @@ fold_bias_kernel(const T* __restrict__ W2, const T* __restrict__ b1, const T* __
 // One block per neuron row: s = max|w| / 127 (fp64), q = rint(w / s) clamped,
 // bounds in code units.  All arithmetic is IEEE fp64 so the codes are a pure
 // function of the inputs.
+// The range the predictor tests against: the neuron's range with the fraction `margin` of its
+// width taken off at either end (margin = 0: the range itself).  A narrower test flags more
+// neurons - flagged neurons are repaired exactly, so this trades time for recall of a coarse sketch.
+__device__ __forceinline__ void predictor_range(double lo, double hi, double margin, double& rl, double& rh) {
+    rl = lo;
+    rh = hi;
+    const double w = hi - lo;
+    if (margin > 0.0 && w > 0.0 && w < INFINITY) {
+        rl = lo + margin * w;
+        rh = hi - margin * w;
+    }
+}
+
 template <typename T>
 __global__ void __launch_bounds__(kBlock)
 sketch_kernel(const T* __restrict__ W1, const T* __restrict__ b1, const float* __restrict__ lo,
               const float* __restrict__ hi, int64_t d, int8_t* __restrict__ Q, float* __restrict__ tlo,
-              float* __restrict__ thi) {
+              float* __restrict__ thi, float margin) {
     __shared__ float red[kBlock / TD_WAVE];
     const int64_t j = blockIdx.x;
     const T* row = W1 + j * d;
@@ -131,6 +144,8 @@ sketch_kernel(const T* __restrict__ W1, const T* __restrict__ b1, const float* _
     for (int w = 1; w < kBlock / TD_WAVE; ++w) m = fmaxf(m, red[w]);
     const double s = (double)m / 127.0;
     const double bj = b1 ? (double)td_load<T>(b1 + j) : 0.0;
+    double rl, rh;
+    predictor_range((double)lo[j], (double)hi[j], (double)margin, rl, rh);
     if (m > 0.0f) {
         for (int64_t k = threadIdx.x; k < d; k += kBlock) {
             double q = rint((double)td_load<T>(row + k) / s);
@@ -138,21 +153,22 @@ sketch_kernel(const T* __restrict__ W1, const T* __restrict__ b1, const float* _
             Q[j * d + k] = (int8_t)(int)q;
         }
         if (threadIdx.x == 0) {
-            tlo[j] = (float)(((double)lo[j] - bj) / s);
-            thi[j] = (float)(((double)hi[j] - bj) / s);
+            tlo[j] = (float)((rl - bj) / s);
+            thi[j] = (float)((rh - bj) / s);
         }
     } else {
         for (int64_t k = threadIdx.x; k < d; k += kBlock) Q[j * d + k] = 0;
         if (threadIdx.x == 0) {
-            const bool inside = ((double)lo[j] <= bj) && (bj < (double)hi[j]);
+            const bool inside = (rl <= bj) && (bj < rh);
             tlo[j] = inside ? -INFINITY : INFINITY;
             thi[j] = INFINITY;
         }
     }
 }
 
-// 4-bit grouped sketch (groups of 32 consecutive columns): group maxima g, row maximum r,
-// s = r / (7*15), multiplier m = ceil(g / (7 s)) in [1, 15], code q = rint(w / (m s)) in [-7, 7];
+// Grouped low-bit sketch (groups of 32 consecutive columns), codes of 4, 3 or 2 bits with the
+// largest code qmax = 7, 3 or 1: group maxima g, row maximum r,
+// s = r / (qmax*15), multiplier m = ceil(g / (qmax s)) in [1, 15], code q = rint(w / (m s)) in [-qmax, qmax];
 // all in fp64, each step one IEEE operation, so every output is a function of the inputs.
 // Outputs: M4 (one byte per group); Q (optional) the effective one-byte code m*q; Q4 (optional,
 // d % 32 == 0) the packed form read by the decode kernel: group G is the 16-byte vector G of the
@@ -161,7 +177,7 @@ template <typename T>
 __global__ void __launch_bounds__(kBlock)
 sketch4_kernel(const T* __restrict__ W1, const T* __restrict__ b1, const float* __restrict__ lo,
                const float* __restrict__ hi, int64_t d, int ng, int8_t* __restrict__ Q, uint8_t* __restrict__ Q4,
-               uint8_t* __restrict__ M4, float* __restrict__ tlo, float* __restrict__ thi) {
+               uint8_t* __restrict__ M4, float* __restrict__ tlo, float* __restrict__ thi, int qmax, float margin) {
     extern __shared__ int gval[];                    // group maxima (bit patterns), then multipliers
     __shared__ float red[kBlock / TD_WAVE];
     const int64_t j = blockIdx.x;
@@ -179,13 +195,13 @@ sketch4_kernel(const T* __restrict__ W1, const T* __restrict__ b1, const float* 
     r = red[0];
 #pragma unroll
     for (int w = 1; w < kBlock / TD_WAVE; ++w) r = fmaxf(r, red[w]);
-    const double s = (double)r / 105.0;
+    const double s = (double)r / (double)(qmax * 15);   // (4 bits: 7 * 15)
     const double bj = b1 ? (double)td_load<T>(b1 + j) : 0.0;
     const bool live = r > 0.0f;
     for (int g = threadIdx.x; g < ng; g += kBlock) {
         int m = 1;
         if (live) {
-            const double t = ceil((double)__int_as_float(gval[g]) / (7.0 * s));
+            const double t = ceil((double)__int_as_float(gval[g]) / ((double)qmax * s));
             m = (int)fmin(fmax(t, 1.0), 15.0);
         }
         gval[g] = m;
@@ -195,7 +211,7 @@ sketch4_kernel(const T* __restrict__ W1, const T* __restrict__ b1, const float* 
     auto code = [&](int64_t k) -> int {              // 4-bit code of column k
         if (!live) return 0;
         const double q = rint((double)td_load<T>(row + k) / ((double)gval[k >> 5] * s));
-        return (int)fmin(fmax(q, -7.0), 7.0);
+        return (int)fmin(fmax(q, -(double)qmax), (double)qmax);
     };
     if (Q4) {   // d is a multiple of 32 here
         uint32_t* out = reinterpret_cast<uint32_t*>(Q4 + j * (d / 2));
@@ -218,11 +234,13 @@ sketch4_kernel(const T* __restrict__ W1, const T* __restrict__ b1, const float* 
         for (int64_t k = threadIdx.x; k < d; k += kBlock) Q[j * d + k] = (int8_t)(gval[k >> 5] * code(k));
     }
     if (threadIdx.x == 0) {
+        double rl, rh;
+        predictor_range((double)lo[j], (double)hi[j], (double)margin, rl, rh);
         if (live) {
-            tlo[j] = (float)(((double)lo[j] - bj) / s);
-            thi[j] = (float)(((double)hi[j] - bj) / s);
+            tlo[j] = (float)((rl - bj) / s);
+            thi[j] = (float)((rh - bj) / s);
         } else {
-            const bool inside = ((double)lo[j] <= bj) && (bj < (double)hi[j]);
+            const bool inside = (rl <= bj) && (bj < rh);
             tlo[j] = inside ? -INFINITY : INFINITY;
             thi[j] = INFINITY;
         }
@@ -754,29 +772,30 @@ tardis_status_t td_transpose(const void* src, void* dst, int64_t rows, int64_t c
 }
 
 tardis_status_t td_build_sketch(const void* W1, const void* b1, const float* lo, const float* hi, int64_t h,
-                                int64_t d, int32_t dtype, int32_t bits, int8_t* Q, uint8_t* Q4, uint8_t* M4,
-                                float* tlo, float* thi, hipStream_t s) {
-    if (bits == 4) {
+                                int64_t d, int32_t dtype, int32_t bits, float margin, int8_t* Q, uint8_t* Q4,
+                                uint8_t* M4, float* tlo, float* thi, hipStream_t s) {
+    if (bits == 4 || bits == 3 || bits == 2) {
+        const int qmax = (1 << (bits - 1)) - 1;
         const int64_t ng = (d + 31) / 32;
         if (!M4 || (Q4 && d % 32 != 0) || ng * 4 > 64 * 1024) return TARDIS_ERR_SHAPE;
         if (dtype == TARDIS_BF16)
             hipLaunchKernelGGL(sketch4_kernel<bf16_t>, dim3((unsigned)h), dim3(kBlock), (size_t)ng * 4, s,
                                static_cast<const bf16_t*>(W1), static_cast<const bf16_t*>(b1), lo, hi, d, (int)ng,
-                               Q, Q4, M4, tlo, thi);
+                               Q, Q4, M4, tlo, thi, qmax, margin);
         else
             hipLaunchKernelGGL(sketch4_kernel<float>, dim3((unsigned)h), dim3(kBlock), (size_t)ng * 4, s,
                                static_cast<const float*>(W1), static_cast<const float*>(b1), lo, hi, d, (int)ng,
-                               Q, Q4, M4, tlo, thi);
+                               Q, Q4, M4, tlo, thi, qmax, margin);
         TD_HIP(hipGetLastError());
         return TARDIS_OK;
     }
     if (bits != 8 || !Q) return TARDIS_ERR_INVALID_ARG;
     if (dtype == TARDIS_BF16)
         hipLaunchKernelGGL(sketch_kernel<bf16_t>, dim3((unsigned)h), dim3(kBlock), 0, s,
-                           static_cast<const bf16_t*>(W1), static_cast<const bf16_t*>(b1), lo, hi, d, Q, tlo, thi);
+                           static_cast<const bf16_t*>(W1), static_cast<const bf16_t*>(b1), lo, hi, d, Q, tlo, thi, margin);
     else
         hipLaunchKernelGGL(sketch_kernel<float>, dim3((unsigned)h), dim3(kBlock), 0, s,
-                           static_cast<const float*>(W1), static_cast<const float*>(b1), lo, hi, d, Q, tlo, thi);
+                           static_cast<const float*>(W1), static_cast<const float*>(b1), lo, hi, d, Q, tlo, thi, margin);
     TD_HIP(hipGetLastError());
     return TARDIS_OK;
 }

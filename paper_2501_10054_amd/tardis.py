@@ -42,7 +42,7 @@ class tardis_ffn_desc(C.Structure):
 
 class tardis_fold_opts(C.Structure):
     _fields_ = [("sketch_bits", C.c_int32), ("folded_dtype", C.c_int32), ("max_batch", C.c_int64),
-                ("deterministic", C.c_int32), ("reserved", C.c_int32)]
+                ("deterministic", C.c_int32), ("margin", C.c_float)]
 
 
 _lib_handle = None
@@ -184,10 +184,10 @@ class Layer:
 
 
 def tardis_fold(ffn: FFN, lo, hi, a, c, max_batch: int = 1, sketch_bits: int = 8, deterministic: bool = False,
-                stream=None) -> Layer:
+                margin: float = 0.0, stream=None) -> Layer:
     for t in (lo, hi, a, c):
         assert t.is_cuda and t.is_contiguous() and t.dtype == torch.float32 and t.numel() == ffn.h
-    opts = tardis_fold_opts(sketch_bits, ffn.dtype, max_batch, 1 if deterministic else 0, 0)
+    opts = tardis_fold_opts(sketch_bits, ffn.dtype, max_batch, 1 if deterministic else 0, float(margin))
     handle = C.c_void_p()
     st = lib().tardis_fold(C.byref(ffn.desc), _ptr(lo), _ptr(hi), _ptr(a), _ptr(c), C.byref(opts),
                            _stream(stream), C.byref(handle))

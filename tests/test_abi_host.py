@@ -61,7 +61,11 @@ def test_fold_rejects_bad_arguments_without_a_gpu():
     assert fold(_desc(dtype=7)) == T.ERR_DTYPE
     assert fold(_desc(act=9)) == T.ERR_INVALID_ARG
     assert fold(_desc(), lo=None) == T.ERR_INVALID_ARG
-    assert fold(_desc(), opts=T.tardis_fold_opts(2, T.F32, 1, 0, 0)) == T.ERR_INVALID_ARG       # 8 and 4 only
+    assert fold(_desc(), opts=T.tardis_fold_opts(5, T.F32, 1, 0, 0)) == T.ERR_INVALID_ARG       # 8, 4, 3, 2 only
+    assert fold(_desc(), opts=T.tardis_fold_opts(1, T.F32, 1, 0, 0)) == T.ERR_INVALID_ARG
+    assert fold(_desc(), opts=T.tardis_fold_opts(4, T.F32, 1, 0, 0.5)) == T.ERR_INVALID_ARG     # margin in [0, 0.5)
+    assert fold(_desc(), opts=T.tardis_fold_opts(4, T.F32, 1, 0, -0.1)) == T.ERR_INVALID_ARG
+    assert fold(_desc(), opts=T.tardis_fold_opts(4, T.F32, 1, 0, float('nan'))) == T.ERR_INVALID_ARG
     assert fold(_desc(), opts=T.tardis_fold_opts(16, T.F32, 1, 0, 0)) == T.ERR_INVALID_ARG
     assert fold(_desc(), opts=T.tardis_fold_opts(8, T.BF16, 1, 0, 0)) == T.ERR_DTYPE
     assert fold(_desc(), opts=T.tardis_fold_opts(8, T.F32, 0, 0, 0)) == T.ERR_SHAPE

@@ -473,6 +473,38 @@ def test_sketch4_tiny_fp32_and_ragged_groups():
              synth.make_tokens(6, 50, "f32", seed, synth.STREAM_TEST), 0.9, sketch_bits=4, batched=True)
 
 
+@pytest.mark.parametrize("bits,margin", [(3, 0.0), (2, 0.0), (4, 0.1), (2, 0.2), (8, 0.15)])
+def test_narrow_sketches_and_predictor_margin(bits, margin):
+    """Codes of 3 and 2 bits (largest code 3 and 1) and the margin that narrows the range the
+    predictor tests against: codes, multipliers, bounds and masks bit for bit, y to the bar, on a
+    bf16 layer through the single-launch kernel, a group, a pass of tokens and the prompt path."""
+    w = synth.decode(d=2048, h=1536, n_cal=512, n_test=70, coverage=0.9)
+    lay = w.layer
+    ffn = make_ffn(lay)
+    lo, hi, a, c = T.tardis_calibrate(ffn, dev(w.X_cal, "bf16"), 0.9)
+    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=70, sketch_bits=bits, margin=margin)
+    F = O.build(lay.W1, None, lay.W2, None, *(t.cpu().numpy() for t in (lo, hi, a, c)), sketch_bits=bits, margin=margin)
+    Q, tlo, thi = T.tardis_get_predictor_state(L)
+    np.testing.assert_array_equal(Q.cpu().numpy(), F.sk.Q)
+    np.testing.assert_array_equal(tlo.cpu().numpy(), F.sk.tlo)
+    np.testing.assert_array_equal(thi.cpu().numpy(), F.sk.thi)
+    if bits < 8:
+        np.testing.assert_array_equal(T.tardis_get_sketch_groups(L).cpu().numpy(), F.sk.m)
+        assert int(np.abs(F.sk.q4).max()) == 2 ** (bits - 1) - 1
+    Yo, FLo = O.forward(F, w.X_test)
+    Xd = dev(w.X_test, "bf16")
+    for n in (1, 6, 40, 70):
+        Y = T.tardis_ffn_forward_batched(L, Xd[:n].contiguous())
+        mask, _, _ = T.tardis_get_last_outliers(L, n, want_list=False)
+        np.testing.assert_array_equal(unpack_mask(mask, lay.h), FLo[:n])
+        assert_y_close(host(Y), Yo[:n], F, w.X_test[:n], FLo[:n])
+    if margin > 0:      # the narrowed test flags a superset of what the plain one flags
+        F0 = O.build(lay.W1, None, lay.W2, None, *(t.cpu().numpy() for t in (lo, hi, a, c)), sketch_bits=bits)
+        _, FL0 = O.forward(F0, w.X_test[:8])
+        assert (FLo[:8] | FL0).sum() == FLo[:8].sum() and FLo[:8].sum() > FL0.sum()
+    L.close()
+
+
 def test_sketch4_zero_rows_and_zero_groups():
     seed = synth.workload_seed(9, 12)
     layer = custom_layer(96, 64, "f32", seed, w1_std=0.3, bias=True)

@@ -504,6 +504,33 @@ def test_calibrate_search_covers_and_fits():
     assert (((hi > qhi) & (lo > qlo)) | ((hi < qhi) & (lo < qlo))).mean() > 0.8
 
 
+def test_predictor_margin_narrows_the_tested_range_by_hand():
+    # one neuron, weights (1, -2, 4): 8-bit scale s = 4/127; range [-1, 3), margin 0.25 of its width 4:
+    # the predictor tests against [0, 2): bounds 0/s and 2/s in code units
+    W1 = np.array([[1.0, -2.0, 4.0]])
+    lo, hi = np.array([-1.0], np.float32), np.array([3.0], np.float32)
+    sk0 = O.sketch(W1, None, lo, hi, 8)
+    sk = O.sketch(W1, None, lo, hi, 8, margin=0.25)
+    s = 4.0 / 127.0
+    assert sk0.tlo[0] == np.float32(-1.0 / s) and sk0.thi[0] == np.float32(3.0 / s)
+    assert sk.tlo[0] == np.float32(0.0 / s) and sk.thi[0] == np.float32(2.0 / s)
+    np.testing.assert_array_equal(sk.Q, sk0.Q)                     # the codes do not depend on the margin
+    # more flags, never fewer; an empty or infinite range is left alone
+    rng, (W1, b1, W2, b2), (lo, hi, a, c), F = _small_folded(seed=21)
+    X = rng.normal(size=(40, F.d)) * 1.5
+    base = np.array([O.predict(O.sketch(W1, b1, lo, hi, 4), x) for x in X])
+    wide = np.array([O.predict(O.sketch(W1, b1, lo, hi, 4, margin=0.1), x) for x in X])
+    assert (wide | base).sum() == wide.sum() and wide.sum() > base.sum()
+    z = X @ W1.T + b1
+    truth = ~((z >= lo) & (z < hi))
+    recall = lambda f: (f & truth).sum() / truth.sum()
+    assert recall(wide) >= recall(base)
+    e = O.sketch(W1, b1, lo, lo, 8, margin=0.2)
+    np.testing.assert_array_equal(e.tlo, O.sketch(W1, b1, lo, lo, 8).tlo)
+    inf = O.sketch(W1, b1, np.full_like(lo, -np.inf), hi, 8, margin=0.2)
+    np.testing.assert_array_equal(inf.thi, O.sketch(W1, b1, np.full_like(lo, -np.inf), hi, 8).thi)
+
+
 # --------------------------------------------------------- adaptive thresholding
 def test_neuron_errors_against_the_error_metric_written_out():
     """err_n(x) as the section defines it - the L2 distance between the neuron's exact and
