@@ -338,6 +338,68 @@ def fold(W1, b1, W2, b2, a, c):
 
 
 # ---------------------------------------------------------------------------
+# 8-bit floating-point storage of the folded matrix  (Sec. "Discussion": the
+# method composes with weight compression; here the compressed thing is W')
+# ---------------------------------------------------------------------------
+def e4m3_values():
+    """The 254 finite values of the 8-bit float with 4 exponent bits (bias 7) and 3
+    mantissa bits, no infinities, one NaN pattern per sign (S.1111.111): byte b has
+    sign b >> 7, exponent field e = (b >> 3) & 15, mantissa m = b & 7 and the value
+    (-1)^s 2^(e-7) (1 + m/8) for e >= 1, (-1)^s 2^(-6) m/8 for e = 0.  Largest: 448.
+    Returns fp64[256] indexed by the byte (NaN at 0x7F and 0xFF)."""
+    out = np.empty(256)
+    for b in range(256):
+        sgn = -1.0 if b & 0x80 else 1.0
+        e, m = (b >> 3) & 15, b & 7
+        if e == 15 and m == 7:
+            out[b] = np.nan
+        elif e == 0:
+            out[b] = sgn * 2.0 ** -6 * (m / 8.0)
+        else:
+            out[b] = sgn * 2.0 ** (e - 7) * (1.0 + m / 8.0)
+    return out
+
+
+def round_e4m3(x):
+    """Nearest e4m3 value of every element (ties to the even mantissa), magnitudes
+    above 448 saturate to 448.  Returns (codes uint8, values fp64)."""
+    x = _f64(x)
+    tab = e4m3_values()[:127]                      # non-negative finite values, ascending with the byte
+    mag = np.minimum(np.abs(x), 448.0)
+    hi = np.searchsorted(tab, mag, side="left").clip(1, 126)
+    lo = hi - 1
+    dlo, dhi = mag - tab[lo], tab[hi] - mag
+    pick_hi = (dhi < dlo) | ((dhi == dlo) & (hi % 2 == 0))      # even byte = even mantissa bit
+    code = np.where(pick_hi, hi, lo).astype(np.uint8)
+    code = np.where(mag == 0.0, 0, code).astype(np.uint8)
+    neg = np.signbit(x) & (code != 0)
+    val = np.where(neg, -tab[code], tab[code])
+    return (code | (neg.astype(np.uint8) << 7)).astype(np.uint8), val
+
+
+def fp8_rows(Wp):
+    """W' as stored with 8-bit floats: every row i gets a power-of-two scale 2^e_i, the
+    smallest with max_k |W'_ik| / 2^e_i <= 448, and its elements are rounded to
+    e4m3 in that scale.  A power of two, so that the stored value code * 2^e_i is
+    also a bfloat16 number and every path of the library multiplies the same
+    matrix.  Returns (values fp64 d x d, codes uint8 d x d, exponents int d)."""
+    Wp = _f64(Wp)
+    mx = np.abs(Wp).max(axis=1)
+    e = np.zeros(Wp.shape[0], np.int64)
+    nz = mx > 0.0
+    e[nz] = np.ceil(np.log2(mx[nz] / 448.0)).astype(np.int64)
+    # log2 may land a hair on the wrong side of an exact power of two: fix up by the definition
+    for i in np.flatnonzero(nz):
+        while mx[i] / 2.0 ** e[i] > 448.0:
+            e[i] += 1
+        while mx[i] / 2.0 ** (e[i] - 1) <= 448.0:
+            e[i] -= 1
+    scale = 2.0 ** e.astype(np.float64)
+    code, val = round_e4m3(Wp / scale[:, None])
+    return val * scale[:, None], code, e
+
+
+# ---------------------------------------------------------------------------
 # predictor  (Sec. "Predictor Generation": a quantised copy of W1 that is just
 # good enough to tell which neurons leave their range)
 # ---------------------------------------------------------------------------

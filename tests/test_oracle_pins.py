@@ -531,6 +531,52 @@ def test_predictor_margin_narrows_the_tested_range_by_hand():
     np.testing.assert_array_equal(inf.thi, O.sketch(W1, b1, np.full_like(lo, -np.inf), hi, 8).thi)
 
 
+# ------------------------------------------------------------ 8-bit float storage
+def test_e4m3_table_and_rounding_by_hand():
+    tab = O.e4m3_values()
+    # landmarks of the format: 1.0 = 0.0111.000, largest 448 = 0.1111.110, smallest 2^-9, one NaN per sign
+    assert tab[0x38] == 1.0 and tab[0x7E] == 448.0 and tab[0x01] == 2.0 ** -9 and tab[0x08] == 2.0 ** -6
+    assert tab[0xB8] == -1.0 and np.isnan(tab[0x7F]) and np.isnan(tab[0xFF]) and np.isfinite(tab).sum() == 254
+    assert (np.diff(tab[:127]) > 0).all()
+    # the same numbers from a library's float8 type
+    import torch
+    t8 = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    np.testing.assert_array_equal(np.nan_to_num(t8, nan=-7.0), np.nan_to_num(tab, nan=-7.0))
+    # rounding by hand: between 1.0 and 1.125 the tie 1.0625 goes to the even mantissa (1.0);
+    # between 1.125 and 1.25 the tie 1.1875 goes to 1.25; saturation; signs; subnormals (steps of 2^-9)
+    code, val = O.round_e4m3(np.array([1.0625, 1.1875, 1.07, 500.0, -500.0, -0.3, 0.0, 2.0 ** -10, 3 * 2.0 ** -10, 1e-9]))
+    np.testing.assert_array_equal(val, [1.0, 1.25, 1.125, 448.0, -448.0, -0.3125, 0.0, 0.0, 2.0 ** -8, 0.0])
+    assert code[0] == 0x38 and code[3] == 0x7E and code[4] == 0xFE and code[6] == 0
+    # against the library's conversion on random values (it rounds to nearest even as well)
+    rng = np.random.default_rng(51)
+    x = np.concatenate([rng.normal(size=4000) * 50, rng.normal(size=2000) * 0.01, rng.uniform(-448, 448, 2000)])
+    x = x.astype(np.float32).astype(np.float64)
+    ref = torch.from_numpy(x).to(torch.float32).clamp(-448, 448).to(torch.float8_e4m3fn).to(torch.float64).numpy()
+    np.testing.assert_array_equal(O.round_e4m3(x)[1], ref)
+
+
+def test_fp8_rows_scale_is_the_smallest_power_of_two_and_values_are_bf16():
+    rng = np.random.default_rng(52)
+    W = rng.normal(size=(9, 40)) * np.array([1e-3, 0.02, 0.5, 1.0, 7.0, 448.0, 449.0, 1e4, 0.0])[:, None]
+    W[5] = np.clip(W[5], -448, 448); W[5, 0] = 448.0            # exactly at the top: scale 2^0
+    val, code, e = O.fp8_rows(W)
+    for i in range(9):
+        mx = np.abs(W[i]).max()
+        if mx == 0:
+            assert e[i] == 0 and (val[i] == 0).all()
+            continue
+        assert mx / 2.0 ** e[i] <= 448.0 < mx / 2.0 ** (e[i] - 1)
+        assert np.abs(val[i] - W[i]).max() <= 2.0 ** -4 * np.abs(W[i]).max()     # half a unit in the last place at most 2^-4 of the value (3 mantissa bits), up to the row's top
+        np.testing.assert_array_equal(O.to_bf16(val[i]), val[i])               # representable as bfloat16
+        np.testing.assert_array_equal(O.e4m3_values()[code[i]] * 2.0 ** e[i], val[i])
+    assert e[5] == 0 and e[6] == 1
+    # relative error of the stored matrix: the budget quoted for this storage (3 mantissa bits)
+    Wn = rng.normal(size=(64, 512))
+    v, _, _ = O.fp8_rows(Wn)
+    rel = np.linalg.norm(v - Wn) / np.linalg.norm(Wn)
+    assert 0.015 < rel < 0.04
+
+
 # --------------------------------------------------------- adaptive thresholding
 def test_neuron_errors_against_the_error_metric_written_out():
     """err_n(x) as the section defines it - the L2 distance between the neuron's exact and
