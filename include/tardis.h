@@ -69,7 +69,8 @@ typedef enum {
 
 typedef enum {
     TARDIS_F32 = 0,
-    TARDIS_BF16 = 1
+    TARDIS_BF16 = 1,
+    TARDIS_FP8_E4M3 = 2 /* storage of the folded matrix only (tardis_fold_opts.folded_dtype) */
 } tardis_dtype_t;
 
 /* One FFN layer (Sec. "Opportunity": FFN(x) = sigma(x W1) W2, here transposed
@@ -89,7 +90,16 @@ typedef struct {
 
 typedef struct {
     int32_t sketch_bits;   /* predictor code width: 8, or 4, 3, 2 (grouped, see tardis_fold) */
-    int32_t folded_dtype;  /* storage of W'; must equal desc.dtype */
+    int32_t folded_dtype;  /* storage of W': desc.dtype, or for a bf16 layer TARDIS_FP8_E4M3 (Sec. "Discussion":
+                              the method composes with weight compression): every row of W' gets the
+                              smallest power-of-two scale 2^e with max|row| / 2^e <= 448 and its elements
+                              are rounded to 8-bit floats (1 sign, 4 exponent bits with bias 7, 3 mantissa
+                              bits, no infinities; ties to even) in that scale.  One- and two-token calls
+                              stream the 8-bit rows (half the bytes of W'); every other path multiplies a
+                              bf16 copy holding the same numbers.  Three mantissa bits move an element by
+                              up to 2^-4 of itself: y is then about 3e-2 (relative L2) away from the exact
+                              folded result - outside the 1e-2 this library otherwise keeps, which is
+                              why it is an option */
     int64_t max_batch;     /* largest n accepted by the batched online calls (1 .. 4096; longer prompts are
                               the caller's to cut); from 65 on the layer
                               also holds scratch for the prompt path, about n * (5 d + 10 h) bytes */

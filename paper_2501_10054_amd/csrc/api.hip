@@ -57,7 +57,7 @@ int env_int(const char* name, int fallback, int lo, int hi) {
 
 void free_layer(tardis_layer_s* L) {
     if (!L) return;
-    void* owned[] = {L->W2T, L->W2, L->Wp, L->bp, L->Q, L->Q4, L->M4, L->tlo, L->thi, L->a, L->c,
+    void* owned[] = {L->W2T, L->W2, L->Wp, L->Wp8, L->wp8_scale, L->bp, L->Q, L->Q4, L->M4, L->tlo, L->thi, L->a, L->c,
                      L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix, L->fx_bound, L->zeros_h, L->xnext, L->rec_count, L->rec_jb, L->rec_tb, L->rec_delta, L->pf_scratch,
                      L->bt_xq, L->bt_e, L->bt_tokmask, L->bt_ulist, L->bt_ucount, L->bt_delta, L->bt_partial};
     for (void* p : owned)
@@ -164,7 +164,11 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     TD_TRY(td_transpose(desc->W2, L->W2T, d, h, desc->dtype, s));
     TD_TRY(td_build_sketch(desc->W1, desc->b1, lo, hi, h, d, desc->dtype, L->sketch_bits, L->margin, L->Q, L->Q4, L->M4, L->tlo,
                            L->thi, s));
-    TD_TRY(td_fold(desc, L->a, L->c, L->Wp, L->bp, s));
+    if (opts && opts->folded_dtype == TARDIS_FP8_E4M3) {
+        TD_TRY(dev_alloc(&L->Wp8, (size_t)d * d));
+        TD_TRY(dev_alloc(&L->wp8_scale, (size_t)d * 4));
+    }
+    TD_TRY(td_fold(desc, L->a, L->c, L->Wp, L->bp, L->Wp8, L->wp8_scale, s));
     if (L->fx) {
         TD_TRY(dev_alloc(&L->fx_bound, 8));
         TD_TRY(td_fx_bounds(L, L->fx_bound, s));
@@ -253,7 +257,9 @@ tardis_status_t tardis_fold(const tardis_ffn_desc* desc, const float* lo, const 
         if (opts->sketch_bits != 8 && opts->sketch_bits != 4 && opts->sketch_bits != 3 && opts->sketch_bits != 2)
             return TARDIS_ERR_INVALID_ARG;
         if (!(opts->margin >= 0.0f) || !(opts->margin < 0.5f)) return TARDIS_ERR_INVALID_ARG;
-        if (opts->folded_dtype != desc->dtype) return TARDIS_ERR_DTYPE;
+        if (opts->folded_dtype != desc->dtype &&
+            !(opts->folded_dtype == TARDIS_FP8_E4M3 && desc->dtype == TARDIS_BF16))
+            return TARDIS_ERR_DTYPE;
         if (opts->max_batch < 1 || opts->max_batch > kMaxBatch) return TARDIS_ERR_SHAPE;
         if (opts->deterministic != 0 && opts->deterministic != 1) return TARDIS_ERR_INVALID_ARG;
     }

@@ -57,6 +57,8 @@ struct tardis_layer_s {
     void* W2T;     // h x d, neuron-major copy of W2
     void* W2;      // d x h, copy of W2 as given (dense baseline)
     void* Wp;      // d x d folded matrix
+    uint8_t* Wp8;      // d x d e4m3 codes of the folded matrix (8-bit storage only, else null): Wp = code * scale
+    float* wp8_scale;  // d power-of-two row scales of Wp8
     float* bp;     // d folded bias
     int8_t* Q;     // h x d predictor codes, one byte each (absent when only the packed 4-bit form is kept)
     uint8_t* Q4;   // packed 4-bit sketch, h x d/2 bytes: one 16-byte vector per group of 32 columns (or null)
@@ -199,8 +201,10 @@ tardis_status_t td_build_sketch(const void* W1, const void* b1, const float* lo,
 // one-byte effective codes (multiplier * 4-bit code) from the packed 4-bit sketch
 tardis_status_t td_unpack_sketch4(const uint8_t* Q4, const uint8_t* M4, int64_t h, int64_t d, int8_t* Q,
                                   hipStream_t s);
+// Wp8 / wp8_scale non-null (bf16 layers): W' is stored as e4m3 codes with a power-of-two scale per row, and Wp
+// receives the same values as bf16
 tardis_status_t td_fold(const tardis_ffn_desc* desc, const float* a, const float* c, void* Wp, float* bp,
-                        hipStream_t s);
+                        uint8_t* Wp8, float* wp8_scale, hipStream_t s);
 // step > 0: greedy range search with that increment; step <= 0: central quantile ranges
 tardis_status_t td_calibrate(const tardis_ffn_desc* desc, const void* X, int64_t n, float coverage,
                              const float* cov_pn, float step, float* lo, float* hi, float* a, float* c,

@@ -49,6 +49,23 @@ __device__ __forceinline__ td_f32x4 load_coherent4(const float* p) {
     return v;
 }
 
+// acc + sum over 16 columns of w (sixteen e4m3 bytes) * x (sixteen bf16 in xa, xb), fp32
+typedef float td_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot_e4m3_bf16(const td_u32x4& w, const td_u32x4& xa, const td_u32x4& xb, float acc) {
+    const uint32_t wq[4] = {w.x, w.y, w.z, w.w};
+    const uint32_t xq[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {   // dword q: columns 4q .. 4q+3
+        const td_f32x2 f01 = __builtin_amdgcn_cvt_pk_f32_fp8((int)wq[q], false);
+        const td_f32x2 f23 = __builtin_amdgcn_cvt_pk_f32_fp8((int)wq[q], true);
+        acc = fmaf(f01.x, __uint_as_float(xq[2 * q] << 16), acc);
+        acc = fmaf(f01.y, __uint_as_float(xq[2 * q] & 0xFFFF0000u), acc);
+        acc = fmaf(f23.x, __uint_as_float(xq[2 * q + 1] << 16), acc);
+        acc = fmaf(f23.y, __uint_as_float(xq[2 * q + 1] & 0xFFFF0000u), acc);
+    }
+    return acc;
+}
+
 // 16-byte vectors it*64 + lane, it = 0..N-1, of one row (N*64 vectors long)
 template <int N>
 __device__ __forceinline__ void load_row(td_u32x4 (&dst)[N], const void* row, int lane) {
@@ -149,7 +166,11 @@ __device__ __forceinline__ void warm_rows(const unsigned char* __restrict__ p, i
 // so the result does not depend on the order in which blocks finish (bit-identical from run to
 // run), and the thread whose add completes a column's count holds that column's finished sum and
 // writes y itself - no completion counter and no assembling block on the way out.
-template <int D, int BLOCK, int RQ, int TB, int SK, bool DEFER, int NG, bool FX>
+//
+// WP8 = true (one kernel, fp32 accumulators only): the block's rows of W' are read in their 8-bit
+// floating-point form (e4m3 codes, a power-of-two scale per row) - half the bytes of the bf16 rows;
+// the values are the same numbers the bf16 copy of the matrix holds.
+template <int D, int BLOCK, int RQ, int TB, int SK, bool DEFER, int NG, bool FX, bool WP8>
 __global__ void __launch_bounds__(BLOCK)
 decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp, const int8_t* __restrict__ Q,
                     const uint8_t* __restrict__ M4, const float* __restrict__ tlo, const float* __restrict__ thi, const bf16_t* __restrict__ W1,
@@ -158,7 +179,8 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                     float* __restrict__ yfold, float* __restrict__ yfix, int copies, uint32_t* __restrict__ mask,
                     int mask_words, int32_t* __restrict__ done, int h, int npb, int rpb, int act, int norm_out,
                     float eps, DeferOut rec, int n_act, const unsigned char* __restrict__ pf_rows, int pf_bytes,
-                    const float* __restrict__ fx_bound, int32_t* __restrict__ fx_exp, int strict_release) {
+                    const float* __restrict__ fx_bound, int32_t* __restrict__ fx_exp, int strict_release,
+                    const uint8_t* __restrict__ Wp8, const float* __restrict__ wp8_scale) {
     // n_act <= TB tokens are real: the remaining slots of the group repeat the last real token and
     // none of their results reaches the caller's buffers
     static_assert(D % 1024 == 0, "rows must be whole multiples of 64 lanes x 16 bytes");
@@ -168,6 +190,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     static_assert(NG == 0 || (SK == 8 && (TB == 8 || TB == 16) && DEFER && (BLOCK / TD_WAVE) % NG == 0),
                   "matrix-core predictor");
     static_assert(TB < 16 || NG > 0, "sixteen tokens only with the matrix-core predictor");
+    static_assert(!WP8 || (!DEFER && !FX && TB <= 2), "8-bit W' rows: one- and two-token launches with fp32 accumulators");
     constexpr int NW = BLOCK / TD_WAVE;
     constexpr int KQ = NW / (NG > 0 ? NG : 1);       // wavefronts sharing a group of 16 rows
     constexpr int KS = D / KQ;                       // columns of one wavefront's slice
@@ -438,18 +461,20 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     };
     const int r0 = blk * rpb;
     const int rn = min(rpb, D - r0);                 // W' rows owned (may be <= 0)
-    td_u32x4 wp[IW];
+    constexpr int IWP = WP8 ? IW / 2 : IW;           // per-lane vectors of one row of W' as stored
+    td_u32x4 wp[IWP > 0 ? IWP : 1];
     // one kernel: wavefront w holds row r0 + w whole.  Deferred path: the block's (up to 16) rows are one
     // matrix-core tile, wavefront w holds columns [w*KW, (w+1)*KW) of all of them - lane: row lane % 16,
     // 16 bytes at step it, k-group lane / 16 - so the tokens are read from LDS once per block, not per row
     const td_u32x4* wp_row =
         DEFER ? reinterpret_cast<const td_u32x4*>(Wp + (size_t)min(r0 + (lane & 15), D - 1) * D + wave * KW) + (lane >> 4)
+        : WP8 ? reinterpret_cast<const td_u32x4*>(Wp8 + (size_t)min(r0 + wave, D - 1) * D) + lane
               : reinterpret_cast<const td_u32x4*>(Wp + (size_t)min(r0 + wave, D - 1) * D) + lane;
     constexpr int WSTEP = DEFER ? 4 : TD_WAVE;       // vectors between a lane's consecutive loads
     const float bias_own = DEFER ? bp[min(r0 + tid / TB, D - 1)] : 0.0f;   // thread (row, token) of the final sum
     // first half of this wave's W' row: requested before the block meets at the barrier, so that
     // the memory pipe stays busy while the flagged list is assembled
-    constexpr int IWA = IW / 2;
+    constexpr int IWA = IWP / 2;
 #pragma unroll
     for (int it = 0; it < IWA; ++it) wp[it] = td_load_stream16(wp_row + it * WSTEP);
 
@@ -554,7 +579,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
         }
         if (nf == 0) {
 #pragma unroll
-            for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * WSTEP);
+            for (int it = IWA; it < IWP; ++it) wp[it] = td_load_stream16(wp_row + it * WSTEP);
         }
         for (int f0 = 0; f0 < nf; f0 += NW) {
             asm volatile("" ::: "memory");
@@ -574,7 +599,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
             if (f0 == 0) {   // the rest of this wave's W' row streams in behind the first batch of W1 rows
                 asm volatile("" ::: "memory");
 #pragma unroll
-                for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * WSTEP);
+                for (int it = IWA; it < IWP; ++it) wp[it] = td_load_stream16(wp_row + it * WSTEP);
             }
             asm volatile("" : "+v"(bj_raw), "+v"(aj), "+v"(cj));
             if (fixer) {
@@ -662,7 +687,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
         if (kFirst) {
             asm volatile("" ::: "memory");
 #pragma unroll
-            for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * WSTEP);
+            for (int it = IWA; it < IWP; ++it) wp[it] = td_load_stream16(wp_row + it * WSTEP);
         }
         // nothing above may wait for a load: the conversion of b1 is pinned below this point
         asm volatile("" : "+v"(bj_raw), "+v"(aj), "+v"(cj));
@@ -697,7 +722,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     };
     if (nf == 0) {
 #pragma unroll
-        for (int it = IWA; it < IW; ++it) wp[it] = td_load_stream16(wp_row + it * WSTEP);
+        for (int it = IWA; it < IWP; ++it) wp[it] = td_load_stream16(wp_row + it * WSTEP);
     } else {
         repair_pass(std::true_type{}, 0);
         for (int f0 = FCH; f0 < nf; f0 += FCH) repair_pass(std::false_type{}, f0);
@@ -731,7 +756,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                     before[t][u] = FxAcc::add(acc64 + (size_t)t * D + ctid + u * BLOCK, FxAcc::encode(yacc[t][u], fxe[t]));
         for (int ri = wave; ri < rn; ri += NW) {
             asm volatile("" ::: "memory");
-            if (ri != wave) load_row<IW>(wp, Wp + (size_t)(r0 + ri) * D, lane);
+            if (ri != wave) load_row<IWP>(wp, Wp + (size_t)(r0 + ri) * D, lane);
             const float bias = ri == wave ? bias_out : bp[r0 + ri];
 #pragma unroll
             for (int t = 0; t < TB; ++t) {
@@ -827,15 +852,28 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     // ---- speculative product rows (the first one from the registers loaded above)
     for (int ri = wave; ri < rn; ri += NW) {
         asm volatile("" ::: "memory");
-        if (ri != wave) load_row<IW>(wp, Wp + (size_t)(r0 + ri) * D, lane);
+        if (ri != wave) {
+            if constexpr (WP8) load_row<IWP>(wp, Wp8 + (size_t)(r0 + ri) * D, lane);
+            else load_row<IWP>(wp, Wp + (size_t)(r0 + ri) * D, lane);
+        }
         const float bias = ri == wave ? bias_out : bp[r0 + ri];
+        float row_scale = 1.0f;
+        if constexpr (WP8) row_scale = wp8_scale[r0 + ri];
 #pragma unroll
         for (int t = 0; t < TB; ++t) {
             if (TB > 1) asm volatile("" ::: "memory");
             float s = 0.0f;
+            if constexpr (WP8) {
+                // vector it*64 + lane of the 8-bit row = 16 columns = two 16-byte vectors of the token
+                const td_u32x4* xt = reinterpret_cast<const td_u32x4*>(xs + (size_t)t * XSP) + 2 * lane;
 #pragma unroll
-            for (int it = 0; it < IW; ++it) s = RowVec<bf16_t>::dot(wp[it], xsv(t, it), s);
-            s = td_wave_sum(s);
+                for (int it = 0; it < IWP; ++it) s = dot_e4m3_bf16(wp[it], xt[it * 2 * TD_WAVE], xt[it * 2 * TD_WAVE + 1], s);
+                s = td_wave_sum(s) * row_scale;
+            } else {
+#pragma unroll
+                for (int it = 0; it < IWP; ++it) s = RowVec<bf16_t>::dot(wp[it], xsv(t, it), s);
+                s = td_wave_sum(s);
+            }
             // written through to memory so that the finishing block, on any XCD, reads it
             if (lane == 0)
                 __hip_atomic_store(yfold + (size_t)t * D + r0 + ri, s + bias, __ATOMIC_RELAXED,
@@ -1272,7 +1310,7 @@ mask_union_kernel(const uint32_t* __restrict__ mask, int words, int n, uint32_t*
 
 constexpr int kFxExpAt = 40;   // where, among the 64 counters of a call's working memory, the tokens' fixed-point exponents sit
 
-template <int D, int BLOCK, int TB, int SK, bool DEFER, int NG, bool FX>
+template <int D, int BLOCK, int TB, int SK, bool DEFER, int NG, bool FX, bool WP8 = false>
 tardis_status_t launch_decode_impl(tardis_layer_s* L, const DecodeScratch& ws, const void* x, void* y, float* yfold,
                                    uint32_t* mask, int n_act, int norm_out, hipStream_t s) {
     constexpr int RQ = 4;
@@ -1287,7 +1325,7 @@ tardis_status_t launch_decode_impl(tardis_layer_s* L, const DecodeScratch& ws, c
     const size_t lds = static_tokens ? 0
                        : TB == 16    ? (size_t)TB * (D + 8) * 2      // the int8 codes share the tokens' place
                                      : (size_t)TB * (DEFER ? D + 8 : D) * 2 + (size_t)TB * (NG > 0 ? D + 16 : D);
-    auto kernel = decode_fused_kernel<D, BLOCK, RQ, TB, SK, DEFER, NG, FX>;
+    auto kernel = decode_fused_kernel<D, BLOCK, RQ, TB, SK, DEFER, NG, FX, WP8>;
     if (FX && (rpb > 64 || G > 65535)) return TARDIS_ERR_SHAPE;   // own-column staging, 16-bit contribution count
     const DeferOut rec{ws.rec_count, ws.rec_jb, ws.rec_tb, ws.rec_delta, npb};
     // the layer that runs next, if the caller said so and it has this layer's geometry
@@ -1303,7 +1341,8 @@ tardis_status_t launch_decode_impl(tardis_layer_s* L, const DecodeScratch& ws, c
                        static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), static_cast<const bf16_t*>(L->W2T),
                        L->a, L->c, static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), yfold, ws.yfix,
                        L->dec_copies, mask, (int)L->mask_words, ws.sync, h, npb, rpb, (int)L->act, norm_out, kRmsEps,
-                       rec, n_act, DEFER ? nullptr : pf_rows, (int)L->prefetch_bytes, L->fx_bound, ws.sync + kFxExpAt, (int)L->strict_release);
+                       rec, n_act, DEFER ? nullptr : pf_rows, (int)L->prefetch_bytes, L->fx_bound, ws.sync + kFxExpAt, (int)L->strict_release,
+                       L->Wp8, L->wp8_scale);
     TD_HIP(hipGetLastError());
     if (DEFER) {
         constexpr int SL = TB >= 16 ? 128 : 256;     // slice width: 16 wavefronts x TB x SL floats of LDS
@@ -1326,6 +1365,10 @@ tardis_status_t launch_decode(tardis_layer_s* L, const DecodeScratch& ws, const 
                               uint32_t* mask, int n_act, int norm_out, hipStream_t s) {
     if constexpr (BLOCK == 1024) {   // (the 512-thread variant keeps fp32 accumulators)
         if (L->fx) return launch_decode_impl<D, BLOCK, TB, SK, DEFER, NG, true>(L, ws, x, y, yfold, mask, n_act, norm_out, s);
+        if constexpr (!DEFER && TB <= 2 && D >= 2048) {   // the compact 8-bit rows of W' where the layer keeps them
+            if (L->Wp8)
+                return launch_decode_impl<D, BLOCK, TB, SK, DEFER, NG, false, true>(L, ws, x, y, yfold, mask, n_act, norm_out, s);
+        }
     }
     return launch_decode_impl<D, BLOCK, TB, SK, DEFER, NG, false>(L, ws, x, y, yfold, mask, n_act, norm_out, s);
 }
@@ -1381,18 +1424,18 @@ template <typename K> hipError_t allow_lds(K kernel, size_t bytes) {
 tardis_status_t td_decode_init() {
     static td_once once;
     return once.run([]() -> tardis_status_t {
-        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 4, false>, (size_t)8 * 4096 * 3 + 256)));
-        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 2, false>, (size_t)8 * 4096 * 3 + 256)));
-        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 4, false>, (size_t)16 * (4096 + 8) * 2)));
-        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 2, false>, (size_t)16 * (4096 + 8) * 2)));
-        TD_HIP((allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 4, false>, (size_t)16 * (2048 + 8) * 2)));
-        TD_HIP((allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 2, false>, (size_t)16 * (2048 + 8) * 2)));
-        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 4, true>, (size_t)8 * 4096 * 3 + 256)));
-        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 2, true>, (size_t)8 * 4096 * 3 + 256)));
-        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 4, true>, (size_t)16 * (4096 + 8) * 2)));
-        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 2, true>, (size_t)16 * (4096 + 8) * 2)));
-        TD_HIP((allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 4, true>, (size_t)16 * (2048 + 8) * 2)));
-        TD_HIP((allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 2, true>, (size_t)16 * (2048 + 8) * 2)));
+        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 4, false, false>, (size_t)8 * 4096 * 3 + 256)));
+        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 2, false, false>, (size_t)8 * 4096 * 3 + 256)));
+        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 4, false, false>, (size_t)16 * (4096 + 8) * 2)));
+        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 2, false, false>, (size_t)16 * (4096 + 8) * 2)));
+        TD_HIP((allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 4, false, false>, (size_t)16 * (2048 + 8) * 2)));
+        TD_HIP((allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 2, false, false>, (size_t)16 * (2048 + 8) * 2)));
+        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 4, true, false>, (size_t)8 * 4096 * 3 + 256)));
+        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 8, 8, true, 2, true, false>, (size_t)8 * 4096 * 3 + 256)));
+        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 4, true, false>, (size_t)16 * (4096 + 8) * 2)));
+        TD_HIP((allow_lds(decode_fused_kernel<4096, 1024, 4, 16, 8, true, 2, true, false>, (size_t)16 * (4096 + 8) * 2)));
+        TD_HIP((allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 4, true, false>, (size_t)16 * (2048 + 8) * 2)));
+        TD_HIP((allow_lds(decode_fused_kernel<2048, 1024, 4, 16, 8, true, 2, true, false>, (size_t)16 * (2048 + 8) * 2)));
         TD_HIP((allow_lds((down_project_kernel<4, 256, false>), (size_t)16 * 4 * 256 * sizeof(float))));
         TD_HIP((allow_lds((down_project_kernel<8, 256, false>), (size_t)16 * 8 * 256 * sizeof(float))));
         TD_HIP((allow_lds((down_project_kernel<16, 128, false>), (size_t)16 * 16 * 128 * sizeof(float))));

@@ -531,6 +531,63 @@ range_search_kernel(const float* __restrict__ Zt, int n, int npad, float coverag
     fit_and_store(vals, n, (float)rlo, (float)rhi, act, red, j, lo, hi, a, c);
 }
 
+// ------------------------------------------------- 8-bit floating-point storage of W'
+// Nearest e4m3 code (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no infinities, largest
+// value 448) of v, ties to the even mantissa, magnitudes above 448 saturate.
+__device__ __forceinline__ uint32_t f32_to_e4m3(float v) {
+    const uint32_t sign = (__float_as_uint(v) >> 24) & 0x80u;
+    float m = fminf(fabsf(v), 448.0f);
+    if (!(m == m)) return sign | 0x7Fu;
+    uint32_t code;
+    if (m < 0.015625f) {                              // below 2^-6: multiples of 2^-9 (8 is the first normal code)
+        code = (uint32_t)rintf(m * 512.0f);
+    } else {
+        uint32_t u = __float_as_uint(m);
+        u += 0x7FFFFu + ((u >> 20) & 1u);            // round the mantissa to 3 bits, ties to even (may carry into the exponent)
+        u &= 0xFFF00000u;
+        const uint32_t e = (u >> 23) - 127u + 7u;
+        code = (e << 3) | ((u >> 20) & 7u);
+        if (code > 0x7Eu) code = 0x7Eu;
+    }
+    return sign | code;
+}
+
+__device__ __forceinline__ float e4m3_to_f32(uint32_t code) {
+    const uint32_t e = (code >> 3) & 15u, m = code & 7u;
+    const float mag = e ? ldexpf(1.0f + (float)m * 0.125f, (int)e - 7) : (float)m * 0.001953125f;
+    return (code & 0x80u) ? -mag : mag;
+}
+
+// One block per row of the fp32 folded matrix: the smallest power of two 2^e with max|row| / 2^e <= 448,
+// the row's e4m3 codes in that scale, and the stored values code * 2^e as bf16 (exactly representable)
+__global__ void __launch_bounds__(kBlock)
+wp_to_fp8_kernel(const float* __restrict__ acc, int64_t d, uint8_t* __restrict__ codes, float* __restrict__ scale,
+                 bf16_t* __restrict__ Wp) {
+    __shared__ float red[kBlock / TD_WAVE];
+    const int64_t i = blockIdx.x;
+    const float* row = acc + i * d;
+    float m = 0.0f;
+    for (int64_t k = threadIdx.x; k < d; k += kBlock) m = fmaxf(m, fabsf(row[k]));
+    m = td_wave_max(m);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x / 64] = m;
+    __syncthreads();
+    m = red[0];
+#pragma unroll
+    for (int w = 1; w < kBlock / TD_WAVE; ++w) m = fmaxf(m, red[w]);
+    int e = 0;
+    if (m > 0.0f && m < INFINITY) {
+        int k;
+        const float f = frexpf(m, &k);               // m = f 2^k, 0.5 <= f < 1; 448 = 0.875 * 2^9
+        e = f <= 0.875f ? k - 9 : k - 8;
+    }
+    if (threadIdx.x == 0) scale[i] = ldexpf(1.0f, e);
+    for (int64_t k = threadIdx.x; k < d; k += kBlock) {
+        const uint32_t cde = f32_to_e4m3(ldexpf(row[k], -e));
+        codes[i * d + k] = (uint8_t)cde;
+        Wp[i * d + k] = td_f32_to_bf16(ldexpf(e4m3_to_f32(cde), e));
+    }
+}
+
 // ------------------------------------------------- adaptive thresholding (Algorithm 1, outer loops)
 // E_n = ||W2[:, n]||_2 * sum over the calibration inputs with lo_n <= z < hi_n of |sigma(z) - (a_n z + c_n)|:
 // the section's per-neuron error metric err_n summed over the calibration set (outside the range
@@ -808,7 +865,8 @@ tardis_status_t td_unpack_sketch4(const uint8_t* Q4, const uint8_t* M4, int64_t 
 }
 
 tardis_status_t td_fold(const tardis_ffn_desc* desc, const float* a, const float* c, void* Wp, float* bp,
-                        hipStream_t s) {
+                        uint8_t* Wp8, float* wp8_scale, hipStream_t s) {
+    if (Wp8 && desc->dtype != TARDIS_BF16) return TARDIS_ERR_DTYPE;
     const int64_t d = desc->d, h = desc->h;
     if ((h + 31) / 32 > 65535 || (d + 31) / 32 > 65535) return TARDIS_ERR_SHAPE;
     if (desc->dtype == TARDIS_BF16) {
@@ -822,8 +880,12 @@ tardis_status_t td_fold(const tardis_ffn_desc* desc, const float* a, const float
         TD_TRY(td_gemm_nt(desc->W2, phi.p, static_cast<float*>(acc.p), d, d, h, TARDIS_BF16, 0, nullptr, s));
         TD_TRY(td_gemm_nt(desc->W2, plo.p, static_cast<float*>(acc.p), d, d, h, TARDIS_BF16, 1, nullptr, s));
         const int64_t n = d * d;
-        hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
-                           static_cast<const float*>(acc.p), static_cast<bf16_t*>(Wp), n);
+        if (Wp8)
+            hipLaunchKernelGGL(wp_to_fp8_kernel, dim3((unsigned)d), dim3(kBlock), 0, s, static_cast<const float*>(acc.p),
+                               d, Wp8, wp8_scale, static_cast<bf16_t*>(Wp));
+        else
+            hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                               static_cast<const float*>(acc.p), static_cast<bf16_t*>(Wp), n);
         hipLaunchKernelGGL(fold_bias_kernel<bf16_t>, dim3((unsigned)d), dim3(kBlock), 0, s,
                            static_cast<const bf16_t*>(desc->W2), static_cast<const bf16_t*>(desc->b1),
                            static_cast<const bf16_t*>(desc->b2), a, c, bp, d, h);

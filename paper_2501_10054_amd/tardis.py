@@ -17,7 +17,7 @@ LIB_PATH = os.environ.get("TARDIS_LIB") or os.path.join(_HERE, "libtardis.so")
 
 OK, ERR_INVALID_ARG, ERR_SHAPE, ERR_DTYPE, ERR_STATE, ERR_OOM, ERR_HIP = range(7)
 ACT = {"gelu_erf": 0, "gelu_tanh": 1, "relu": 2, "identity": 3}
-F32, BF16 = 0, 1
+F32, BF16, FP8_E4M3 = 0, 1, 2
 _TORCH_DTYPE = {F32: torch.float32, BF16: torch.bfloat16}
 _DTYPE_CODE = {torch.float32: F32, torch.bfloat16: BF16}
 
@@ -184,10 +184,11 @@ class Layer:
 
 
 def tardis_fold(ffn: FFN, lo, hi, a, c, max_batch: int = 1, sketch_bits: int = 8, deterministic: bool = False,
-                margin: float = 0.0, stream=None) -> Layer:
+                margin: float = 0.0, folded_fp8: bool = False, stream=None) -> Layer:
     for t in (lo, hi, a, c):
         assert t.is_cuda and t.is_contiguous() and t.dtype == torch.float32 and t.numel() == ffn.h
-    opts = tardis_fold_opts(sketch_bits, ffn.dtype, max_batch, 1 if deterministic else 0, float(margin))
+    opts = tardis_fold_opts(sketch_bits, FP8_E4M3 if folded_fp8 else ffn.dtype, max_batch, 1 if deterministic else 0,
+                            float(margin))
     handle = C.c_void_p()
     st = lib().tardis_fold(C.byref(ffn.desc), _ptr(lo), _ptr(hi), _ptr(a), _ptr(c), C.byref(opts),
                            _stream(stream), C.byref(handle))

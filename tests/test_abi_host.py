@@ -68,6 +68,7 @@ def test_fold_rejects_bad_arguments_without_a_gpu():
     assert fold(_desc(), opts=T.tardis_fold_opts(4, T.F32, 1, 0, float('nan'))) == T.ERR_INVALID_ARG
     assert fold(_desc(), opts=T.tardis_fold_opts(16, T.F32, 1, 0, 0)) == T.ERR_INVALID_ARG
     assert fold(_desc(), opts=T.tardis_fold_opts(8, T.BF16, 1, 0, 0)) == T.ERR_DTYPE
+    assert fold(_desc(), opts=T.tardis_fold_opts(8, T.FP8_E4M3, 1, 0, 0)) == T.ERR_DTYPE       # 8-bit W' needs a bf16 layer
     assert fold(_desc(), opts=T.tardis_fold_opts(8, T.F32, 0, 0, 0)) == T.ERR_SHAPE
     assert fold(_desc(), opts=T.tardis_fold_opts(8, T.F32, 1, 2, 0)) == T.ERR_INVALID_ARG       # deterministic is 0 or 1
     assert h.value is None

@@ -505,6 +505,47 @@ def test_narrow_sketches_and_predictor_margin(bits, margin):
     L.close()
 
 
+@pytest.mark.parametrize("d,h", [(2048, 4096), (4096, 2048), (1024, 1000)])
+def test_fp8_storage_of_the_folded_matrix(d, h):
+    """folded_dtype = e4m3: the stored matrix is the checker's 8-bit rounding of W' (row scales
+    powers of two, values on the format's grid, all but a sliver of the elements identical - the
+    two sides' fp32 / fp64 sums differ in the last bits, which moves an element sitting on a rounding
+    boundary by one step); with THAT matrix the online results meet the usual bars on every path;
+    against the exact folded matrix y is a few percent off - the budget the header quotes."""
+    w = synth.decode(d=d, h=h, n_cal=512, n_test=40, coverage=0.9)
+    lay = w.layer
+    ffn = make_ffn(lay)
+    lo, hi, a, c = T.tardis_calibrate(ffn, dev(w.X_cal, "bf16"), 0.9)
+    cal = tuple(t.cpu().numpy() for t in (lo, hi, a, c))
+    L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=40, folded_fp8=True)
+    Wp, bp = T.tardis_get_folded(L)
+    got = host(Wp)
+    F = O.build(lay.W1, None, lay.W2, None, *cal)
+    vals, codes, e = O.fp8_rows(F.Wp)
+    assert (got == vals).mean() > 0.99 and rel_l2(got, vals) < 1e-2
+    # on the grid: each row is e4m3 numbers times one power of two
+    mx = np.abs(got).max(axis=1)
+    sc = 2.0 ** np.ceil(np.log2(np.maximum(mx, 1e-300) / 448.0))
+    np.testing.assert_array_equal(O.round_e4m3(got / sc[:, None])[1] * sc[:, None], got)
+    # the online paths with the library's own stored matrix
+    F8 = O.build(lay.W1, None, lay.W2, None, *cal, wp_round=lambda W: got)
+    Yo, FLo = O.forward(F8, w.X_test)
+    Ye, _ = O.forward(F, w.X_test)
+    Xd = dev(w.X_test, "bf16")
+    for n in (1, 2, 5, 16, 40):
+        Y = T.tardis_ffn_forward_batched(L, Xd[:n].contiguous())
+        mask, _, _ = T.tardis_get_last_outliers(L, n, want_list=False)
+        np.testing.assert_array_equal(unpack_mask(mask, lay.h), FLo[:n])
+        assert_y_close(host(Y), Yo[:n], F8, w.X_test[:n], FLo[:n])
+        assert rel_l2(host(Y), Yo[:n]) < 3e-3                    # same matrix on both sides: accumulation and output rounding only
+    y1 = host(T.tardis_ffn_forward(L, Xd[0]))
+    y5 = host(T.tardis_ffn_forward_batched(L, Xd[:5].contiguous()))[0]
+    assert rel_l2(y1, y5) < 3e-3                                 # the 8-bit rows and the bf16 copy hold the same numbers
+    budget = rel_l2(host(T.tardis_ffn_forward_batched(L, Xd)), Ye)
+    assert 5e-3 < budget < 8e-2, budget                          # three mantissa bits: a few percent against the exact fold
+    L.close()
+
+
 def test_sketch4_zero_rows_and_zero_groups():
     seed = synth.workload_seed(9, 12)
     layer = custom_layer(96, 64, "f32", seed, w1_std=0.3, bias=True)
