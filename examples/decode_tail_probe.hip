@@ -1,0 +1,224 @@
+// Micro-benchmark of the decode kernel's tail: 256 blocks x 1024 threads stream some KiB each and then combine a
+// 4096-float vector per block in one of several ways.  Build and run on an MI355X:
+//   hipcc --offload-arch=gfx950 -O3 -std=c++17 examples/decode_tail_probe.hip -o /tmp/decode_tail_probe && /tmp/decode_tail_probe
+//   mode 0: stream only
+//   mode 1: fp32 atomics into 2 copies + completion counter + last-block assembly (the present design)
+//   mode 2: LL exchange: (value, flag) 8-byte stores to a private slot, arrival counter as a hint,
+//           bounded spin, every block reduces its own 16 columns over the 256 slots
+//   mode 3: as 2 but plain stores + ack + counter, plain coherent loads (no flags)
+//   mode 4: int32 atomics instead of fp32 (same protocol as 1)
+//   mode 5: packed f16 atomics (half the atomic lanes)
+//   mode 6: counted 64-bit fixed-point atomics with return; the add that completes a column writes it
+//   mode 7: as 6, with 96 KiB of further loads requested behind the atomics
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <stdint.h>
+#define CK(x) do { hipError_t e = (x); if (e != hipSuccess) { printf("HIP error %s at %d\n", hipGetErrorString(e), __LINE__); exit(1);} } while (0)
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int D = 4096, G = 256, BLOCK = 1024;
+
+struct Sync { int counter; int epoch; int done; int err; };
+
+__device__ __forceinline__ unsigned long long ld64(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int MODE>
+__global__ void __launch_bounds__(BLOCK) k(const u32x4* __restrict__ data, int vec_per_thread, float* acc /*2 x D*/,
+                                          unsigned long long* slots /*G x D*/, float* plain /*G x D*/,
+                                          Sync* sy, float* y, int spin_limit) {
+  const int tid = threadIdx.x, blk = blockIdx.x, lane = tid & 63, wave = tid >> 6;
+  __shared__ int is_last;
+  __shared__ int s_epoch;
+  __shared__ float red[16][16];
+  int epoch = 0;
+  if (MODE == 2 || MODE == 3) {
+    if (tid == 0) s_epoch = __hip_atomic_load(&sy->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  // ---- stream
+  u32x4 s = {0, 0, 0, 0};
+  const u32x4* p = data + (size_t)blk * vec_per_thread * BLOCK + tid;
+  for (int i = 0; i < vec_per_thread; i += 8) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(p + (size_t)(i + u) * BLOCK);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s ^= v[u];
+  }
+  float part[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) part[u] = 1.0f + (float)((s.x ^ s.y ^ s.z ^ s.w) & 1u) * 1e-30f;
+  const int ctid = (tid + 64 * (blk >> 3)) & (BLOCK - 1);
+  if (MODE == 0) {
+    if (part[0] == 12345.0f) y[tid] = part[0];
+    return;
+  }
+  if (MODE == 6 || MODE == 7) {
+    // acc64[col]: low 16 bits count the contributions, the rest is their fixed-point sum; the thread whose add
+    // brings the count to G holds the complete sum: it writes y and re-arms the accumulator
+    unsigned long long* a64 = slots + ctid;
+    unsigned long long old[4], enc[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      enc[u] = ((unsigned long long)(long long)__float2ll_rn(part[u] * 1048576.0f) << 16) + 1ull;
+      old[u] = __hip_atomic_fetch_add(a64 + u * BLOCK, enc[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (MODE == 7) {   // requests behind the atomics (the next launch's rows): 96 KiB per block
+      u32x4 w[6];
+#pragma unroll
+      for (int u = 0; u < 6; ++u) w[u] = data[(size_t)((blk * 6 + u) * BLOCK + tid) % ((size_t)G * 8 * BLOCK)];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if ((old[u] & 0xFFFFull) == (unsigned long long)(G - 1)) {
+          const long long tot = (long long)(old[u] + enc[u]) >> 16;
+          y[ctid + u * BLOCK] = (float)tot * (1.0f / 1048576.0f);
+          a64[u * BLOCK] = 0ull;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 6; ++u) asm volatile("" ::"v"(w[u]));
+      return;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if ((old[u] & 0xFFFFull) == (unsigned long long)(G - 1)) {
+        const long long tot = (long long)(old[u] + enc[u]) >> 16;
+        y[ctid + u * BLOCK] = (float)tot * (1.0f / 1048576.0f);
+        a64[u * BLOCK] = 0ull;
+      }
+    }
+    return;
+  }
+  if (MODE == 1 || MODE == 4 || MODE == 5) {
+    float* dst = acc + (size_t)(blk & 1) * D + ctid;
+    if (MODE == 1) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) __hip_atomic_fetch_add(dst + u * BLOCK, part[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else if (MODE == 4) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) __hip_atomic_fetch_add(reinterpret_cast<int*>(dst) + u * BLOCK, (int)(part[u] * 1024.0f), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      // threads pair up columns: thread owns columns 2*tid', so half the atomic lanes; emulate by lanes < 32 of each wave... simply 2 atomics per thread
+      __half2* d2 = reinterpret_cast<__half2*>(acc + (size_t)(blk & 1) * D) + ctid;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) unsafeAtomicAdd(d2 + u * BLOCK, __floats2half2_rn(part[2 * u], part[2 * u + 1]));
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) is_last = (__hip_atomic_fetch_add(&sy->done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == G - 1);
+    __syncthreads();
+    if (!is_last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    const f32x4 a0 = reinterpret_cast<const f32x4*>(acc)[tid];
+    const f32x4 a1 = reinterpret_cast<const f32x4*>(acc + D)[tid];
+    const f32x4 z = {0, 0, 0, 0};
+    reinterpret_cast<f32x4*>(acc)[tid] = z;
+    reinterpret_cast<f32x4*>(acc + D)[tid] = z;
+    reinterpret_cast<f32x4*>(y)[tid] = a0 + a1;
+    if (tid == 0) __hip_atomic_store(&sy->done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return;
+  }
+  // ---- exchange through private slots
+  __syncthreads();
+  epoch = s_epoch + 1;
+  if (MODE == 2) {
+    unsigned long long* dst = slots + (size_t)blk * D + ctid;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      __hip_atomic_store(dst + u * BLOCK, ((unsigned long long)(unsigned)epoch << 32) | __float_as_uint(part[u]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  } else {
+    float* dst = plain + (size_t)blk * D + ctid;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) __hip_atomic_store(dst + u * BLOCK, part[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  }
+  if (tid == 0) {
+    __hip_atomic_fetch_add(&sy->counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int spins = 0;
+    while (__hip_atomic_load(&sy->counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < epoch * G && ++spins < spin_limit)
+      __builtin_amdgcn_s_sleep(8);
+    if (spins >= spin_limit) __hip_atomic_store(&sy->err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __syncthreads();
+  // thread: slot row r = tid / 4, columns 16 blk + 4 (tid % 4) ..+3
+  const int r = tid >> 2, q = tid & 3;
+  float v[4];
+  if (MODE == 2) {
+    const unsigned long long* src = slots + (size_t)r * D + 16 * blk + 4 * q;
+    int tries = 0;
+    for (;;) {
+      unsigned long long w[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) w[u] = ld64(src + u);
+      bool ok = true;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { ok = ok && (int)(w[u] >> 32) == epoch; v[u] = __uint_as_float((unsigned)w[u]); }
+      if (ok || ++tries >= spin_limit) break;
+    }
+  } else {
+    const float* src = plain + (size_t)r * D + 16 * blk + 4 * q;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = __hip_atomic_load(src + u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  // sum over the 16 rows of this wavefront (lane bits 2..5), then over the 16 wavefronts through LDS
+#pragma unroll
+  for (int o = 4; o < 64; o <<= 1)
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] += __shfl_xor(v[u], o, 64);
+  if (lane < 4)
+#pragma unroll
+    for (int u = 0; u < 4; ++u) red[wave][4 * lane + u] = v[u];
+  __syncthreads();
+  if (tid < 16) {
+    float t = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) t += red[w][tid];
+    y[16 * blk + tid] = t;
+  }
+  if (blk == 0 && tid == 0) __hip_atomic_store(&sy->epoch, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+int main() {
+  const int copies = 6;
+  const size_t vec_max = 32;                      // 16-byte vectors per thread: 32 x 1024 x 16 B = 512 KiB per block
+  const size_t bytes = (size_t)G * vec_max * BLOCK * 16;
+  u32x4* data[copies];
+  for (int c = 0; c < copies; ++c) { CK(hipMalloc(&data[c], bytes)); CK(hipMemset(data[c], c + 1, bytes)); }
+  float *acc, *plain, *y; unsigned long long* slots; Sync* sy;
+  CK(hipMalloc(&acc, 2 * D * 4)); CK(hipMemset(acc, 0, 2 * D * 4));
+  CK(hipMalloc(&plain, (size_t)G * D * 4)); CK(hipMemset(plain, 0, (size_t)G * D * 4));
+  CK(hipMalloc(&slots, (size_t)G * D * 8)); CK(hipMemset(slots, 0, (size_t)G * D * 8));
+  CK(hipMalloc(&y, D * 4)); CK(hipMalloc(&sy, sizeof(Sync))); CK(hipMemset(sy, 0, sizeof(Sync)));
+  hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
+  const int reps = 300;
+  auto timeit = [&](auto launch) {
+    for (int r = 0; r < 12; ++r) launch(r);
+    CK(hipDeviceSynchronize()); CK(hipEventRecord(e0));
+    for (int r = 0; r < reps; ++r) launch(r);
+    CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1)); float ms; CK(hipEventElapsedTime(&ms, e0, e1)); return ms * 1e3f / reps; };
+  const int spin = 1 << 16;
+  for (int vpt : {0, 8, 24, 32}) {
+    printf("stream %4d KiB/block (%.1f MB per launch)\n", vpt * 16, vpt * 16.0 * 1024 * G / 1e6);
+    printf("  mode 0 stream only      : %.2f us\n", timeit([&](int r) { k<0><<<G, BLOCK>>>(data[r % copies], vpt, acc, slots, plain, sy, y, spin); }));
+    printf("  mode 1 f32 atomics+last : %.2f us\n", timeit([&](int r) { k<1><<<G, BLOCK>>>(data[r % copies], vpt, acc, slots, plain, sy, y, spin); }));
+    printf("  mode 4 i32 atomics+last : %.2f us\n", timeit([&](int r) { k<4><<<G, BLOCK>>>(data[r % copies], vpt, acc, slots, plain, sy, y, spin); }));
+    printf("  mode 5 pk f16 atom+last : %.2f us\n", timeit([&](int r) { k<5><<<G, BLOCK>>>(data[r % copies], vpt, acc, slots, plain, sy, y, spin); }));
+    CK(hipMemset(slots, 0, (size_t)G * D * 8));
+    printf("  mode 6 counted i64 atom : %.2f us\n", timeit([&](int r) { k<6><<<G, BLOCK>>>(data[r % copies], vpt, acc, slots, plain, sy, y, spin); }));
+    { float yh[4]; CK(hipMemcpy(yh, y, 16, hipMemcpyDeviceToHost)); unsigned long long a0; CK(hipMemcpy(&a0, slots, 8, hipMemcpyDeviceToHost)); printf("    y[0] %.3f (expect 256) acc[0] %llu (expect 0)\n", yh[0], a0); }
+    printf("  mode 7 counted + warm   : %.2f us\n", timeit([&](int r) { k<7><<<G, BLOCK>>>(data[r % copies], vpt, acc, slots, plain, sy, y, spin); }));
+    CK(hipMemset(slots, 0, (size_t)G * D * 8));
+    printf("  mode 2 LL exchange      : %.2f us\n", timeit([&](int r) { k<2><<<G, BLOCK>>>(data[r % copies], vpt, acc, slots, plain, sy, y, spin); }));
+    printf("  mode 3 ack exchange     : %.2f us\n", timeit([&](int r) { k<3><<<G, BLOCK>>>(data[r % copies], vpt, acc, slots, plain, sy, y, spin); }));
+    Sync h; CK(hipMemcpy(&h, sy, sizeof(Sync), hipMemcpyDeviceToHost));
+    float yh[4]; CK(hipMemcpy(yh, y, 16, hipMemcpyDeviceToHost));
+    printf("  err flag %d  y[0] %.1f (expect 256)\n", h.err, yh[0]);
+    fflush(stdout);
+  }
+  return 0;
+}
