@@ -875,6 +875,8 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                 s = td_wave_sum(s);
             }
             // written through to memory so that the finishing block, on any XCD, reads it
+            // (adding the value to the repair accumulators instead, so that the assembling block reads 16 KB
+            //  less, was measured: 23.3 against 23.4 us per token - within the noise, not kept)
             if (lane == 0)
                 __hip_atomic_store(yfold + (size_t)t * D + r0 + ri, s + bias, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
