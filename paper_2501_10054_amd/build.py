@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtardis.so")
 
-SOURCES = ["api.hip", "batched.hip", "decode.hip", "forward.hip", "gemm.hip", "offline.hip", "prefill.hip"]
+SOURCES = ["api.hip", "batched.hip", "decode.hip", "forward.hip", "gemm.hip", "offline.hip", "prefill.hip", "stack.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",

@@ -58,7 +58,7 @@ int env_int(const char* name, int fallback, int lo, int hi) {
 void free_layer(tardis_layer_s* L) {
     if (!L) return;
     void* owned[] = {L->W2T, L->W2, L->Wp, L->Wp8, L->wp8_scale, L->bp, L->Q, L->Q4, L->M4, L->tlo, L->thi, L->a, L->c,
-                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix, L->fx_bound, L->zeros_h, L->xnext, L->rec_count, L->rec_jb, L->rec_tb, L->rec_delta, L->pf_scratch,
+                     L->yacc, L->mask, L->counts, L->list, L->hidden, L->sync, L->yfix, L->fx_bound, L->stack_desc, L->zeros_h, L->xnext, L->rec_count, L->rec_jb, L->rec_tb, L->rec_delta, L->pf_scratch,
                      L->bt_xq, L->bt_e, L->bt_tokmask, L->bt_ulist, L->bt_ucount, L->bt_delta, L->bt_partial};
     for (void* p : owned)
         if (p) (void)hipFree(p);
@@ -169,6 +169,18 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
         TD_TRY(dev_alloc(&L->wp8_scale, (size_t)d * 4));
     }
     TD_TRY(td_fold(desc, L->a, L->c, L->Wp, L->bp, L->Wp8, L->wp8_scale, s));
+    L->stack_fused = env_int("TARDIS_STACK_FUSED", 0, 0, 2);   // 2: refuse a one-token stack the single launch cannot serve
+    if (L->use_fused && L->dtype == TARDIS_BF16 && L->Q) {   // this layer's entry for the single-launch stack kernel
+        const int64_t npb = ((h + L->dec_blocks - 1) / L->dec_blocks + 31) / 32 * 32;
+        const td_stack_layer_dev hd{static_cast<const bf16_t*>(L->Wp), L->bp, L->Q, L->tlo, L->thi,
+                                    static_cast<const bf16_t*>(L->W1),
+                                    static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h),
+                                    static_cast<const bf16_t*>(L->W2T), L->a, L->c, L->mask,
+                                    static_cast<bf16_t*>(L->xnext), (int32_t)h, (int32_t)npb, L->act, 0};
+        TD_TRY(dev_alloc(&L->stack_desc, sizeof(hd)));
+        TD_HIP(hipMemcpyAsync(L->stack_desc, &hd, sizeof(hd), hipMemcpyHostToDevice, s));
+        TD_HIP(hipStreamSynchronize(s));   // (hd lives on this stack frame)
+    }
     if (L->fx) {
         TD_TRY(dev_alloc(&L->fx_bound, 8));
         TD_TRY(td_fx_bounds(L, L->fx_bound, s));
@@ -309,6 +321,22 @@ tardis_status_t tardis_stack_forward(const tardis_handle_t* layers, int32_t n_la
             if (layers[m] == layers[l]) return TARDIS_ERR_INVALID_ARG;   // each handle owns its hand-over buffer
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
+    // one token through layers the single-token kernel serves: the whole stack in ONE launch whose grid
+    // stays resident (not while the stream is being captured: a captured graph keeps the per-layer launches)
+    if (n == 1 && n_layers >= 2 && n_layers <= 64 && layers[0]->stack_fused) {
+        bool ok = true;
+        for (int32_t l = 0; l < n_layers && ok; ++l)
+            ok = td_stack_decode_supported(layers[l]) && layers[l]->dec_blocks == layers[0]->dec_blocks &&
+                 layers[l]->deterministic == 0;
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (ok && hipStreamIsCapturing(s, &cap) == hipSuccess && cap == hipStreamCaptureStatusNone) {
+            const tardis_status_t st = online_result(layers[0], td_stack_decode(layers, n_layers, x, y, s));
+            if (st == TARDIS_OK)
+                for (int32_t l = 0; l < n_layers; ++l) layers[l]->last_n = 1;
+            return st;
+        }
+        if (layers[0]->stack_fused == 2) return TARDIS_ERR_SHAPE;
+    }
     const void* cur = x;
     for (int32_t l = 0; l < n_layers; ++l) {
         const bool last = l == n_layers - 1;

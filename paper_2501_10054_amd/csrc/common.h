@@ -43,6 +43,24 @@ struct td_once {
     }
 };
 
+// What the single-launch stack kernel needs of one layer (a copy lives in device memory, filled when
+// the layer is folded).
+struct td_stack_layer_dev {
+    const bf16_t* Wp;
+    const float* bp;
+    const int8_t* Q;
+    const float* tlo;
+    const float* thi;
+    const bf16_t* W1;
+    const bf16_t* b1;
+    const bf16_t* W2T;
+    const float* a;
+    const float* c;
+    uint32_t* mask;
+    bf16_t* xnext;
+    int32_t h, npb, act, reserved;
+};
+
 // Everything one folded layer owns.  Pointers are device memory.
 struct tardis_layer_s {
     int64_t d, h;
@@ -108,6 +126,8 @@ struct tardis_layer_s {
     int32_t fx;        // decode kernels accumulate the repair in counted fixed-point words (deterministic results)
     int32_t deterministic;   // every online call runs as decode groups on those accumulators
     float* fx_bound;   // K1, K2 of the accumulators' magnitude bound (device, 2 floats)
+    td_stack_layer_dev* stack_desc;   // device copy of this layer's entry for the single-launch stack kernel (or null)
+    int32_t stack_fused;              // knob: one-token stacks of such layers run in one launch
     int32_t poisoned;  // a launch of an online call failed half way: counters and accumulators may be left armed
 };
 
@@ -242,6 +262,9 @@ tardis_status_t td_static_scratch_setup();
 tardis_status_t td_mask_union(const tardis_layer_s* L, int64_t n, uint32_t* union_mask, int32_t* union_count,
                               hipStream_t s);
 tardis_status_t td_mask_to_list(const tardis_layer_s* L, int64_t n, int32_t* counts, int32_t* list, hipStream_t s);
+// stack.hip
+bool td_stack_decode_supported(const tardis_layer_s* L);
+tardis_status_t td_stack_decode(tardis_layer_s* const* layers, int n_layers, const void* x, void* y, hipStream_t s);
 // batched.hip
 bool td_batched_supported(const tardis_layer_s* L);
 size_t td_batched_partial_floats(const tardis_layer_s* L);

@@ -1035,6 +1035,54 @@ def test_stack_teacher_forced(d, h, dtype, n):
         L.close()
 
 
+@pytest.mark.parametrize("d,h,nl", [(2048, 4096, 6), (1024, 3000, 5), (4096, 4096, 4)])
+def test_single_token_stack_in_one_launch(d, h, nl, monkeypatch):
+    """One token through a stack runs as ONE resident launch (blocks wait for each layer's published
+    output).  Several tokens one after the other - the counters and accumulators must come back
+    re-armed - each checked layer by layer on the GPU's own hand-over; the per-layer launches
+    (TARDIS_STACK_FUSED=0 at fold time) serve as a second opinion on the final output."""
+    calib, lays, oracles = [], [], []
+    for li in range(nl):
+        seed = synth.workload_seed(14, li)
+        lay = synth.make_layer(d, h, "bf16", seed, w1_std=0.03, w2_std=0.03, heavy_frac=0.01)
+        ffn = make_ffn(lay)
+        X_cal = synth.make_tokens(384, d, "bf16", seed, synth.STREAM_CAL)
+        lo, hi, a, c = T.tardis_calibrate(ffn, dev(X_cal, "bf16"), 0.9)
+        calib.append((ffn, lo, hi, a, c))
+        lays.append(lay)
+        oracles.append(O.build(lay.W1, None, lay.W2, None, *(t.cpu().numpy() for t in (lo, hi, a, c))))
+    monkeypatch.setenv("TARDIS_STACK_FUSED", "2")      # refuse instead of falling back to a launch per layer
+    fused = [T.tardis_fold(*cal, max_batch=1) for cal in calib]
+    monkeypatch.setenv("TARDIS_STACK_FUSED", "0")
+    layerwise = [T.tardis_fold(*cal, max_batch=1) for cal in calib]
+    monkeypatch.delenv("TARDIS_STACK_FUSED")
+    X = synth.make_tokens(3, d, "bf16", synth.workload_seed(14, 99), synth.STREAM_TEST)
+    for t in (0, 1, 2, 0):
+        x0 = X[t:t + 1]
+        y = T.tardis_stack_forward(fused, dev(x0, "bf16"))
+        y2 = T.tardis_stack_forward(layerwise, dev(x0, "bf16"))
+        torch.cuda.synchronize()
+        x_in = x0.astype(np.float64)
+        for li in range(nl):
+            Yo, FLo = O.forward(oracles[li], x_in)
+            mask, counts, _ = T.tardis_get_last_outliers(fused[li], 1, want_list=False)
+            np.testing.assert_array_equal(unpack_mask(mask, h), FLo, err_msg=f"token {t} layer {li}")
+            assert (counts.cpu().numpy() == FLo.sum(1)).all()
+            if li < nl - 1:
+                xn = host(T.tardis_get_handover(fused[li], 1))
+                assert rel_l2(xn, O.to_bf16(O.rmsnorm(Yo))) <= Y_TOL["bf16"], (t, li)
+                if li == 0:     # same input, same mask: the two paths differ by summation order only
+                    m2, _, _ = T.tardis_get_last_outliers(layerwise[0], 1, want_list=False)
+                    assert torch.equal(mask, m2)
+                    assert rel_l2(host(T.tardis_get_handover(layerwise[0], 1)), xn) <= 1e-2
+                x_in = xn
+            else:
+                assert_y_close(host(y), Yo, oracles[li], x_in, FLo, "bf16")
+        assert torch.isfinite(y2.float()).all()
+    for L in fused + layerwise:
+        L.close()
+
+
 # ------------------------------------------------ config 1 at full size (d=4096, h=16384, bf16)
 @pytest.fixture(scope="module")
 def decode_full():
