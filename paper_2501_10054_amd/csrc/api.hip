@@ -176,7 +176,8 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
                                     static_cast<const bf16_t*>(L->W1),
                                     static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h),
                                     static_cast<const bf16_t*>(L->W2T), L->a, L->c, L->mask,
-                                    static_cast<bf16_t*>(L->xnext), (int32_t)h, (int32_t)npb, L->act, 0};
+                                    static_cast<bf16_t*>(L->xnext), L->yfix, L->sync, (int32_t)h, (int32_t)npb, L->act, 0};
+        TD_TRY(td_stack_init());
         TD_TRY(dev_alloc(&L->stack_desc, sizeof(hd)));
         TD_HIP(hipMemcpyAsync(L->stack_desc, &hd, sizeof(hd), hipMemcpyHostToDevice, s));
         TD_HIP(hipStreamSynchronize(s));   // (hd lives on this stack frame)

@@ -58,6 +58,8 @@ struct td_stack_layer_dev {
     const float* c;
     uint32_t* mask;
     bf16_t* xnext;
+    float* yfix;       // the layer's accumulator copies (zero between launches)
+    int32_t* sync;     // the layer's counters (zero between launches)
     int32_t h, npb, act, reserved;
 };
 
@@ -263,6 +265,7 @@ tardis_status_t td_mask_union(const tardis_layer_s* L, int64_t n, uint32_t* unio
                               hipStream_t s);
 tardis_status_t td_mask_to_list(const tardis_layer_s* L, int64_t n, int32_t* counts, int32_t* list, hipStream_t s);
 // stack.hip
+tardis_status_t td_stack_init();
 bool td_stack_decode_supported(const tardis_layer_s* L);
 tardis_status_t td_stack_decode(tardis_layer_s* const* layers, int n_layers, const void* x, void* y, hipStream_t s);
 // batched.hip
