@@ -170,6 +170,7 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     }
     TD_TRY(td_fold(desc, L->a, L->c, L->Wp, L->bp, L->Wp8, L->wp8_scale, s));
     L->stack_fused = env_int("TARDIS_STACK_FUSED", 0, 0, 2);   // 2: refuse a one-token stack the single launch cannot serve
+    L->stack_spin_limit = env_int("TARDIS_STACK_SPIN_LIMIT", 1 << 22, 1, 1 << 30);
     if (L->use_fused && L->dtype == TARDIS_BF16 && L->Q) {   // this layer's entry for the single-launch stack kernel
         const int64_t npb = ((h + L->dec_blocks - 1) / L->dec_blocks + 31) / 32 * 32;
         const td_stack_layer_dev hd{static_cast<const bf16_t*>(L->Wp), L->bp, L->Q, L->tlo, L->thi,

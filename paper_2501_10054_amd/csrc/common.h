@@ -130,6 +130,7 @@ struct tardis_layer_s {
     float* fx_bound;   // K1, K2 of the accumulators' magnitude bound (device, 2 floats)
     td_stack_layer_dev* stack_desc;   // device copy of this layer's entry for the single-launch stack kernel (or null)
     int32_t stack_fused;              // knob: one-token stacks of such layers run in one launch
+    int32_t stack_spin_limit;         // knob: polls a block of that launch spends on one layer's counter before it gives up
     int32_t poisoned;  // a launch of an online call failed half way: counters and accumulators may be left armed
 };
 

@@ -466,7 +466,7 @@ tardis_status_t td_stack_decode(tardis_layer_s* const* layers, int n_layers, con
     A.y = static_cast<bf16_t*>(y);
     A.err = L0->sync + kErrAt;
     A.eps = kRmsEps;
-    A.spin_limit = 1 << 22;
+    A.spin_limit = L0->stack_spin_limit;
 #ifdef TD_STACK_TRACE
     static unsigned long long* trace_dev = nullptr;
     const size_t trace_n = (size_t)kMaxStackLayers * 1024 * 8;

@@ -1083,6 +1083,44 @@ def test_single_token_stack_in_one_launch(d, h, nl, monkeypatch):
         L.close()
 
 
+def test_single_launch_stack_gives_up_loudly_and_recovers(monkeypatch):
+    """The resident launch waits for every layer's counter with a bounded number of polls.  With the
+    bound forced down to one poll from the host (every kernel still runs to its end) the blocks give
+    up: the call's output is all NaN rather than a plausible wrong vector, and the kernel behind the
+    launch has re-armed every layer - the same handles then serve a two-token call (a launch per
+    layer) correctly."""
+    d, h, nl = 1024, 2048, 4
+    monkeypatch.setenv("TARDIS_STACK_FUSED", "1")
+    monkeypatch.setenv("TARDIS_STACK_SPIN_LIMIT", "1")
+    layers, oracles = [], []
+    for li in range(nl):
+        seed = synth.workload_seed(15, li)
+        lay = synth.make_layer(d, h, "bf16", seed, w1_std=0.03, w2_std=0.03, heavy_frac=0.01)
+        ffn = make_ffn(lay)
+        X_cal = synth.make_tokens(256, d, "bf16", seed, synth.STREAM_CAL)
+        lo, hi, a, c = T.tardis_calibrate(ffn, dev(X_cal, "bf16"), 0.9)
+        layers.append(T.tardis_fold(ffn, lo, hi, a, c, max_batch=2))
+        oracles.append(O.build(lay.W1, None, lay.W2, None, *(t.cpu().numpy() for t in (lo, hi, a, c))))
+    X = synth.make_tokens(2, d, "bf16", synth.workload_seed(15, 99), synth.STREAM_TEST)
+    for rep in range(2):
+        y = T.tardis_stack_forward(layers, dev(X[:1], "bf16"))
+        torch.cuda.synchronize()
+        assert torch.isnan(y.float()).all(), rep
+    y2 = T.tardis_stack_forward(layers, dev(X, "bf16"))
+    torch.cuda.synchronize()
+    x_in = X.astype(np.float64)
+    for li in range(nl):
+        Yo, FLo = O.forward(oracles[li], x_in)
+        mask, _, _ = T.tardis_get_last_outliers(layers[li], 2, want_list=False)
+        np.testing.assert_array_equal(unpack_mask(mask, h), FLo)
+        if li < nl - 1:
+            x_in = host(T.tardis_get_handover(layers[li], 2))
+        else:
+            assert_y_close(host(y2), Yo, oracles[li], x_in, FLo, "bf16")
+    for L in layers:
+        L.close()
+
+
 # ------------------------------------------------ config 1 at full size (d=4096, h=16384, bf16)
 @pytest.fixture(scope="module")
 def decode_full():
