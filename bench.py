@@ -402,6 +402,44 @@ def main() -> int:
     stream_ms = None
     if use_graph and not args.headline_only:
         stream_ms, _ = timed(handles, max(2, args.steps // 4), 1)
+    # Context for the roofline figure, not part of it: the same 1024 single-token launches issued
+    # alternately on TWO streams (independent request streams, each at batch 1, each walking its
+    # own half of the layer copies).  The blocks of one launch start as the blocks of the other
+    # finish, so a launch's ramp and tail overlap the neighbour's stream; every token still
+    # streams its own 114 MB.  Wall clock over whole steps, both streams drained.
+    two = None
+    if not args.headline_only and len(handles) >= 4:
+        sA, sB = torch.cuda.Stream(), torch.cuda.Stream()
+        pa, pb = T._stream(sA), T._stream(sB)
+        la, lb = layers[0::2], layers[1::2]
+        if chained:
+            for grp in (la, lb):
+                for i, L in enumerate(grp):
+                    T.tardis_set_next_layer(L, grp[(i + 1) % len(grp)])
+        ha, hb = [L.handle for L in la], [L.handle for L in lb]
+
+        def two_step():
+            for t in range(0, TOKENS_PER_STEP, 2):
+                k = t // 2
+                if fwd(ha[k % len(ha)], xp[t], yp[t], pa) != 0 or fwd(hb[k % len(hb)], xp[t + 1], yp[t + 1], pb) != 0:
+                    raise RuntimeError("forward failed")
+        torch.cuda.synchronize()
+        sA.wait_stream(stream)
+        sB.wait_stream(stream)
+        two_step()
+        torch.cuda.synchronize()
+        reps = max(2, args.steps // 2)
+        t0 = time.time()
+        for _ in range(reps):
+            two_step()
+        torch.cuda.synchronize()
+        two_ms = (time.time() - t0) / reps * 1e3
+        two = {"tokens_per_s": TOKENS_PER_STEP / (two_ms * 1e-3), "us_per_token": two_ms * 1e3 / TOKENS_PER_STEP,
+               "note": "two independent batch-1 streams interleaved on two HIP streams (host wall clock); "
+                       "context for where the single-stream time goes, not the headline"}
+        if chained:
+            for i, L in enumerate(layers):
+                T.tardis_set_next_layer(L, layers[(i + 1) % len(layers)])
     res_dense = {}
     if not args.no_dense:
         dms, _ = timed(handles, max(2, args.steps // 4), 1, fn=dense, dense_call=True)
@@ -481,6 +519,7 @@ def main() -> int:
         "launch_mode": "hip graph replay (one graph = one 1024-token step)" if use_graph else "stream",
         "stream_launch_tokens_per_s": (TOKENS_PER_STEP / (stream_ms * 1e-3)) if stream_ms else None,
         "host_wall_ms_per_step": cold_wall,
+        "two_streams": (dict(two, algorithmic_GBs=bytes_tok / (two["us_per_token"] * 1e-6) / 1e9) if two else None),
         "offline": offline,
         "setup_s": time.time() - t_setup,
     }
