@@ -272,7 +272,15 @@ tardis_status_t tardis_ffn_forward_static(tardis_handle_t L, const void* x, int6
  * the layer dtype.  y receives the last layer's (un-normalised) output.
  * `layers` is a HOST array of n_layers distinct handles; each layer's predictor
  * output stays readable through tardis_get_last_outliers on its handle.
- * 1 <= n <= every layer's max_batch.  x, y: n x d. */
+ * 1 <= n <= every layer's max_batch.  x, y: n x d.
+ * One launch per layer by default.  Layers folded with the environment
+ * variable TARDIS_STACK_FUSED=1 run a one-token call (bf16, d in {1024, 2048,
+ * 4096}, 2..64 layers, not under stream capture) as ONE resident launch whose
+ * blocks wait for one another with a bounded number of polls; should a wait
+ * ever run out, y is filled with NaNs and the layers are re-armed (results of
+ * that call are lost, the handles stay usable).  Same results up to summation
+ * order; =2 returns TARDIS_ERR_SHAPE where that launch cannot serve the call
+ * instead of falling back. */
 tardis_status_t tardis_stack_forward(const tardis_handle_t* layers, int32_t n_layers, const void* x,
                                      int64_t n, void* y, void* stream);
 
