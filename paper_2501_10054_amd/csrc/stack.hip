@@ -105,7 +105,7 @@ __global__ void __launch_bounds__(1024) stack_decode_kernel(StackArgs A) {
     constexpr int IW = NVW / TD_WAVE;                // per-lane vectors of a bf16 row
     constexpr int IWA = IW / 2;                      // vectors of the W' row requested before the flags are known
     constexpr int CPT = D / BLOCK;                   // output columns per thread
-    constexpr int KPRE = RQ / 2;                            // predictor rows of the next layer requested before the layer barrier
+    constexpr int KPRE = RQ / 2;                     // predictor rows of the next layer requested before the wait for this one
     constexpr int NLIVE = D / 4;                     // threads that hold four values of the token
     static_assert(D % 1024 == 0 && D <= 4096, "four values of the token per thread");
     static_assert(kStackNpbMax == NW * RQ, "one predictor pass per layer");
@@ -455,7 +455,8 @@ bool td_stack_decode_supported(const tardis_layer_s* L) {
 }
 
 // x (d values) through layers[0..n): the handed-over activations land in every layer's xnext, the masks in
-// every layer's own mask words, y receives the last layer's output.  Working memory: layers[0]'s.
+// every layer's own mask words, y receives the last layer's output.  Working memory: every layer's own
+// accumulators and counter (left zero again by the kernel behind the launch); the error word is layers[0]'s.
 tardis_status_t td_stack_decode(tardis_layer_s* const* layers, int n_layers, const void* x, void* y, hipStream_t s) {
     if (n_layers < 1 || n_layers > kMaxStackLayers) return TARDIS_ERR_SHAPE;
     tardis_layer_s* L0 = layers[0];
