@@ -546,6 +546,42 @@ def test_fp8_storage_of_the_folded_matrix(d, h):
     L.close()
 
 
+@pytest.mark.parametrize("n", [1, 2, 6])
+def test_stack_of_layers_with_fp8_folded_matrices(n):
+    """Chained layers whose folded matrices are stored in 8 bits (the one- and two-token kernels apply
+    the norm glue while streaming the 8-bit rows): each layer on the GPU's own hand-over against the
+    checker holding the library's stored matrix."""
+    d, h, nl = 2048, 2048, 3
+    layers, oracles = [], []
+    for li in range(nl):
+        seed = synth.workload_seed(16, li)
+        lay = synth.make_layer(d, h, "bf16", seed, w1_std=0.03, w2_std=0.03, heavy_frac=0.01)
+        ffn = make_ffn(lay)
+        X_cal = synth.make_tokens(384, d, "bf16", seed, synth.STREAM_CAL)
+        lo, hi, a, c = T.tardis_calibrate(ffn, dev(X_cal, "bf16"), 0.9)
+        L = T.tardis_fold(ffn, lo, hi, a, c, max_batch=n, folded_fp8=True)
+        stored = host(T.tardis_get_folded(L)[0])
+        layers.append(L)
+        oracles.append(O.build(lay.W1, None, lay.W2, None, *(t.cpu().numpy() for t in (lo, hi, a, c)),
+                               wp_round=lambda W, stored=stored: stored))
+    x0 = synth.make_tokens(n, d, "bf16", synth.workload_seed(16, 99), synth.STREAM_TEST)
+    y = T.tardis_stack_forward(layers, dev(x0, "bf16"))
+    torch.cuda.synchronize()
+    x_in = x0.astype(np.float64)
+    for li in range(nl):
+        Yo, FLo = O.forward(oracles[li], x_in)
+        mask, _, _ = T.tardis_get_last_outliers(layers[li], n, want_list=False)
+        np.testing.assert_array_equal(unpack_mask(mask, h), FLo)
+        if li < nl - 1:
+            xn = host(T.tardis_get_handover(layers[li], n))
+            assert rel_l2(xn, O.to_bf16(O.rmsnorm(Yo))) <= Y_TOL["bf16"]
+            x_in = xn
+        else:
+            assert_y_close(host(y), Yo, oracles[li], x_in, FLo, "bf16")
+    for L in layers:
+        L.close()
+
+
 def test_sketch4_zero_rows_and_zero_groups():
     seed = synth.workload_seed(9, 12)
     layer = custom_layer(96, 64, "f32", seed, w1_std=0.3, bias=True)

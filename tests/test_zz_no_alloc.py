@@ -66,6 +66,25 @@ def test_static_matches_batched_two_calls(d, h, n1, n2):
     layer.close()
 
 
+@pytest.mark.parametrize("opts", [dict(sketch_bits=4), dict(folded_fp8=True), dict(sketch_bits=4, folded_fp8=True),
+                                  dict(deterministic=True), dict(sketch_bits=3, margin=0.1)])
+def test_static_with_fold_options(opts):
+    """The static entry point serves layers folded with the other options too (packed sketch, 8-bit
+    folded matrix, deterministic accumulators - there the two calls agree bit for bit)."""
+    w = synth.decode(d=2048, h=4096, n_cal=512, n_test=16, coverage=0.9)
+    L_ = w.layer
+    ffn = T.FFN(_dev(L_.W1), _dev(L_.W2))
+    lo, hi, a, c = T.tardis_calibrate(ffn, _dev(w.X_cal), w.coverage)
+    layer = T.tardis_fold(ffn, lo, hi, a, c, max_batch=16, **opts)
+    X = _dev(w.X_test)
+    for n in (16, 3, 1, 2):
+        got, _ = _check_pair(layer, X, n)
+        if opts.get("deterministic"):
+            ref = _host(T.tardis_ffn_forward_batched(layer, X[:n].contiguous()))
+            assert np.array_equal(got, ref)
+    layer.close()
+
+
 def test_static_rejects_what_it_cannot_hold():
     w = synth.decode(d=1024, h=4096, n_cal=256, n_test=32, coverage=0.9)
     L_ = w.layer
