@@ -106,6 +106,9 @@ tardis_status_t fold_impl(const tardis_ffn_desc* desc, const float* lo, const fl
     L->dec_copies = env_int("TARDIS_DECODE_COPIES", 2, 1, 4);
     L->prefetch_bytes = env_int("TARDIS_PREFETCH_KB", 96, 0, 256) * 1024;
     L->strict_release = env_int("TARDIS_STRICT_RELEASE", 0, 0, 1);
+    // what a finished block of the single-token kernel requests of the next layer, in sixteenths of prefetch_bytes:
+    // the first block to finish / the last one (linear in between)
+    L->prefetch_shape = env_int("TARDIS_PREFETCH_FIRST16", 32, 0, 255) | (env_int("TARDIS_PREFETCH_LAST16", 0, 0, 255) << 8);
     // (at least two copies' worth: the fixed-point accumulators are 8 bytes per token and column)
     const size_t yfix_bytes = (size_t)(L->dec_copies < 2 ? 2 : L->dec_copies) * kDecodeMaxTokens * d * 4;
     TD_TRY(dev_alloc(&L->yfix, yfix_bytes));

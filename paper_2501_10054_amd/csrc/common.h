@@ -102,6 +102,7 @@ struct tardis_layer_s {
     const tardis_layer_s* next_layer;   // the layer that runs after this one (hint, may be null; not owned)
     int32_t prefetch_bytes;             // bytes of that layer's predictor rows each finished block requests
     int32_t strict_release;             // the signalling thread of a decode block also executes an agent-scope release fence
+    int32_t prefetch_shape;             // next-layer warming by order of arrival: first16 | last16 << 8 (sixteenths of prefetch_bytes; 0 = flat)
     int32_t dec_blocks;   // grid of the fused decode kernel
     int32_t dec_threads;  // block size of the fused decode kernel (512 or 1024)
     int32_t dec_copies;   // number of repair accumulator copies

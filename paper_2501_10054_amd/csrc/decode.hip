@@ -179,7 +179,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                     float* __restrict__ yfold, float* __restrict__ yfix, int copies, uint32_t* __restrict__ mask,
                     int mask_words, int32_t* __restrict__ done, int h, int npb, int rpb, int act, int norm_out,
                     float eps, DeferOut rec, int n_act, const unsigned char* __restrict__ pf_rows, int pf_bytes,
-                    const float* __restrict__ fx_bound, int32_t* __restrict__ fx_exp, int strict_release,
+                    const float* __restrict__ fx_bound, int32_t* __restrict__ fx_exp, int strict_release, int pf_shape,
                     const uint8_t* __restrict__ Wp8, const float* __restrict__ wp8_scale) {
     // n_act <= TB tokens are real: the remaining slots of the group repeat the last real token and
     // none of their results reaches the caller's buffers
@@ -225,7 +225,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     __shared__ uint32_t words[TB][MW];
     __shared__ int tmax[TB];                         // max |x| per token (bit pattern of a non-negative float)
     __shared__ int nflag;
-    __shared__ int is_last;
+    __shared__ int is_last, arrival;
     // partial sums of the matrix-core predictor (int32) and, later, of the matrix-core W' product (fp32)
     __shared__ int pacc[DEFER ? NW : 1][16][DEFER ? TB : 1];
     float (*wpart)[16][DEFER ? TB : 1] = reinterpret_cast<float (*)[16][DEFER ? TB : 1]>(pacc);
@@ -893,7 +893,9 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
     if (tid == 0) {
         // (strict_release: a formal agent-scope release by the signalling thread on top of the waits above)
         if (strict_release) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        is_last = (__hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1);
+        const int before = __hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        arrival = before;
+        is_last = before == (int)gridDim.x - 1;
     }
     __syncthreads();
     if (!is_last) {
@@ -902,7 +904,19 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
         //      first in the layer that runs next (pf_rows = that layer's codes, null if unknown).
         //      (Requesting them BEFORE the block signals - behind its own stores, waiting only for
         //      the older operations - was measured slower: 24.2 against 23.4 us per token.)
-        if (pf_rows != nullptr && jn > 0) warm_rows<BLOCK>(pf_rows + (size_t)j0 * QROW, min(pf_bytes, jn * QROW), tid);
+        if (pf_rows != nullptr && jn > 0) {
+            // How much: the earlier a block finished (its number in the order of arrival at the counter), the
+            // longer its wait for the launch to end - pf_shape holds, in sixteenths of pf_bytes, what the first
+            // block to arrive asks for (low byte) and what the last would (next byte), linear in between; late
+            // blocks ask for little, so that the launch does not end on their requests (0: pf_bytes for all).
+            int want = pf_bytes;
+            if (pf_shape != 0) {
+                const int first16 = pf_shape & 255, last16 = (pf_shape >> 8) & 255;
+                const int m16 = first16 - ((first16 - last16) * arrival) / (int)gridDim.x;
+                want = max(16, ((pf_bytes >> 4) * m16) & ~15);
+            }
+            warm_rows<BLOCK>(pf_rows + (size_t)j0 * QROW, min(want, jn * QROW), tid);
+        }
         return;
     }
 
@@ -1343,7 +1357,7 @@ tardis_status_t launch_decode_impl(tardis_layer_s* L, const DecodeScratch& ws, c
                        static_cast<const bf16_t*>(L->b1 ? L->b1 : L->zeros_h), static_cast<const bf16_t*>(L->W2T),
                        L->a, L->c, static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), yfold, ws.yfix,
                        L->dec_copies, mask, (int)L->mask_words, ws.sync, h, npb, rpb, (int)L->act, norm_out, kRmsEps,
-                       rec, n_act, DEFER ? nullptr : pf_rows, (int)L->prefetch_bytes, L->fx_bound, ws.sync + kFxExpAt, (int)L->strict_release,
+                       rec, n_act, DEFER ? nullptr : pf_rows, (int)L->prefetch_bytes, L->fx_bound, ws.sync + kFxExpAt, (int)L->strict_release, (int)L->prefetch_shape,
                        L->Wp8, L->wp8_scale);
     TD_HIP(hipGetLastError());
     if (DEFER) {
