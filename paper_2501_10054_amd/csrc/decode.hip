@@ -1009,14 +1009,14 @@ __global__ void __launch_bounds__(1024)
 down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int pbw, float* __restrict__ yfold,
                     float* __restrict__ yfix, bf16_t* __restrict__ y, int32_t* __restrict__ done, int D, int nslices,
                     int norm_out, float eps, int n_act, const unsigned char* __restrict__ pf_rows, int pf_bytes,
-                    int pf_row_bytes, int npb, int h, const int32_t* __restrict__ fx_exp) {
+                    int pf_row_bytes, int npb, int h, const int32_t* __restrict__ fx_exp, int pf_shape) {
     constexpr int NW = 16, U = SL == 128 ? 48 : 16;  // wavefronts; rows in flight per wavefront (4- or 8-byte loads)
     constexpr int CPL = SL / TD_WAVE;                // columns per lane: 4 (8-byte loads) or 2 (4-byte loads)
     static_assert(CPL == 4 || CPL == 2, "slice width");
     typedef float f32x4 __attribute__((ext_vector_type(4)));
     typedef float f32xc __attribute__((ext_vector_type(CPL)));
     extern __shared__ __align__(16) float accL[];    // NW x TB x SL
-    __shared__ int is_last;
+    __shared__ int is_last, arrival;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int slice = blockIdx.x % nslices, group = blockIdx.x / nslices;
     float* acc = accL + (size_t)wave * TB * SL + lane * CPL;
@@ -1028,10 +1028,17 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
     }
     // a block that is not the last to finish warms the caches for the next layer's first kernel:
     // the predictor rows of block index blockIdx.x there (same grid size as that kernel)
-    auto warm_next = [&]() {
+    // (how much follows the block's place `a` among the `cnt` blocks that share its counter, as in the
+    //  single-token kernel; cnt = 0: the flat amount)
+    auto warm_next = [&](int a = 0, int cnt = 0) {
         const int j0n = (int)blockIdx.x * npb, jnn = min(npb, h - j0n);
+        int want = pf_bytes;
+        if (pf_shape != 0 && cnt > 0) {
+            const int first16 = pf_shape & 255, last16 = (pf_shape >> 8) & 255;
+            want = max(16, ((pf_bytes >> 4) * (first16 - ((first16 - last16) * a) / cnt)) & ~15);
+        }
         if (pf_rows != nullptr && (int)blockIdx.x < nblk && jnn > 0)
-            warm_rows<1024>(pf_rows + (size_t)j0n * pf_row_bytes, min(pf_bytes, jnn * pf_row_bytes), tid);
+            warm_rows<1024>(pf_rows + (size_t)j0n * pf_row_bytes, min(want, jnn * pf_row_bytes), tid);
     };
     const bf16_t* base = W2T + (size_t)slice * SL + lane * CPL;
     // a wavefront takes `pbw` predictor blocks in turn
@@ -1169,12 +1176,13 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
         // ---- no row-wide quantity is needed: the last of the blocks that share this slice of
         //      columns assembles the slice (counter 1 + slice), all slices in parallel
         const int ngroups = (int)gridDim.x / nslices;
-        if (tid == 0)
-            is_last = (__hip_atomic_fetch_add(done + 1 + slice, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                       ngroups - 1);
+        if (tid == 0) {
+            arrival = __hip_atomic_fetch_add(done + 1 + slice, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            is_last = arrival == ngroups - 1;
+        }
         __syncthreads();
         if (!is_last) {
-            warm_next();
+            warm_next(arrival, ngroups);
             return;
         }
         for (int k = tid; k < TB * (SL / 4); k += 1024) {
@@ -1193,11 +1201,13 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
         return;
     }
     if constexpr (!FX) {
-        if (tid == 0)
-            is_last = (__hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1);
+        if (tid == 0) {
+            arrival = __hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            is_last = arrival == (int)gridDim.x - 1;
+        }
         __syncthreads();
         if (!is_last) {
-            warm_next();
+            warm_next(arrival, (int)gridDim.x);
             return;
         }
     }
@@ -1370,7 +1380,7 @@ tardis_status_t launch_decode_impl(tardis_layer_s* L, const DecodeScratch& ws, c
         hipLaunchKernelGGL(k2, dim3(nslices * ngroups), dim3(1024), lds2, s, static_cast<const bf16_t*>(L->W2T), rec,
                            G, pbw, yfold, ws.yfix, static_cast<bf16_t*>(y), ws.sync, D, nslices, norm_out, kRmsEps, n_act,
                            TB >= 16 ? nullptr : pf_rows,   // (sixteen tokens: its blocks end too close together for the warming to pay)
-                           (int)L->prefetch_bytes, SK == 8 ? D : D / 2, npb, h, ws.sync + kFxExpAt);
+                           (int)L->prefetch_bytes, SK == 8 ? D : D / 2, npb, h, ws.sync + kFxExpAt, (int)L->prefetch_shape);
         TD_HIP(hipGetLastError());
     }
     return TARDIS_OK;
