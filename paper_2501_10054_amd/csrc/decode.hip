@@ -809,7 +809,6 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
         }
         __syncthreads();
         if (!is_last) return;
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         float* redt = &dl[0][0];
 #pragma unroll
         for (int t = 0; t < TB; ++t) {
@@ -817,7 +816,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
             float ss = 0.0f;
 #pragma unroll
             for (int u = 0; u < CPT; ++u) {
-                v[u] = yfold[(size_t)t * D + tid + u * BLOCK];
+                v[u] = load_coherent(yfold + (size_t)t * D + tid + u * BLOCK);    // (parked by blocks on any XCD)
                 ss += v[u] * v[u];
             }
             ss = td_wave_sum(ss);
@@ -922,12 +921,82 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
 
     // ---- the last block to finish assembles y and re-arms the scratch (one cache invalidation,
     //      then 16-byte loads: faster here than four-byte device-coherent loads, many per thread)
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     typedef float f32x4 __attribute__((ext_vector_type(4)));
     constexpr int OI = (D / 4 + BLOCK - 1) / BLOCK;   // float4 pieces of one token's y per thread
     const f32x4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
     f32x4 out[TB][OI];
     f32x4 part[TB][OI][kMaxCopies];
+    if constexpr (TB == 1 && OI == 1) {
+        // One token: 16-byte device-coherent loads (what an agent-scope atomic load is, four dwords wide) instead
+        // of an agent-scope acquire, whose cache invalidation would also drop from this XCD's L2 the rows just
+        // requested for the next layer.  (One statement for the loads and their wait: the compiler does not
+        // know that the registers are in flight and would otherwise be free to copy them before the wait.
+        // Copies the layer does not use re-read copy 0 and are discarded.)
+        const int k4 = min(tid, D / 4 - 1);
+        const f32x4* pa = reinterpret_cast<const f32x4*>(yfold) + k4;
+        const f32x4* p0 = reinterpret_cast<const f32x4*>(yfix) + k4;
+        const f32x4* p1 = reinterpret_cast<const f32x4*>(yfix + (size_t)(copies > 1 ? 1 : 0) * D) + k4;
+        const f32x4* p2 = reinterpret_cast<const f32x4*>(yfix + (size_t)(copies > 2 ? 2 : 0) * D) + k4;
+        const f32x4* p3 = reinterpret_cast<const f32x4*>(yfix + (size_t)(copies > 3 ? 3 : 0) * D) + k4;
+        static_assert(kMaxCopies == 4, "one load per copy below");
+        f32x4 va, v0, v1, v2, v3;
+        asm volatile(
+            "global_load_dwordx4 %0, %5, off sc1\n\t"
+            "global_load_dwordx4 %1, %6, off sc1\n\t"
+            "global_load_dwordx4 %2, %7, off sc1\n\t"
+            "global_load_dwordx4 %3, %8, off sc1\n\t"
+            "global_load_dwordx4 %4, %9, off sc1\n\t"
+            "s_waitcnt vmcnt(0)"
+            : "=&v"(va), "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3)
+            : "v"(pa), "v"(p0), "v"(p1), "v"(p2), "v"(p3)
+            : "memory");
+        const bool live = tid < D / 4;
+        out[0][0] = live ? va : zero4;
+        part[0][0][0] = live ? v0 : zero4;
+        part[0][0][1] = (live && copies > 1) ? v1 : zero4;
+        part[0][0][2] = (live && copies > 2) ? v2 : zero4;
+        part[0][0][3] = (live && copies > 3) ? v3 : zero4;
+    } else if constexpr (TB == 2 && OI == 1) {
+        // two tokens: the same, ten loads behind one wait
+        const int k4 = min(tid, D / 4 - 1);
+        const f32x4* pa[2];
+        const f32x4* pc[2][kMaxCopies];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            pa[t] = reinterpret_cast<const f32x4*>(yfold + (size_t)t * D) + k4;
+#pragma unroll
+            for (int cidx = 0; cidx < kMaxCopies; ++cidx)
+                pc[t][cidx] = reinterpret_cast<const f32x4*>(yfix + ((size_t)(cidx < copies ? cidx : 0) * TB + t) * D) + k4;
+        }
+        f32x4 va0, va1, v00, v01, v02, v03, v10, v11, v12, v13;
+        asm volatile(
+            "global_load_dwordx4 %0, %10, off sc1\n\t"
+            "global_load_dwordx4 %1, %11, off sc1\n\t"
+            "global_load_dwordx4 %2, %12, off sc1\n\t"
+            "global_load_dwordx4 %3, %13, off sc1\n\t"
+            "global_load_dwordx4 %4, %14, off sc1\n\t"
+            "global_load_dwordx4 %5, %15, off sc1\n\t"
+            "global_load_dwordx4 %6, %16, off sc1\n\t"
+            "global_load_dwordx4 %7, %17, off sc1\n\t"
+            "global_load_dwordx4 %8, %18, off sc1\n\t"
+            "global_load_dwordx4 %9, %19, off sc1\n\t"
+            "s_waitcnt vmcnt(0)"
+            : "=&v"(va0), "=&v"(va1), "=&v"(v00), "=&v"(v01), "=&v"(v02), "=&v"(v03), "=&v"(v10), "=&v"(v11), "=&v"(v12), "=&v"(v13)
+            : "v"(pa[0]), "v"(pa[1]), "v"(pc[0][0]), "v"(pc[0][1]), "v"(pc[0][2]), "v"(pc[0][3]), "v"(pc[1][0]), "v"(pc[1][1]), "v"(pc[1][2]), "v"(pc[1][3])
+            : "memory");
+        const bool live = tid < D / 4;
+        out[0][0] = live ? va0 : zero4;
+        out[1][0] = live ? va1 : zero4;
+        part[0][0][0] = live ? v00 : zero4;
+        part[0][0][1] = (live && copies > 1) ? v01 : zero4;
+        part[0][0][2] = (live && copies > 2) ? v02 : zero4;
+        part[0][0][3] = (live && copies > 3) ? v03 : zero4;
+        part[1][0][0] = live ? v10 : zero4;
+        part[1][0][1] = (live && copies > 1) ? v11 : zero4;
+        part[1][0][2] = (live && copies > 2) ? v12 : zero4;
+        part[1][0][3] = (live && copies > 3) ? v13 : zero4;
+    } else {
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 #pragma unroll
     for (int t = 0; t < TB; ++t)                      // every load of every token requested before any is used
 #pragma unroll
@@ -941,6 +1010,7 @@ decode_fused_kernel(const bf16_t* __restrict__ Wp, const float* __restrict__ bp,
                                         ? reinterpret_cast<const f32x4*>(yfix + ((size_t)cidx * TB + t) * D)[k4]
                                         : zero4;
         }
+    }
     float ss[TB];
 #pragma unroll
     for (int t = 0; t < TB; ++t) {
@@ -1213,23 +1283,49 @@ down_project_kernel(const bf16_t* __restrict__ W2T, DeferOut rec, int nblk, int 
     }
 
     // ---- the last block assembles the tokens (with their row-wide norm) and re-arms the scratch
-    //      (a single block at the very end: one cache invalidation and 16-byte loads are cheaper
-    //      here than many four-byte device-coherent loads per thread)
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     float* redt = accL;                              // NW x TB floats, free by now
     constexpr int TH = TB < 4 ? TB : 4;              // tokens assembled together
     for (int t0 = 0; t0 < TB; t0 += TH) {
         for (int k0 = 0; k0 < D / 4; k0 += 1024) {   // one pass when d = 4096
             const int k4 = k0 + tid;
             const bool live = k4 < D / 4;
+            const int k4c = min(k4, D / 4 - 1);
             f32x4 v[TH];
+            // device-coherent loads, not an agent-scope acquire and plain loads: the acquire's cache invalidation
+            // costs about a microsecond and drops what has been requested for the next layer
+            if constexpr (TH == 4) {
+                f32x4 f[4], g[4];
+                const f32x4* pf[4];
+                const f32x4* pg[4];
 #pragma unroll
-            for (int t = 0; t < TH; ++t) {
-                const f32x4 f = (live && t0 + t < n_act) ? reinterpret_cast<const f32x4*>(yfold + (size_t)(t0 + t) * D)[k4]
-                                                         : zero4;
-                // (FX: the parked rows are complete and the accumulators re-armed already)
-                const f32x4 g = (live && !FX) ? reinterpret_cast<const f32x4*>(yfix + (size_t)(t0 + t) * D)[k4] : zero4;
-                v[t] = f + g;
+                for (int t = 0; t < 4; ++t) {
+                    pf[t] = reinterpret_cast<const f32x4*>(yfold + (size_t)(t0 + t) * D) + k4c;
+                    pg[t] = reinterpret_cast<const f32x4*>(yfix + (size_t)(t0 + t) * D) + k4c;
+                }
+                // (one statement for the loads and their wait: the compiler does not know the registers are in flight)
+                asm volatile(
+                    "global_load_dwordx4 %0, %8, off sc1\n\t"
+                    "global_load_dwordx4 %1, %9, off sc1\n\t"
+                    "global_load_dwordx4 %2, %10, off sc1\n\t"
+                    "global_load_dwordx4 %3, %11, off sc1\n\t"
+                    "global_load_dwordx4 %4, %12, off sc1\n\t"
+                    "global_load_dwordx4 %5, %13, off sc1\n\t"
+                    "global_load_dwordx4 %6, %14, off sc1\n\t"
+                    "global_load_dwordx4 %7, %15, off sc1\n\t"
+                    "s_waitcnt vmcnt(0)"
+                    : "=&v"(f[0]), "=&v"(f[1]), "=&v"(f[2]), "=&v"(f[3]), "=&v"(g[0]), "=&v"(g[1]), "=&v"(g[2]), "=&v"(g[3])
+                    : "v"(pf[0]), "v"(pf[1]), "v"(pf[2]), "v"(pf[3]), "v"(pg[0]), "v"(pg[1]), "v"(pg[2]), "v"(pg[3])
+                    : "memory");
+#pragma unroll
+                for (int t = 0; t < 4; ++t)          // (FX: the parked rows are complete and the accumulators re-armed already)
+                    v[t] = ((live && t0 + t < n_act) ? f[t] : zero4) + ((live && !FX) ? g[t] : zero4);
+            } else {
+#pragma unroll
+                for (int t = 0; t < TH; ++t) {
+                    const f32x4 f = (live && t0 + t < n_act) ? load_coherent4(yfold + (size_t)(t0 + t) * D + 4 * k4c) : zero4;
+                    const f32x4 g = (live && !FX) ? load_coherent4(yfix + (size_t)(t0 + t) * D + 4 * k4c) : zero4;
+                    v[t] = f + g;
+                }
             }
             if (live && !FX) {
 #pragma unroll
