@@ -10,6 +10,8 @@
 //   mode 5: packed f16 atomics (half the atomic lanes)
 //   mode 6: counted 64-bit fixed-point atomics with return; the add that completes a column writes it
 //   mode 7: as 6, with 96 KiB of further loads requested behind the atomics
+//   mode 8: as 1, but the last block reads the accumulators with 16-byte device-coherent loads instead of
+//           an agent-scope acquire (cache invalidation) and plain loads
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stdio.h>
@@ -93,9 +95,9 @@ __global__ void __launch_bounds__(BLOCK) k(const u32x4* __restrict__ data, int v
     }
     return;
   }
-  if (MODE == 1 || MODE == 4 || MODE == 5) {
+  if (MODE == 1 || MODE == 4 || MODE == 5 || MODE == 8) {
     float* dst = acc + (size_t)(blk & 1) * D + ctid;
-    if (MODE == 1) {
+    if (MODE == 1 || MODE == 8) {
 #pragma unroll
       for (int u = 0; u < 4; ++u) __hip_atomic_fetch_add(dst + u * BLOCK, part[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     } else if (MODE == 4) {
@@ -112,9 +114,17 @@ __global__ void __launch_bounds__(BLOCK) k(const u32x4* __restrict__ data, int v
     if (tid == 0) is_last = (__hip_atomic_fetch_add(&sy->done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == G - 1);
     __syncthreads();
     if (!is_last) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    const f32x4 a0 = reinterpret_cast<const f32x4*>(acc)[tid];
-    const f32x4 a1 = reinterpret_cast<const f32x4*>(acc + D)[tid];
+    f32x4 a0, a1;
+    if (MODE == 8) {   // (loads and their wait in one statement: the compiler does not know the registers are in flight)
+      asm volatile("global_load_dwordx4 %0, %2, off sc1\n\tglobal_load_dwordx4 %1, %3, off sc1\n\ts_waitcnt vmcnt(0)"
+                   : "=&v"(a0), "=&v"(a1)
+                   : "v"(reinterpret_cast<const f32x4*>(acc) + tid), "v"(reinterpret_cast<const f32x4*>(acc + D) + tid)
+                   : "memory");
+    } else {
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      a0 = reinterpret_cast<const f32x4*>(acc)[tid];
+      a1 = reinterpret_cast<const f32x4*>(acc + D)[tid];
+    }
     const f32x4 z = {0, 0, 0, 0};
     reinterpret_cast<f32x4*>(acc)[tid] = z;
     reinterpret_cast<f32x4*>(acc + D)[tid] = z;
@@ -206,6 +216,7 @@ int main() {
     printf("stream %4d KiB/block (%.1f MB per launch)\n", vpt * 16, vpt * 16.0 * 1024 * G / 1e6);
     printf("  mode 0 stream only      : %.2f us\n", timeit([&](int r) { k<0><<<G, BLOCK>>>(data[r % copies], vpt, acc, slots, plain, sy, y, spin); }));
     printf("  mode 1 f32 atomics+last : %.2f us\n", timeit([&](int r) { k<1><<<G, BLOCK>>>(data[r % copies], vpt, acc, slots, plain, sy, y, spin); }));
+    printf("  mode 8 f32, coherent lds: %.2f us\n", timeit([&](int r) { k<8><<<G, BLOCK>>>(data[r % copies], vpt, acc, slots, plain, sy, y, spin); }));
     printf("  mode 4 i32 atomics+last : %.2f us\n", timeit([&](int r) { k<4><<<G, BLOCK>>>(data[r % copies], vpt, acc, slots, plain, sy, y, spin); }));
     printf("  mode 5 pk f16 atom+last : %.2f us\n", timeit([&](int r) { k<5><<<G, BLOCK>>>(data[r % copies], vpt, acc, slots, plain, sy, y, spin); }));
     CK(hipMemset(slots, 0, (size_t)G * D * 8));
